@@ -1,0 +1,131 @@
+/*
+ * rnnd.h -- C ABI of librnnd: graph construction by Relative NN-Descent
+ * (arXiv 2310.20419) on one AMD MI355X (gfx950).
+ *
+ * Everything behind these calls runs in hand-written HIP kernels.  There is no
+ * CPU fallback: without a usable GPU every compute call returns RNND_ERR_HIP.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory owned by the caller; the library
+ *     never keeps a pointer after a call returns.
+ *   - X is row-major N x d, contiguous, uint8 or float32.
+ *   - vertex ids are 0-based (the paper's V = {1..n}, Sec. 2.2, shifted by one).
+ *   - delta(u,v) is the squared Euclidean distance of x_u and x_v (Eq. 3 with
+ *     dist = squared L2; every comparison of Alg. 3-5 is monotone in it).
+ *     uint8 data: exact int32.  float data: accumulated in double, rounded once
+ *     to float, bit-identical for delta(u,v) and delta(v,u).
+ *   - every call enqueues its work on `stream` (a hipStream_t, may be NULL for
+ *     the default stream) and returns after that work has completed, so the
+ *     status reflects kernel errors too.
+ *   - return value: RNND_OK (0) or a negative rnnd_status; outputs are
+ *     unspecified after an error.  No call aborts or throws.
+ *
+ * Graph state ("snapshot") used by the step-wise entry points
+ *   keys : device uint64 [N * R], row u = neighbour list of u, deg[u] valid entries in
+ *          ascending order, each  (dist_bits << 32) | (id << 1) | is_new
+ *          where dist_bits is the int32 distance (uint8 data) or the IEEE bit pattern of
+ *          the float distance (float data; non-negative, so the unsigned order is the
+ *          numeric order) and is_new is the paper's "new"/"old" flag of Alg. 4.
+ *          Ascending key order is ascending (delta, id).  Entries past deg[u] are unspecified.
+ *   deg  : device int32 [N].
+ */
+#ifndef RNND_H
+#define RNND_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RNND_MAX_R 128          /* largest supported degree cap R */
+#define RNND_MAX_ROUNDS 256     /* per-round statistics are kept for the first 256 rounds */
+
+typedef enum { RNND_U8 = 0, RNND_F32 = 1 } rnnd_dtype;
+typedef enum { RNND_L2SQ = 0 } rnnd_metric;
+
+typedef enum {
+    RNND_OK = 0,
+    RNND_ERR_NULL = -1,         /* a required pointer is NULL */
+    RNND_ERR_BAD_SHAPE = -2,    /* N < 2, N > 2^31-2, d < 1, or uint8 d > 33025 (int32 overflow) */
+    RNND_ERR_BAD_PARAM = -3,    /* S < 1, S > R, S > N-1, R < 1, R > RNND_MAX_R, T1 < 1, T2 < 1 */
+    RNND_ERR_UNSUPPORTED = -4,  /* unknown dtype or metric */
+    RNND_ERR_OOM = -5,          /* workspace allocation failed */
+    RNND_ERR_HIP = -6           /* a HIP call or kernel failed (no GPU, launch error, ...) */
+} rnnd_status;
+
+/* Counters of one build, filled on the host.  "algo" evaluations are the delta(v,w)
+ * evaluations Alg. 4 line 11 performs (with the old/old skip of lines 8-9 and the break of
+ * line 14); "exec" are the distances the kernels actually computed. */
+typedef struct {
+    int32_t rounds;                         /* UpdateNeighbors rounds run (T1*T2) */
+    int32_t reverse_calls;                  /* AddReverseEdges calls run (T1-1) */
+    float total_ms, init_ms;                /* GPU time of the whole call / of RandomGraph */
+    float round_ms[RNND_MAX_ROUNDS];        /* GPU time of each UpdateNeighbors round */
+    float reverse_ms[RNND_MAX_ROUNDS];      /* GPU time of each AddReverseEdges call */
+    int64_t init_evals;                     /* N*S */
+    int64_t active[RNND_MAX_ROUNDS];        /* vertices with at least one "new" entry */
+    int64_t proposals[RNND_MAX_ROUNDS];     /* redirected edges emitted (Alg. 4 line 13) */
+    int64_t algo_evals[RNND_MAX_ROUNDS];
+    int64_t exec_evals[RNND_MAX_ROUNDS];
+    int64_t gathered_rows[RNND_MAX_ROUNDS]; /* rows of X the round kernel fetched */
+} rnnd_stats;
+
+/* Alg. 6, RNN-Descent(S, R, T1, T2), with synchronous rounds:
+ *   G <- RandomGraph(S), all flags new; T1 x { T2 x UpdateNeighbors; AddReverseEdges unless last }.
+ * Each UpdateNeighbors round scans every vertex against the same snapshot (Alg. 4 lines 2-15)
+ * and then rebuilds every list as the first R entries, in (delta, id) order and without
+ * duplicates, of its kept entries plus the edges redirected to it (line 13: v enters w's list).
+ *   X          device, N x d
+ *   graph_out  device int32 [N * R]: row u = neighbour ids of u, ascending (delta, id), -1 padded
+ *   degree_out device int32 [N]
+ *   seed       seeds RandomGraph's counter-based generator; same seed, same graph, bit for bit
+ */
+int rnnd_build(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+               int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out, int32_t *degree_out,
+               void *stream);
+
+/* Same build; additionally returns the final snapshot (keys_out: device uint64 [N*R], may be
+ * NULL) and the counters (stats: host, may be NULL). */
+int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+                  int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out, int32_t *degree_out,
+                  uint64_t *keys_out, rnnd_stats *stats, void *stream);
+
+/* Bytes of device workspace rnnd_build allocates (and frees) internally for these sizes. */
+int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, size_t *bytes);
+
+/* RandomGraph(S) (Alg. 6 lines 1-2): row u <- S distinct ids != u drawn from a counter-based
+ * generator (draw j of vertex u = mix64(mix64(seed + G*(u+1)) + G*(j+1)), mix64 = splitmix64's
+ * output function, G = 0x9E3779B97F4A7C15; id = c + (c >= u) with c = ((draw >> 32) * (N-1)) >> 32;
+ * repeats are skipped), with delta(u, id), flag new, sorted.  Writes keys [N*R] and deg [N]. */
+int rnnd_random_graph(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
+                      int32_t R, uint64_t seed, uint64_t *keys, int32_t *deg, void *stream);
+
+/* n_rounds synchronous UpdateNeighbors rounds (Alg. 4) applied in place to a snapshot.
+ * stats (host, may be NULL) receives the per-round counters. */
+int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t R,
+                          uint64_t *keys, int32_t *deg, int32_t n_rounds, rnnd_stats *stats,
+                          void *stream);
+
+/* AddReverseEdges(G, R) (Alg. 5) applied in place to a snapshot: union with the reversed edges
+ * (flag new, existing entries keep theirs), then every out-list is cut to its R shortest, then
+ * every in-list is cut to its R shortest by (delta, source id). */
+int rnnd_add_reverse_edges(int64_t N, int32_t R, uint64_t *keys, int32_t *deg, void *stream);
+
+/* Snapshot -> output format of rnnd_build (ids, -1 padded; degrees). */
+int rnnd_export_graph(int64_t N, int32_t R, const uint64_t *keys, const int32_t *deg,
+                      int32_t *graph_out, int32_t *degree_out, void *stream);
+
+/* Selects the UpdateNeighbors kernel: 0 = automatic (default), 1 = generic pair-at-a-time
+ * kernel, 2 = dense MFMA block kernel (uint8 data with d a multiple of 64 only; other inputs
+ * fall back to 1).  Both give identical graphs; this exists for testing and profiling. */
+int rnnd_set_kernel_variant(int variant);
+
+const char *rnnd_strerror(int status);
+int rnnd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNND_H */

@@ -1,0 +1,13 @@
+"""Relative NN-Descent graph construction on AMD MI355X (gfx950).
+
+Thin binding over the C ABI of ``include/rnnd.h`` (``librnnd.so``, built in-tree by
+``paper_2310_20419_amd.build``).  Every step runs in the library's HIP kernels; this module only
+marshals arguments.  PyTorch is used for device memory and streams, nothing else.  There is no
+CPU fallback: if the library is missing or no GPU is usable, calls raise.
+"""
+from ._binding import (  # noqa: F401
+    RnndError, Stats, lib_path, load_library, exported_symbols,
+    rnnd_build, rnnd_build_ex, rnnd_workspace_bytes, rnnd_random_graph, rnnd_update_neighbors,
+    rnnd_add_reverse_edges, rnnd_export_graph, rnnd_set_kernel_variant, rnnd_strerror, rnnd_version,
+    pack_keys, unpack_keys, RNND_U8, RNND_F32, RNND_L2SQ, RNND_MAX_R,
+)

@@ -1,0 +1,76 @@
+// delta(a, b) = squared Euclidean distance of two rows of X (Eq. 3 with dist = squared L2),
+// computed by a group of 8 consecutive lanes; all 8 receive the result.
+//
+//   uint8 rows : exact int32, sum of (a-b)^2 through three byte dot products per word.
+//   float rows : each lane accumulates (double)(a-b)^2 over its 16-byte chunks in chunk order,
+//                the 8 partial sums are combined in a fixed xor tree, and the double is rounded
+//                once to float.  (a-b)^2 == (b-a)^2 exactly, so delta(a,b) and delta(b,a) are the
+//                same bits wherever they are computed.
+// The result is returned as the 32 "dist_bits" of a key: the int32 value, or the float's bit pattern.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define DT_U8 0
+#define DT_F32 1
+
+__device__ __forceinline__ int sqdiff_word_u8(uint32_t a, uint32_t b, int acc)
+{
+    // sum over 4 bytes of (a-b)^2 = a.a + b.b - 2 a.b ; every term fits comfortably in 32 bits
+    uint32_t aa = __builtin_amdgcn_udot4(a, a, 0u, false);
+    uint32_t bb = __builtin_amdgcn_udot4(b, b, 0u, false);
+    uint32_t ab = __builtin_amdgcn_udot4(a, b, 0u, false);
+    return acc + (int)(aa + bb - 2u * ab);
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void *pb, int d,
+                                                     int vec_ok, int sub)
+{
+    if (DT == DT_U8) {
+        const uint8_t *a = (const uint8_t *)pa, *b = (const uint8_t *)pb;
+        int acc = 0;
+        if (vec_ok) {
+            const int nchunk = d >> 4;
+            for (int c = sub; c < nchunk; c += 8) {
+                uint4 va = ((const uint4 *)a)[c], vb = ((const uint4 *)b)[c];
+                acc = sqdiff_word_u8(va.x, vb.x, acc);
+                acc = sqdiff_word_u8(va.y, vb.y, acc);
+                acc = sqdiff_word_u8(va.z, vb.z, acc);
+                acc = sqdiff_word_u8(va.w, vb.w, acc);
+            }
+        } else {
+            for (int e = sub; e < d; e += 8) {
+                int t = (int)a[e] - (int)b[e];
+                acc += t * t;
+            }
+        }
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        acc += __shfl_xor(acc, 4);
+        return (uint32_t)acc;
+    } else {
+        const float *a = (const float *)pa, *b = (const float *)pb;
+        double acc = 0.0;
+        if (vec_ok) {
+            const int nchunk = d >> 2;
+            for (int c = sub; c < nchunk; c += 8) {
+                float4 va = ((const float4 *)a)[c], vb = ((const float4 *)b)[c];
+                double t;
+                t = (double)va.x - (double)vb.x; acc = fma(t, t, acc);
+                t = (double)va.y - (double)vb.y; acc = fma(t, t, acc);
+                t = (double)va.z - (double)vb.z; acc = fma(t, t, acc);
+                t = (double)va.w - (double)vb.w; acc = fma(t, t, acc);
+            }
+        } else {
+            for (int e = sub; e < d; e += 8) {
+                double t = (double)a[e] - (double)b[e];
+                acc = fma(t, t, acc);
+            }
+        }
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        acc += __shfl_xor(acc, 4);
+        return __float_as_uint((float)acc);
+    }
+}

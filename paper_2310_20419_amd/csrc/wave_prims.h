@@ -1,0 +1,160 @@
+// Wavefront-level building blocks (gfx950, wave64): key packing, a register bitonic sort
+// over 64*E keys, and the "first R distinct keys" selection that every merge step uses.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef unsigned long long u64;
+typedef uint32_t u32;
+
+#define KEY_PAD 0xFFFFFFFFFFFFFFFFull   // sorts after every real key
+
+// (dist_bits << 32) | (id << 1) | is_new : ascending key order is ascending (delta, id), and of two
+// entries for the same edge the "old" one comes first.
+__device__ __forceinline__ u64 make_key(u32 dist_bits, u32 id, u32 is_new)
+{
+    return ((u64)dist_bits << 32) | ((u64)id << 1) | (u64)is_new;
+}
+__device__ __forceinline__ u32 key_id(u64 k) { return (u32)(k >> 1) & 0x7FFFFFFFu; }
+__device__ __forceinline__ u32 key_dist(u64 k) { return (u32)(k >> 32); }
+
+// Orders LDS traffic between lanes of one wavefront.  A wavefront executes its LDS
+// instructions in program order, so only the compiler has to be kept from moving them.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ u64 lanes_below(int lane) { return lane == 0 ? 0ull : (~0ull >> (64 - lane)); }
+
+__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m)
+{
+    u32 lo = (u32)v, hi = (u32)(v >> 32);
+    lo = __shfl_xor(lo, m);
+    hi = __shfl_xor(hi, m);
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ u64 shfl_u64(u64 v, int src)
+{
+    u32 lo = (u32)v, hi = (u32)(v >> 32);
+    lo = __shfl(lo, src);
+    hi = __shfl(hi, src);
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ u64 shfl_up1_u64(u64 v)
+{
+    u32 lo = (u32)v, hi = (u32)(v >> 32);
+    lo = __shfl_up(lo, 1);
+    hi = __shfl_up(hi, 1);
+    return ((u64)hi << 32) | lo;
+}
+
+// Ascending bitonic sort of 64*E keys held as k[r] in lane l  <->  element index r*64 + l.
+template <int E>
+__device__ __forceinline__ void wave_sort(u64 (&k)[E], int lane)
+{
+#pragma unroll
+    for (int size = 2; size <= 64 * E; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            if (stride >= 64) {
+                const int rs = stride / 64;
+#pragma unroll
+                for (int r = 0; r < E; ++r) {
+                    if ((r & rs) == 0) {
+                        const bool up = (((r * 64) & size) == 0);
+                        u64 a = k[r], b = k[r | rs];
+                        u64 lo = a < b ? a : b, hi = a < b ? b : a;
+                        k[r] = up ? lo : hi;
+                        k[r | rs] = up ? hi : lo;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < E; ++r) {
+                    const bool up = ((((r * 64) + lane) & size) == 0);
+                    u64 o = shfl_xor_u64(k[r], stride);
+                    const bool lower = (lane & stride) == 0;
+                    u64 mn = k[r] < o ? k[r] : o, mx = k[r] < o ? o : k[r];
+                    k[r] = (lower == up) ? mn : mx;
+                }
+            }
+        }
+    }
+}
+
+// k[] sorted ascending.  Drops KEY_PAD and every key equal (ignoring the flag bit) to its
+// predecessor, and writes the first `cap` survivors, in order, to out[0..) (LDS or global).
+// Returns how many were written; *any_new is set if one of them has the flag bit.
+template <int E>
+__device__ __forceinline__ int wave_unique_prefix(const u64 (&k)[E], int lane, int cap, u64 *out,
+                                                 bool *any_new)
+{
+    int base = 0;
+    u64 newacc = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        u64 prev = shfl_up1_u64(k[r]);
+        if (lane == 0) prev = KEY_PAD;
+        if (r > 0) {
+            u64 last = shfl_u64(k[r - 1], 63);
+            if (lane == 0) prev = last;
+        }
+        bool keep = (k[r] != KEY_PAD) && ((k[r] >> 1) != (prev >> 1));
+        u64 m = __builtin_amdgcn_ballot_w64(keep);
+        int pos = base + __popcll(m & lanes_below(lane));
+        bool w = keep && pos < cap;
+        if (w) out[pos] = k[r];
+        newacc |= __builtin_amdgcn_ballot_w64(w && (k[r] & 1ull));
+        base += __popcll(m);
+    }
+    *any_new = newacc != 0;
+    return base < cap ? base : cap;
+}
+
+// Row `row` (nb sorted keys) merged with `bin` (c keys in any order): the first R distinct keys of
+// the union, ascending, are written back to row[0..); returns the new length.  `stage` is 128 keys
+// of LDS private to this wavefront.
+__device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *bin, int c, int R,
+                                              u64 *stage, int lane, bool *any_new)
+{
+    const int total = nb + c;
+    int n;
+    if (total <= 64) {
+        u64 k[1];
+        k[0] = lane < nb ? row[lane] : (lane < total ? bin[lane - nb] : KEY_PAD);
+        wave_sort<1>(k, lane);
+        n = wave_unique_prefix<1>(k, lane, R, row, any_new);
+    } else if (total <= 128) {
+        u64 k[2];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            int e = r * 64 + lane;
+            k[r] = e < nb ? row[e] : (e < total ? bin[e - nb] : KEY_PAD);
+        }
+        wave_sort<2>(k, lane);
+        n = wave_unique_prefix<2>(k, lane, R, row, any_new);
+    } else {
+        // stream the bin through in chunks of 128 against the best R found so far
+        u64 k[4];
+        k[0] = lane < nb ? row[lane] : KEY_PAD;
+        k[1] = lane + 64 < nb ? row[lane + 64] : KEY_PAD;
+        n = nb;
+        for (int done = 0; done < c; done += 128) {
+            int e0 = done + lane, e1 = done + 64 + lane;
+            k[2] = e0 < c ? bin[e0] : KEY_PAD;
+            k[3] = e1 < c ? bin[e1] : KEY_PAD;
+            wave_sort<4>(k, lane);
+            n = wave_unique_prefix<4>(k, lane, R, stage, any_new);
+            wave_sync();
+            k[0] = lane < n ? stage[lane] : KEY_PAD;
+            k[1] = lane + 64 < n ? stage[lane + 64] : KEY_PAD;
+            wave_sync();
+        }
+        if (lane < n) row[lane] = k[0];
+        if (lane + 64 < n) row[lane + 64] = k[1];
+    }
+    return n;
+}

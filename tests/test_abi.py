@@ -1,0 +1,70 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol include/rnnd.h declares,
+and rejects bad arguments with the documented status codes before touching the GPU."""
+import ctypes
+import os
+
+import pytest
+
+import paper_2310_20419_amd as rn
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(rn.lib_path()):
+        from paper_2310_20419_amd import build
+        build.build()
+    return rn.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = rn.exported_symbols()
+    assert {"rnnd_build", "rnnd_build_ex", "rnnd_random_graph", "rnnd_update_neighbors",
+            "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_workspace_bytes",
+            "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_messages(lib):
+    assert rn.rnnd_version() >= 100
+    assert rn.rnnd_strerror(0) == "ok"
+    for s in range(-6, 0):
+        assert rn.rnnd_strerror(s) not in ("ok", "unknown status")
+    assert rn.rnnd_strerror(-99) == "unknown status"
+
+
+def test_bad_arguments_are_rejected_without_a_gpu(lib):
+    one = ctypes.c_void_p(1)   # never dereferenced: validation comes first
+    ok = dict(X=one, N=100, d=16, dtype=0, metric=0, S=4, R=8, T1=1, T2=1)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return lib.rnnd_build(a["X"], a["N"], a["d"], a["dtype"], a["metric"], a["S"], a["R"], a["T1"],
+                              a["T2"], 0, a.get("g", one), a.get("deg", one), None)
+
+    assert call(X=None) == -1 and call(g=None) == -1 and call(deg=None) == -1
+    assert call(N=1) == -2 and call(d=0) == -2 and call(d=33026) == -2 and call(N=2**31 - 1) == -2
+    assert call(S=0) == -3 and call(S=9) == -3 and call(R=0) == -3 and call(R=129) == -3
+    assert call(T1=0) == -3 and call(T2=0) == -3 and call(N=5, S=5, R=8) == -3
+    assert call(dtype=2) == -4 and call(metric=1) == -4
+    assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(0) == 0
+
+
+def test_workspace_bytes(lib):
+    b = rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 96)
+    # graph (8 B) + redirected edges (16 B) + bins (8 B) per slot dominate
+    assert 1_000_000 * 96 * 32 <= b < 1_000_000 * 96 * 34
+    with pytest.raises(rn.RnndError):
+        rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 500)
+
+
+def test_key_packing_roundtrip():
+    import numpy as np
+    ids = np.array([[5, 9, -1], [2, -1, -1]], np.int32)
+    bits = np.array([[10, 20, 0], [7, 0, 0]], np.uint32)
+    flags = np.array([[1, 0, 0], [0, 0, 0]], np.uint8)
+    deg = np.array([2, 1], np.int32)
+    k = rn.pack_keys(ids, bits, flags, deg)
+    assert k[0, 0] == (10 << 32) | (5 << 1) | 1 and k[0, 2] == 2**64 - 1
+    i2, b2, f2 = rn.unpack_keys(k, deg)
+    assert (i2 == ids).all() and (b2 == bits).all() and (f2 == flags).all()

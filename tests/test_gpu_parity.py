@@ -1,0 +1,198 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  uint8 data: adjacency, distances, flags, degrees and evaluation counts bit-identical.
+float data: distances are double-accumulated and rounded once on both sides, so the same
+bit-exact comparison is applied (the stated tolerance -- 1e-5 relative, >= 99 % edges -- is the
+fallback bar and is checked too).
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_util import assert_snapshot_equal, device_to_arrays, dist_bits_of, snapshot_to_device
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rn():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2310_20419_amd as m
+    m.load_library()
+    return m
+
+
+def cuda(X):
+    import torch
+    return torch.from_numpy(X).cuda()
+
+
+def gauss_f32(n, d, seed):
+    return np.random.default_rng(seed).normal(size=(n, d)).astype(np.float32)
+
+
+def clustered_u8(n, d, seed, k=8, spread=6):
+    g = np.random.default_rng(seed)
+    c = g.integers(20, 236, size=(k, d))
+    x = c[g.integers(0, k, size=n)] + g.integers(-spread, spread + 1, size=(n, d))
+    return np.clip(x, 0, 255).astype(np.uint8)
+
+
+DATASETS = {
+    "cfg1": lambda: wl.make_data(wl.CONFIGS["cfg1"]),
+    "u8_d128": lambda: wl.custom("heavy_u8", 3000, 128, 7),
+    "u8_d33_ties": lambda: clustered_u8(1500, 33, 3),          # odd d: element-wise path; many ties
+    "u8_dups": lambda: np.repeat(clustered_u8(300, 16, 4), 4, axis=0),   # exact duplicates, delta = 0
+    "f32_d96": lambda: wl.custom("unit_f32", 3000, 96, 9),
+    "f32_d960": lambda: wl.custom("beta_f32", 1200, 960, 11),
+    "f32_d7": lambda: gauss_f32(1000, 7, 5),
+}
+
+
+@pytest.mark.parametrize("name,S,R", [("cfg1", 10, 32), ("u8_d128", 20, 96), ("u8_d33_ties", 5, 16),
+                                      ("f32_d96", 20, 96), ("f32_d960", 8, 24), ("f32_d7", 128, 128),
+                                      ("u8_dups", 12, 12)])
+def test_random_graph(rn, oracle_mod, name, S, R):
+    X = DATASETS[name]()
+    want = oracle_mod.random_graph(X, S, 2310, R)
+    keys, deg = rn.rnnd_random_graph(cuda(X), S, R, 2310)
+    assert_snapshot_equal(want, X.dtype == np.float32, keys, deg, name)
+
+
+@pytest.mark.parametrize("name,S,R", [("cfg1", 10, 32), ("u8_d128", 20, 96), ("u8_d33_ties", 6, 16),
+                                      ("u8_dups", 8, 12), ("f32_d96", 20, 96), ("f32_d960", 8, 24),
+                                      ("f32_d7", 100, 128)])
+def test_rounds_from_shared_snapshots(rn, oracle_mod, name, S, R):
+    """Every step starts from the oracle's snapshot, so one divergence cannot hide the next."""
+    X = DATASETS[name]()
+    isf = X.dtype == np.float32
+    Xd = cuda(X)
+    snap = oracle_mod.random_graph(X, S, 99, R)
+    for step in ["u", "u", "u", "r", "u", "u", "r", "u"]:
+        keys, deg = snapshot_to_device(snap, isf, R)
+        if step == "u":
+            snap, evals, props = oracle_mod.update_neighbors_sync(X, snap, R)
+            st = rn.rnnd_update_neighbors(Xd, keys, deg, R, 1)
+            assert st.algo_evals[0] == evals and st.proposals[0] == props
+        else:
+            snap = oracle_mod.add_reverse_edges(snap, R)
+            rn.rnnd_add_reverse_edges(keys, deg, R)
+        assert_snapshot_equal(snap, isf, keys, deg, "%s step %s" % (name, step))
+
+
+@pytest.mark.parametrize("name,S,R,T1,T2", [
+    ("cfg1", 10, 32, 2, 4), ("u8_d128", 20, 96, 3, 5), ("u8_d33_ties", 6, 16, 3, 4),
+    ("u8_dups", 8, 12, 3, 4), ("f32_d96", 20, 96, 3, 5), ("f32_d960", 8, 24, 2, 4), ("f32_d7", 16, 128, 2, 6)])
+def test_full_build(rn, oracle_mod, name, S, R, T1, T2):
+    X = DATASETS[name]()
+    isf = X.dtype == np.float32
+    want = oracle_mod.build_sync(X, S, R, T1, T2, wl.BUILD_SEED)
+    graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), S, R, T1, T2, wl.BUILD_SEED)
+    assert_snapshot_equal(want.snap, isf, keys, degree, name)
+    assert (graph.cpu().numpy() == want.snap.ids).all()
+    assert st.rounds == T1 * T2 and st.init_evals == len(X) * S
+    assert list(st.algo_evals[:T1 * T2]) == want.round_evals.tolist()
+    assert list(st.proposals[:T1 * T2]) == want.round_props.tolist()
+    g2, d2 = rn.rnnd_build(cuda(X), S, R, T1, T2, wl.BUILD_SEED)      # plain entry point, and determinism
+    assert (g2 == graph).all() and (d2 == degree).all()
+
+
+def test_float_tolerance_bar(rn, oracle_mod):
+    """The stated float bar, independent of bit-exactness: delta within 1e-5 relative of a float64
+    numpy evaluation, >= 99 % of edges equal to the oracle's."""
+    X = DATASETS["f32_d96"]()
+    want = oracle_mod.build_sync(X, 20, 48, 2, 5, 1)
+    graph, degree, keys, _ = rn.rnnd_build_ex(cuda(X), 20, 48, 2, 5, 1)
+    ids, bits, _, deg = device_to_arrays(keys, degree)
+    Xd = X.astype(np.float64)
+    edges = eq = 0
+    for u in range(0, len(X), 7):
+        m = deg[u]
+        ref = ((Xd[ids[u, :m]] - Xd[u]) ** 2).sum(1)
+        got = bits[u, :m].view(np.float32).astype(np.float64)
+        assert np.all(np.abs(got - ref) <= 1e-5 * ref)
+        mo = want.snap.deg[u]
+        edges += max(m, mo)
+        eq += len(set(ids[u, :m].tolist()) & set(want.snap.ids[u, :mo].tolist()))
+    assert eq >= 0.99 * edges
+
+
+def test_hub_vertex_streams_through_the_merge(rn, oracle_mod):
+    """A star: vertex 0 sits at the centre of everything, so hundreds of edges are redirected to
+    it in one round and hundreds of reverse edges enter it (the > 128-key path of the merge and
+    the in-degree cap of Alg. 5)."""
+    g = np.random.default_rng(8)
+    n, d, R = 2500, 16, 16
+    X = np.clip(128 + g.normal(0, 40, size=(n, d)), 0, 255).astype(np.uint8)
+    X[0] = 128
+    snap = oracle_mod.random_graph(X, 8, 5, R)
+    for u in range(1, n):                      # plant 0 in every list
+        if 0 not in snap.ids[u, :snap.deg[u]]:
+            k = snap.deg[u] - 1
+            snap.ids[u, k] = 0
+            snap.dist[u, k] = float(((X[u].astype(np.int64) - 128) ** 2).sum())
+        m = snap.deg[u]
+        order = np.lexsort((snap.ids[u, :m], snap.dist[u, :m]))
+        snap.ids[u, :m], snap.dist[u, :m] = snap.ids[u, :m][order], snap.dist[u, :m][order]
+    Xd = cuda(X)
+    for step in ["u", "r", "u", "u", "r", "u"]:
+        keys, deg = snapshot_to_device(snap, False, R)
+        if step == "u":
+            snap, evals, props = oracle_mod.update_neighbors_sync(X, snap, R)
+            st = rn.rnnd_update_neighbors(Xd, keys, deg, R, 1)
+            assert st.algo_evals[0] == evals and st.proposals[0] == props
+        else:
+            snap = oracle_mod.add_reverse_edges(snap, R)
+            rn.rnnd_add_reverse_edges(keys, deg, R)
+        assert_snapshot_equal(snap, False, keys, deg, "hub step " + step)
+
+
+def test_tiny_and_degenerate_inputs(rn, oracle_mod):
+    # N = 2: the only possible graph
+    X = np.array([[0, 0], [3, 4]], np.uint8)
+    g, d = rn.rnnd_build(cuda(X), 1, 1, 2, 2, 0)
+    assert g.cpu().numpy().tolist() == [[1], [0]] and d.cpu().numpy().tolist() == [1, 1]
+    # all points identical: every delta is 0, every test ties, order is by id alone
+    X = np.full((40, 16), 7, np.uint8)
+    want = oracle_mod.build_sync(X, 5, 8, 2, 3, 4)
+    graph, degree, keys, _ = rn.rnnd_build_ex(cuda(X), 5, 8, 2, 3, 4)
+    assert_snapshot_equal(want.snap, False, keys, degree, "identical points")
+    # complete initialisation, R = RNND_MAX_R
+    X = clustered_u8(129, 16, 6)
+    want = oracle_mod.build_sync(X, 128, 128, 2, 3, 4)
+    graph, degree, keys, _ = rn.rnnd_build_ex(cuda(X), 128, 128, 2, 3, 4)
+    assert_snapshot_equal(want.snap, False, keys, degree, "complete init")
+    # a snapshot with empty rows and no "new" entry at all: nothing may change
+    snap = oracle_mod.Snapshot.empty(50, 8)
+    X = clustered_u8(50, 16, 7)
+    keys, deg = snapshot_to_device(snap, False, 8)
+    st = rn.rnnd_update_neighbors(cuda(X), keys, deg, 8, 2)
+    assert st.active[0] == 0 and (deg == 0).all()
+    rn.rnnd_add_reverse_edges(keys, deg, 8)
+    assert (deg == 0).all()
+
+
+def test_argument_errors_on_device(rn):
+    import torch
+    X = torch.zeros((10, 16), dtype=torch.uint8, device="cuda")
+    for kw, status in [(dict(S=0, R=4), -3), (dict(S=5, R=4), -3), (dict(S=2, R=129), -3),
+                       (dict(S=10, R=12), -3)]:
+        with pytest.raises(rn.RnndError) as e:
+            rn.rnnd_build(X, kw["S"], kw["R"], 1, 1, 0)
+        assert e.value.status == status
+    with pytest.raises(rn.RnndError) as e:
+        rn.rnnd_build(X, 2, 4, 1, 1, 0, metric=3)
+    assert e.value.status == -4
+    with pytest.raises(rn.RnndError) as e:
+        rn.rnnd_build(X[:1].contiguous(), 1, 4, 1, 1, 0)
+    assert e.value.status == -2
+
+
+def test_cfg2_full_parity(rn, oracle_mod):
+    """BASELINE configuration 2 (N = 100,000, d = 128 uint8, paper parameters): ~20 s of oracle."""
+    c = wl.CONFIGS["cfg2"]
+    X = wl.make_data(c)
+    want = oracle_mod.build_sync(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    assert_snapshot_equal(want.snap, False, keys, degree, "cfg2")
+    assert list(st.algo_evals[:60]) == want.round_evals.tolist()
