@@ -63,6 +63,7 @@ typedef struct {
     int32_t reverse_calls;                  /* AddReverseEdges calls run (T1-1) */
     float total_ms, init_ms;                /* GPU time of the whole call / of RandomGraph */
     float round_ms[RNND_MAX_ROUNDS];        /* GPU time of each UpdateNeighbors round */
+    float scan_ms[RNND_MAX_ROUNDS];         /* of which: the scan kernel (Alg. 4 lines 2-15) */
     float reverse_ms[RNND_MAX_ROUNDS];      /* GPU time of each AddReverseEdges call */
     int64_t init_evals;                     /* N*S */
     int64_t active[RNND_MAX_ROUNDS];        /* vertices with at least one "new" entry */

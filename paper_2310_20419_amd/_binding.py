@@ -28,6 +28,7 @@ class Stats(ctypes.Structure):
         ("total_ms", ctypes.c_float),
         ("init_ms", ctypes.c_float),
         ("round_ms", ctypes.c_float * RNND_MAX_ROUNDS),
+        ("scan_ms", ctypes.c_float * RNND_MAX_ROUNDS),
         ("reverse_ms", ctypes.c_float * RNND_MAX_ROUNDS),
         ("init_evals", ctypes.c_int64),
         ("active", ctypes.c_int64 * RNND_MAX_ROUNDS),
@@ -42,7 +43,7 @@ class Stats(ctypes.Structure):
         return {
             "rounds": self.rounds, "reverse_calls": self.reverse_calls,
             "total_ms": self.total_ms, "init_ms": self.init_ms,
-            "round_ms": list(self.round_ms[:n]),
+            "round_ms": list(self.round_ms[:n]), "scan_ms": list(self.scan_ms[:n]),
             "reverse_ms": list(self.reverse_ms[:max(0, self.reverse_calls)]),
             "init_evals": self.init_evals, "active": list(self.active[:n]),
             "proposals": list(self.proposals[:n]), "algo_evals": list(self.algo_evals[:n]),
@@ -71,6 +72,9 @@ def load_library():
         if not os.path.exists(_LIB):
             raise RnndError(-6, "librnnd.so is not built (run `python -m paper_2310_20419_amd.build`); "
                                 "there is no CPU fallback")
+        # PyTorch owns the device memory and streams handed to the library, so both must share one
+        # HIP runtime: import torch first, so that librnnd.so binds to the runtime torch has loaded.
+        import torch  # noqa: F401
         L = ctypes.CDLL(_LIB)
         c = ctypes
         vp, i64, i32, u64 = c.c_void_p, c.c_int64, c.c_int32, c.c_uint64

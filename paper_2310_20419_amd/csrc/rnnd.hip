@@ -511,7 +511,8 @@ static inline int vertex_blocks(long long N) { return (int)((N + WAVES_PER_BLOCK
 
 // One synchronous UpdateNeighbors round t (ctr[t] -> ctr[t+1]).
 static hipError_t launch_update_round(const Workspace &w, const void *X, int d, int dtype, int vec_ok,
-                                      int R, u64 *keys, int *deg, int t, hipStream_t st)
+                                      int R, u64 *keys, int *deg, int t, hipStream_t st,
+                                      hipEvent_t after_scan = nullptr)
 {
     const int pb = persistent_blocks();
     RoundCtr *c = w.ctr + t;
@@ -523,6 +524,7 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, int d, 
     else
         hipLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
                            act, c, w.props, w.cnt, w.touched);
+    if (after_scan) (void)hipEventRecord(after_scan, st);
     hipLaunchKernelGGL(k_bin_offsets, dim3(pb), dim3(256), 0, st, w.touched, w.cnt, w.binoff, c);
     hipLaunchKernelGGL(k_bin_scatter, dim3(pb), dim3(256), 0, st, w.props, w.binoff, w.bins, c);
     hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched, w.cnt, w.binoff,
@@ -591,7 +593,8 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
     if ((int64_t)T1 * T2 > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int rounds = T1 * T2, n_ctr = rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int n_ev = rounds + T1 + 3;
+    // events: start, after init, (after scan, after round) per round, after each reverse, end
+    const int n_ev = 2 * rounds + T1 + 3;
     Workspace w;
     hipEvent_t *ev = nullptr;
     RoundCtr *hctr = nullptr;
@@ -618,7 +621,8 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
         HIPCHK(hipEventRecord(ev[e++], st));
         for (int t1 = 0; t1 < T1; ++t1) {
             for (int t2 = 0; t2 < T2; ++t2, ++t) {
-                HIPCHK(launch_update_round(w, X, d, dtype, vec_ok, R, w.keys, w.deg, t, st));
+                HIPCHK(launch_update_round(w, X, d, dtype, vec_ok, R, w.keys, w.deg, t, st, ev[e]));
+                ++e;
                 HIPCHK(hipEventRecord(ev[e++], st));
             }
             if (t1 != T1 - 1) {
@@ -639,15 +643,14 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
             fill_round_stats(stats, hctr, rounds);
             stats->reverse_calls = T1 - 1;
             stats->init_evals = (int64_t)N * S;
-            int q = 0;
             float ms = 0;
             (void)hipEventElapsedTime(&ms, ev[0], ev[1]); stats->init_ms = ms;
-            q = 1;
-            int tt = 0;
+            int q = 1, tt = 0;   // ev[q] = end of the previous phase
             for (int t1 = 0; t1 < T1; ++t1) {
-                for (int t2 = 0; t2 < T2; ++t2, ++tt, ++q) {
-                    (void)hipEventElapsedTime(&ms, ev[q], ev[q + 1]);
-                    if (tt < RNND_MAX_ROUNDS) stats->round_ms[tt] = ms;
+                for (int t2 = 0; t2 < T2; ++t2, ++tt, q += 2) {
+                    if (tt >= RNND_MAX_ROUNDS) continue;
+                    (void)hipEventElapsedTime(&ms, ev[q], ev[q + 1]); stats->scan_ms[tt] = ms;
+                    (void)hipEventElapsedTime(&ms, ev[q], ev[q + 2]); stats->round_ms[tt] = ms;
                 }
                 if (t1 != T1 - 1) {
                     (void)hipEventElapsedTime(&ms, ev[q], ev[q + 1]);
