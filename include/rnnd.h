@@ -61,6 +61,8 @@ typedef enum {
 typedef struct {
     int32_t rounds;                         /* UpdateNeighbors rounds run (T1*T2) */
     int32_t reverse_calls;                  /* AddReverseEdges calls run (T1-1) */
+    int32_t kernel_variant;                 /* UpdateNeighbors scan kernel used: 1 generic, 2 MFMA */
+    int32_t reserved;
     float total_ms, init_ms;                /* GPU time of the whole call / of RandomGraph */
     float round_ms[RNND_MAX_ROUNDS];        /* GPU time of each UpdateNeighbors round */
     float scan_ms[RNND_MAX_ROUNDS];         /* of which: the scan kernel (Alg. 4 lines 2-15) */
@@ -118,9 +120,10 @@ int rnnd_add_reverse_edges(int64_t N, int32_t R, uint64_t *keys, int32_t *deg, v
 int rnnd_export_graph(int64_t N, int32_t R, const uint64_t *keys, const int32_t *deg,
                       int32_t *graph_out, int32_t *degree_out, void *stream);
 
-/* Selects the UpdateNeighbors kernel: 0 = automatic (default), 1 = generic pair-at-a-time
- * kernel, 2 = dense MFMA block kernel (uint8 data with d a multiple of 64 only; other inputs
- * fall back to 1).  Both give identical graphs; this exists for testing and profiling. */
+/* Selects the UpdateNeighbors scan kernel: 0 = automatic (default), 1 = generic pair-at-a-time
+ * kernel, 2 = dense Gram-block kernel on the matrix cores (uint8 data with d = 32, 64 or 128;
+ * other inputs use 1; automatic picks 2 where it applies).  Both give identical graphs; this
+ * exists for testing and profiling.  Process-wide, not thread-safe. */
 int rnnd_set_kernel_variant(int variant);
 
 const char *rnnd_strerror(int status);

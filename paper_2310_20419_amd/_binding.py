@@ -25,6 +25,8 @@ class Stats(ctypes.Structure):
     _fields_ = [
         ("rounds", ctypes.c_int32),
         ("reverse_calls", ctypes.c_int32),
+        ("kernel_variant", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
         ("total_ms", ctypes.c_float),
         ("init_ms", ctypes.c_float),
         ("round_ms", ctypes.c_float * RNND_MAX_ROUNDS),
@@ -42,6 +44,7 @@ class Stats(ctypes.Structure):
         n = min(self.rounds, RNND_MAX_ROUNDS)
         return {
             "rounds": self.rounds, "reverse_calls": self.reverse_calls,
+            "kernel_variant": self.kernel_variant,
             "total_ms": self.total_ms, "init_ms": self.init_ms,
             "round_ms": list(self.round_ms[:n]), "scan_ms": list(self.scan_ms[:n]),
             "reverse_ms": list(self.reverse_ms[:max(0, self.reverse_calls)]),

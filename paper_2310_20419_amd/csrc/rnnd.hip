@@ -1,37 +1,63 @@
 // librnnd: Relative NN-Descent graph construction (arXiv 2310.20419, Alg. 4-6) on gfx950.
-// One wavefront owns one vertex in every per-vertex kernel; rounds are synchronous: a scan kernel
-// reads the snapshot and emits redirected edges, a merge kernel rebuilds the touched lists.
+//
+// One wavefront owns one vertex in every per-vertex kernel.  A round is synchronous:
+//   scan     every active vertex (one holding a "new" entry) runs Alg. 4 lines 2-15 on its own list,
+//            writes its kept entries back in place and leaves its redirected edges in its slot of `props`
+//   offsets  every vertex that received edges gets a bin; those vertices form the `touched` list
+//   scatter  redirected edges move into their target's bin
+//   merge    every touched list becomes the first R distinct keys of (kept entries + bin)
+//   compact  touched vertices whose new list holds a "new" entry form the next active lists,
+//            one per degree class (lists of up to 32, 64, 96, 128 entries)
+// Counters that many wavefronts would hit at one address are aggregated per block first.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <string.h>
 
 #include "../../include/rnnd.h"
-#include "dist.h"
 #include "wave_prims.h"
 
 #define WAVES_PER_BLOCK 4
 #define BLOCK (64 * WAVES_PER_BLOCK)
 #define GOLDEN64 0x9E3779B97F4A7C15ull
+#define NCLS 4
 
-// Per-round device counters.  Round t reads ctr[t].n_active and fills the rest; its merge step
-// writes ctr[t+1].n_active.  Zeroed once per call, never reset, so they double as statistics.
+// Per-round device counters.  Round t reads ctr[t].n_active[] and fills the rest; its compact step
+// writes ctr[t+1].n_active[].  Zeroed once per call, never reset, so they double as statistics.
+#define STAT_SLOTS 64
 struct RoundCtr {
-    u32 n_active;      // length of this round's active list
-    u32 n_props;       // redirected edges emitted
-    u32 n_touched;     // distinct targets of those edges
-    u32 bin_cursor;    // space handed out in the bin array
-    u64 algo_evals;
-    u64 exec_evals;
-    u64 gathered_rows;
-    u64 pad;
+    u32 n_active[NCLS];   // lengths of this round's active lists
+    u32 n_touched;        // distinct targets of the redirected edges
+    u32 bin_cursor;       // space handed out in the bin array
+    u32 pad[2];
+    // statistics, spread over STAT_SLOTS addresses so that the adds of many blocks do not queue up
+    // on one: [slot][0..3] = algorithmic evals, executed evals, rows gathered, edges redirected
+    u64 stat[STAT_SLOTS][4];
 };
+
+// One add per wavefront into the slot of its block.
+__device__ __forceinline__ void add_round_stats(RoundCtr *ctr, u64 algo, u64 exec, u64 rows, u64 props)
+{
+    u64 *s = ctr->stat[blockIdx.x & (STAT_SLOTS - 1)];
+    atomicAdd(&s[0], algo);
+    atomicAdd(&s[1], exec);
+    atomicAdd(&s[2], rows);
+    atomicAdd(&s[3], props);
+}
 
 struct Prop {          // one redirected edge (Alg. 4 line 13): `key` enters `tgt`'s list
     u64 key;
     u32 tgt;
     u32 slot;          // arrival number among the edges for tgt (gives its place in tgt's bin)
 };
+
+#include "dist.h"
+#include "scan_mfma.h"
+
+__device__ __forceinline__ int degree_class(int m, int use_classes)
+{
+    return use_classes ? (m <= 32 ? 0 : (m - 1) >> 5) : 0;
+}
 
 // ------------------------------------------------------------------ RandomGraph
 __device__ __forceinline__ u64 mix64(u64 z)
@@ -47,7 +73,7 @@ __device__ __forceinline__ u64 mix64(u64 z)
 template <int DT>
 __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long N, int d, int vec_ok,
                                                         int S, int R, u64 seed, u64 *keys, int *deg,
-                                                        int *active, u32 *n_active)
+                                                        int8_t *vcls, int use_classes)
 {
     __shared__ int s_ids[WAVES_PER_BLOCK][RNND_MAX_R];
     __shared__ u32 s_dist[WAVES_PER_BLOCK][RNND_MAX_R];
@@ -110,8 +136,7 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
     if (lane + 64 < S) row[lane + 64] = k[1];
     if (lane == 0) {
         deg[u] = S;
-        active[u] = (int)u;
-        if (u == 0 && n_active) *n_active = (u32)N;   // every vertex starts with "new" entries
+        if (vcls) vcls[u] = (int8_t)degree_class(S, use_classes);   // every vertex starts with "new" entries
     }
 }
 
@@ -122,22 +147,23 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
 // prunes v and redirects it.  Kept entries are written back in place with the flag cleared.
 template <int DT>
 __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int vec_ok, int R,
-                                                       u64 *keys, int *deg, const int *active,
-                                                       RoundCtr *ctr, Prop *props, int *cnt,
-                                                       int *touched)
+                                                       u64 *keys, int *deg, const int *list,
+                                                       const u32 *n_list, Prop *props, int *nprop,
+                                                       int *cnt, RoundCtr *ctr)
 {
     __shared__ u64 s_key[WAVES_PER_BLOCK][RNND_MAX_R];
     __shared__ u64 s_pkey[WAVES_PER_BLOCK][RNND_MAX_R];
     __shared__ u32 s_ptgt[WAVES_PER_BLOCK][RNND_MAX_R];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, sub = lane & 7, grp = lane >> 3;
     const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
-    const u32 n_active = ctr->n_active;
+    const u32 n_active = *n_list;
     const size_t rowbytes = (size_t)d * (DT == DT_U8 ? 1 : 4);
     u64 *sk = s_key[wave];
-    u64 evals_algo = 0, evals_exec = 0, rows = 0;
+    u64 evals_algo = 0, evals_exec = 0, rows = 0, nprops_total = 0;
     for (u32 it = gw; it < n_active; it += nw) {
-        const int u = active[it];
-        const int m = deg[u];
+        const int u = list[it];
+        int m = deg[u];
+        if (m > R) m = R;
         u64 *row = keys + (size_t)u * R;
         u64 k0 = lane < m ? row[lane] : KEY_PAD;
         u64 k1 = lane + 64 < m ? row[lane + 64] : KEY_PAD;
@@ -147,7 +173,10 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
         const u64 new0 = __builtin_amdgcn_ballot_w64(lane < m && (k0 & 1ull));
         const u64 new1 = __builtin_amdgcn_ballot_w64(lane + 64 < m && (k1 & 1ull));
         wave_sync();
-        if ((new0 | new1) == 0) continue;
+        if ((new0 | new1) == 0) {
+            if (lane == 0) nprop[u] = 0;
+            continue;
+        }
         rows += m;
         u64 K0 = 0, K1 = 0;   // U' as positions in the sorted list
         int np = 0;
@@ -198,55 +227,87 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
         const int nk0 = __popcll(K0);
         if ((K0 >> lane) & 1ull) row[__popcll(K0 & lanes_below(lane))] = k0 & ~1ull;
         if ((K1 >> lane) & 1ull) row[nk0 + __popcll(K1 & lanes_below(lane))] = k1 & ~1ull;
-        if (lane == 0) deg[u] = nk0 + __popcll(K1);
-        wave_sync();
-        if (np > 0) {
-            u32 base = 0;
-            if (lane == 0) base = atomicAdd(&ctr->n_props, (u32)np);
-            base = __shfl(base, 0);
-            for (int p = lane; p < np; p += 64) {
-                const u32 tgt = s_ptgt[wave][p];
-                const u32 slot = (u32)atomicAdd(&cnt[tgt], 1);
-                if (slot == 0) touched[atomicAdd(&ctr->n_touched, 1u)] = (int)tgt;
-                Prop pr;
-                pr.key = s_pkey[wave][p];
-                pr.tgt = tgt;
-                pr.slot = slot;
-                props[base + p] = pr;
-            }
+        if (lane == 0) {
+            deg[u] = nk0 + __popcll(K1);
+            nprop[u] = np;
         }
+        wave_sync();
+        for (int p = lane; p < np; p += 64) {
+            Prop pr;
+            pr.key = s_pkey[wave][p];
+            pr.tgt = s_ptgt[wave][p];
+            pr.slot = (u32)atomicAdd(&cnt[pr.tgt], 1);
+            props[(size_t)u * R + p] = pr;
+        }
+        nprops_total += np;
     }
-    if (lane == 0 && rows) {
-        atomicAdd(&ctr->algo_evals, evals_algo);
-        atomicAdd(&ctr->exec_evals, evals_exec);
-        atomicAdd(&ctr->gathered_rows, rows);
-    }
+    if (lane == 0 && rows) add_round_stats(ctr, evals_algo, evals_exec, rows, nprops_total);
 }
 
 // ------------------------------------------------------ UpdateNeighbors: merge
-__global__ void k_bin_offsets(const int *touched, const int *cnt, int *binoff, RoundCtr *ctr)
+// binoff[x] <- start of x's bin, for every x with cnt[x] > min_cnt (others: -1); those x are appended
+// to `list`.  One pair of atomics per 1024 vertices.  Optionally clears fill[] and sets thr[] to "keep all".
+__global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cnt, int min_cnt, int *binoff,
+                                                      u32 *bin_cursor, int *list, u32 *n_list, int *fill,
+                                                      u64 *thr)
 {
-    const u32 n = ctr->n_touched;
-    for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-        int x = touched[i];
-        binoff[x] = (int)atomicAdd(&ctr->bin_cursor, (u32)cnt[x]);
+    __shared__ u32 s_sum[16], s_num[16], s_base[2];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long x = (long long)blockIdx.x * 1024 + threadIdx.x;
+    int c = 0;
+    if (x < N) {
+        c = cnt[x];
+        if (fill) fill[x] = 0;
+        if (thr) thr[x] = KEY_PAD;
+    }
+    const bool has = c > min_cnt;
+    const u32 mine = has ? (u32)c : 0u;
+    u32 incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        u32 v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
+    }
+    const u64 hb = __builtin_amdgcn_ballot_w64(has);
+    if (lane == 63) { s_sum[wave] = incl; s_num[wave] = (u32)__popcll(hb); }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 ts = 0, tn = 0;
+        for (int w = 0; w < 16; ++w) { u32 a = s_sum[w], b = s_num[w]; s_sum[w] = ts; s_num[w] = tn; ts += a; tn += b; }
+        s_base[0] = ts ? atomicAdd(bin_cursor, ts) : 0u;
+        s_base[1] = tn ? atomicAdd(n_list, tn) : 0u;
+    }
+    __syncthreads();
+    if (x < N) {
+        binoff[x] = has ? (int)(s_base[0] + s_sum[wave] + incl - mine) : -1;
+        if (has) list[s_base[1] + s_num[wave] + __popcll(hb & lanes_below(lane))] = (int)x;
     }
 }
 
-__global__ void k_bin_scatter(const Prop *props, const int *binoff, u64 *bins, const RoundCtr *ctr)
+// every active vertex moves its redirected edges into the bins of their targets
+__global__ __launch_bounds__(BLOCK) void k_bin_scatter(long long N, int R, const int *lists,
+                                                       const RoundCtr *ctr, const Prop *props,
+                                                       const int *nprop, const int *binoff, u64 *bins)
 {
-    const u32 n = ctr->n_props;
-    for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-        Prop p = props[i];
-        bins[(size_t)binoff[p.tgt] + p.slot] = p.key;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = blockIdx.y;
+    const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
+    const u32 n = ctr->n_active[c];
+    const int *list = lists + (size_t)c * N;
+    for (u32 it = gw; it < n; it += nw) {
+        const int u = list[it];
+        const int np = nprop[u];
+        for (int p = lane; p < np; p += 64) {
+            Prop pr = props[(size_t)u * R + p];
+            bins[(size_t)binoff[pr.tgt] + pr.slot] = pr.key;
+        }
     }
 }
 
 // For every touched vertex x: list <- first R distinct of (kept entries + edges redirected to x).
-// Vertices whose new list holds a "new" entry form the next round's active list.
+// tcls[it] <- degree class of x if its new list holds a "new" entry, else -1.
 __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, const int *touched,
                                                  int *cnt, const int *binoff, const u64 *bins,
-                                                 const RoundCtr *ctr, RoundCtr *next, int *active_next)
+                                                 const RoundCtr *ctr, int8_t *tcls, int use_classes)
 {
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -260,8 +321,45 @@ __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, con
         if (lane == 0) {
             deg[x] = nd;
             cnt[x] = 0;
-            if (any_new) active_next[atomicAdd(&next->n_active, 1u)] = x;
+            tcls[it] = any_new ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
         }
+    }
+}
+
+// Items i < n with cls[i] >= 0 are appended to list cls[i]; item i stands for vertex idx[i] (or i).
+// One atomic per class per 1024 items.
+__global__ __launch_bounds__(1024) void k_compact_classes(const u32 *n_ptr, u32 n_fixed, const int *idx,
+                                                          const int8_t *cls, int *lists, long long N,
+                                                          u32 *n_out)
+{
+    __shared__ u32 s_cnt[16][NCLS], s_base[NCLS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const u32 n = n_ptr ? *n_ptr : n_fixed;
+    for (u32 base = blockIdx.x * 1024u; base < n; base += gridDim.x * 1024u) {
+        const u32 i = base + threadIdx.x;
+        const int c = i < n ? (int)cls[i] : -1;
+        u64 b[NCLS];
+#pragma unroll
+        for (int k = 0; k < NCLS; ++k) b[k] = __builtin_amdgcn_ballot_w64(c == k);
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < NCLS; ++k) s_cnt[wave][k] = (u32)__popcll(b[k]);
+        }
+        __syncthreads();
+        if (threadIdx.x < NCLS) {
+            u32 tot = 0;
+            for (int w = 0; w < 16; ++w) { u32 a = s_cnt[w][threadIdx.x]; s_cnt[w][threadIdx.x] = tot; tot += a; }
+            s_base[threadIdx.x] = tot ? atomicAdd(&n_out[threadIdx.x], tot) : 0u;
+        }
+        __syncthreads();
+        if (c >= 0 && c < NCLS) {
+            u64 mine = b[0];
+#pragma unroll
+            for (int k = 1; k < NCLS; ++k) mine = (c == k) ? b[k] : mine;
+            const u32 off = s_base[c] + s_cnt[wave][c] + (u32)__popcll(mine & lanes_below(lane));
+            lists[(size_t)c * N + off] = idx ? idx[i] : (int)i;
+        }
+        __syncthreads();
     }
 }
 
@@ -275,23 +373,6 @@ __global__ __launch_bounds__(BLOCK) void k_count_targets(long long N, int R, con
     if (u >= N) return;
     const int m = deg[u];
     for (int e = lane; e < m; e += 64) atomicAdd(&cnt[key_id(keys[(size_t)u * R + e])], 1);
-}
-
-// Gives every vertex with cnt[v] > min_cnt a bin of cnt[v] keys; others get binoff = -1.
-// Clears fill[] and (thread 0) the counter the next step appends to.
-__global__ void k_assign_bins(long long N, const int *cnt, int min_cnt, int *binoff, int *fill,
-                              u32 *cursor, int *list, u32 *n_list, u64 *thr)
-{
-    long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v >= N) return;
-    fill[v] = 0;
-    if (thr) thr[v] = KEY_PAD;
-    if (cnt[v] > min_cnt) {
-        binoff[v] = (int)atomicAdd(cursor, (u32)cnt[v]);
-        if (list) list[atomicAdd(n_list, 1u)] = (int)v;
-    } else {
-        binoff[v] = -1;
-    }
 }
 
 // For every edge (u, v) whose v owns a bin: bins[v] <- key(delta, u, flag)
@@ -349,11 +430,11 @@ __global__ __launch_bounds__(BLOCK) void k_incap_threshold(int R, const int *lis
     }
 }
 
-// Alg. 5 lines 6-8, second half: edge (u, v) survives iff (delta, u) <= thr[v].  Also rebuilds the
-// active list (vertices holding a "new" entry) for the next UpdateNeighbors round and clears cnt.
+// Alg. 5 lines 6-8, second half: edge (u, v) survives iff (delta, u) <= thr[v].  vcls[u] <- degree
+// class if the list holds a "new" entry, else -1.  Clears cnt for the next use.
 __global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 *keys, int *deg,
-                                                        const u64 *thr, int *cnt, RoundCtr *next,
-                                                        int *active_next)
+                                                        const u64 *thr, int *cnt, int8_t *vcls,
+                                                        int use_classes)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
@@ -375,9 +456,10 @@ __global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 
     if (keep[0]) row[__popcll(m0 & lanes_below(lane))] = k[0];
     if (keep[1]) row[c0 + __popcll(m1 & lanes_below(lane))] = k[1];
     if (lane == 0) {
-        deg[u] = c0 + __popcll(m1);
+        const int nd = c0 + __popcll(m1);
+        deg[u] = nd;
         cnt[u] = 0;
-        if (n0 | n1) active_next[atomicAdd(&next->n_active, 1u)] = (int)u;
+        vcls[u] = (n0 | n1) ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
     }
 }
 
@@ -387,18 +469,19 @@ __global__ void k_zero_u32(u32 *p, int n)
     if (i < n) p[i] = 0;
 }
 
-// Rebuilds the active list from the flags of a snapshot handed in by the caller.
-__global__ __launch_bounds__(BLOCK) void k_collect_active(long long N, int R, const u64 *keys,
-                                                          const int *deg, RoundCtr *next, int *active_next)
+// vcls[u] for a snapshot handed in by the caller
+__global__ __launch_bounds__(BLOCK) void k_classify(long long N, int R, const u64 *keys, const int *deg,
+                                                    int8_t *vcls, int use_classes)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
     if (u >= N) return;
-    const int m = deg[u];
+    int m = deg[u];
+    if (m > R) m = R;
     bool nw = false;
     for (int e = lane; e < m; e += 64) nw = nw || (keys[(size_t)u * R + e] & 1ull);
     const u64 b = __builtin_amdgcn_ballot_w64(nw);
-    if (lane == 0 && b) active_next[atomicAdd(&next->n_active, 1u)] = (int)u;
+    if (lane == 0) vcls[u] = b ? (int8_t)degree_class(m, use_classes) : (int8_t)-1;
 }
 
 __global__ void k_export(long long N, int R, const u64 *keys, const int *deg, int *graph_out,
@@ -434,11 +517,12 @@ struct Workspace {
     size_t bytes = 0;
     u64 *keys = nullptr;    // [N*R]   (unless the caller supplies a snapshot)
     int *deg = nullptr;     // [N]
-    Prop *props = nullptr;  // [N*R]
+    Prop *props = nullptr;  // [N*R]   slot u*R.. holds the edges vertex u redirected this round
     u64 *bins = nullptr;    // [N*R]
     u64 *thr = nullptr;     // [N]
-    int *cnt = nullptr, *binoff = nullptr, *fill = nullptr, *touched = nullptr, *hubs = nullptr;
-    int *active[2] = {nullptr, nullptr};
+    int *cnt = nullptr, *binoff = nullptr, *fill = nullptr, *touched = nullptr, *hubs = nullptr, *nprop = nullptr;
+    int *lists = nullptr;   // [NCLS*N] active lists by degree class
+    int8_t *vcls = nullptr, *tcls = nullptr;   // [N] each
     RoundCtr *ctr = nullptr;   // [n_ctr]
     u32 *misc = nullptr;       // [8]: small cursors for AddReverseEdges
     int n_ctr = 0;
@@ -454,8 +538,9 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
     size_t o_bins = take((size_t)N * R * 8);
     size_t o_thr = take((size_t)N * 8);
     size_t o_cnt = take((size_t)N * 4), o_binoff = take((size_t)N * 4), o_fill = take((size_t)N * 4);
-    size_t o_touched = take((size_t)N * 4), o_hubs = take((size_t)N * 4);
-    size_t o_a0 = take((size_t)N * 4), o_a1 = take((size_t)N * 4);
+    size_t o_touched = take((size_t)N * 4), o_hubs = take((size_t)N * 4), o_nprop = take((size_t)N * 4);
+    size_t o_lists = take((size_t)N * 4 * NCLS);
+    size_t o_vcls = take((size_t)N), o_tcls = take((size_t)N);
     size_t o_ctr = take((size_t)n_ctr * sizeof(RoundCtr));
     size_t o_misc = take(8 * 4);
     if (w.base) {
@@ -468,8 +553,10 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
         w.fill = (int *)(w.base + o_fill);
         w.touched = (int *)(w.base + o_touched);
         w.hubs = (int *)(w.base + o_hubs);
-        w.active[0] = (int *)(w.base + o_a0);
-        w.active[1] = (int *)(w.base + o_a1);
+        w.nprop = (int *)(w.base + o_nprop);
+        w.lists = (int *)(w.base + o_lists);
+        w.vcls = (int8_t *)(w.base + o_vcls);
+        w.tcls = (int8_t *)(w.base + o_tcls);
         w.ctr = (RoundCtr *)(w.base + o_ctr);
         w.misc = (u32 *)(w.base + o_misc);
         w.n_ctr = n_ctr;
@@ -494,68 +581,115 @@ static int vec_ok_for(const void *X, int d, int dtype)
     return (rowbytes % 16 == 0) && (((uintptr_t)X) % 16 == 0);
 }
 
-static int persistent_blocks()
+// How UpdateNeighbors scans for this input: 2 = MFMA Gram kernel, 1 = generic kernel.
+static int scan_variant_for(const void *X, int d, int dtype)
 {
-    static int nb = 0;
-    if (!nb) {
-        int dev = 0, cus = 0;
+    const bool mfma_ok = dtype == RNND_U8 && (d == 32 || d == 64 || d == 128) && (((uintptr_t)X) % 16 == 0);
+    if (g_kernel_variant == 1 || !mfma_ok) return 1;
+    return 2;
+}
+
+static int cu_count()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             cus = 256;
-        nb = cus * 8;   // 32 wavefronts per CU
     }
-    return nb;
+    return cus;
 }
+
+static int persistent_blocks() { return cu_count() * 8; }   // 32 wavefronts per CU
 
 static inline int vertex_blocks(long long N) { return (int)((N + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK); }
 
+template <int NG, int KS>
+static void launch_mfma_scan(const Workspace &w, const void *X, int R, u64 *keys, int *deg, long long N,
+                             RoundCtr *c, hipStream_t st)
+{
+    // blocks per CU limited by the LDS one block takes (160 KB per CU)
+    const size_t smem = sizeof(MfmaScanSmem<NG>) * 4;
+    int per_cu = (int)((160 * 1024) / smem);
+    if (per_cu > 8) per_cu = 8;
+    if (per_cu < 1) per_cu = 1;
+    hipLaunchKernelGGL((k_update_scan_mfma_u8<NG, KS>), dim3(cu_count() * per_cu), dim3(256), 0, st,
+                       (const uint8_t *)X, R, keys, deg, w.lists + (size_t)(NG - 1) * N, &c->n_active[NG - 1],
+                       w.props, w.nprop, w.cnt, c);
+}
+
+template <int KS>
+static void launch_mfma_scan_classes(const Workspace &w, const void *X, int R, u64 *keys, int *deg,
+                                     long long N, RoundCtr *c, hipStream_t st)
+{
+    launch_mfma_scan<1, KS>(w, X, R, keys, deg, N, c, st);
+    if (R > 32) launch_mfma_scan<2, KS>(w, X, R, keys, deg, N, c, st);
+    if (R > 64) launch_mfma_scan<3, KS>(w, X, R, keys, deg, N, c, st);
+    if (R > 96) launch_mfma_scan<4, KS>(w, X, R, keys, deg, N, c, st);
+}
+
 // One synchronous UpdateNeighbors round t (ctr[t] -> ctr[t+1]).
-static hipError_t launch_update_round(const Workspace &w, const void *X, int d, int dtype, int vec_ok,
-                                      int R, u64 *keys, int *deg, int t, hipStream_t st,
-                                      hipEvent_t after_scan = nullptr)
+static hipError_t launch_update_round(const Workspace &w, const void *X, long long N, int d, int dtype,
+                                      int vec_ok, int variant, int R, u64 *keys, int *deg, int t,
+                                      hipStream_t st, hipEvent_t after_scan = nullptr)
 {
     const int pb = persistent_blocks();
     RoundCtr *c = w.ctr + t;
-    const int *act = w.active[t & 1];
-    int *act_next = w.active[(t + 1) & 1];
-    if (dtype == RNND_U8)
+    const int use_classes = variant == 2;
+    if (variant == 2) {
+        if (d == 32) launch_mfma_scan_classes<1>(w, X, R, keys, deg, N, c, st);
+        else if (d == 64) launch_mfma_scan_classes<2>(w, X, R, keys, deg, N, c, st);
+        else launch_mfma_scan_classes<4>(w, X, R, keys, deg, N, c, st);
+    } else if (dtype == RNND_U8) {
         hipLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
-                           act, c, w.props, w.cnt, w.touched);
-    else
+                           w.lists, &c->n_active[0], w.props, w.nprop, w.cnt, c);
+    } else {
         hipLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
-                           act, c, w.props, w.cnt, w.touched);
+                           w.lists, &c->n_active[0], w.props, w.nprop, w.cnt, c);
+    }
     if (after_scan) (void)hipEventRecord(after_scan, st);
-    hipLaunchKernelGGL(k_bin_offsets, dim3(pb), dim3(256), 0, st, w.touched, w.cnt, w.binoff, c);
-    hipLaunchKernelGGL(k_bin_scatter, dim3(pb), dim3(256), 0, st, w.props, w.binoff, w.bins, c);
+    hipLaunchKernelGGL(k_assign_bins, dim3((unsigned)((N + 1023) / 1024)), dim3(1024), 0, st, N, w.cnt, 0,
+                       w.binoff, &c->bin_cursor, w.touched, &c->n_touched, (int *)nullptr, (u64 *)nullptr);
+    hipLaunchKernelGGL(k_bin_scatter, dim3(pb, use_classes ? NCLS : 1), dim3(BLOCK), 0, st, N, R, w.lists, c,
+                       w.props, w.nprop, w.binoff, w.bins);
     hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched, w.cnt, w.binoff,
-                       w.bins, c, c + 1, act_next);
+                       w.bins, c, w.tcls, use_classes);
+    hipLaunchKernelGGL(k_compact_classes, dim3(256), dim3(1024), 0, st, &c->n_touched, 0u, w.touched, w.tcls,
+                       w.lists, N, (c + 1)->n_active);
     return hipGetLastError();
 }
 
-// AddReverseEdges; the active list for round t_next is rebuilt from scratch.
-static hipError_t launch_reverse(const Workspace &w, long long N, int R, u64 *keys, int *deg, int t_next,
-                                 hipStream_t st)
+// vcls[] (class of every vertex holding a "new" entry) -> active lists of round t_next
+static void launch_compact_all(const Workspace &w, long long N, int t_next, hipStream_t st)
 {
-    const int vb = vertex_blocks(N), tb = (int)((N + 255) / 256);
-    RoundCtr *next = w.ctr + t_next;
-    int *act_next = w.active[t_next & 1];
+    hipLaunchKernelGGL(k_compact_classes, dim3(256), dim3(1024), 0, st, (const u32 *)nullptr, (u32)N,
+                       (const int *)nullptr, w.vcls, w.lists, N, w.ctr[t_next].n_active);
+}
+
+// AddReverseEdges; the active lists for round t_next are rebuilt from scratch.
+static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use_classes, u64 *keys, int *deg,
+                                 int t_next, hipStream_t st)
+{
+    const int vb = vertex_blocks(N), tb = (int)((N + 1023) / 1024);
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, 8);
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, &next->n_active, 1);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NCLS);
     // lines 1-5: union with reversed edges, out-lists cut to R
     hipLaunchKernelGGL(k_count_targets, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.cnt);
-    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(256), 0, st, N, w.cnt, 0, w.binoff, w.fill, w.misc + 0,
-                       (int *)nullptr, (u32 *)nullptr, (u64 *)nullptr);
+    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.cnt, 0, w.binoff, w.misc + 0, w.hubs,
+                       w.misc + 3, w.fill, (u64 *)nullptr);
     hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.fill, w.bins, 1u);
     hipLaunchKernelGGL(k_reverse_merge, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.cnt, w.binoff, w.bins);
     // lines 6-8: in-lists cut to R; only vertices with more than R incoming edges need a bin
     hipLaunchKernelGGL(k_count_targets, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.cnt);
-    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(256), 0, st, N, w.cnt, R, w.binoff, w.fill, w.misc + 1,
-                       w.hubs, w.misc + 2, w.thr);
+    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.cnt, R, w.binoff, w.misc + 1, w.hubs,
+                       w.misc + 2, w.fill, w.thr);
     hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.fill, w.bins, 0u);
     hipLaunchKernelGGL(k_incap_threshold, dim3(persistent_blocks()), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 2,
                        w.cnt, w.binoff, w.bins, w.thr);
-    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, w.cnt, next,
-                       act_next);
+    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, w.cnt, w.vcls,
+                       use_classes);
+    launch_compact_all(w, N, t_next, st);
     return hipGetLastError();
 }
 
@@ -563,11 +697,14 @@ static void fill_round_stats(rnnd_stats *s, const RoundCtr *h, int rounds)
 {
     s->rounds = rounds;
     for (int t = 0; t < rounds && t < RNND_MAX_ROUNDS; ++t) {
-        s->active[t] = h[t].n_active;
-        s->proposals[t] = h[t].n_props;
-        s->algo_evals[t] = (int64_t)h[t].algo_evals;
-        s->exec_evals[t] = (int64_t)h[t].exec_evals;
-        s->gathered_rows[t] = (int64_t)h[t].gathered_rows;
+        s->active[t] = 0;
+        for (int c = 0; c < NCLS; ++c) s->active[t] += h[t].n_active[c];
+        for (int k = 0; k < STAT_SLOTS; ++k) {
+            s->algo_evals[t] += (int64_t)h[t].stat[k][0];
+            s->exec_evals[t] += (int64_t)h[t].stat[k][1];
+            s->gathered_rows[t] += (int64_t)h[t].stat[k][2];
+            s->proposals[t] += (int64_t)h[t].stat[k][3];
+        }
     }
 }
 
@@ -593,6 +730,7 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
     if ((int64_t)T1 * T2 > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int rounds = T1 * T2, n_ctr = rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2;
     // events: start, after init, (after scan, after round) per round, after each reverse, end
     const int n_ev = 2 * rounds + T1 + 3;
     Workspace w;
@@ -613,20 +751,21 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
         HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
         if (dtype == RNND_U8)
             hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.active[0], &w.ctr[0].n_active);
+                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
         else
             hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.active[0], &w.ctr[0].n_active);
+                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+        launch_compact_all(w, N, 0, st);
         HIPCHK(hipGetLastError());
         HIPCHK(hipEventRecord(ev[e++], st));
         for (int t1 = 0; t1 < T1; ++t1) {
             for (int t2 = 0; t2 < T2; ++t2, ++t) {
-                HIPCHK(launch_update_round(w, X, d, dtype, vec_ok, R, w.keys, w.deg, t, st, ev[e]));
+                HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, w.keys, w.deg, t, st, ev[e]));
                 ++e;
                 HIPCHK(hipEventRecord(ev[e++], st));
             }
             if (t1 != T1 - 1) {
-                HIPCHK(launch_reverse(w, N, R, w.keys, w.deg, t, st));
+                HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, t, st));
                 HIPCHK(hipEventRecord(ev[e++], st));
             }
         }
@@ -643,6 +782,7 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
             fill_round_stats(stats, hctr, rounds);
             stats->reverse_calls = T1 - 1;
             stats->init_evals = (int64_t)N * S;
+            stats->kernel_variant = variant;
             float ms = 0;
             (void)hipEventElapsedTime(&ms, ev[0], ev[1]); stats->init_ms = ms;
             int q = 1, tt = 0;   // ev[q] = end of the previous phase
@@ -685,19 +825,16 @@ extern "C" int rnnd_random_graph(const void *X, int64_t N, int32_t d, int dtype,
     if (!keys || !deg) return RNND_ERR_NULL;
     if (S < 1 || S > R || (int64_t)S > N - 1) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
-    int *scratch = nullptr;
     const int vec_ok = vec_ok_for(X, d, dtype);
-    HIPCHK(hipMalloc((void **)&scratch, (size_t)N * 4));
     if (dtype == RNND_U8)
         hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
-                           S, R, (u64)seed, (u64 *)keys, deg, scratch, (u32 *)nullptr);
+                           S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
     else
         hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
-                           S, R, (u64)seed, (u64 *)keys, deg, scratch, (u32 *)nullptr);
+                           S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
     HIPCHK(hipGetLastError());
     HIPCHK(hipStreamSynchronize(st));
 done:
-    if (scratch) (void)hipFree(scratch);
     return rc;
 }
 
@@ -711,6 +848,7 @@ extern "C" int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dt
     if (n_rounds < 1 || n_rounds > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int n_ctr = n_rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2;
     Workspace w;
     RoundCtr *hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
     if (!hctr) return RNND_ERR_OOM;
@@ -719,16 +857,18 @@ extern "C" int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dt
     ws_layout(w, N, R, n_ctr, false);
     HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
     HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
-    hipLaunchKernelGGL(k_collect_active, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, (long long)N, R,
-                       (const u64 *)keys, deg, w.ctr, w.active[0]);
+    hipLaunchKernelGGL(k_classify, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, (long long)N, R, (const u64 *)keys,
+                       deg, w.vcls, use_classes);
+    launch_compact_all(w, N, 0, st);
     HIPCHK(hipGetLastError());
     for (int t = 0; t < n_rounds; ++t)
-        HIPCHK(launch_update_round(w, X, d, dtype, vec_ok, R, (u64 *)keys, deg, t, st));
+        HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, (u64 *)keys, deg, t, st));
     HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
     HIPCHK(hipStreamSynchronize(st));
     if (stats) {
         memset(stats, 0, sizeof *stats);
         fill_round_stats(stats, hctr, n_rounds);
+        stats->kernel_variant = variant;
     }
 done:
     free(hctr);
@@ -749,7 +889,7 @@ extern "C" int rnnd_add_reverse_edges(int64_t N, int32_t R, uint64_t *keys, int3
     ws_layout(w, N, R, 2, false);
     HIPCHK(hipMemsetAsync(w.ctr, 0, 2 * sizeof(RoundCtr), st));
     HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
-    HIPCHK(launch_reverse(w, N, R, (u64 *)keys, deg, 0, st));
+    HIPCHK(launch_reverse(w, N, R, 0, (u64 *)keys, deg, 0, st));
     HIPCHK(hipStreamSynchronize(st));
 done:
     if (w.base) (void)hipFree(w.base);
@@ -793,4 +933,4 @@ extern "C" const char *rnnd_strerror(int status)
     }
 }
 
-extern "C" int rnnd_version(void) { return 100; }
+extern "C" int rnnd_version(void) { return 101; }

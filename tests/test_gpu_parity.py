@@ -22,6 +22,18 @@ def rn():
     return m
 
 
+@pytest.fixture(params=[0, 1], ids=["auto", "generic"])
+def variant(request, rn):
+    """0 = automatic choice (the MFMA Gram kernel for uint8 d in {32, 64, 128}), 1 = generic kernel."""
+    rn.rnnd_set_kernel_variant(request.param)
+    yield request.param
+    rn.rnnd_set_kernel_variant(0)
+
+
+def mfma_applies(X):
+    return X.dtype == np.uint8 and X.shape[1] in (32, 64, 128)
+
+
 def cuda(X):
     import torch
     return torch.from_numpy(X).cuda()
@@ -40,6 +52,7 @@ def clustered_u8(n, d, seed, k=8, spread=6):
 
 DATASETS = {
     "cfg1": lambda: wl.make_data(wl.CONFIGS["cfg1"]),
+    "u8_d64_dense": lambda: clustered_u8(900, 64, 12, k=3, spread=9),   # three tight clusters: long lists
     "u8_d128": lambda: wl.custom("heavy_u8", 3000, 128, 7),
     "u8_d33_ties": lambda: clustered_u8(1500, 33, 3),          # odd d: element-wise path; many ties
     "u8_dups": lambda: np.repeat(clustered_u8(300, 16, 4), 4, axis=0),   # exact duplicates, delta = 0
@@ -61,10 +74,12 @@ def test_random_graph(rn, oracle_mod, name, S, R):
 
 @pytest.mark.parametrize("name,S,R", [("cfg1", 10, 32), ("u8_d128", 20, 96), ("u8_d33_ties", 6, 16),
                                       ("u8_dups", 8, 12), ("f32_d96", 20, 96), ("f32_d960", 8, 24),
-                                      ("f32_d7", 100, 128)])
-def test_rounds_from_shared_snapshots(rn, oracle_mod, name, S, R):
+                                      ("f32_d7", 100, 128), ("u8_d64_dense", 100, 128), ("u8_d128", 70, 70)])
+def test_rounds_from_shared_snapshots(rn, oracle_mod, variant, name, S, R):
     """Every step starts from the oracle's snapshot, so one divergence cannot hide the next."""
     X = DATASETS[name]()
+    if variant == 1 and not mfma_applies(X):
+        pytest.skip("automatic choice already is the generic kernel")
     isf = X.dtype == np.float32
     Xd = cuda(X)
     snap = oracle_mod.random_graph(X, S, 99, R)
@@ -73,6 +88,7 @@ def test_rounds_from_shared_snapshots(rn, oracle_mod, name, S, R):
         if step == "u":
             snap, evals, props = oracle_mod.update_neighbors_sync(X, snap, R)
             st = rn.rnnd_update_neighbors(Xd, keys, deg, R, 1)
+            assert st.kernel_variant == (2 if variant == 0 and mfma_applies(X) else 1)
             assert st.algo_evals[0] == evals and st.proposals[0] == props
         else:
             snap = oracle_mod.add_reverse_edges(snap, R)
@@ -82,9 +98,12 @@ def test_rounds_from_shared_snapshots(rn, oracle_mod, name, S, R):
 
 @pytest.mark.parametrize("name,S,R,T1,T2", [
     ("cfg1", 10, 32, 2, 4), ("u8_d128", 20, 96, 3, 5), ("u8_d33_ties", 6, 16, 3, 4),
-    ("u8_dups", 8, 12, 3, 4), ("f32_d96", 20, 96, 3, 5), ("f32_d960", 8, 24, 2, 4), ("f32_d7", 16, 128, 2, 6)])
-def test_full_build(rn, oracle_mod, name, S, R, T1, T2):
+    ("u8_dups", 8, 12, 3, 4), ("u8_d64_dense", 40, 128, 3, 4), ("u8_d128", 60, 64, 2, 3),
+    ("f32_d96", 20, 96, 3, 5), ("f32_d960", 8, 24, 2, 4), ("f32_d7", 16, 128, 2, 6)])
+def test_full_build(rn, oracle_mod, variant, name, S, R, T1, T2):
     X = DATASETS[name]()
+    if variant == 1 and not mfma_applies(X):
+        pytest.skip("automatic choice already is the generic kernel")
     isf = X.dtype == np.float32
     want = oracle_mod.build_sync(X, S, R, T1, T2, wl.BUILD_SEED)
     graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), S, R, T1, T2, wl.BUILD_SEED)
@@ -117,12 +136,12 @@ def test_float_tolerance_bar(rn, oracle_mod):
     assert eq >= 0.99 * edges
 
 
-def test_hub_vertex_streams_through_the_merge(rn, oracle_mod):
+def test_hub_vertex_streams_through_the_merge(rn, oracle_mod, variant):
     """A star: vertex 0 sits at the centre of everything, so hundreds of edges are redirected to
     it in one round and hundreds of reverse edges enter it (the > 128-key path of the merge and
     the in-degree cap of Alg. 5)."""
     g = np.random.default_rng(8)
-    n, d, R = 2500, 16, 16
+    n, d, R = 2500, 32, 16
     X = np.clip(128 + g.normal(0, 40, size=(n, d)), 0, 255).astype(np.uint8)
     X[0] = 128
     snap = oracle_mod.random_graph(X, 8, 5, R)
@@ -147,24 +166,24 @@ def test_hub_vertex_streams_through_the_merge(rn, oracle_mod):
         assert_snapshot_equal(snap, False, keys, deg, "hub step " + step)
 
 
-def test_tiny_and_degenerate_inputs(rn, oracle_mod):
+def test_tiny_and_degenerate_inputs(rn, oracle_mod, variant):
     # N = 2: the only possible graph
     X = np.array([[0, 0], [3, 4]], np.uint8)
     g, d = rn.rnnd_build(cuda(X), 1, 1, 2, 2, 0)
     assert g.cpu().numpy().tolist() == [[1], [0]] and d.cpu().numpy().tolist() == [1, 1]
     # all points identical: every delta is 0, every test ties, order is by id alone
-    X = np.full((40, 16), 7, np.uint8)
+    X = np.full((40, 32), 7, np.uint8)
     want = oracle_mod.build_sync(X, 5, 8, 2, 3, 4)
     graph, degree, keys, _ = rn.rnnd_build_ex(cuda(X), 5, 8, 2, 3, 4)
     assert_snapshot_equal(want.snap, False, keys, degree, "identical points")
     # complete initialisation, R = RNND_MAX_R
-    X = clustered_u8(129, 16, 6)
+    X = clustered_u8(129, 32, 6)
     want = oracle_mod.build_sync(X, 128, 128, 2, 3, 4)
     graph, degree, keys, _ = rn.rnnd_build_ex(cuda(X), 128, 128, 2, 3, 4)
     assert_snapshot_equal(want.snap, False, keys, degree, "complete init")
     # a snapshot with empty rows and no "new" entry at all: nothing may change
     snap = oracle_mod.Snapshot.empty(50, 8)
-    X = clustered_u8(50, 16, 7)
+    X = clustered_u8(50, 32, 7)
     keys, deg = snapshot_to_device(snap, False, 8)
     st = rn.rnnd_update_neighbors(cuda(X), keys, deg, 8, 2)
     assert st.active[0] == 0 and (deg == 0).all()
@@ -188,7 +207,7 @@ def test_argument_errors_on_device(rn):
     assert e.value.status == -2
 
 
-def test_cfg2_full_parity(rn, oracle_mod):
+def test_cfg2_full_parity(rn, oracle_mod, variant):
     """BASELINE configuration 2 (N = 100,000, d = 128 uint8, paper parameters): ~20 s of oracle."""
     c = wl.CONFIGS["cfg2"]
     X = wl.make_data(c)
