@@ -48,7 +48,7 @@ __device__ __forceinline__ void add_round_stats(RoundCtr *ctr, u64 algo, u64 exe
 struct Prop {          // one redirected edge (Alg. 4 line 13): `key` enters `tgt`'s list
     u64 key;
     u32 tgt;
-    u32 slot;          // arrival number among the edges for tgt (gives its place in tgt's bin)
+    u32 pad;
 };
 
 #include "dist.h"
@@ -236,7 +236,8 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
             Prop pr;
             pr.key = s_pkey[wave][p];
             pr.tgt = s_ptgt[wave][p];
-            pr.slot = (u32)atomicAdd(&cnt[pr.tgt], 1);
+            pr.pad = 0;
+            atomicAdd(&cnt[pr.tgt], 1);
             props[(size_t)u * R + p] = pr;
         }
         nprops_total += np;
@@ -287,7 +288,8 @@ __global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cn
 // every active vertex moves its redirected edges into the bins of their targets
 __global__ __launch_bounds__(BLOCK) void k_bin_scatter(long long N, int R, const int *lists,
                                                        const RoundCtr *ctr, const Prop *props,
-                                                       const int *nprop, const int *binoff, u64 *bins)
+                                                       const int *nprop, const int *binoff, int *fill,
+                                                       u64 *bins)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = blockIdx.y;
     const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(BLOCK) void k_bin_scatter(long long N, int R, const
         const int np = nprop[u];
         for (int p = lane; p < np; p += 64) {
             Prop pr = props[(size_t)u * R + p];
-            bins[(size_t)binoff[pr.tgt] + pr.slot] = pr.key;
+            bins[(size_t)binoff[pr.tgt] + atomicAdd(&fill[pr.tgt], 1)] = pr.key;
         }
     }
 }
@@ -306,7 +308,7 @@ __global__ __launch_bounds__(BLOCK) void k_bin_scatter(long long N, int R, const
 // For every touched vertex x: list <- first R distinct of (kept entries + edges redirected to x).
 // tcls[it] <- degree class of x if its new list holds a "new" entry, else -1.
 __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, const int *touched,
-                                                 int *cnt, const int *binoff, const u64 *bins,
+                                                 int *cnt, int *fill, const int *binoff, const u64 *bins,
                                                  const RoundCtr *ctr, int8_t *tcls, int use_classes)
 {
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
@@ -321,6 +323,7 @@ __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, con
         if (lane == 0) {
             deg[x] = nd;
             cnt[x] = 0;
+            fill[x] = 0;
             tcls[it] = any_new ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
         }
     }
@@ -433,7 +436,7 @@ __global__ __launch_bounds__(BLOCK) void k_incap_threshold(int R, const int *lis
 // Alg. 5 lines 6-8, second half: edge (u, v) survives iff (delta, u) <= thr[v].  vcls[u] <- degree
 // class if the list holds a "new" entry, else -1.  Clears cnt for the next use.
 __global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 *keys, int *deg,
-                                                        const u64 *thr, int *cnt, int8_t *vcls,
+                                                        const u64 *thr, int *cnt, int *fill, int8_t *vcls,
                                                         int use_classes)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -459,6 +462,7 @@ __global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 
         const int nd = c0 + __popcll(m1);
         deg[u] = nd;
         cnt[u] = 0;
+        fill[u] = 0;
         vcls[u] = (n0 | n1) ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
     }
 }
@@ -652,8 +656,8 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
     hipLaunchKernelGGL(k_assign_bins, dim3((unsigned)((N + 1023) / 1024)), dim3(1024), 0, st, N, w.cnt, 0,
                        w.binoff, &c->bin_cursor, w.touched, &c->n_touched, (int *)nullptr, (u64 *)nullptr);
     hipLaunchKernelGGL(k_bin_scatter, dim3(pb, use_classes ? NCLS : 1), dim3(BLOCK), 0, st, N, R, w.lists, c,
-                       w.props, w.nprop, w.binoff, w.bins);
-    hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched, w.cnt, w.binoff,
+                       w.props, w.nprop, w.binoff, w.fill, w.bins);
+    hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched, w.cnt, w.fill, w.binoff,
                        w.bins, c, w.tcls, use_classes);
     hipLaunchKernelGGL(k_compact_classes, dim3(256), dim3(1024), 0, st, &c->n_touched, 0u, w.touched, w.tcls,
                        w.lists, N, (c + 1)->n_active);
@@ -687,7 +691,7 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.fill, w.bins, 0u);
     hipLaunchKernelGGL(k_incap_threshold, dim3(persistent_blocks()), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 2,
                        w.cnt, w.binoff, w.bins, w.thr);
-    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, w.cnt, w.vcls,
+    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, w.cnt, w.fill, w.vcls,
                        use_classes);
     launch_compact_all(w, N, t_next, st);
     return hipGetLastError();
@@ -749,6 +753,7 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
         HIPCHK(hipEventRecord(ev[e++], st));
         HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
         HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
+        HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
         if (dtype == RNND_U8)
             hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
                                vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
@@ -857,6 +862,7 @@ extern "C" int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dt
     ws_layout(w, N, R, n_ctr, false);
     HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
     HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
+    HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
     hipLaunchKernelGGL(k_classify, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, (long long)N, R, (const u64 *)keys,
                        deg, w.vcls, use_classes);
     launch_compact_all(w, N, 0, st);
