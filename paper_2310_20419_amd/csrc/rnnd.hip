@@ -2,10 +2,12 @@
 //
 // One wavefront owns one vertex in every per-vertex kernel.  A round is synchronous:
 //   scan     every active vertex (one holding a "new" entry) runs Alg. 4 lines 2-15 on its own list,
-//            writes its kept entries back in place and leaves its redirected edges in its slot of `props`
-//   offsets  every vertex that received edges gets a bin; those vertices form the `touched` list
-//   scatter  redirected edges move into their target's bin
-//   merge    every touched list becomes the first R distinct keys of (kept entries + bin)
+//            writes its kept entries back in place, leaves its redirected edges in its slot of `props`
+//            and counts them per target (adds whose result nobody waits for)
+//   offsets  vertices that received edges form the `touched` list; those that received more than
+//            INBOX_CAP also get a bin for the surplus
+//   scatter  redirected edges move into their target's inbox (INBOX_CAP slots per vertex) or bin
+//   merge    every touched list becomes the first R distinct keys of (kept entries + inbox + bin)
 //   compact  touched vertices whose new list holds a "new" entry form the next active lists,
 //            one per degree class (lists of up to 32, 64, 96, 128 entries)
 // Counters that many wavefronts would hit at one address are aggregated per block first.
@@ -21,6 +23,7 @@
 #define BLOCK (64 * WAVES_PER_BLOCK)
 #define GOLDEN64 0x9E3779B97F4A7C15ull
 #define NCLS 4
+#define INBOX_CAP 64   // redirected edges a vertex can receive per round without the overflow path
 
 // Per-round device counters.  Round t reads ctr[t].n_active[] and fills the rest; its compact step
 // writes ctr[t+1].n_active[].  Zeroed once per call, never reset, so they double as statistics.
@@ -50,6 +53,17 @@ struct Prop {          // one redirected edge (Alg. 4 line 13): `key` enters `tg
     u32 tgt;
     u32 pad;
 };
+
+// Line 13: (w, v) enters E.  Recorded in the scanning vertex's own slot; the target is only counted.
+__device__ __forceinline__ void emit_redirect(u64 key, u32 tgt, Prop *slot, int *cnt)
+{
+    Prop pr;
+    pr.key = key;
+    pr.tgt = tgt;
+    pr.pad = 0;
+    *slot = pr;
+    atomicAdd(&cnt[tgt], 1);   // result unused: no wait
+}
 
 #include "dist.h"
 #include "scan_mfma.h"
@@ -232,25 +246,20 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
             nprop[u] = np;
         }
         wave_sync();
-        for (int p = lane; p < np; p += 64) {
-            Prop pr;
-            pr.key = s_pkey[wave][p];
-            pr.tgt = s_ptgt[wave][p];
-            pr.pad = 0;
-            atomicAdd(&cnt[pr.tgt], 1);
-            props[(size_t)u * R + p] = pr;
-        }
+        for (int p = lane; p < np; p += 64)
+            emit_redirect(s_pkey[wave][p], s_ptgt[wave][p], props + (size_t)u * R + p, cnt);
         nprops_total += np;
     }
     if (lane == 0 && rows) add_round_stats(ctr, evals_algo, evals_exec, rows, nprops_total);
 }
 
 // ------------------------------------------------------ UpdateNeighbors: merge
-// binoff[x] <- start of x's bin, for every x with cnt[x] > min_cnt (others: -1); those x are appended
-// to `list`.  One pair of atomics per 1024 vertices.  Optionally clears fill[] and sets thr[] to "keep all".
-__global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cnt, int min_cnt, int *binoff,
-                                                      u32 *bin_cursor, int *list, u32 *n_list, int *fill,
-                                                      u64 *thr)
+// Vertices x with cnt[x] > list_min are appended to `list`; those with cnt[x] > bin_min get a bin of
+// cnt[x] - bin_sub keys starting at binoff[x] (others: binoff = -1).  One pair of atomics per 1024
+// vertices.  Optionally clears fill[] and sets thr[] to "keep all".
+__global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cnt, int list_min, int bin_min,
+                                                      int bin_sub, int *binoff, u32 *bin_cursor, int *list,
+                                                      u32 *n_list, int *fill, u64 *thr)
 {
     __shared__ u32 s_sum[16], s_num[16], s_base[2];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -261,15 +270,15 @@ __global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cn
         if (fill) fill[x] = 0;
         if (thr) thr[x] = KEY_PAD;
     }
-    const bool has = c > min_cnt;
-    const u32 mine = has ? (u32)c : 0u;
+    const bool in_list = c > list_min;
+    const u32 mine = c > bin_min ? (u32)(c - bin_sub) : 0u;
     u32 incl = mine;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
         u32 v = __shfl_up(incl, o);
         if (lane >= o) incl += v;
     }
-    const u64 hb = __builtin_amdgcn_ballot_w64(has);
+    const u64 hb = __builtin_amdgcn_ballot_w64(in_list);
     if (lane == 63) { s_sum[wave] = incl; s_num[wave] = (u32)__popcll(hb); }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -280,27 +289,29 @@ __global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cn
     }
     __syncthreads();
     if (x < N) {
-        binoff[x] = has ? (int)(s_base[0] + s_sum[wave] + incl - mine) : -1;
-        if (has) list[s_base[1] + s_num[wave] + __popcll(hb & lanes_below(lane))] = (int)x;
+        binoff[x] = mine ? (int)(s_base[0] + s_sum[wave] + incl - mine) : -1;
+        if (in_list) list[s_base[1] + s_num[wave] + __popcll(hb & lanes_below(lane))] = (int)x;
     }
 }
 
-// every active vertex moves its redirected edges into the bins of their targets
-__global__ __launch_bounds__(BLOCK) void k_bin_scatter(long long N, int R, const int *lists,
-                                                       const RoundCtr *ctr, const Prop *props,
-                                                       const int *nprop, const int *binoff, int *fill,
-                                                       u64 *bins)
+// Every active vertex moves its redirected edges to their targets: arrival number s = fill[tgt]++;
+// the first INBOX_CAP arrivals go to the target's inbox, later ones to its bin.  16 lanes per vertex.
+__global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int *lists, const RoundCtr *ctr,
+                                                   const Prop *props, const int *nprop, const int *binoff,
+                                                   int *fill, u64 *inbox, u64 *bins)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = blockIdx.y;
-    const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
+    const int sub = threadIdx.x & 15, c = blockIdx.y;
+    const u32 g = (blockIdx.x * BLOCK + threadIdx.x) >> 4, ng = (gridDim.x * BLOCK) >> 4;
     const u32 n = ctr->n_active[c];
     const int *list = lists + (size_t)c * N;
-    for (u32 it = gw; it < n; it += nw) {
+    for (u32 it = g; it < n; it += ng) {
         const int u = list[it];
         const int np = nprop[u];
-        for (int p = lane; p < np; p += 64) {
-            Prop pr = props[(size_t)u * R + p];
-            bins[(size_t)binoff[pr.tgt] + atomicAdd(&fill[pr.tgt], 1)] = pr.key;
+        for (int p = sub; p < np; p += 16) {
+            const Prop pr = props[(size_t)u * R + p];
+            const int s = atomicAdd(&fill[pr.tgt], 1);
+            if (s < INBOX_CAP) inbox[(size_t)pr.tgt * INBOX_CAP + s] = pr.key;
+            else bins[(size_t)binoff[pr.tgt] + (s - INBOX_CAP)] = pr.key;
         }
     }
 }
@@ -308,8 +319,9 @@ __global__ __launch_bounds__(BLOCK) void k_bin_scatter(long long N, int R, const
 // For every touched vertex x: list <- first R distinct of (kept entries + edges redirected to x).
 // tcls[it] <- degree class of x if its new list holds a "new" entry, else -1.
 __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, const int *touched,
-                                                 int *cnt, int *fill, const int *binoff, const u64 *bins,
-                                                 const RoundCtr *ctr, int8_t *tcls, int use_classes)
+                                                 int *cnt, int *fill, const u64 *inbox, const int *binoff,
+                                                 const u64 *bins, const RoundCtr *ctr, int8_t *tcls,
+                                                 int use_classes)
 {
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -318,8 +330,9 @@ __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, con
     for (u32 it = gw; it < n; it += nw) {
         const int x = touched[it];
         bool any_new = false;
-        const int nd = wave_merge_row(keys + (size_t)x * R, deg[x], bins + binoff[x], cnt[x], R,
-                                      s_stage[wave], lane, &any_new);
+        const int c = cnt[x], ca = c < INBOX_CAP ? c : INBOX_CAP;
+        const int nd = wave_merge_row(keys + (size_t)x * R, deg[x], inbox + (size_t)x * INBOX_CAP, ca,
+                                      bins + (c > ca ? binoff[x] : 0), c - ca, R, s_stage[wave], lane, &any_new);
         if (lane == 0) {
             deg[x] = nd;
             cnt[x] = 0;
@@ -405,7 +418,7 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64
     const int c = cnt[x];
     if (c > 0) {
         bool any_new;
-        const int nd = wave_merge_row(keys + (size_t)x * R, deg[x], bins + binoff[x], c, R,
+        const int nd = wave_merge_row(keys + (size_t)x * R, deg[x], bins + binoff[x], c, bins, 0, R,
                                       s_stage[wave], lane, &any_new);
         if (lane == 0) deg[x] = nd;
     }
@@ -426,8 +439,8 @@ __global__ __launch_bounds__(BLOCK) void k_incap_threshold(int R, const int *lis
         const int v = list[it];
         bool any_new;
         wave_sync();
-        const int nd = wave_merge_row(s_row[wave], 0, bins + binoff[v], cnt[v], R, s_stage[wave], lane,
-                                      &any_new);
+        const int nd = wave_merge_row(s_row[wave], 0, bins + binoff[v], cnt[v], bins, 0, R, s_stage[wave],
+                                      lane, &any_new);
         wave_sync();
         if (lane == 0) thr[v] = s_row[wave][nd - 1];
     }
@@ -522,7 +535,8 @@ struct Workspace {
     u64 *keys = nullptr;    // [N*R]   (unless the caller supplies a snapshot)
     int *deg = nullptr;     // [N]
     Prop *props = nullptr;  // [N*R]   slot u*R.. holds the edges vertex u redirected this round
-    u64 *bins = nullptr;    // [N*R]
+    u64 *inbox = nullptr;   // [N*INBOX_CAP] redirected edges received this round, by target
+    u64 *bins = nullptr;    // [N*R]   surplus of the inboxes; AddReverseEdges' bins
     u64 *thr = nullptr;     // [N]
     int *cnt = nullptr, *binoff = nullptr, *fill = nullptr, *touched = nullptr, *hubs = nullptr, *nprop = nullptr;
     int *lists = nullptr;   // [NCLS*N] active lists by degree class
@@ -538,6 +552,7 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
     auto take = [&](size_t b) { size_t o = off; off += align_up(b); return o; };
     size_t o_keys = own_graph ? take((size_t)N * R * 8) : 0;
     size_t o_deg = own_graph ? take((size_t)N * 4) : 0;
+    size_t o_inbox = take((size_t)N * INBOX_CAP * 8);
     size_t o_props = take((size_t)N * R * sizeof(Prop));
     size_t o_bins = take((size_t)N * R * 8);
     size_t o_thr = take((size_t)N * 8);
@@ -549,7 +564,9 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
     size_t o_misc = take(8 * 4);
     if (w.base) {
         if (own_graph) { w.keys = (u64 *)(w.base + o_keys); w.deg = (int *)(w.base + o_deg); }
+        w.inbox = (u64 *)(w.base + o_inbox);
         w.props = (Prop *)(w.base + o_props);
+        w.nprop = (int *)(w.base + o_nprop);
         w.bins = (u64 *)(w.base + o_bins);
         w.thr = (u64 *)(w.base + o_thr);
         w.cnt = (int *)(w.base + o_cnt);
@@ -557,7 +574,6 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
         w.fill = (int *)(w.base + o_fill);
         w.touched = (int *)(w.base + o_touched);
         w.hubs = (int *)(w.base + o_hubs);
-        w.nprop = (int *)(w.base + o_nprop);
         w.lists = (int *)(w.base + o_lists);
         w.vcls = (int8_t *)(w.base + o_vcls);
         w.tcls = (int8_t *)(w.base + o_tcls);
@@ -654,11 +670,12 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
     }
     if (after_scan) (void)hipEventRecord(after_scan, st);
     hipLaunchKernelGGL(k_assign_bins, dim3((unsigned)((N + 1023) / 1024)), dim3(1024), 0, st, N, w.cnt, 0,
-                       w.binoff, &c->bin_cursor, w.touched, &c->n_touched, (int *)nullptr, (u64 *)nullptr);
-    hipLaunchKernelGGL(k_bin_scatter, dim3(pb, use_classes ? NCLS : 1), dim3(BLOCK), 0, st, N, R, w.lists, c,
-                       w.props, w.nprop, w.binoff, w.fill, w.bins);
-    hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched, w.cnt, w.fill, w.binoff,
-                       w.bins, c, w.tcls, use_classes);
+                       INBOX_CAP, INBOX_CAP, w.binoff, &c->bin_cursor, w.touched, &c->n_touched, (int *)nullptr,
+                       (u64 *)nullptr);
+    hipLaunchKernelGGL(k_scatter, dim3(pb, use_classes ? NCLS : 1), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props,
+                       w.nprop, w.binoff, w.fill, w.inbox, w.bins);
+    hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched, w.cnt, w.fill, w.inbox,
+                       w.binoff, w.bins, c, w.tcls, use_classes);
     hipLaunchKernelGGL(k_compact_classes, dim3(256), dim3(1024), 0, st, &c->n_touched, 0u, w.touched, w.tcls,
                        w.lists, N, (c + 1)->n_active);
     return hipGetLastError();
@@ -680,13 +697,13 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NCLS);
     // lines 1-5: union with reversed edges, out-lists cut to R
     hipLaunchKernelGGL(k_count_targets, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.cnt);
-    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.cnt, 0, w.binoff, w.misc + 0, w.hubs,
+    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.cnt, 0, 0, 0, w.binoff, w.misc + 0, w.hubs,
                        w.misc + 3, w.fill, (u64 *)nullptr);
     hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.fill, w.bins, 1u);
     hipLaunchKernelGGL(k_reverse_merge, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.cnt, w.binoff, w.bins);
     // lines 6-8: in-lists cut to R; only vertices with more than R incoming edges need a bin
     hipLaunchKernelGGL(k_count_targets, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.cnt);
-    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.cnt, R, w.binoff, w.misc + 1, w.hubs,
+    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.cnt, R, R, 0, w.binoff, w.misc + 1, w.hubs,
                        w.misc + 2, w.fill, w.thr);
     hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.fill, w.bins, 0u);
     hipLaunchKernelGGL(k_incap_threshold, dim3(persistent_blocks()), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 2,

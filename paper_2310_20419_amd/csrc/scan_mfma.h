@@ -273,13 +273,9 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_u8(
                     if (pruned) {
                         const int g = sm.gt[tgt * GT_STRIDE + l32];
                         const u32 dvw = (u32)(nrm[I] + sm.nrm[tgt] - 2 * g);
-                        const u32 tid = (u32)sm.id[tgt];
-                        Prop pr;
-                        pr.key = make_key(dvw, key_id(kb), 1u);   // line 13: v enters w's list
-                        pr.tgt = tid;
-                        pr.pad = 0;
-                        atomicAdd(&cnt[tid], 1);                  // result unused: no wait
-                        props[(size_t)u * R + np_base + __popcll(pm & lanes_below(lane))] = pr;
+                        // line 13: v enters w's list
+                        emit_redirect(make_key(dvw, key_id(kb), 1u), (u32)sm.id[tgt],
+                                      props + (size_t)u * R + np_base + __popcll(pm & lanes_below(lane)), cnt);
                     }
                     np_base += __popcll(pm);
                     wave_sync();   // before the next block overwrites t and G^T

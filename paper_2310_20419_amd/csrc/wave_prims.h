@@ -114,17 +114,19 @@ __device__ __forceinline__ int wave_unique_prefix(const u64 (&k)[E], int lane, i
     return base < cap ? base : cap;
 }
 
-// Row `row` (nb sorted keys) merged with `bin` (c keys in any order): the first R distinct keys of
-// the union, ascending, are written back to row[0..); returns the new length.  `stage` is 128 keys
-// of LDS private to this wavefront.
-__device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *bin, int c, int R,
-                                              u64 *stage, int lane, bool *any_new)
+// Row `row` (nb sorted keys) merged with c = ca + cb keys in any order (the first ca at binA, the
+// rest at binB): the first R distinct keys of the union, ascending, are written back to row[0..);
+// returns the new length.  `stage` is 128 keys of LDS private to this wavefront.
+__device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *binA, int ca, const u64 *binB,
+                                              int cb, int R, u64 *stage, int lane, bool *any_new)
 {
+    const int c = ca + cb;
     const int total = nb + c;
+    auto bin_at = [&](int e) -> u64 { return e < ca ? binA[e] : binB[e - ca]; };
     int n;
     if (total <= 64) {
         u64 k[1];
-        k[0] = lane < nb ? row[lane] : (lane < total ? bin[lane - nb] : KEY_PAD);
+        k[0] = lane < nb ? row[lane] : (lane < total ? bin_at(lane - nb) : KEY_PAD);
         wave_sort<1>(k, lane);
         n = wave_unique_prefix<1>(k, lane, R, row, any_new);
     } else if (total <= 128) {
@@ -132,7 +134,7 @@ __device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *bin, 
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             int e = r * 64 + lane;
-            k[r] = e < nb ? row[e] : (e < total ? bin[e - nb] : KEY_PAD);
+            k[r] = e < nb ? row[e] : (e < total ? bin_at(e - nb) : KEY_PAD);
         }
         wave_sort<2>(k, lane);
         n = wave_unique_prefix<2>(k, lane, R, row, any_new);
@@ -144,8 +146,8 @@ __device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *bin, 
         n = nb;
         for (int done = 0; done < c; done += 128) {
             int e0 = done + lane, e1 = done + 64 + lane;
-            k[2] = e0 < c ? bin[e0] : KEY_PAD;
-            k[3] = e1 < c ? bin[e1] : KEY_PAD;
+            k[2] = e0 < c ? bin_at(e0) : KEY_PAD;
+            k[3] = e1 < c ? bin_at(e1) : KEY_PAD;
             wave_sort<4>(k, lane);
             n = wave_unique_prefix<4>(k, lane, R, stage, any_new);
             wave_sync();

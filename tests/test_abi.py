@@ -52,8 +52,8 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
 
 def test_workspace_bytes(lib):
     b = rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 96)
-    # graph (8 B) + redirected edges (16 B) + bins (8 B) per slot dominate
-    assert 1_000_000 * 96 * 32 <= b < 1_000_000 * 96 * 34
+    # graph (8 B) + overflow list (16 B) + bins (8 B) per slot, plus a 64-key inbox per vertex, dominate
+    assert 1_000_000 * (96 * 32 + 512) <= b < 1_000_000 * (96 * 32 + 512 + 128)
     with pytest.raises(rn.RnndError):
         rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 500)
 
