@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--variant", type=int, default=0, help="UpdateNeighbors kernel: 0 auto, 1 generic, 2 MFMA")
     ap.add_argument("--cpu-sample", type=int, default=0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not "
@@ -92,6 +94,15 @@ def main():
     Xd = torch.from_numpy(X).cuda()
     esz = 1 if cfg.dtype == "u8" else 4
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        a.fill_(3)
+        torch.cuda.synchronize()
+        b.copy_(a)          # the calibration kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
 
     def step():
         return rn.rnnd_build_ex(Xd, cfg.S, cfg.R, cfg.T1, cfg.T2, wl.BUILD_SEED, want_keys=False)

@@ -30,9 +30,9 @@
 #define STAT_SLOTS 64
 struct RoundCtr {
     u32 n_active[NCLS];   // lengths of this round's active lists
-    u32 n_touched;        // distinct targets of the redirected edges
+    u32 n_touched[NCLS];  // distinct targets of the redirected edges, by size of the merge they need
     u32 bin_cursor;       // space handed out in the bin array
-    u32 pad[2];
+    u32 pad[3];
     // statistics, spread over STAT_SLOTS addresses so that the adds of many blocks do not queue up
     // on one: [slot][0..3] = algorithmic evals, executed evals, rows gathered, edges redirected
     u64 stat[STAT_SLOTS][4];
@@ -316,19 +316,113 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int
     }
 }
 
-// For every touched vertex x: list <- first R distinct of (kept entries + edges redirected to x).
-// tcls[it] <- degree class of x if its new list holds a "new" entry, else -1.
-__global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, const int *touched,
-                                                 int *cnt, int *fill, const u64 *inbox, const int *binoff,
-                                                 const u64 *bins, const RoundCtr *ctr, int8_t *tcls,
+// Merge class of a vertex that holds nb entries and received c: how wide a sort its merge needs.
+__device__ __forceinline__ int merge_class(int nb, int c)
+{
+    const int total = nb + c;
+    return total <= 16 ? 0 : total <= 32 ? 1 : total <= 64 ? 2 : 3;
+}
+
+// Every vertex x with cnt[x] > 0 is appended to the touched list of its merge class; if it received
+// more than INBOX_CAP edges it also gets a bin for the surplus.  Five atomics per 1024 vertices.
+__global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int *cnt, const int *deg,
+                                                         int *binoff, RoundCtr *ctr, int *tlists)
+{
+    __shared__ u32 s_cnt[16][NCLS], s_sum[16], s_base[NCLS + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long x = (long long)blockIdx.x * 1024 + threadIdx.x;
+    int c = 0, mc = -1;
+    if (x < N) {
+        c = cnt[x];
+        if (c > 0) mc = merge_class(deg[x], c);
+    }
+    const u32 mine = c > INBOX_CAP ? (u32)(c - INBOX_CAP) : 0u;
+    u32 incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        u32 v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
+    }
+    u64 b[NCLS];
+#pragma unroll
+    for (int k = 0; k < NCLS; ++k) b[k] = __builtin_amdgcn_ballot_w64(mc == k);
+    if (lane == 63) s_sum[wave] = incl;
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < NCLS; ++k) s_cnt[wave][k] = (u32)__popcll(b[k]);
+    }
+    __syncthreads();
+    if (threadIdx.x < NCLS) {
+        u32 tot = 0;
+        for (int w = 0; w < 16; ++w) { u32 a = s_cnt[w][threadIdx.x]; s_cnt[w][threadIdx.x] = tot; tot += a; }
+        s_base[threadIdx.x] = tot ? atomicAdd(&ctr->n_touched[threadIdx.x], tot) : 0u;
+    } else if (threadIdx.x == NCLS) {
+        u32 ts = 0;
+        for (int w = 0; w < 16; ++w) { u32 a = s_sum[w]; s_sum[w] = ts; ts += a; }
+        s_base[NCLS] = ts ? atomicAdd(&ctr->bin_cursor, ts) : 0u;
+    }
+    __syncthreads();
+    if (x < N) {
+        binoff[x] = mine ? (int)(s_base[NCLS] + s_sum[wave] + incl - mine) : -1;
+        if (mc >= 0) {
+            u64 mb = b[0];
+#pragma unroll
+            for (int k = 1; k < NCLS; ++k) mb = (mc == k) ? b[k] : mb;
+            tlists[(size_t)mc * N + s_base[mc] + s_cnt[wave][mc] + __popcll(mb & lanes_below(lane))] = (int)x;
+        }
+    }
+}
+
+// Merge of the touched vertices whose kept entries + received edges number at most G: one vertex per
+// group of G lanes.  list <- first R distinct keys; tcls[it] <- degree class if a "new" entry survives, else -1.
+template <int G>
+__global__ __launch_bounds__(BLOCK) void k_merge_group(int R, u64 *keys, int *deg, const int *tlist,
+                                                       const u32 *n_ptr, int *cnt, int *fill,
+                                                       const u64 *inbox, int8_t *tcls, int use_classes)
+{
+    const int lane = threadIdx.x & 63, sub = lane & (G - 1), shift = lane & ~(G - 1);
+    const u64 gmask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull);
+    const u32 gid = (blockIdx.x * BLOCK + threadIdx.x) / G, ngrp = (gridDim.x * BLOCK) / G;
+    const u32 n = *n_ptr;
+    for (u32 it = gid; it < n; it += ngrp) {
+        const int x = tlist[it];
+        const int nb = deg[x], c = cnt[x];
+        u64 *row = keys + (size_t)x * R;
+        u64 k = KEY_PAD;
+        if (sub < nb) k = row[sub];
+        else if (sub < nb + c) k = inbox[(size_t)x * INBOX_CAP + (sub - nb)];
+        k = group_sort<G>(k, lane);
+        u64 prev = shfl_up1_u64(k);
+        if (sub == 0) prev = KEY_PAD;
+        const bool keep = (k != KEY_PAD) && ((k >> 1) != (prev >> 1));
+        const u64 m = (__builtin_amdgcn_ballot_w64(keep) >> shift) & gmask;
+        const int pos = __popcll(m & lanes_below(sub));
+        const bool w = keep && pos < R;
+        if (w) row[pos] = k;
+        const u64 nm = (__builtin_amdgcn_ballot_w64(w && (k & 1ull)) >> shift) & gmask;
+        if (sub == 0) {
+            int nd = __popcll(m);
+            if (nd > R) nd = R;
+            deg[x] = nd;
+            cnt[x] = 0;
+            fill[x] = 0;
+            tcls[it] = nm ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
+        }
+    }
+}
+
+// General merge (any size): one touched vertex per wavefront; kept entries + inbox + surplus bin.
+__global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, const int *tlist,
+                                                 const u32 *n_ptr, int *cnt, int *fill, const u64 *inbox,
+                                                 const int *binoff, const u64 *bins, int8_t *tcls,
                                                  int use_classes)
 {
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
-    const u32 n = ctr->n_touched;
+    const u32 n = *n_ptr;
     for (u32 it = gw; it < n; it += nw) {
-        const int x = touched[it];
+        const int x = tlist[it];
         bool any_new = false;
         const int c = cnt[x], ca = c < INBOX_CAP ? c : INBOX_CAP;
         const int nd = wave_merge_row(keys + (size_t)x * R, deg[x], inbox + (size_t)x * INBOX_CAP, ca,
@@ -343,14 +437,16 @@ __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, con
 }
 
 // Items i < n with cls[i] >= 0 are appended to list cls[i]; item i stands for vertex idx[i] (or i).
-// One atomic per class per 1024 items.
+// blockIdx.y = s selects source list s: n_ptr[s], idx + s*N, cls + s*N.  One atomic per class per 1024 items.
 __global__ __launch_bounds__(1024) void k_compact_classes(const u32 *n_ptr, u32 n_fixed, const int *idx,
                                                           const int8_t *cls, int *lists, long long N,
                                                           u32 *n_out)
 {
     __shared__ u32 s_cnt[16][NCLS], s_base[NCLS];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const u32 n = n_ptr ? *n_ptr : n_fixed;
+    const u32 n = n_ptr ? n_ptr[blockIdx.y] : n_fixed;
+    if (idx) idx += (size_t)blockIdx.y * N;
+    cls += (size_t)blockIdx.y * N;
     for (u32 base = blockIdx.x * 1024u; base < n; base += gridDim.x * 1024u) {
         const u32 i = base + threadIdx.x;
         const int c = i < n ? (int)cls[i] : -1;
@@ -540,7 +636,7 @@ struct Workspace {
     u64 *thr = nullptr;     // [N]
     int *cnt = nullptr, *binoff = nullptr, *fill = nullptr, *touched = nullptr, *hubs = nullptr, *nprop = nullptr;
     int *lists = nullptr;   // [NCLS*N] active lists by degree class
-    int8_t *vcls = nullptr, *tcls = nullptr;   // [N] each
+    int8_t *vcls = nullptr, *tcls = nullptr;   // [N], [NCLS*N]
     RoundCtr *ctr = nullptr;   // [n_ctr]
     u32 *misc = nullptr;       // [8]: small cursors for AddReverseEdges
     int n_ctr = 0;
@@ -557,9 +653,9 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
     size_t o_bins = take((size_t)N * R * 8);
     size_t o_thr = take((size_t)N * 8);
     size_t o_cnt = take((size_t)N * 4), o_binoff = take((size_t)N * 4), o_fill = take((size_t)N * 4);
-    size_t o_touched = take((size_t)N * 4), o_hubs = take((size_t)N * 4), o_nprop = take((size_t)N * 4);
+    size_t o_touched = take((size_t)N * 4 * NCLS), o_hubs = take((size_t)N * 4), o_nprop = take((size_t)N * 4);
     size_t o_lists = take((size_t)N * 4 * NCLS);
-    size_t o_vcls = take((size_t)N), o_tcls = take((size_t)N);
+    size_t o_vcls = take((size_t)N), o_tcls = take((size_t)N * NCLS);
     size_t o_ctr = take((size_t)n_ctr * sizeof(RoundCtr));
     size_t o_misc = take(8 * 4);
     if (w.base) {
@@ -669,14 +765,19 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
                            w.lists, &c->n_active[0], w.props, w.nprop, w.cnt, c);
     }
     if (after_scan) (void)hipEventRecord(after_scan, st);
-    hipLaunchKernelGGL(k_assign_bins, dim3((unsigned)((N + 1023) / 1024)), dim3(1024), 0, st, N, w.cnt, 0,
-                       INBOX_CAP, INBOX_CAP, w.binoff, &c->bin_cursor, w.touched, &c->n_touched, (int *)nullptr,
-                       (u64 *)nullptr);
+    hipLaunchKernelGGL(k_touch_classify, dim3((unsigned)((N + 1023) / 1024)), dim3(1024), 0, st, N, w.cnt, deg,
+                       w.binoff, c, w.touched);
     hipLaunchKernelGGL(k_scatter, dim3(pb, use_classes ? NCLS : 1), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props,
                        w.nprop, w.binoff, w.fill, w.inbox, w.bins);
-    hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched, w.cnt, w.fill, w.inbox,
-                       w.binoff, w.bins, c, w.tcls, use_classes);
-    hipLaunchKernelGGL(k_compact_classes, dim3(256), dim3(1024), 0, st, &c->n_touched, 0u, w.touched, w.tcls,
+    hipLaunchKernelGGL(k_merge_group<16>, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 0 * N,
+                       &c->n_touched[0], w.cnt, w.fill, w.inbox, w.tcls + 0 * N, use_classes);
+    hipLaunchKernelGGL(k_merge_group<32>, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 1 * N,
+                       &c->n_touched[1], w.cnt, w.fill, w.inbox, w.tcls + 1 * N, use_classes);
+    hipLaunchKernelGGL(k_merge_group<64>, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 2 * N,
+                       &c->n_touched[2], w.cnt, w.fill, w.inbox, w.tcls + 2 * N, use_classes);
+    hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 3 * N, &c->n_touched[3],
+                       w.cnt, w.fill, w.inbox, w.binoff, w.bins, w.tcls + 3 * N, use_classes);
+    hipLaunchKernelGGL(k_compact_classes, dim3(128, NCLS), dim3(1024), 0, st, c->n_touched, 0u, w.touched, w.tcls,
                        w.lists, N, (c + 1)->n_active);
     return hipGetLastError();
 }
@@ -684,7 +785,7 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
 // vcls[] (class of every vertex holding a "new" entry) -> active lists of round t_next
 static void launch_compact_all(const Workspace &w, long long N, int t_next, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_compact_classes, dim3(256), dim3(1024), 0, st, (const u32 *)nullptr, (u32)N,
+    hipLaunchKernelGGL(k_compact_classes, dim3(256, 1), dim3(1024), 0, st, (const u32 *)nullptr, (u32)N,
                        (const int *)nullptr, w.vcls, w.lists, N, w.ctr[t_next].n_active);
 }
 

@@ -85,6 +85,25 @@ __device__ __forceinline__ void wave_sort(u64 (&k)[E], int lane)
     }
 }
 
+// Ascending bitonic sort inside every group of G consecutive lanes (G = 16, 32 or 64), one key per lane.
+template <int G>
+__device__ __forceinline__ u64 group_sort(u64 k, int lane)
+{
+    const int sub = lane & (G - 1);
+#pragma unroll
+    for (int size = 2; size <= G; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            const bool up = (sub & size) == 0;      // for size == G: always ascending
+            const u64 o = shfl_xor_u64(k, stride);
+            const bool lower = (lane & stride) == 0;
+            const u64 mn = k < o ? k : o, mx = k < o ? o : k;
+            k = (lower == up) ? mn : mx;
+        }
+    }
+    return k;
+}
+
 // k[] sorted ascending.  Drops KEY_PAD and every key equal (ignoring the flag bit) to its
 // predecessor, and writes the first `cap` survivors, in order, to out[0..) (LDS or global).
 // Returns how many were written; *any_new is set if one of them has the flag bit.
