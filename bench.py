@@ -144,7 +144,7 @@ def main():
         "gpu_ms": {"total": s["total_ms"], "init": s["init_ms"], "rounds": sum(s["round_ms"]),
                    "scan": scan_ms, "reverse": sum(s["reverse_ms"])},
         "mean_degree": float(degree.float().mean().item()), "max_degree": int(degree.max().item()),
-        "roofline": {"bound": "hbm", "kernel": "k_update_scan", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "k_update_scan_mfma_u8<NG,4> (NG = 1,2,3 launched back to back per round)" if s["kernel_variant"] == 2 else "k_update_scan", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "launches": rounds, "avg_launch_ms": scan_ms / max(1, rounds),
                      "algorithmic_bytes_per_launch": scan_bytes / max(1, rounds)},
@@ -158,7 +158,7 @@ def main():
             out["recall_at_10"] = None
             out["recall_error"] = repr(e)
     if not args.no_cpu_baseline:
-        n_s = args.cpu_sample or min(cfg.N, 60_000 if cfg.d <= 128 else 8_000)
+        n_s = args.cpu_sample or min(cfg.N, 200_000 if cfg.d <= 128 else 20_000)
         out["cpu_baseline"] = cpu_baseline(cfg, X, n_s)
     print(json.dumps(out))
 

@@ -215,3 +215,23 @@ def test_cfg2_full_parity(rn, oracle_mod, variant):
     graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
     assert_snapshot_equal(want.snap, False, keys, degree, "cfg2")
     assert list(st.algo_evals[:60]) == want.round_evals.tolist()
+
+
+@pytest.mark.slow
+def test_cfg3_full_size_parity(rn, oracle_mod):
+    """BASELINE configuration 3 -- the benchmark's workload (N = 1,000,000, d = 128 uint8, S=20 R=96
+    T1=4 T2=15) in the launch configuration bench.py times: the whole graph, every distance, flag,
+    degree and per-round evaluation count against a full oracle run (about a minute of CPU)."""
+    import time
+    c = wl.CONFIGS["cfg3"]
+    X = wl.make_data(c)
+    print("cfg3 data ready", wl.sha256_of(X)[:16], flush=True)
+    graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    print("gpu build done: %.1f ms" % st.total_ms, flush=True)
+    t0 = time.time()
+    want = oracle_mod.build_sync(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    print("oracle build done: %.1f s" % (time.time() - t0), flush=True)
+    assert_snapshot_equal(want.snap, False, keys, degree, "cfg3")
+    assert (graph.cpu().numpy() == want.snap.ids).all()
+    assert list(st.algo_evals[:60]) == want.round_evals.tolist()
+    assert list(st.proposals[:60]) == want.round_props.tolist()
