@@ -2,11 +2,11 @@
 //
 // One wavefront owns one vertex in every per-vertex kernel.  A round is synchronous:
 //   scan     every active vertex (one holding a "new" entry) runs Alg. 4 lines 2-15 on its own list,
-//            writes its kept entries back in place, leaves its redirected edges in its slot of `props`
-//            and counts them per target (adds whose result nobody waits for)
-//   offsets  vertices that received edges form the `touched` list; those that received more than
-//            INBOX_CAP also get a bin for the surplus
-//   scatter  redirected edges move into their target's inbox (INBOX_CAP slots per vertex) or bin
+//            writes its kept entries back in place and leaves its redirected edges in its slot of `props`
+//   scatter  every redirected edge takes an arrival number at its target (the round's only atomic per
+//            edge) and moves into the target's inbox (INBOX_CAP slots per vertex); later arrivals wait
+//   classify vertices that received edges form the `touched` lists, by the size of the merge they need;
+//            those that received more than INBOX_CAP get a bin, which a second scatter pass fills
 //   merge    every touched list becomes the first R distinct keys of (kept entries + inbox + bin)
 //   compact  touched vertices whose new list holds a "new" entry form the next active lists,
 //            one per degree class (lists of up to 32, 64, 96, 128 entries)
@@ -23,7 +23,9 @@
 #define BLOCK (64 * WAVES_PER_BLOCK)
 #define GOLDEN64 0x9E3779B97F4A7C15ull
 #define NCLS 4
+#ifndef INBOX_CAP
 #define INBOX_CAP 64   // redirected edges a vertex can receive per round without the overflow path
+#endif
 
 // Per-round device counters.  Round t reads ctr[t].n_active[] and fills the rest; its compact step
 // writes ctr[t+1].n_active[].  Zeroed once per call, never reset, so they double as statistics.
@@ -32,7 +34,8 @@ struct RoundCtr {
     u32 n_active[NCLS];   // lengths of this round's active lists
     u32 n_touched[NCLS];  // distinct targets of the redirected edges, by size of the merge they need
     u32 bin_cursor;       // space handed out in the bin array
-    u32 pad[3];
+    u32 has_surplus;      // some vertex received more than INBOX_CAP edges this round
+    u32 pad[2];
     // statistics, spread over STAT_SLOTS addresses so that the adds of many blocks do not queue up
     // on one: [slot][0..3] = algorithmic evals, executed evals, rows gathered, edges redirected
     u64 stat[STAT_SLOTS][4];
@@ -51,18 +54,17 @@ __device__ __forceinline__ void add_round_stats(RoundCtr *ctr, u64 algo, u64 exe
 struct Prop {          // one redirected edge (Alg. 4 line 13): `key` enters `tgt`'s list
     u64 key;
     u32 tgt;
-    u32 pad;
+    u32 arrival;       // set by the scatter: arrival number at tgt, for edges past the inbox
 };
 
-// Line 13: (w, v) enters E.  Recorded in the scanning vertex's own slot; the target is only counted.
-__device__ __forceinline__ void emit_redirect(u64 key, u32 tgt, Prop *slot, int *cnt)
+// Line 13: (w, v) enters E.  Recorded in the scanning vertex's own slot.
+__device__ __forceinline__ void emit_redirect(u64 key, u32 tgt, Prop *slot)
 {
     Prop pr;
     pr.key = key;
     pr.tgt = tgt;
-    pr.pad = 0;
+    pr.arrival = 0;
     *slot = pr;
-    atomicAdd(&cnt[tgt], 1);   // result unused: no wait
 }
 
 #include "dist.h"
@@ -163,7 +165,7 @@ template <int DT>
 __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int vec_ok, int R,
                                                        u64 *keys, int *deg, const int *list,
                                                        const u32 *n_list, Prop *props, int *nprop,
-                                                       int *cnt, RoundCtr *ctr)
+                                                       RoundCtr *ctr)
 {
     __shared__ u64 s_key[WAVES_PER_BLOCK][RNND_MAX_R];
     __shared__ u64 s_pkey[WAVES_PER_BLOCK][RNND_MAX_R];
@@ -247,7 +249,7 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
         }
         wave_sync();
         for (int p = lane; p < np; p += 64)
-            emit_redirect(s_pkey[wave][p], s_ptgt[wave][p], props + (size_t)u * R + p, cnt);
+            emit_redirect(s_pkey[wave][p], s_ptgt[wave][p], props + (size_t)u * R + p);
         nprops_total += np;
     }
     if (lane == 0 && rows) add_round_stats(ctr, evals_algo, evals_exec, rows, nprops_total);
@@ -294,12 +296,58 @@ __global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cn
     }
 }
 
-// Every active vertex moves its redirected edges to their targets: arrival number s = fill[tgt]++;
-// the first INBOX_CAP arrivals go to the target's inbox, later ones to its bin.  16 lanes per vertex.
-__global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int *lists, const RoundCtr *ctr,
-                                                   const Prop *props, const int *nprop, const int *binoff,
-                                                   int *fill, u64 *inbox, u64 *bins)
+// Every active vertex moves its redirected edges to their targets, 16 lanes per vertex.  Lanes of a
+// group that share a target take their arrival numbers with one atomic (a vertex usually redirects
+// several entries to the same kept neighbour).  Arrivals below INBOX_CAP go to the target's inbox;
+// later ones record their number in the edge and are placed by k_scatter_surplus once bins exist.
+__global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int *lists, RoundCtr *ctr,
+                                                   Prop *props, const int *nprop, int *fill, u64 *inbox)
 {
+    const int lane = threadIdx.x & 63, sub = lane & 15, gbase = lane & ~15, c = blockIdx.y;
+    const u32 g = (blockIdx.x * BLOCK + threadIdx.x) >> 4, ng = (gridDim.x * BLOCK) >> 4;
+    const u32 n = ctr->n_active[c];
+    const int *list = lists + (size_t)c * N;
+    bool surplus = false;
+    for (u32 it = g; it < n; it += ng) {
+        const int u = list[it];
+        const int np = nprop[u];
+        for (int p0 = 0; p0 < np; p0 += 16) {      // same trip count for the whole group
+            const int p = p0 + sub;
+            const bool have = p < np;
+            Prop pr;
+            pr.key = 0; pr.tgt = 0xFFFFFFFFu; pr.arrival = 0;
+            if (have) pr = props[(size_t)u * R + p];
+            // lanes of my group with my target
+            u32 same = 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const u32 t = (u32)__shfl((int)pr.tgt, gbase + j);
+                same |= (t == pr.tgt ? 1u : 0u) << j;
+            }
+            const int leader = __builtin_ctz(same), rank = __popc(same & ((1u << sub) - 1u));
+            int base = 0;
+            if (have && sub == leader) base = atomicAdd(&fill[pr.tgt], __popc(same));
+            base = __shfl(base, gbase + leader);
+            if (have) {
+                const int s = base + rank;
+                if (s < INBOX_CAP) {
+                    inbox[(size_t)pr.tgt * INBOX_CAP + s] = pr.key;
+                } else {
+                    props[(size_t)u * R + p].arrival = (u32)s;
+                    surplus = true;
+                }
+            }
+        }
+    }
+    if (surplus) ctr->has_surplus = 1u;
+}
+
+// Second pass, only when some vertex received more than INBOX_CAP edges: the late arrivals go to bins.
+__global__ __launch_bounds__(BLOCK) void k_scatter_surplus(long long N, int R, const int *lists,
+                                                           const RoundCtr *ctr, const Prop *props,
+                                                           const int *nprop, const int *binoff, u64 *bins)
+{
+    if (ctr->has_surplus == 0) return;
     const int sub = threadIdx.x & 15, c = blockIdx.y;
     const u32 g = (blockIdx.x * BLOCK + threadIdx.x) >> 4, ng = (gridDim.x * BLOCK) >> 4;
     const u32 n = ctr->n_active[c];
@@ -309,9 +357,8 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int
         const int np = nprop[u];
         for (int p = sub; p < np; p += 16) {
             const Prop pr = props[(size_t)u * R + p];
-            const int s = atomicAdd(&fill[pr.tgt], 1);
-            if (s < INBOX_CAP) inbox[(size_t)pr.tgt * INBOX_CAP + s] = pr.key;
-            else bins[(size_t)binoff[pr.tgt] + (s - INBOX_CAP)] = pr.key;
+            if (pr.arrival >= (u32)INBOX_CAP)
+                bins[(size_t)binoff[pr.tgt] + (pr.arrival - INBOX_CAP)] = pr.key;
         }
     }
 }
@@ -323,8 +370,8 @@ __device__ __forceinline__ int merge_class(int nb, int c)
     return total <= 16 ? 0 : total <= 32 ? 1 : total <= 64 ? 2 : 3;
 }
 
-// Every vertex x with cnt[x] > 0 is appended to the touched list of its merge class; if it received
-// more than INBOX_CAP edges it also gets a bin for the surplus.  Five atomics per 1024 vertices.
+// Every vertex x that received edges (cnt[x] > 0) is appended to the touched list of its merge class;
+// if it received more than INBOX_CAP it also gets a bin for the surplus.  Five atomics per 1024 vertices.
 __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int *cnt, const int *deg,
                                                          int *binoff, RoundCtr *ctr, int *tlists)
 {
@@ -377,8 +424,9 @@ __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int 
 // group of G lanes.  list <- first R distinct keys; tcls[it] <- degree class if a "new" entry survives, else -1.
 template <int G>
 __global__ __launch_bounds__(BLOCK) void k_merge_group(int R, u64 *keys, int *deg, const int *tlist,
-                                                       const u32 *n_ptr, int *cnt, int *fill,
-                                                       const u64 *inbox, int8_t *tcls, int use_classes)
+                                                       const u32 *n_ptr, int *cnt,
+                                                       const u64 *inbox, const int *binoff, const u64 *bins,
+                                                       int8_t *tcls, int use_classes)
 {
     const int lane = threadIdx.x & 63, sub = lane & (G - 1), shift = lane & ~(G - 1);
     const u64 gmask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull);
@@ -389,8 +437,12 @@ __global__ __launch_bounds__(BLOCK) void k_merge_group(int R, u64 *keys, int *de
         const int nb = deg[x], c = cnt[x];
         u64 *row = keys + (size_t)x * R;
         u64 k = KEY_PAD;
-        if (sub < nb) k = row[sub];
-        else if (sub < nb + c) k = inbox[(size_t)x * INBOX_CAP + (sub - nb)];
+        if (sub < nb) {
+            k = row[sub];
+        } else if (sub < nb + c) {
+            const int e = sub - nb;
+            k = e < INBOX_CAP ? inbox[(size_t)x * INBOX_CAP + e] : bins[(size_t)binoff[x] + (e - INBOX_CAP)];
+        }
         k = group_sort<G>(k, lane);
         u64 prev = shfl_up1_u64(k);
         if (sub == 0) prev = KEY_PAD;
@@ -405,7 +457,6 @@ __global__ __launch_bounds__(BLOCK) void k_merge_group(int R, u64 *keys, int *de
             if (nd > R) nd = R;
             deg[x] = nd;
             cnt[x] = 0;
-            fill[x] = 0;
             tcls[it] = nm ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
         }
     }
@@ -413,7 +464,7 @@ __global__ __launch_bounds__(BLOCK) void k_merge_group(int R, u64 *keys, int *de
 
 // General merge (any size): one touched vertex per wavefront; kept entries + inbox + surplus bin.
 __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, const int *tlist,
-                                                 const u32 *n_ptr, int *cnt, int *fill, const u64 *inbox,
+                                                 const u32 *n_ptr, int *cnt, const u64 *inbox,
                                                  const int *binoff, const u64 *bins, int8_t *tcls,
                                                  int use_classes)
 {
@@ -430,7 +481,6 @@ __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, con
         if (lane == 0) {
             deg[x] = nd;
             cnt[x] = 0;
-            fill[x] = 0;
             tcls[it] = any_new ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
         }
     }
@@ -732,7 +782,7 @@ static void launch_mfma_scan(const Workspace &w, const void *X, int R, u64 *keys
     if (per_cu < 1) per_cu = 1;
     hipLaunchKernelGGL((k_update_scan_mfma_u8<NG, KS>), dim3(cu_count() * per_cu), dim3(256), 0, st,
                        (const uint8_t *)X, R, keys, deg, w.lists + (size_t)(NG - 1) * N, &c->n_active[NG - 1],
-                       w.props, w.nprop, w.cnt, c);
+                       w.props, w.nprop, c);
 }
 
 template <int KS>
@@ -759,24 +809,28 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
         else launch_mfma_scan_classes<4>(w, X, R, keys, deg, N, c, st);
     } else if (dtype == RNND_U8) {
         hipLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
-                           w.lists, &c->n_active[0], w.props, w.nprop, w.cnt, c);
+                           w.lists, &c->n_active[0], w.props, w.nprop, c);
     } else {
         hipLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
-                           w.lists, &c->n_active[0], w.props, w.nprop, w.cnt, c);
+                           w.lists, &c->n_active[0], w.props, w.nprop, c);
     }
     if (after_scan) (void)hipEventRecord(after_scan, st);
-    hipLaunchKernelGGL(k_touch_classify, dim3((unsigned)((N + 1023) / 1024)), dim3(1024), 0, st, N, w.cnt, deg,
+    // from here on `fill` plays the role of the per-target count of this round
+    const int ncl = use_classes ? NCLS : 1;
+    hipLaunchKernelGGL(k_scatter, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop, w.fill,
+                       w.inbox);
+    hipLaunchKernelGGL(k_touch_classify, dim3((unsigned)((N + 1023) / 1024)), dim3(1024), 0, st, N, w.fill, deg,
                        w.binoff, c, w.touched);
-    hipLaunchKernelGGL(k_scatter, dim3(pb, use_classes ? NCLS : 1), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props,
-                       w.nprop, w.binoff, w.fill, w.inbox, w.bins);
+    hipLaunchKernelGGL(k_scatter_surplus, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop,
+                       w.binoff, w.bins);
     hipLaunchKernelGGL(k_merge_group<16>, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 0 * N,
-                       &c->n_touched[0], w.cnt, w.fill, w.inbox, w.tcls + 0 * N, use_classes);
+                       &c->n_touched[0], w.fill, w.inbox, w.binoff, w.bins, w.tcls + 0 * N, use_classes);
     hipLaunchKernelGGL(k_merge_group<32>, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 1 * N,
-                       &c->n_touched[1], w.cnt, w.fill, w.inbox, w.tcls + 1 * N, use_classes);
+                       &c->n_touched[1], w.fill, w.inbox, w.binoff, w.bins, w.tcls + 1 * N, use_classes);
     hipLaunchKernelGGL(k_merge_group<64>, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 2 * N,
-                       &c->n_touched[2], w.cnt, w.fill, w.inbox, w.tcls + 2 * N, use_classes);
+                       &c->n_touched[2], w.fill, w.inbox, w.binoff, w.bins, w.tcls + 2 * N, use_classes);
     hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 3 * N, &c->n_touched[3],
-                       w.cnt, w.fill, w.inbox, w.binoff, w.bins, w.tcls + 3 * N, use_classes);
+                       w.fill, w.inbox, w.binoff, w.bins, w.tcls + 3 * N, use_classes);
     hipLaunchKernelGGL(k_compact_classes, dim3(128, NCLS), dim3(1024), 0, st, c->n_touched, 0u, w.touched, w.tcls,
                        w.lists, N, (c + 1)->n_active);
     return hipGetLastError();

@@ -111,7 +111,7 @@ template <int NG, int KS>
 __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_u8(
     const uint8_t *__restrict__ X, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
-    int *__restrict__ nprop, int *__restrict__ cnt, RoundCtr *__restrict__ ctr)
+    int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
 {
     __shared__ MfmaScanSmem<NG> smem[4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_u8(
                         const u32 dvw = (u32)(nrm[I] + sm.nrm[tgt] - 2 * g);
                         // line 13: v enters w's list
                         emit_redirect(make_key(dvw, key_id(kb), 1u), (u32)sm.id[tgt],
-                                      props + (size_t)u * R + np_base + __popcll(pm & lanes_below(lane)), cnt);
+                                      props + (size_t)u * R + np_base + __popcll(pm & lanes_below(lane)));
                     }
                     np_base += __popcll(pm);
                     wave_sync();   // before the next block overwrites t and G^T
