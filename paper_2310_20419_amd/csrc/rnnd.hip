@@ -101,14 +101,16 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
     const u64 hu = mix64(seed + GOLDEN64 * (u64)(u + 1));
     const u64 jmax = 64ull * (u64)S + 1024ull;
     int cnt = 0;
-    for (u64 j0 = 0; j0 < jmax && cnt < S; j0 += 64) {
+    for (u64 j0 = 0; j0 < jmax && cnt < S;) {
+        // examine the next W draws (a few more than still needed; any W gives the same result)
+        const int W = (S - cnt) + 12 < 64 ? (S - cnt) + 12 : 64;
         u64 j = j0 + lane;
         u64 z = mix64(hu + GOLDEN64 * (j + 1));
         u64 c = ((z >> 32) * (u64)(N - 1)) >> 32;
         int id = (int)(c + (c >= (u64)u ? 1 : 0));
-        bool ok = j < jmax;
+        bool ok = lane < W && j < jmax;
         for (int k = 0; k < cnt; ++k) ok = ok && (ids[k] != id);
-        for (int l = 0; l < 63; ++l) {
+        for (int l = 0; l < W - 1; ++l) {
             int o = __shfl(id, l);
             if (l < lane && o == id) ok = false;
         }
@@ -117,6 +119,7 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
         if (ok && pos < S) ids[pos] = id;
         cnt += __popcll(m);
         if (cnt > S) cnt = S;
+        j0 += W;
         wave_sync();
     }
     if (cnt < S) {   // fallback, practically unreachable: smallest unused ids
@@ -140,16 +143,23 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
         if (p < S && sub == 0) s_dist[wave][p] = db;
     }
     wave_sync();
-    u64 k[2];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        int e = r * 64 + lane;
-        k[r] = e < S ? make_key(s_dist[wave][e], (u32)ids[e], 1u) : KEY_PAD;
-    }
-    wave_sort<2>(k, lane);
     u64 *row = keys + (size_t)u * R;
-    if (lane < S) row[lane] = k[0];
-    if (lane + 64 < S) row[lane + 64] = k[1];
+    if (S <= 64) {
+        u64 k[1];
+        k[0] = lane < S ? make_key(s_dist[wave][lane], (u32)ids[lane], 1u) : KEY_PAD;
+        wave_sort<1>(k, lane);
+        if (lane < S) row[lane] = k[0];
+    } else {
+        u64 k[2];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            int e = r * 64 + lane;
+            k[r] = e < S ? make_key(s_dist[wave][e], (u32)ids[e], 1u) : KEY_PAD;
+        }
+        wave_sort<2>(k, lane);
+        if (lane < S) row[lane] = k[0];
+        if (lane + 64 < S) row[lane + 64] = k[1];
+    }
     if (lane == 0) {
         deg[u] = S;
         if (vcls) vcls[u] = (int8_t)degree_class(S, use_classes);   // every vertex starts with "new" entries
@@ -423,10 +433,10 @@ __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int 
 // Merge of the touched vertices whose kept entries + received edges number at most G: one vertex per
 // group of G lanes.  list <- first R distinct keys; tcls[it] <- degree class if a "new" entry survives, else -1.
 template <int G>
-__global__ __launch_bounds__(BLOCK) void k_merge_group(int R, u64 *keys, int *deg, const int *tlist,
-                                                       const u32 *n_ptr, int *cnt,
-                                                       const u64 *inbox, const int *binoff, const u64 *bins,
-                                                       int8_t *tcls, int use_classes)
+__device__ __forceinline__ void merge_group_body(int R, u64 *keys, int *deg, const int *tlist,
+                                                 const u32 *n_ptr, int *cnt,
+                                                 const u64 *inbox, const int *binoff, const u64 *bins,
+                                                 int8_t *tcls, int use_classes)
 {
     const int lane = threadIdx.x & 63, sub = lane & (G - 1), shift = lane & ~(G - 1);
     const u64 gmask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull);
@@ -463,12 +473,11 @@ __global__ __launch_bounds__(BLOCK) void k_merge_group(int R, u64 *keys, int *de
 }
 
 // General merge (any size): one touched vertex per wavefront; kept entries + inbox + surplus bin.
-__global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, const int *tlist,
-                                                 const u32 *n_ptr, int *cnt, const u64 *inbox,
-                                                 const int *binoff, const u64 *bins, int8_t *tcls,
-                                                 int use_classes)
+__device__ __forceinline__ void merge_general_body(int R, u64 *keys, int *deg, const int *tlist,
+                                                   const u32 *n_ptr, int *cnt, const u64 *inbox,
+                                                   const int *binoff, const u64 *bins, int8_t *tcls,
+                                                   int use_classes, u64 (*s_stage)[RNND_MAX_R])
 {
-    __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
     const u32 n = *n_ptr;
@@ -484,6 +493,22 @@ __global__ __launch_bounds__(BLOCK) void k_merge(int R, u64 *keys, int *deg, con
             tcls[it] = any_new ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
         }
     }
+}
+
+// All four merge classes in one launch: blockIdx.y = merge class (touched list y, tcls + y*N).
+__global__ __launch_bounds__(BLOCK) void k_merge(long long N, int R, u64 *keys, int *deg, const int *tlists,
+                                                 const u32 *n_touched, int *cnt, const u64 *inbox,
+                                                 const int *binoff, const u64 *bins, int8_t *tcls,
+                                                 int use_classes)
+{
+    __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
+    const int y = blockIdx.y;
+    const int *tlist = tlists + (size_t)y * N;
+    int8_t *tc = tcls + (size_t)y * N;
+    if (y == 0) merge_group_body<16>(R, keys, deg, tlist, n_touched + 0, cnt, inbox, binoff, bins, tc, use_classes);
+    else if (y == 1) merge_group_body<32>(R, keys, deg, tlist, n_touched + 1, cnt, inbox, binoff, bins, tc, use_classes);
+    else if (y == 2) merge_group_body<64>(R, keys, deg, tlist, n_touched + 2, cnt, inbox, binoff, bins, tc, use_classes);
+    else merge_general_body(R, keys, deg, tlist, n_touched + 3, cnt, inbox, binoff, bins, tc, use_classes, s_stage);
 }
 
 // Items i < n with cls[i] >= 0 are appended to list cls[i]; item i stands for vertex idx[i] (or i).
@@ -823,14 +848,8 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
                        w.binoff, c, w.touched);
     hipLaunchKernelGGL(k_scatter_surplus, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop,
                        w.binoff, w.bins);
-    hipLaunchKernelGGL(k_merge_group<16>, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 0 * N,
-                       &c->n_touched[0], w.fill, w.inbox, w.binoff, w.bins, w.tcls + 0 * N, use_classes);
-    hipLaunchKernelGGL(k_merge_group<32>, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 1 * N,
-                       &c->n_touched[1], w.fill, w.inbox, w.binoff, w.bins, w.tcls + 1 * N, use_classes);
-    hipLaunchKernelGGL(k_merge_group<64>, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 2 * N,
-                       &c->n_touched[2], w.fill, w.inbox, w.binoff, w.bins, w.tcls + 2 * N, use_classes);
-    hipLaunchKernelGGL(k_merge, dim3(pb), dim3(BLOCK), 0, st, R, keys, deg, w.touched + 3 * N, &c->n_touched[3],
-                       w.fill, w.inbox, w.binoff, w.bins, w.tcls + 3 * N, use_classes);
+    hipLaunchKernelGGL(k_merge, dim3(pb, NCLS), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
+                       w.fill, w.inbox, w.binoff, w.bins, w.tcls, use_classes);
     hipLaunchKernelGGL(k_compact_classes, dim3(128, NCLS), dim3(1024), 0, st, c->n_touched, 0u, w.touched, w.tcls,
                        w.lists, N, (c + 1)->n_active);
     return hipGetLastError();

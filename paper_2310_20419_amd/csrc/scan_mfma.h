@@ -118,7 +118,7 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_u8(
     const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
     const u32 n_active = *n_list;
     MfmaScanSmem<NG> &sm = smem[wave];
-    u64 evals_exec = 0, rows = 0, nprops_total = 0;
+    u64 tiles = 0, rows = 0, nprops_total = 0;   // tiles: 32x32 blocks of pair distances computed
     u32 ev_lane = 0;   // per-lane share of the algorithmic evaluation count, summed at the end
 
     if (gw >= n_active) return;
@@ -156,8 +156,6 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_u8(
             if (lane < 32 * NG) sm.id[lane] = (int)key_id(kreg[0]);
             if (NG > 2 && lane + 64 < 32 * NG) sm.id[64 + lane] = (int)key_id(kreg[1]);
             rows += m;
-            const int ng_used = (m + 31) >> 5;
-            evals_exec += (u64)(ng_used * (ng_used + 1) / 2) * 1024ull;
 
             // ---- rows as int8 (x - 128) and their squared norms
             int nrm[NG];
@@ -203,6 +201,11 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_u8(
                     for (int J = 0; J < NG; ++J) F[J] = 0;
 #pragma unroll
                     for (int J = 0; J <= I; ++J) {
+                        // a tile without a new row and without a new column holds only old/old pairs (lines 8-9)
+                        const u32 new_I = (u32)(newm[I >> 1] >> (32 * (I & 1)));
+                        const u32 new_J = (u32)(newm[J >> 1] >> (32 * (J & 1)));
+                        if ((new_I | new_J) == 0) continue;
+                        tiles += 1;
                         v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
                         for (int s = 0; s < KS; ++s)
@@ -305,5 +308,5 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_u8(
     u64 evals_algo = ev_lane;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) evals_algo += shfl_xor_u64(evals_algo, o);
-    if (lane == 0 && rows) add_round_stats(ctr, evals_algo, evals_exec, rows, nprops_total);
+    if (lane == 0 && rows) add_round_stats(ctr, evals_algo, tiles * 1024ull, rows, nprops_total);
 }
