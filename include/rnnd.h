@@ -61,7 +61,7 @@ typedef enum {
 typedef struct {
     int32_t rounds;                         /* UpdateNeighbors rounds run (T1*T2) */
     int32_t reverse_calls;                  /* AddReverseEdges calls run (T1-1) */
-    int32_t kernel_variant;                 /* UpdateNeighbors scan kernel used: 1 generic, 2 MFMA */
+    int32_t kernel_variant;                 /* UpdateNeighbors scan kernel used: 1 generic, 2 int8 MFMA, 3 f64 MFMA */
     int32_t reserved;
     float total_ms, init_ms;                /* GPU time of the whole call / of RandomGraph */
     float round_ms[RNND_MAX_ROUNDS];        /* GPU time of each UpdateNeighbors round */
@@ -121,9 +121,10 @@ int rnnd_export_graph(int64_t N, int32_t R, const uint64_t *keys, const int32_t 
                       int32_t *graph_out, int32_t *degree_out, void *stream);
 
 /* Selects the UpdateNeighbors scan kernel: 0 = automatic (default), 1 = generic pair-at-a-time
- * kernel, 2 = dense Gram-block kernel on the matrix cores (uint8 data with d = 32, 64 or 128;
- * other inputs use 1; automatic picks 2 where it applies).  Both give identical graphs; this
- * exists for testing and profiling.  Process-wide, not thread-safe. */
+ * kernel for every input.  Automatic uses the dense Gram-block kernels on the matrix cores where
+ * they apply (uint8 with d = 32, 64 or 128: int8 MFMA; float32 with d a multiple of 16: f64 MFMA)
+ * and the generic kernel otherwise.  All give identical graphs; this exists for testing and
+ * profiling.  Process-wide, not thread-safe. */
 int rnnd_set_kernel_variant(int variant);
 
 const char *rnnd_strerror(int status);

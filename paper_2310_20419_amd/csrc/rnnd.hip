@@ -69,6 +69,7 @@ __device__ __forceinline__ void emit_redirect(u64 key, u32 tgt, Prop *slot)
 
 #include "dist.h"
 #include "scan_mfma.h"
+#include "scan_mfma_f32.h"
 
 __device__ __forceinline__ int degree_class(int m, int use_classes)
 {
@@ -772,12 +773,15 @@ static int vec_ok_for(const void *X, int d, int dtype)
     return (rowbytes % 16 == 0) && (((uintptr_t)X) % 16 == 0);
 }
 
-// How UpdateNeighbors scans for this input: 2 = MFMA Gram kernel, 1 = generic kernel.
+// How UpdateNeighbors scans for this input: 1 = generic kernel, 2 = int8 MFMA Gram kernel (uint8 rows),
+// 3 = double-precision MFMA Gram kernel (float rows).
 static int scan_variant_for(const void *X, int d, int dtype)
 {
-    const bool mfma_ok = dtype == RNND_U8 && (d == 32 || d == 64 || d == 128) && (((uintptr_t)X) % 16 == 0);
-    if (g_kernel_variant == 1 || !mfma_ok) return 1;
-    return 2;
+    const bool aligned = (((uintptr_t)X) % 16 == 0);
+    if (g_kernel_variant == 1 || !aligned) return 1;
+    if (dtype == RNND_U8 && (d == 32 || d == 64 || d == 128)) return 2;
+    if (dtype == RNND_F32 && d % 16 == 0) return 3;
+    return 1;
 }
 
 static int cu_count()
@@ -820,6 +824,16 @@ static void launch_mfma_scan_classes(const Workspace &w, const void *X, int R, u
     if (R > 96) launch_mfma_scan<4, KS>(w, X, R, keys, deg, N, c, st);
 }
 
+template <int NG>
+static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, long long N,
+                            RoundCtr *c, hipStream_t st)
+{
+    // NG = 1: ~6 wavefronts per SIMD fit; NG = 3 holds 21 accumulator tiles and runs one per SIMD
+    const int per_cu = NG == 1 ? 6 : NG == 2 ? 2 : 1;
+    hipLaunchKernelGGL((k_update_scan_mfma_f32<NG>), dim3(cu_count() * per_cu), dim3(256), 0, st, (const float *)X, d,
+                       R, keys, deg, w.lists + (size_t)(NG - 1) * N, &c->n_active[NG - 1], w.props, w.nprop, c);
+}
+
 // One synchronous UpdateNeighbors round t (ctr[t] -> ctr[t+1]).
 static hipError_t launch_update_round(const Workspace &w, const void *X, long long N, int d, int dtype,
                                       int vec_ok, int variant, int R, u64 *keys, int *deg, int t,
@@ -827,11 +841,18 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
 {
     const int pb = persistent_blocks();
     RoundCtr *c = w.ctr + t;
-    const int use_classes = variant == 2;
+    const int use_classes = variant >= 2;
     if (variant == 2) {
         if (d == 32) launch_mfma_scan_classes<1>(w, X, R, keys, deg, N, c, st);
         else if (d == 64) launch_mfma_scan_classes<2>(w, X, R, keys, deg, N, c, st);
         else launch_mfma_scan_classes<4>(w, X, R, keys, deg, N, c, st);
+    } else if (variant == 3) {
+        launch_f32_scan<1>(w, X, d, R, keys, deg, N, c, st);
+        if (R > 32) launch_f32_scan<2>(w, X, d, R, keys, deg, N, c, st);
+        if (R > 64) launch_f32_scan<3>(w, X, d, R, keys, deg, N, c, st);
+        if (R > 96)   // lists of 97..128 entries: too many accumulator tiles, generic kernel
+            hipLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
+                               w.lists + (size_t)3 * N, &c->n_active[3], w.props, w.nprop, c);
     } else if (dtype == RNND_U8) {
         hipLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
                            w.lists, &c->n_active[0], w.props, w.nprop, c);
@@ -925,7 +946,7 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
     if ((int64_t)T1 * T2 > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int rounds = T1 * T2, n_ctr = rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2;
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant >= 2;
     // events: start, after init, (after scan, after round) per round, after each reverse, end
     const int n_ev = 2 * rounds + T1 + 3;
     Workspace w;
@@ -1044,7 +1065,7 @@ extern "C" int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dt
     if (n_rounds < 1 || n_rounds > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int n_ctr = n_rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2;
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant >= 2;
     Workspace w;
     RoundCtr *hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
     if (!hctr) return RNND_ERR_OOM;

@@ -24,14 +24,19 @@ def rn():
 
 @pytest.fixture(params=[0, 1], ids=["auto", "generic"])
 def variant(request, rn):
-    """0 = automatic choice (the MFMA Gram kernel for uint8 d in {32, 64, 128}), 1 = generic kernel."""
+    """0 = automatic choice (matrix-core Gram kernels where they apply), 1 = generic kernel."""
     rn.rnnd_set_kernel_variant(request.param)
     yield request.param
     rn.rnnd_set_kernel_variant(0)
 
 
 def mfma_applies(X):
-    return X.dtype == np.uint8 and X.shape[1] in (32, 64, 128)
+    """Which matrix-core scan kernel the automatic choice takes for X (0: none, generic kernel)."""
+    if X.dtype == np.uint8 and X.shape[1] in (32, 64, 128):
+        return 2
+    if X.dtype == np.float32 and X.shape[1] % 16 == 0:
+        return 3
+    return 0
 
 
 def cuda(X):
@@ -57,6 +62,7 @@ DATASETS = {
     "u8_d33_ties": lambda: clustered_u8(1500, 33, 3),          # odd d: element-wise path; many ties
     "u8_dups": lambda: np.repeat(clustered_u8(300, 16, 4), 4, axis=0),   # exact duplicates, delta = 0
     "f32_d96": lambda: wl.custom("unit_f32", 3000, 96, 9),
+    "f32_d32_dense": lambda: (clustered_u8(900, 32, 13, k=3, spread=9).astype(np.float32) / 7.0),   # long lists, ties
     "f32_d960": lambda: wl.custom("beta_f32", 1200, 960, 11),
     "f32_d7": lambda: gauss_f32(1000, 7, 5),
 }
@@ -74,7 +80,8 @@ def test_random_graph(rn, oracle_mod, name, S, R):
 
 @pytest.mark.parametrize("name,S,R", [("cfg1", 10, 32), ("u8_d128", 20, 96), ("u8_d33_ties", 6, 16),
                                       ("u8_dups", 8, 12), ("f32_d96", 20, 96), ("f32_d960", 8, 24),
-                                      ("f32_d7", 100, 128), ("u8_d64_dense", 100, 128), ("u8_d128", 70, 70)])
+                                      ("f32_d7", 100, 128), ("u8_d64_dense", 100, 128), ("u8_d128", 70, 70),
+                                      ("f32_d32_dense", 90, 96), ("f32_d32_dense", 100, 128)])
 def test_rounds_from_shared_snapshots(rn, oracle_mod, variant, name, S, R):
     """Every step starts from the oracle's snapshot, so one divergence cannot hide the next."""
     X = DATASETS[name]()
@@ -88,7 +95,7 @@ def test_rounds_from_shared_snapshots(rn, oracle_mod, variant, name, S, R):
         if step == "u":
             snap, evals, props = oracle_mod.update_neighbors_sync(X, snap, R)
             st = rn.rnnd_update_neighbors(Xd, keys, deg, R, 1)
-            assert st.kernel_variant == (2 if variant == 0 and mfma_applies(X) else 1)
+            assert st.kernel_variant == (mfma_applies(X) if variant == 0 and mfma_applies(X) else 1)
             assert st.algo_evals[0] == evals and st.proposals[0] == props
         else:
             snap = oracle_mod.add_reverse_edges(snap, R)
@@ -99,7 +106,8 @@ def test_rounds_from_shared_snapshots(rn, oracle_mod, variant, name, S, R):
 @pytest.mark.parametrize("name,S,R,T1,T2", [
     ("cfg1", 10, 32, 2, 4), ("u8_d128", 20, 96, 3, 5), ("u8_d33_ties", 6, 16, 3, 4),
     ("u8_dups", 8, 12, 3, 4), ("u8_d64_dense", 40, 128, 3, 4), ("u8_d128", 60, 64, 2, 3),
-    ("f32_d96", 20, 96, 3, 5), ("f32_d960", 8, 24, 2, 4), ("f32_d7", 16, 128, 2, 6)])
+    ("f32_d96", 20, 96, 3, 5), ("f32_d960", 8, 24, 2, 4), ("f32_d7", 16, 128, 2, 6),
+    ("f32_d32_dense", 40, 96, 3, 4), ("f32_d32_dense", 40, 128, 2, 3)])
 def test_full_build(rn, oracle_mod, variant, name, S, R, T1, T2):
     X = DATASETS[name]()
     if variant == 1 and not mfma_applies(X):
@@ -116,7 +124,7 @@ def test_full_build(rn, oracle_mod, variant, name, S, R, T1, T2):
     assert (g2 == graph).all() and (d2 == degree).all()
 
 
-def test_float_tolerance_bar(rn, oracle_mod):
+def test_float_tolerance_bar(rn, oracle_mod, variant):
     """The stated float bar, independent of bit-exactness: delta within 1e-5 relative of a float64
     numpy evaluation, >= 99 % of edges equal to the oracle's."""
     X = DATASETS["f32_d96"]()
