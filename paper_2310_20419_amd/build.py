@@ -13,6 +13,7 @@ SOURCES = [os.path.join(CSRC, "rnnd.hip")]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU ops
+    "-mllvm", "-amdgpu-mfma-vgpr-form",     # MFMA accumulators stay in VGPRs: no AGPR round trips in loops
     "-ffp-contract=off", "-Wall", "-Wno-unused-command-line-argument",
 ]
 

@@ -54,8 +54,24 @@ __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void 
         double acc = 0.0;
         if (vec_ok) {
             const int nchunk = d >> 2;
-            for (int c = sub; c < nchunk; c += 8) {
-                float4 va = ((const float4 *)a)[c], vb = ((const float4 *)b)[c];
+            const float4 *pa4 = (const float4 *)a, *pb4 = (const float4 *)b;
+            int c = sub;
+            // four chunks per trip, all eight loads issued before the (ordered) accumulation
+            for (; c + 24 < nchunk; c += 32) {
+                float4 va[4], vb[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) { va[k] = pa4[c + 8 * k]; vb[k] = pb4[c + 8 * k]; }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    double t;
+                    t = (double)va[k].x - (double)vb[k].x; acc = fma(t, t, acc);
+                    t = (double)va[k].y - (double)vb[k].y; acc = fma(t, t, acc);
+                    t = (double)va[k].z - (double)vb[k].z; acc = fma(t, t, acc);
+                    t = (double)va[k].w - (double)vb[k].w; acc = fma(t, t, acc);
+                }
+            }
+            for (; c < nchunk; c += 8) {
+                float4 va = pa4[c], vb = pb4[c];
                 double t;
                 t = (double)va.x - (double)vb.x; acc = fma(t, t, acc);
                 t = (double)va.y - (double)vb.y; acc = fma(t, t, acc);

@@ -824,14 +824,14 @@ static void launch_mfma_scan_classes(const Workspace &w, const void *X, int R, u
     if (R > 96) launch_mfma_scan<4, KS>(w, X, R, keys, deg, N, c, st);
 }
 
-template <int NG>
+template <int NG, int CH>
 static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, long long N,
                             RoundCtr *c, hipStream_t st)
 {
-    // NG = 1: ~6 wavefronts per SIMD fit; NG = 3 holds 21 accumulator tiles and runs one per SIMD
-    const int per_cu = NG == 1 ? 6 : NG == 2 ? 2 : 1;
-    hipLaunchKernelGGL((k_update_scan_mfma_f32<NG>), dim3(cu_count() * per_cu), dim3(256), 0, st, (const float *)X, d,
-                       R, keys, deg, w.lists + (size_t)(NG - 1) * N, &c->n_active[NG - 1], w.props, w.nprop, c);
+    // wavefronts that fit per SIMD: about 4 for NG = 1, 2 for NG = 2, 1 for NG = 3 (21 accumulator tiles)
+    const int per_cu = NG == 1 ? 4 : NG == 2 ? 2 : 1;
+    hipLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH>), dim3(cu_count() * per_cu), dim3(256), 0, st, (const float *)X,
+                       d, R, keys, deg, w.lists + (size_t)(NG - 1) * N, &c->n_active[NG - 1], w.props, w.nprop, c);
 }
 
 // One synchronous UpdateNeighbors round t (ctr[t] -> ctr[t+1]).
@@ -847,9 +847,10 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
         else if (d == 64) launch_mfma_scan_classes<2>(w, X, R, keys, deg, N, c, st);
         else launch_mfma_scan_classes<4>(w, X, R, keys, deg, N, c, st);
     } else if (variant == 3) {
-        launch_f32_scan<1>(w, X, d, R, keys, deg, N, c, st);
-        if (R > 32) launch_f32_scan<2>(w, X, d, R, keys, deg, N, c, st);
-        if (R > 64) launch_f32_scan<3>(w, X, d, R, keys, deg, N, c, st);
+        if (d % 32 == 0) launch_f32_scan<1, 2>(w, X, d, R, keys, deg, N, c, st);
+        else launch_f32_scan<1, 1>(w, X, d, R, keys, deg, N, c, st);
+        if (R > 32) launch_f32_scan<2, 1>(w, X, d, R, keys, deg, N, c, st);
+        if (R > 64) launch_f32_scan<3, 1>(w, X, d, R, keys, deg, N, c, st);
         if (R > 96)   // lists of 97..128 entries: too many accumulator tiles, generic kernel
             hipLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
                                w.lists + (size_t)3 * N, &c->n_active[3], w.props, w.nprop, c);

@@ -49,7 +49,58 @@ __device__ __forceinline__ u32 transpose16_bits(u32 w, int lane)
     return w & 0xFFFFu;
 }
 
-template <int NG>
+// The Gram block of all NR 16-row groups over all d dimensions.  Per iteration: wait for the chunk,
+// widen it to double, immediately issue the loads of the next chunk into the same registers, then run
+// the matrix instructions on the doubles -- the next chunk travels while the matrix cores work.  The
+// body is straight-line: loads are unconditional (lanes without a row read row 0 of X; what they
+// produce is masked later) and the last iteration re-reads the last chunk.
+template <int NR, int CH>
+__device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int nchunk, v4d (&acc)[NR * (NR + 1) / 2],
+                                              double (&nr)[NR])
+{
+    float4 x[NR][CH];
+#pragma unroll
+    for (int g = 0; g < NR; ++g)
+#pragma unroll
+        for (int j = 0; j < CH; ++j) x[g][j] = *(const float4 *)(rp[g] + 16 * j);
+#pragma unroll 1
+    for (int c = 0; c < nchunk; ++c) {
+        double a[NR][CH][4];
+#pragma unroll
+        for (int g = 0; g < NR; ++g)
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                a[g][j][0] = (double)x[g][j].x;
+                a[g][j][1] = (double)x[g][j].y;
+                a[g][j][2] = (double)x[g][j].z;
+                a[g][j][3] = (double)x[g][j].w;
+            }
+        const int cn = c + 1 < nchunk ? c + 1 : c;
+        __builtin_amdgcn_sched_barrier(0);   // keep the three phases in this order
+#pragma unroll
+        for (int g = 0; g < NR; ++g)
+#pragma unroll
+            for (int j = 0; j < CH; ++j) x[g][j] = *(const float4 *)(rp[g] + 16 * (CH * cn + j));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+#pragma unroll
+                for (int g = 0; g < NR; ++g) nr[g] = fma(a[g][j][t], a[g][j][t], nr[g]);
+#pragma unroll
+                for (int I = 0; I < NR; ++I)
+#pragma unroll
+                    for (int J = 0; J <= I; ++J)
+                        acc[I * (I + 1) / 2 + J] = __builtin_amdgcn_mfma_f64_16x16x4f64(
+                            a[I][j][t], a[J][j][t], acc[I * (I + 1) / 2 + J], 0, 0, 0);
+            }
+    }
+}
+
+// CH = 16-dimension chunks fetched per loop iteration (d must be a multiple of 16*CH): a longer iteration
+// gives the prefetch of the next one more matrix work to hide behind.
+template <int NG, int CH>
 __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_f32(
     const float *__restrict__ X, int d, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
@@ -63,7 +114,7 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_f32(
     const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
     const u32 n_active = *n_list;
     F32ScanSmem<NG> &sm = smem[wave];
-    const int nchunk = d >> 4;
+    const int nchunk = d / (16 * CH);
     u64 tiles = 0, rows = 0, nprops_total = 0;
     u32 ev_lane = 0;
 
@@ -112,7 +163,7 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_f32(
                 const u32 idr = key_id(kreg[p >> 6]);
                 const int id = __shfl((int)idr, (p & 63) + r16);
                 valid[g] = p + r16 < m;
-                rp[g] = X + (size_t)(valid[g] ? id : 0) * d + 4 * q;
+                rp[g] = X + (size_t)(valid[g] ? id : 0) * d + 4 * q;   // lanes without a row read row 0
             }
 
             // ---- Gram block over d in chunks of 16 dimensions
@@ -122,43 +173,7 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_f32(
             double nr[NR];
 #pragma unroll
             for (int g = 0; g < NR; ++g) nr[g] = 0.0;
-            float4 xc[NR];
-#pragma unroll
-            for (int g = 0; g < NR; ++g) {
-                xc[g] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (valid[g] && 16 * g < m) xc[g] = *(const float4 *)(rp[g]);
-            }
-            for (int c = 0; c < nchunk; ++c) {
-                float4 xn[NR];
-#pragma unroll
-                for (int g = 0; g < NR; ++g) {
-                    xn[g] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (valid[g] && c + 1 < nchunk) xn[g] = *(const float4 *)(rp[g] + 16 * (c + 1));
-                }
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    double a[NR];
-#pragma unroll
-                    for (int g = 0; g < NR; ++g) {
-                        const float f = t == 0 ? xc[g].x : t == 1 ? xc[g].y : t == 2 ? xc[g].z : xc[g].w;
-                        a[g] = (double)f;
-                        nr[g] = fma(a[g], a[g], nr[g]);
-                    }
-#pragma unroll
-                    for (int I = 0; I < NR; ++I) {
-                        if (16 * I < m) {
-#pragma unroll
-                            for (int J = 0; J <= I; ++J) {
-                                if ((new16[I] | new16[J]) != 0)
-                                    acc[I * (I + 1) / 2 + J] = __builtin_amdgcn_mfma_f64_16x16x4f64(
-                                        a[I], a[J], acc[I * (I + 1) / 2 + J], 0, 0, 0);
-                            }
-                        }
-                    }
-                }
-#pragma unroll
-                for (int g = 0; g < NR; ++g) xc[g] = xn[g];
-            }
+            gram_f64_loop<NR, CH>(rp, nchunk, acc, nr);
 #pragma unroll
             for (int g = 0; g < NR; ++g) {
                 nr[g] += __shfl_xor(nr[g], 16);
@@ -175,8 +190,8 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_f32(
                 for (int J = 0; J <= I; ++J) {
                     const int t = I * (I + 1) / 2 + J;
                     T[t] = 0;
+                    tiles += 1;   // every tile of the class is computed
                     if (16 * I < m && (new16[I] | new16[J]) != 0) {
-                        tiles += 1;
                         u32 ft = 0;   // lane = column r16 (row r16 of group J); accumulator v = row 4v + q of group I
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
