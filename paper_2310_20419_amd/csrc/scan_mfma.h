@@ -138,8 +138,8 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_u8(
         }
 
         // ---- vertex `cur`
-        const int u = cur.u;
-        int m = cur.m;
+        const int u = __builtin_amdgcn_readfirstlane(cur.u);      // same in every lane: keep it scalar
+        int m = __builtin_amdgcn_readfirstlane(cur.m);
         if (m > 32 * NG) m = 32 * NG;   // cannot happen: the list is built per degree class
         if (m > R) m = R;
         u64 *row = keys + (size_t)u * R;

@@ -56,7 +56,7 @@ __device__ __forceinline__ u32 transpose16_bits(u32 w, int lane)
 // produce is masked later) and the last iteration re-reads the last chunk.
 template <int NR, int CH>
 __device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int nchunk, v4d (&acc)[NR * (NR + 1) / 2],
-                                              double (&nr)[NR])
+                                              double (&nr)[NR], u32 need)
 {
     float4 x[NR][CH];
 #pragma unroll
@@ -92,8 +92,9 @@ __device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int 
                 for (int I = 0; I < NR; ++I)
 #pragma unroll
                     for (int J = 0; J <= I; ++J)
-                        acc[I * (I + 1) / 2 + J] = __builtin_amdgcn_mfma_f64_16x16x4f64(
-                            a[I][j][t], a[J][j][t], acc[I * (I + 1) / 2 + J], 0, 0, 0);
+                        if (NR <= 2 || ((need >> (I * (I + 1) / 2 + J)) & 1u))   // wave-uniform
+                            acc[I * (I + 1) / 2 + J] = __builtin_amdgcn_mfma_f64_16x16x4f64(
+                                a[I][j][t], a[J][j][t], acc[I * (I + 1) / 2 + J], 0, 0, 0);
             }
     }
 }
@@ -101,7 +102,7 @@ __device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int 
 // CH = 16-dimension chunks fetched per loop iteration (d must be a multiple of 16*CH): a longer iteration
 // gives the prefetch of the next one more matrix work to hide behind.
 template <int NG, int CH>
-__global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_f32(
+__global__ __launch_bounds__(64 * 4, (NG == 1 ? 4 : NG == 2 ? 2 : 1)) void k_update_scan_mfma_f32(
     const float *__restrict__ X, int d, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
     int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
@@ -130,8 +131,8 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_f32(
         }
         ScanItem aft = scan_item_load<NG>(u_after, keys, deg, R, lane);
 
-        const int u = cur.u;
-        int m = cur.m;
+        const int u = __builtin_amdgcn_readfirstlane(cur.u);      // same in every lane: keep it scalar
+        int m = __builtin_amdgcn_readfirstlane(cur.m);
         if (m > 32 * NG) m = 32 * NG;
         if (m > R) m = R;
         u64 *row = keys + (size_t)u * R;
@@ -173,7 +174,16 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_f32(
             double nr[NR];
 #pragma unroll
             for (int g = 0; g < NR; ++g) nr[g] = 0.0;
-            gram_f64_loop<NR, CH>(rp, nchunk, acc, nr);
+            // tiles worth computing: rows in use, and a new entry among the rows or the columns (lines 8-9)
+            u32 need = 0;
+#pragma unroll
+            for (int I = 0; I < NR; ++I)
+#pragma unroll
+                for (int J = 0; J <= I; ++J)
+                    if (16 * I < m && (new16[I] | new16[J]) != 0) need |= 1u << (I * (I + 1) / 2 + J);
+            if (NR <= 2) need = (1u << NT) - 1u;
+            need = (u32)__builtin_amdgcn_readfirstlane((int)need);
+            gram_f64_loop<NR, CH>(rp, nchunk, acc, nr, need);
 #pragma unroll
             for (int g = 0; g < NR; ++g) {
                 nr[g] += __shfl_xor(nr[g], 16);
@@ -190,7 +200,7 @@ __global__ __launch_bounds__(64 * 4) void k_update_scan_mfma_f32(
                 for (int J = 0; J <= I; ++J) {
                     const int t = I * (I + 1) / 2 + J;
                     T[t] = 0;
-                    tiles += 1;   // every tile of the class is computed
+                    if ((need >> t) & 1u) tiles += 1;
                     if (16 * I < m && (new16[I] | new16[J]) != 0) {
                         u32 ft = 0;   // lane = column r16 (row r16 of group J); accumulator v = row 4v + q of group I
 #pragma unroll
