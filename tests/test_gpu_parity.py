@@ -4,6 +4,8 @@ float data: distances are double-accumulated and rounded once on both sides, so 
 bit-exact comparison is applied (the stated tolerance -- 1e-5 relative, >= 99 % edges -- is the
 fallback bar and is checked too).
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -243,3 +245,90 @@ def test_cfg3_full_size_parity(rn, oracle_mod):
     assert (graph.cpu().numpy() == want.snap.ids).all()
     assert list(st.algo_evals[:60]) == want.round_evals.tolist()
     assert list(st.proposals[:60]) == want.round_props.tolist()
+
+
+FULL = os.environ.get("RNND_FULL_PARITY", "") == "1"
+
+
+@pytest.mark.slow
+@pytest.mark.skipif(not FULL, reason="set RNND_FULL_PARITY=1: several minutes of single-threaded oracle")
+def test_cfg4_full_size_parity(rn, oracle_mod):
+    """BASELINE configuration 4 (N = 1,000,000, d = 96 float32, unit vectors) against a full oracle run."""
+    import time
+    c = wl.CONFIGS["cfg4"]
+    X = wl.make_data(c)
+    print("cfg4 data ready", wl.sha256_of(X)[:16], flush=True)
+    graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    print("gpu build done: %.1f ms" % st.total_ms, flush=True)
+    t0 = time.time()
+    want = oracle_mod.build_sync(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    print("oracle build done: %.1f s" % (time.time() - t0), flush=True)
+    ids, bits, flags, deg = device_to_arrays(keys, degree)
+    rows_equal = ((ids == want.snap.ids).all(1) & (deg == want.snap.deg)).mean()
+    print("rows identical: %.6f" % rows_equal, flush=True)
+    assert_snapshot_equal(want.snap, True, keys, degree, "cfg4")
+    assert list(st.algo_evals[:60]) == want.round_evals.tolist()
+
+
+@pytest.mark.slow
+def test_cfg5_full_size_sampled_parity(rn, oracle_mod):
+    """BASELINE configuration 5 (N = 1,000,000, d = 960 float32) in the launch configuration bench.py
+    times.  A full oracle run would take hours, so outputs are sampled: after the GPU has run RandomGraph
+    and k rounds, one more round is run on the GPU, and for 2,000 sampled vertices the oracle computes
+    that round one vertex at a time (a snapshot in which only the sampled lists are non-empty).  The
+    entries the GPU kept for a sampled vertex (flag old) must equal the oracle's kept list, key for key
+    (up to the cut at R when the full graph redirected more edges to it than the sample can know);
+    RandomGraph rows of the sample are compared the same way; structure (sorted, distinct, no self loop,
+    degree <= R, distances = float64 numpy) is checked on the sample of the final graph."""
+    c = wl.CONFIGS["cfg5"]
+    X = wl.make_data(c)
+    print("cfg5 data ready", flush=True)
+    Xd = cuda(X)
+    R = c.R
+    g = np.random.default_rng(1)
+    sample = np.sort(g.choice(c.N, 2000, replace=False))
+    keys, deg = rn.rnnd_random_graph(Xd, c.S, R, wl.BUILD_SEED)
+    ids0, bits0, flags0, deg0 = device_to_arrays(keys, deg)
+    for u in sample[:300]:
+        want_ids = oracle_mod.random_ids(c.N, int(u), c.S, wl.BUILD_SEED)
+        assert sorted(ids0[u, :c.S].tolist()) == sorted(want_ids.tolist())
+    for k_before in (0, 3):
+        if k_before:
+            rn.rnnd_update_neighbors(Xd, keys, deg, R, k_before)
+        ids_b, bits_b, flags_b, deg_b = device_to_arrays(keys, deg)
+        snap = oracle_mod.Snapshot.empty(c.N, R)
+        for u in sample:
+            m = deg_b[u]
+            snap.ids[u, :m] = ids_b[u, :m]
+            snap.dist[u, :m] = bits_b[u, :m].view(np.float32).astype(np.float64)
+            snap.flags[u, :m] = flags_b[u, :m]
+            snap.deg[u] = m
+        want, _, _ = oracle_mod.update_neighbors_sync(X, snap, R)
+        rn.rnnd_update_neighbors(Xd, keys, deg, R, 1)
+        ids_a, bits_a, flags_a, deg_a = device_to_arrays(keys, deg)
+        sampled = set(sample.tolist())
+        for u in sample:
+            got = [(int(bits_a[u, k]), int(ids_a[u, k])) for k in range(deg_a[u]) if flags_a[u, k] == 0]
+            # in the reduced snapshot nothing is redirected INTO u unless its source is sampled too
+            wk = [(int(np.float32(want.dist[u, k]).view(np.uint32)), int(want.ids[u, k]))
+                  for k in range(want.deg[u]) if want.flags[u, k] == 0]
+            if deg_a[u] < R:
+                assert got == wk, "vertex %d after %d rounds" % (u, k_before)
+            else:
+                # a full row: edges redirected to u by vertices outside the sample may have pushed the
+                # farthest kept entries past the cut at R; what is missing must lie beyond the last key
+                last = (int(bits_a[u, R - 1]), int(ids_a[u, R - 1]))
+                assert set(got) <= set(wk) and all(k > last for k in set(wk) - set(got)), "vertex %d" % u
+        print("sampled round parity ok after %d rounds" % k_before, flush=True)
+    graph, degree, fkeys, st = rn.rnnd_build_ex(Xd, c.S, R, c.T1, c.T2, wl.BUILD_SEED)
+    print("gpu build done: %.1f ms" % st.total_ms, flush=True)
+    ids, bits, flags, dg = device_to_arrays(fkeys, degree)
+    Xs = X.astype(np.float64)
+    for u in sample[:500]:
+        m = dg[u]
+        row = ids[u, :m]
+        assert m <= R and len(set(row.tolist())) == m and u not in row
+        ref = ((Xs[row] - Xs[u]) ** 2).sum(1).astype(np.float32)
+        assert (bits[u, :m].view(np.float32) == ref).all()
+        key = list(zip(bits[u, :m].tolist(), row.tolist()))
+        assert key == sorted(key)
