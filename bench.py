@@ -20,6 +20,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
+# HBM bytes per scan launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by
+# a plain 1 GiB copy in the same run); see profiles/update_scan_cfg3_hbm_traffic.txt.  Keyed by
+# (workload, kernel variant); None where it has not been measured.
+TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.176e9}
+
 
 def cpu_baseline(cfg, X, sample_n):
     """The oracle as it stands, single-threaded, on the first sample_n rows (same S, R, T1, T2)."""
@@ -121,19 +126,37 @@ def main():
     rounds = s["rounds"]
     algo = s["init_evals"] + sum(s["algo_evals"])
     execd = s["init_evals"] + sum(s["exec_evals"])
-    # dominant kernel: the UpdateNeighbors scan.  Algorithmic bytes of one launch = rows of X it must
-    # gather (d*esz each) + the list entries it reads (8 B) and writes back (8 B) + the redirected
-    # edges it emits (16 B); averaged over the T1*T2 launches of the last timed build, durations by
-    # HIP events on the build's stream.
+    # dominant kernel: the UpdateNeighbors scan (the class launches of one round taken together).
+    # Algorithmic bytes of one launch = rows of X it must gather (d*esz each) + the list entries it reads
+    # (8 B) and writes back (8 B) + the redirected edges it emits (16 B); summed over the T1*T2 launches of
+    # the last timed build, durations by HIP events on the build's stream.
     scan_bytes = sum(g * (cfg.d * esz + 16) + 16 * p for g, p in zip(s["gathered_rows"], s["proposals"]))
     scan_ms = sum(s["scan_ms"])
-    achieved = scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+    hbm_gbs = scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+    kv = s["kernel_variant"]
+    kname = {1: "k_update_scan", 2: "k_update_scan_mfma_u8<NG,%d> (NG = 1,2,3 back to back per round)" % (cfg.d // 32),
+             3: "k_update_scan_mfma_f32<NG,CH> (NG = 1,2,3 back to back per round)"}[kv]
+    if kv == 3:
+        # float rows: the Gram tiles run on the f64 matrix cores and bound the kernel for large d;
+        # executed flops = computed pair distances * 2 d
+        flops = sum(s["exec_evals"]) * 2.0 * cfg.d
+        achieved = flops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0
+        roof = {"bound": "mfma", "kernel": kname, "achieved": achieved, "peak": 78.6, "unit": "TFLOP/s",
+                "frac": achieved / 78.6, "traffic": None, "launches": rounds,
+                "avg_launch_ms": scan_ms / max(1, rounds), "flops_per_launch": flops / max(1, rounds),
+                "hbm_algorithmic_GBps": hbm_gbs, "hbm_frac": hbm_gbs / HBM_PEAK_GBS,
+                "algorithmic_bytes_per_launch": scan_bytes / max(1, rounds)}
+    else:
+        roof = {"bound": "hbm", "kernel": kname, "achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC_PER_LAUNCH.get((cfg.name, kv)),
+                "launches": rounds, "avg_launch_ms": scan_ms / max(1, rounds),
+                "algorithmic_bytes_per_launch": scan_bytes / max(1, rounds)}
     out = {
         "metric": "1M-vector graph build time" if cfg.N == 1_000_000 else "graph build time",
         "value": ms_per_step / 1000.0, "unit": "s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8 (int32 distances)" if cfg.dtype == "u8" else "f32 (f64 accumulation)",
+        "dtype": "u8 (int8 MFMA, int32 distances)" if cfg.dtype == "u8" else "f32 (f64 MFMA / f64 accumulation, float distances)",
         "data": "synthetic",
         "config": {"workload": "%s: N=%d d=%d %s, S=%d R=%d T1=%d T2=%d, seeded %s mixture"
                                % (cfg.name, cfg.N, cfg.d, cfg.dtype, cfg.S, cfg.R, cfg.T1, cfg.T2, cfg.kind),
@@ -144,10 +167,7 @@ def main():
         "gpu_ms": {"total": s["total_ms"], "init": s["init_ms"], "rounds": sum(s["round_ms"]),
                    "scan": scan_ms, "reverse": sum(s["reverse_ms"])},
         "mean_degree": float(degree.float().mean().item()), "max_degree": int(degree.max().item()),
-        "roofline": {"bound": "hbm", "kernel": "k_update_scan_mfma_u8<NG,4> (NG = 1,2,3 launched back to back per round)" if s["kernel_variant"] == 2 else "k_update_scan", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "launches": rounds, "avg_launch_ms": scan_ms / max(1, rounds),
-                     "algorithmic_bytes_per_launch": scan_bytes / max(1, rounds)},
+        "roofline": roof,
         "data_gen_s": gen_s,
     }
     if not args.no_recall:

@@ -154,8 +154,10 @@ class BuildResult:
 
 
 def build_sync(X: np.ndarray, S: int, R: int, T1: int, T2: int, seed: int,
-               use_flag_skip: bool = True, W: int | None = None) -> BuildResult:
+               use_flag_skip: bool = True, W: int | None = None, progress: bool = False) -> BuildResult:
+    """progress=True prints one stderr line per finished round (for runs of several minutes)."""
     _chk(X)
+    _load().orc_set_progress(ctypes.c_int(1 if progress else 0))
     n, d = X.shape
     W = R if W is None else W
     s = Snapshot.empty(n, W)

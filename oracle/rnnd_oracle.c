@@ -46,6 +46,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include <math.h>
+#include <stdio.h>
 
 #define ORC_U8 0
 #define ORC_F32 1
@@ -451,6 +452,10 @@ int orc_add_reverse_edges(int64_t n, int32_t R, int32_t W, int32_t *ids, double 
     return 0;
 }
 
+/* Optional progress lines on stderr, one per finished round (long runs only; no effect on results). */
+static int g_progress = 0;
+void orc_set_progress(int on) { g_progress = on; }
+
 /* Alg. 6 with synchronous rounds.  round_evals (optional) receives T1*T2
  * counts of the delta(v,w) evaluations Alg. 4 performs; *init_evals = n*S. */
 int orc_build_sync(const void *X, int64_t n, int32_t d, int dtype, int32_t S, int32_t R,
@@ -468,6 +473,11 @@ int orc_build_sync(const void *X, int64_t n, int32_t d, int dtype, int32_t S, in
             update_neighbors_sync(&D, G, R, use_flag_skip, &ev, &np);   /* L5 */
             if (round_evals) round_evals[t1 * T2 + t2] = ev;
             if (round_props) round_props[t1 * T2 + t2] = np;
+            if (g_progress) {
+                fprintf(stderr, "oracle: round %d of %d done, %lld evaluations\n",
+                        (int)(t1 * T2 + t2 + 1), (int)(T1 * T2), (long long)ev);
+                fflush(stderr);
+            }
         }
         if (t1 != T1 - 1) add_reverse_edges(G, n, R);           /* L6-7 */
     }

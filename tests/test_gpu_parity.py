@@ -239,7 +239,7 @@ def test_cfg3_full_size_parity(rn, oracle_mod):
     graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
     print("gpu build done: %.1f ms" % st.total_ms, flush=True)
     t0 = time.time()
-    want = oracle_mod.build_sync(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    want = oracle_mod.build_sync(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED, progress=True)
     print("oracle build done: %.1f s" % (time.time() - t0), flush=True)
     assert_snapshot_equal(want.snap, False, keys, degree, "cfg3")
     assert (graph.cpu().numpy() == want.snap.ids).all()
@@ -261,7 +261,7 @@ def test_cfg4_full_size_parity(rn, oracle_mod):
     graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
     print("gpu build done: %.1f ms" % st.total_ms, flush=True)
     t0 = time.time()
-    want = oracle_mod.build_sync(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    want = oracle_mod.build_sync(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED, progress=True)
     print("oracle build done: %.1f s" % (time.time() - t0), flush=True)
     ids, bits, flags, deg = device_to_arrays(keys, degree)
     rows_equal = ((ids == want.snap.ids).all(1) & (deg == want.snap.deg)).mean()
