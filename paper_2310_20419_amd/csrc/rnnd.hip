@@ -269,10 +269,12 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
 // ------------------------------------------------------ UpdateNeighbors: merge
 // Vertices x with cnt[x] > list_min are appended to `list`; those with cnt[x] > bin_min get a bin of
 // cnt[x] - bin_sub keys starting at binoff[x] (others: binoff = -1).  One pair of atomics per 1024
-// vertices.  Optionally clears fill[] and sets thr[] to "keep all".
+// vertices.  Optionally clears zero_a[] and zero_b[], sets thr[] to "keep all", and marks in cand[]
+// the vertices with deg[x] + cnt[x] > cand_R.
 __global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cnt, int list_min, int bin_min,
                                                       int bin_sub, int *binoff, u32 *bin_cursor, int *list,
-                                                      u32 *n_list, int *fill, u64 *thr)
+                                                      u32 *n_list, int *zero_a, int *zero_b, u64 *thr,
+                                                      const int *deg, int cand_R, int8_t *cand)
 {
     __shared__ u32 s_sum[16], s_num[16], s_base[2];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -280,8 +282,10 @@ __global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cn
     int c = 0;
     if (x < N) {
         c = cnt[x];
-        if (fill) fill[x] = 0;
+        if (zero_a) zero_a[x] = 0;
+        if (zero_b) zero_b[x] = 0;
         if (thr) thr[x] = KEY_PAD;
+        if (cand) cand[x] = (int8_t)(deg[x] + c > cand_R);
     }
     const bool in_list = c > list_min;
     const u32 mine = c > bin_min ? (u32)(c - bin_sub) : 0u;
@@ -552,21 +556,32 @@ __global__ __launch_bounds__(1024) void k_compact_classes(const u32 *n_ptr, u32 
 }
 
 // ------------------------------------------------------------ AddReverseEdges
-// cnt[v] += 1 for every edge (u, v)
-__global__ __launch_bounds__(BLOCK) void k_count_targets(long long N, int R, const u64 *keys,
-                                                         const int *deg, int *cnt)
+// Alg. 5 lines 1-5 need, for every x, the edges that point to x.  Every edge (u, v) takes an arrival
+// number at v (one atomic on fill[v]); the first INBOX_CAP arrivals are written to v's inbox as
+// key(delta, u, new).  A vertex that receives more gets a bin afterwards and k_fill_bins places all of
+// its incoming edges there.
+__global__ __launch_bounds__(BLOCK) void k_reverse_scatter(long long N, int R, const u64 *keys, const int *deg,
+                                                           int *fill, u64 *inbox)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
     if (u >= N) return;
     const int m = deg[u];
-    for (int e = lane; e < m; e += 64) atomicAdd(&cnt[key_id(keys[(size_t)u * R + e])], 1);
+    for (int e = lane; e < m; e += 64) {
+        const u64 k = keys[(size_t)u * R + e];
+        const u32 v = key_id(k);
+        const int a = atomicAdd(&fill[v], 1);
+        if (a < INBOX_CAP) inbox[(size_t)v * INBOX_CAP + a] = make_key(key_dist(k), (u32)u, 1u);
+    }
 }
 
-// For every edge (u, v) whose v owns a bin: bins[v] <- key(delta, u, flag)
+// For every edge (u, v) whose v owns a bin: bins[v] <- key(delta, u, flag).  Nothing to do when no
+// bin was handed out (*n_binned == 0).
 __global__ __launch_bounds__(BLOCK) void k_fill_bins(long long N, int R, const u64 *keys, const int *deg,
-                                                     const int *binoff, int *fill, u64 *bins, u32 flag)
+                                                     const int *binoff, int *fill, u64 *bins, u32 flag,
+                                                     const u32 *n_binned)
 {
+    if (*n_binned == 0u) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
     if (u >= N) return;
@@ -580,21 +595,41 @@ __global__ __launch_bounds__(BLOCK) void k_fill_bins(long long N, int R, const u
 }
 
 // Alg. 5 lines 1-5: list(x) <- first R distinct of list(x) + reversed edges into x (flag new).
-__global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64 *keys, int *deg,
-                                                         int *cnt, const int *binoff, const u64 *bins)
+// Then the edges of the new list are counted at those targets that can end up with more than R
+// incoming edges (cand[v]: |list(v)| + |edges into v| > R before the union; for every other vertex
+// the union itself bounds the in-degree by R).  vcls[x] <- degree class if the list holds a "new"
+// entry, else -1.
+__global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64 *keys, int *deg, int *fill,
+                                                         const u64 *inbox, const int *binoff, const u64 *bins,
+                                                         const int8_t *cand, int *cnt_in, int8_t *vcls,
+                                                         int use_classes)
 {
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long x = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
     if (x >= N) return;
-    const int c = cnt[x];
+    u64 *row = keys + (size_t)x * R;
+    const int c = fill[x];
+    int nd = deg[x];
     if (c > 0) {
         bool any_new;
-        const int nd = wave_merge_row(keys + (size_t)x * R, deg[x], bins + binoff[x], c, bins, 0, R,
-                                      s_stage[wave], lane, &any_new);
-        if (lane == 0) deg[x] = nd;
+        const u64 *src = c <= INBOX_CAP ? inbox + (size_t)x * INBOX_CAP : bins + binoff[x];
+        nd = wave_merge_row(row, nd, src, c, src, 0, R, s_stage[wave], lane, &any_new);
+        wave_sync();    // the list is read back below by other lanes of this wavefront
     }
-    if (lane == 0) cnt[x] = 0;
+    bool nw = false;
+    for (int e = lane; e < nd; e += 64) {
+        const u64 k = row[e];
+        nw = nw || (k & 1ull);
+        const u32 v = key_id(k);
+        if (cand[v]) atomicAdd(&cnt_in[v], 1);
+    }
+    const u64 b = __builtin_amdgcn_ballot_w64(nw);
+    if (lane == 0) {
+        deg[x] = nd;
+        fill[x] = 0;
+        vcls[x] = b ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
+    }
 }
 
 // Alg. 5 lines 6-8, first half: thr[v] <- the R-th smallest (delta, source) among the edges into v.
@@ -618,12 +653,13 @@ __global__ __launch_bounds__(BLOCK) void k_incap_threshold(int R, const int *lis
     }
 }
 
-// Alg. 5 lines 6-8, second half: edge (u, v) survives iff (delta, u) <= thr[v].  vcls[u] <- degree
-// class if the list holds a "new" entry, else -1.  Clears cnt for the next use.
+// Alg. 5 lines 6-8, second half: edge (u, v) survives iff (delta, u) <= thr[v]; vcls[u] follows the
+// new degree.  Nothing to do when no vertex has more than R incoming edges (*n_hubs == 0).
 __global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 *keys, int *deg,
-                                                        const u64 *thr, int *cnt, int *fill, int8_t *vcls,
-                                                        int use_classes)
+                                                        const u64 *thr, int8_t *vcls, int use_classes,
+                                                        const u32 *n_hubs)
 {
+    if (*n_hubs == 0u) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
     if (u >= N) return;
@@ -646,8 +682,6 @@ __global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 
     if (lane == 0) {
         const int nd = c0 + __popcll(m1);
         deg[u] = nd;
-        cnt[u] = 0;
-        fill[u] = 0;
         vcls[u] = (n0 | n1) ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
     }
 }
@@ -884,28 +918,35 @@ static void launch_compact_all(const Workspace &w, long long N, int t_next, hipS
                        (const int *)nullptr, w.vcls, w.lists, N, w.ctr[t_next].n_active);
 }
 
-// AddReverseEdges; the active lists for round t_next are rebuilt from scratch.
+// AddReverseEdges; the active lists for round t_next are rebuilt from scratch.  Expects fill[] == 0
+// and leaves it so.  Between rounds nprop[] and tcls[] are free: they serve as the second in-edge
+// count and the candidate marks.  misc: [0] bin cursor, [1] vertices with a bin (lines 1-5),
+// [2] bin cursor, [3] vertices with more than R incoming edges (lines 6-8).
 static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use_classes, u64 *keys, int *deg,
                                  int t_next, hipStream_t st)
 {
     const int vb = vertex_blocks(N), tb = (int)((N + 1023) / 1024);
+    int *cnt_in = w.nprop;
+    int8_t *cand = w.tcls;
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, 8);
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NCLS);
     // lines 1-5: union with reversed edges, out-lists cut to R
-    hipLaunchKernelGGL(k_count_targets, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.cnt);
-    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.cnt, 0, 0, 0, w.binoff, w.misc + 0, w.hubs,
-                       w.misc + 3, w.fill, (u64 *)nullptr);
-    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.fill, w.bins, 1u);
-    hipLaunchKernelGGL(k_reverse_merge, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.cnt, w.binoff, w.bins);
+    hipLaunchKernelGGL(k_reverse_scatter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox);
+    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.fill, INBOX_CAP, INBOX_CAP, 0, w.binoff,
+                       w.misc + 0, w.hubs, w.misc + 1, w.cnt, cnt_in, (u64 *)nullptr, deg, R, cand);
+    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.cnt, w.bins, 1u,
+                       w.misc + 1);
+    hipLaunchKernelGGL(k_reverse_merge, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, w.binoff,
+                       w.bins, cand, cnt_in, w.vcls, use_classes);
     // lines 6-8: in-lists cut to R; only vertices with more than R incoming edges need a bin
-    hipLaunchKernelGGL(k_count_targets, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.cnt);
-    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.cnt, R, R, 0, w.binoff, w.misc + 1, w.hubs,
-                       w.misc + 2, w.fill, w.thr);
-    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.fill, w.bins, 0u);
-    hipLaunchKernelGGL(k_incap_threshold, dim3(persistent_blocks()), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 2,
-                       w.cnt, w.binoff, w.bins, w.thr);
-    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, w.cnt, w.fill, w.vcls,
-                       use_classes);
+    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, cnt_in, R, R, 0, w.binoff, w.misc + 2, w.hubs,
+                       w.misc + 3, w.cnt, (int *)nullptr, w.thr, (const int *)nullptr, 0, (int8_t *)nullptr);
+    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.cnt, w.bins, 0u,
+                       w.misc + 3);
+    hipLaunchKernelGGL(k_incap_threshold, dim3(persistent_blocks()), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 3,
+                       cnt_in, w.binoff, w.bins, w.thr);
+    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, w.vcls, use_classes,
+                       w.misc + 3);
     launch_compact_all(w, N, t_next, st);
     return hipGetLastError();
 }
