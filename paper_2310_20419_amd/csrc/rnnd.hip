@@ -22,7 +22,8 @@
 #define WAVES_PER_BLOCK 4
 #define BLOCK (64 * WAVES_PER_BLOCK)
 #define GOLDEN64 0x9E3779B97F4A7C15ull
-#define NCLS 4
+#define NDEG 6   // degree classes of the active lists: at most 8, 16, 32, 64, 96, 128 entries
+#define NMRG 4   // merge classes of the touched lists: kept + received at most 16, 32, 64, more
 #ifndef INBOX_CAP
 #define INBOX_CAP 64   // redirected edges a vertex can receive per round without the overflow path
 #endif
@@ -31,11 +32,11 @@
 // writes ctr[t+1].n_active[].  Zeroed once per call, never reset, so they double as statistics.
 #define STAT_SLOTS 64
 struct RoundCtr {
-    u32 n_active[NCLS];   // lengths of this round's active lists
-    u32 n_touched[NCLS];  // distinct targets of the redirected edges, by size of the merge they need
+    u32 n_active[NDEG];   // lengths of this round's active lists
+    u32 n_touched[NMRG];  // distinct targets of the redirected edges, by size of the merge they need
     u32 bin_cursor;       // space handed out in the bin array
     u32 has_surplus;      // some vertex received more than INBOX_CAP edges this round
-    u32 pad[2];
+    u32 pad[4];
     // statistics, spread over STAT_SLOTS addresses so that the adds of many blocks do not queue up
     // on one: [slot][0..3] = algorithmic evals, executed evals, rows gathered, edges redirected
     u64 stat[STAT_SLOTS][4];
@@ -71,9 +72,14 @@ __device__ __forceinline__ void emit_redirect(u64 key, u32 tgt, Prop *slot)
 #include "scan_mfma.h"
 #include "scan_mfma_f32.h"
 
+// Degree class of a list of m entries.  use_classes 0: one list for all (generic scan);
+// 1: lists 2..5 (up to 32, 64, 96, 128 entries: one, two, three, four 32-row blocks per wavefront);
+// 2: also lists 0 and 1 (up to 8 and 16 entries: four and two vertices share a wavefront).
 __device__ __forceinline__ int degree_class(int m, int use_classes)
 {
-    return use_classes ? (m <= 32 ? 0 : (m - 1) >> 5) : 0;
+    if (!use_classes) return 0;
+    if (use_classes == 2 && m <= 16) return m <= 8 ? 0 : 1;
+    return m <= 32 ? 2 : 2 + ((m - 1) >> 5);
 }
 
 // ------------------------------------------------------------------ RandomGraph
@@ -390,7 +396,7 @@ __device__ __forceinline__ int merge_class(int nb, int c)
 __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int *cnt, const int *deg,
                                                          int *binoff, RoundCtr *ctr, int *tlists)
 {
-    __shared__ u32 s_cnt[16][NCLS], s_sum[16], s_base[NCLS + 1];
+    __shared__ u32 s_cnt[16][NMRG], s_sum[16], s_base[NMRG + 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long long x = (long long)blockIdx.x * 1024 + threadIdx.x;
     int c = 0, mc = -1;
@@ -405,31 +411,31 @@ __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int 
         u32 v = __shfl_up(incl, o);
         if (lane >= o) incl += v;
     }
-    u64 b[NCLS];
+    u64 b[NMRG];
 #pragma unroll
-    for (int k = 0; k < NCLS; ++k) b[k] = __builtin_amdgcn_ballot_w64(mc == k);
+    for (int k = 0; k < NMRG; ++k) b[k] = __builtin_amdgcn_ballot_w64(mc == k);
     if (lane == 63) s_sum[wave] = incl;
     if (lane == 0) {
 #pragma unroll
-        for (int k = 0; k < NCLS; ++k) s_cnt[wave][k] = (u32)__popcll(b[k]);
+        for (int k = 0; k < NMRG; ++k) s_cnt[wave][k] = (u32)__popcll(b[k]);
     }
     __syncthreads();
-    if (threadIdx.x < NCLS) {
+    if (threadIdx.x < NMRG) {
         u32 tot = 0;
         for (int w = 0; w < 16; ++w) { u32 a = s_cnt[w][threadIdx.x]; s_cnt[w][threadIdx.x] = tot; tot += a; }
         s_base[threadIdx.x] = tot ? atomicAdd(&ctr->n_touched[threadIdx.x], tot) : 0u;
-    } else if (threadIdx.x == NCLS) {
+    } else if (threadIdx.x == NMRG) {
         u32 ts = 0;
         for (int w = 0; w < 16; ++w) { u32 a = s_sum[w]; s_sum[w] = ts; ts += a; }
-        s_base[NCLS] = ts ? atomicAdd(&ctr->bin_cursor, ts) : 0u;
+        s_base[NMRG] = ts ? atomicAdd(&ctr->bin_cursor, ts) : 0u;
     }
     __syncthreads();
     if (x < N) {
-        binoff[x] = mine ? (int)(s_base[NCLS] + s_sum[wave] + incl - mine) : -1;
+        binoff[x] = mine ? (int)(s_base[NMRG] + s_sum[wave] + incl - mine) : -1;
         if (mc >= 0) {
             u64 mb = b[0];
 #pragma unroll
-            for (int k = 1; k < NCLS; ++k) mb = (mc == k) ? b[k] : mb;
+            for (int k = 1; k < NMRG; ++k) mb = (mc == k) ? b[k] : mb;
             tlists[(size_t)mc * N + s_base[mc] + s_cnt[wave][mc] + __popcll(mb & lanes_below(lane))] = (int)x;
         }
     }
@@ -522,7 +528,7 @@ __global__ __launch_bounds__(1024) void k_compact_classes(const u32 *n_ptr, u32 
                                                           const int8_t *cls, int *lists, long long N,
                                                           u32 *n_out)
 {
-    __shared__ u32 s_cnt[16][NCLS], s_base[NCLS];
+    __shared__ u32 s_cnt[16][NDEG], s_base[NDEG];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const u32 n = n_ptr ? n_ptr[blockIdx.y] : n_fixed;
     if (idx) idx += (size_t)blockIdx.y * N;
@@ -530,24 +536,24 @@ __global__ __launch_bounds__(1024) void k_compact_classes(const u32 *n_ptr, u32 
     for (u32 base = blockIdx.x * 1024u; base < n; base += gridDim.x * 1024u) {
         const u32 i = base + threadIdx.x;
         const int c = i < n ? (int)cls[i] : -1;
-        u64 b[NCLS];
+        u64 b[NDEG];
 #pragma unroll
-        for (int k = 0; k < NCLS; ++k) b[k] = __builtin_amdgcn_ballot_w64(c == k);
+        for (int k = 0; k < NDEG; ++k) b[k] = __builtin_amdgcn_ballot_w64(c == k);
         if (lane == 0) {
 #pragma unroll
-            for (int k = 0; k < NCLS; ++k) s_cnt[wave][k] = (u32)__popcll(b[k]);
+            for (int k = 0; k < NDEG; ++k) s_cnt[wave][k] = (u32)__popcll(b[k]);
         }
         __syncthreads();
-        if (threadIdx.x < NCLS) {
+        if (threadIdx.x < NDEG) {
             u32 tot = 0;
             for (int w = 0; w < 16; ++w) { u32 a = s_cnt[w][threadIdx.x]; s_cnt[w][threadIdx.x] = tot; tot += a; }
             s_base[threadIdx.x] = tot ? atomicAdd(&n_out[threadIdx.x], tot) : 0u;
         }
         __syncthreads();
-        if (c >= 0 && c < NCLS) {
+        if (c >= 0 && c < NDEG) {
             u64 mine = b[0];
 #pragma unroll
-            for (int k = 1; k < NCLS; ++k) mine = (c == k) ? b[k] : mine;
+            for (int k = 1; k < NDEG; ++k) mine = (c == k) ? b[k] : mine;
             const u32 off = s_base[c] + s_cnt[wave][c] + (u32)__popcll(mine & lanes_below(lane));
             lists[(size_t)c * N + off] = idx ? idx[i] : (int)i;
         }
@@ -745,14 +751,15 @@ struct Workspace {
     u64 *bins = nullptr;    // [N*R]   surplus of the inboxes; AddReverseEdges' bins
     u64 *thr = nullptr;     // [N]
     int *cnt = nullptr, *binoff = nullptr, *fill = nullptr, *touched = nullptr, *hubs = nullptr, *nprop = nullptr;
-    int *lists = nullptr;   // [NCLS*N] active lists by degree class
-    int8_t *vcls = nullptr, *tcls = nullptr;   // [N], [NCLS*N]
+    int8_t *xs = nullptr;     // X - 128 as int8 (uint8 MFMA scan)
+    int *lists = nullptr;   // [NDEG*N] active lists by degree class
+    int8_t *vcls = nullptr, *tcls = nullptr;   // [N], [NMRG*N]
     RoundCtr *ctr = nullptr;   // [n_ctr]
     u32 *misc = nullptr;       // [8]: small cursors for AddReverseEdges
     int n_ctr = 0;
 };
 
-static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_graph)
+static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_graph, size_t xs_bytes)
 {
     size_t off = 0;
     auto take = [&](size_t b) { size_t o = off; off += align_up(b); return o; };
@@ -763,9 +770,10 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
     size_t o_bins = take((size_t)N * R * 8);
     size_t o_thr = take((size_t)N * 8);
     size_t o_cnt = take((size_t)N * 4), o_binoff = take((size_t)N * 4), o_fill = take((size_t)N * 4);
-    size_t o_touched = take((size_t)N * 4 * NCLS), o_hubs = take((size_t)N * 4), o_nprop = take((size_t)N * 4);
-    size_t o_lists = take((size_t)N * 4 * NCLS);
-    size_t o_vcls = take((size_t)N), o_tcls = take((size_t)N * NCLS);
+    size_t o_touched = take((size_t)N * 4 * NMRG), o_hubs = take((size_t)N * 4), o_nprop = take((size_t)N * 4);
+    size_t o_xs = take(xs_bytes);
+    size_t o_lists = take((size_t)N * 4 * NDEG);
+    size_t o_vcls = take((size_t)N), o_tcls = take((size_t)N * NMRG);
     size_t o_ctr = take((size_t)n_ctr * sizeof(RoundCtr));
     size_t o_misc = take(8 * 4);
     if (w.base) {
@@ -780,6 +788,7 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
         w.fill = (int *)(w.base + o_fill);
         w.touched = (int *)(w.base + o_touched);
         w.hubs = (int *)(w.base + o_hubs);
+        w.xs = (int8_t *)(w.base + o_xs);
         w.lists = (int *)(w.base + o_lists);
         w.vcls = (int8_t *)(w.base + o_vcls);
         w.tcls = (int8_t *)(w.base + o_tcls);
@@ -834,25 +843,58 @@ static int persistent_blocks() { return cu_count() * 8; }   // 32 wavefronts per
 
 static inline int vertex_blocks(long long N) { return (int)((N + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK); }
 
+// Blocks of `kernel` (256 threads, static LDS only) that one CU keeps resident; the persistent
+// scans launch exactly that many per CU so that every wavefront starts at once.
+template <typename K>
+static int resident_blocks_per_cu(K kernel, int fallback)
+{
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, 256, 0) != hipSuccess || nb < 1) {
+        (void)hipGetLastError();
+        nb = fallback;
+    }
+    return nb;
+}
+
 template <int NG, int KS>
 static void launch_mfma_scan(const Workspace &w, const void *X, int R, u64 *keys, int *deg, long long N,
                              RoundCtr *c, hipStream_t st)
 {
-    // blocks per CU limited by the LDS one block takes (160 KB per CU)
-    const size_t smem = sizeof(MfmaScanSmem<NG>) * 4;
-    int per_cu = (int)((160 * 1024) / smem);
-    if (per_cu > 8) per_cu = 8;
-    if (per_cu < 1) per_cu = 1;
+    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8<NG, KS>, NG == 2 ? 3 : 2);
     hipLaunchKernelGGL((k_update_scan_mfma_u8<NG, KS>), dim3(cu_count() * per_cu), dim3(256), 0, st,
-                       (const uint8_t *)X, R, keys, deg, w.lists + (size_t)(NG - 1) * N, &c->n_active[NG - 1],
-                       w.props, w.nprop, c);
+                       (const int8_t *)w.xs, R, keys, deg, w.lists + (size_t)(NG + 1) * N,
+                       &c->n_active[NG + 1], w.props, w.nprop, c);
 }
+
+// Lists of at most 32 / P entries (degree class cls), P vertices per wavefront.
+template <int P, int KS>
+static void launch_mfma_scan_packed(const Workspace &w, int cls, int R, u64 *keys, int *deg, long long N,
+                                    RoundCtr *c, hipStream_t st)
+{
+    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_packed<P, KS>, 5);
+    hipLaunchKernelGGL((k_update_scan_mfma_u8_packed<P, KS>), dim3(cu_count() * per_cu), dim3(256), 0, st,
+                       (const int8_t *)w.xs, R, keys, deg, w.lists + (size_t)cls * N, &c->n_active[cls], w.props,
+                       w.nprop, c);
+}
+
+// Fills w.xs for the uint8 MFMA scan (d = 32, 64 or 128; X is 16-byte aligned).
+static void launch_prepare_u8(const Workspace &w, const void *X, long long N, int d, hipStream_t st)
+{
+    const size_t n = (size_t)N * d;
+    hipLaunchKernelGGL(k_prepare_u8, dim3((unsigned)((n / 16 + 255) / 256)), dim3(256), 0, st, (const uint8_t *)X, n,
+                       w.xs);
+}
+
+// Bytes of the int8 copy of X that the uint8 MFMA scan works on (0 for every other scan).
+static size_t xs_bytes_for(long long N, int d, int variant) { return variant == 2 ? (size_t)N * d : 0; }
 
 template <int KS>
 static void launch_mfma_scan_classes(const Workspace &w, const void *X, int R, u64 *keys, int *deg,
                                      long long N, RoundCtr *c, hipStream_t st)
 {
-    launch_mfma_scan<1, KS>(w, X, R, keys, deg, N, c, st);
+    launch_mfma_scan_packed<4, KS>(w, 0, R, keys, deg, N, c, st);
+    if (R > 8) launch_mfma_scan_packed<2, KS>(w, 1, R, keys, deg, N, c, st);
+    if (R > 16) launch_mfma_scan_packed<1, KS>(w, 2, R, keys, deg, N, c, st);
     if (R > 32) launch_mfma_scan<2, KS>(w, X, R, keys, deg, N, c, st);
     if (R > 64) launch_mfma_scan<3, KS>(w, X, R, keys, deg, N, c, st);
     if (R > 96) launch_mfma_scan<4, KS>(w, X, R, keys, deg, N, c, st);
@@ -865,7 +907,7 @@ static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64
     // wavefronts that fit per SIMD: about 4 for NG = 1, 2 for NG = 2, 1 for NG = 3 (21 accumulator tiles)
     const int per_cu = NG == 1 ? 4 : NG == 2 ? 2 : 1;
     hipLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH>), dim3(cu_count() * per_cu), dim3(256), 0, st, (const float *)X,
-                       d, R, keys, deg, w.lists + (size_t)(NG - 1) * N, &c->n_active[NG - 1], w.props, w.nprop, c);
+                       d, R, keys, deg, w.lists + (size_t)(NG + 1) * N, &c->n_active[NG + 1], w.props, w.nprop, c);
 }
 
 // One synchronous UpdateNeighbors round t (ctr[t] -> ctr[t+1]).
@@ -875,7 +917,7 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
 {
     const int pb = persistent_blocks();
     RoundCtr *c = w.ctr + t;
-    const int use_classes = variant >= 2;
+    const int use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
     if (variant == 2) {
         if (d == 32) launch_mfma_scan_classes<1>(w, X, R, keys, deg, N, c, st);
         else if (d == 64) launch_mfma_scan_classes<2>(w, X, R, keys, deg, N, c, st);
@@ -887,7 +929,7 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
         if (R > 64) launch_f32_scan<3, 1>(w, X, d, R, keys, deg, N, c, st);
         if (R > 96)   // lists of 97..128 entries: too many accumulator tiles, generic kernel
             hipLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
-                               w.lists + (size_t)3 * N, &c->n_active[3], w.props, w.nprop, c);
+                               w.lists + (size_t)5 * N, &c->n_active[5], w.props, w.nprop, c);
     } else if (dtype == RNND_U8) {
         hipLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
                            w.lists, &c->n_active[0], w.props, w.nprop, c);
@@ -897,16 +939,16 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
     }
     if (after_scan) (void)hipEventRecord(after_scan, st);
     // from here on `fill` plays the role of the per-target count of this round
-    const int ncl = use_classes ? NCLS : 1;
+    const int ncl = use_classes ? NDEG : 1;
     hipLaunchKernelGGL(k_scatter, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop, w.fill,
                        w.inbox);
     hipLaunchKernelGGL(k_touch_classify, dim3((unsigned)((N + 1023) / 1024)), dim3(1024), 0, st, N, w.fill, deg,
                        w.binoff, c, w.touched);
     hipLaunchKernelGGL(k_scatter_surplus, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop,
                        w.binoff, w.bins);
-    hipLaunchKernelGGL(k_merge, dim3(pb, NCLS), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
+    hipLaunchKernelGGL(k_merge, dim3(pb, NMRG), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
                        w.fill, w.inbox, w.binoff, w.bins, w.tcls, use_classes);
-    hipLaunchKernelGGL(k_compact_classes, dim3(128, NCLS), dim3(1024), 0, st, c->n_touched, 0u, w.touched, w.tcls,
+    hipLaunchKernelGGL(k_compact_classes, dim3(128, NMRG), dim3(1024), 0, st, c->n_touched, 0u, w.touched, w.tcls,
                        w.lists, N, (c + 1)->n_active);
     return hipGetLastError();
 }
@@ -929,7 +971,7 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     int *cnt_in = w.nprop;
     int8_t *cand = w.tcls;
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, 8);
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NCLS);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NDEG);
     // lines 1-5: union with reversed edges, out-lists cut to R
     hipLaunchKernelGGL(k_reverse_scatter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox);
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.fill, INBOX_CAP, INBOX_CAP, 0, w.binoff,
@@ -956,7 +998,7 @@ static void fill_round_stats(rnnd_stats *s, const RoundCtr *h, int rounds)
     s->rounds = rounds;
     for (int t = 0; t < rounds && t < RNND_MAX_ROUNDS; ++t) {
         s->active[t] = 0;
-        for (int c = 0; c < NCLS; ++c) s->active[t] += h[t].n_active[c];
+        for (int c = 0; c < NDEG; ++c) s->active[t] += h[t].n_active[c];
         for (int k = 0; k < STAT_SLOTS; ++k) {
             s->algo_evals[t] += (int64_t)h[t].stat[k][0];
             s->exec_evals[t] += (int64_t)h[t].stat[k][1];
@@ -973,7 +1015,9 @@ extern "C" int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, 
     if (N < 2 || N > 2147483646LL || d < 1) return RNND_ERR_BAD_SHAPE;
     if (R < 1 || R > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
     Workspace w;
-    *bytes = ws_layout(w, N, R, RNND_MAX_ROUNDS + 2, true);
+    // upper bound: the int8 copy exists only for uint8 rows of 32, 64 or 128 bytes
+    *bytes = ws_layout(w, N, R, RNND_MAX_ROUNDS + 2, true,
+                       (dtype == RNND_U8 && (d == 32 || d == 64 || d == 128)) ? (size_t)N * d : 0);
     return RNND_OK;
 }
 
@@ -988,16 +1032,16 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
     if ((int64_t)T1 * T2 > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int rounds = T1 * T2, n_ctr = rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant >= 2;
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
     // events: start, after init, (after scan, after round) per round, after each reverse, end
     const int n_ev = 2 * rounds + T1 + 3;
     Workspace w;
     hipEvent_t *ev = nullptr;
     RoundCtr *hctr = nullptr;
     int n_ev_made = 0;
-    w.bytes = ws_layout(w, N, R, n_ctr, true);
+    w.bytes = ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
     HIPCHK(hipMalloc((void **)&w.base, w.bytes));
-    ws_layout(w, N, R, n_ctr, true);
+    ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
     ev = (hipEvent_t *)calloc(n_ev, sizeof(hipEvent_t));
     hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
     if (!ev || !hctr) { rc = RNND_ERR_OOM; goto done; }
@@ -1008,6 +1052,7 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
         HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
         HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
         HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
+        if (variant == 2) launch_prepare_u8(w, X, N, d, st);
         if (dtype == RNND_U8)
             hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
                                vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
@@ -1107,16 +1152,17 @@ extern "C" int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dt
     if (n_rounds < 1 || n_rounds > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int n_ctr = n_rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant >= 2;
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
     Workspace w;
     RoundCtr *hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
     if (!hctr) return RNND_ERR_OOM;
-    w.bytes = ws_layout(w, N, R, n_ctr, false);
+    w.bytes = ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
     HIPCHK(hipMalloc((void **)&w.base, w.bytes));
-    ws_layout(w, N, R, n_ctr, false);
+    ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
     HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
     HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
     HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
+    if (variant == 2) launch_prepare_u8(w, X, N, d, st);
     hipLaunchKernelGGL(k_classify, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, (long long)N, R, (const u64 *)keys,
                        deg, w.vcls, use_classes);
     launch_compact_all(w, N, 0, st);
@@ -1144,9 +1190,9 @@ extern "C" int rnnd_add_reverse_edges(int64_t N, int32_t R, uint64_t *keys, int3
     if (R < 1 || R > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     Workspace w;
-    w.bytes = ws_layout(w, N, R, 2, false);
+    w.bytes = ws_layout(w, N, R, 2, false, 0);
     HIPCHK(hipMalloc((void **)&w.base, w.bytes));
-    ws_layout(w, N, R, 2, false);
+    ws_layout(w, N, R, 2, false, 0);
     HIPCHK(hipMemsetAsync(w.ctr, 0, 2 * sizeof(RoundCtr), st));
     HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
     HIPCHK(launch_reverse(w, N, R, 0, (u64 *)keys, deg, 0, st));
