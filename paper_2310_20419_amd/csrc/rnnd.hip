@@ -12,6 +12,7 @@
 //            one per degree class (lists of up to 32, 64, 96, 128 entries)
 // Counters that many wavefronts would hit at one address are aggregated per block first.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <string.h>
@@ -392,51 +393,62 @@ __device__ __forceinline__ int merge_class(int nb, int c)
 }
 
 // Every vertex x that received edges (cnt[x] > 0) is appended to the touched list of its merge class;
-// if it received more than INBOX_CAP it also gets a bin for the surplus.  Five atomics per 1024 vertices.
+// if it received more than INBOX_CAP it also gets a bin for the surplus.  A block covers TC_TILES x 1024
+// vertices and takes its space with one atomic per class (and one for the bins).
+#define TC_TILES 4
 __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int *cnt, const int *deg,
                                                          int *binoff, RoundCtr *ctr, int *tlists)
 {
-    __shared__ u32 s_cnt[16][NMRG], s_sum[16], s_base[NMRG + 1];
+    __shared__ u32 s_cnt[TC_TILES][16][NMRG], s_sum[TC_TILES][16], s_base[NMRG + 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long x = (long long)blockIdx.x * 1024 + threadIdx.x;
-    int c = 0, mc = -1;
-    if (x < N) {
-        c = cnt[x];
-        if (c > 0) mc = merge_class(deg[x], c);
-    }
-    const u32 mine = c > INBOX_CAP ? (u32)(c - INBOX_CAP) : 0u;
-    u32 incl = mine;
+    int mc[TC_TILES];
+    u32 mine[TC_TILES], incl[TC_TILES], rank[TC_TILES];
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        u32 v = __shfl_up(incl, o);
-        if (lane >= o) incl += v;
-    }
-    u64 b[NMRG];
+    for (int k = 0; k < TC_TILES; ++k) {
+        const long long x = ((long long)blockIdx.x * TC_TILES + k) * 1024 + threadIdx.x;
+        int c = 0;
+        mc[k] = -1;
+        if (x < N) {
+            c = cnt[x];
+            if (c > 0) mc[k] = merge_class(deg[x], c);
+        }
+        mine[k] = c > INBOX_CAP ? (u32)(c - INBOX_CAP) : 0u;
+        u32 in = mine[k];
 #pragma unroll
-    for (int k = 0; k < NMRG; ++k) b[k] = __builtin_amdgcn_ballot_w64(mc == k);
-    if (lane == 63) s_sum[wave] = incl;
-    if (lane == 0) {
+        for (int o = 1; o < 64; o <<= 1) {
+            u32 v = __shfl_up(in, o);
+            if (lane >= o) in += v;
+        }
+        incl[k] = in;
+        rank[k] = 0;
 #pragma unroll
-        for (int k = 0; k < NMRG; ++k) s_cnt[wave][k] = (u32)__popcll(b[k]);
+        for (int q = 0; q < NMRG; ++q) {
+            const u64 b = __builtin_amdgcn_ballot_w64(mc[k] == q);
+            if (mc[k] == q) rank[k] = (u32)__popcll(b & lanes_below(lane));
+            if (lane == 0) s_cnt[k][wave][q] = (u32)__popcll(b);
+        }
+        if (lane == 63) s_sum[k][wave] = in;
     }
     __syncthreads();
     if (threadIdx.x < NMRG) {
         u32 tot = 0;
-        for (int w = 0; w < 16; ++w) { u32 a = s_cnt[w][threadIdx.x]; s_cnt[w][threadIdx.x] = tot; tot += a; }
+        for (int k = 0; k < TC_TILES; ++k)
+            for (int w = 0; w < 16; ++w) { u32 a = s_cnt[k][w][threadIdx.x]; s_cnt[k][w][threadIdx.x] = tot; tot += a; }
         s_base[threadIdx.x] = tot ? atomicAdd(&ctr->n_touched[threadIdx.x], tot) : 0u;
     } else if (threadIdx.x == NMRG) {
         u32 ts = 0;
-        for (int w = 0; w < 16; ++w) { u32 a = s_sum[w]; s_sum[w] = ts; ts += a; }
+        for (int k = 0; k < TC_TILES; ++k)
+            for (int w = 0; w < 16; ++w) { u32 a = s_sum[k][w]; s_sum[k][w] = ts; ts += a; }
         s_base[NMRG] = ts ? atomicAdd(&ctr->bin_cursor, ts) : 0u;
     }
     __syncthreads();
-    if (x < N) {
-        binoff[x] = mine ? (int)(s_base[NMRG] + s_sum[wave] + incl - mine) : -1;
-        if (mc >= 0) {
-            u64 mb = b[0];
 #pragma unroll
-            for (int k = 1; k < NMRG; ++k) mb = (mc == k) ? b[k] : mb;
-            tlists[(size_t)mc * N + s_base[mc] + s_cnt[wave][mc] + __popcll(mb & lanes_below(lane))] = (int)x;
+    for (int k = 0; k < TC_TILES; ++k) {
+        const long long x = ((long long)blockIdx.x * TC_TILES + k) * 1024 + threadIdx.x;
+        if (x < N) {
+            binoff[x] = mine[k] ? (int)(s_base[NMRG] + s_sum[k][wave] + incl[k] - mine[k]) : -1;
+            if (mc[k] >= 0)
+                tlists[(size_t)mc[k] * N + s_base[mc[k]] + s_cnt[k][wave][mc[k]] + rank[k]] = (int)x;
         }
     }
 }
@@ -856,25 +868,22 @@ static int resident_blocks_per_cu(K kernel, int fallback)
     return nb;
 }
 
+// Events tied to kernels of one round (null: not wanted).  They are attached to the launches
+// themselves, which costs no extra packet on the stream.
+struct RoundEvents {
+    hipEvent_t scan_start = nullptr;   // start of the first scan kernel
+    hipEvent_t scan_stop = nullptr;    // end of the last scan kernel
+    hipEvent_t round_stop = nullptr;   // end of the round's last kernel
+};
+
 template <int NG, int KS>
 static void launch_mfma_scan(const Workspace &w, const void *X, int R, u64 *keys, int *deg, long long N,
-                             RoundCtr *c, hipStream_t st)
+                             RoundCtr *c, hipStream_t st, hipEvent_t e_stop)
 {
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8<NG, KS>, NG == 2 ? 3 : 2);
-    hipLaunchKernelGGL((k_update_scan_mfma_u8<NG, KS>), dim3(cu_count() * per_cu), dim3(256), 0, st,
-                       (const int8_t *)w.xs, R, keys, deg, w.lists + (size_t)(NG + 1) * N,
-                       &c->n_active[NG + 1], w.props, w.nprop, c);
-}
-
-// Lists of at most 32 / P entries (degree class cls), P vertices per wavefront.
-template <int P, int KS>
-static void launch_mfma_scan_packed(const Workspace &w, int cls, int R, u64 *keys, int *deg, long long N,
-                                    RoundCtr *c, hipStream_t st)
-{
-    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_packed<P, KS>, 5);
-    hipLaunchKernelGGL((k_update_scan_mfma_u8_packed<P, KS>), dim3(cu_count() * per_cu), dim3(256), 0, st,
-                       (const int8_t *)w.xs, R, keys, deg, w.lists + (size_t)cls * N, &c->n_active[cls], w.props,
-                       w.nprop, c);
+    hipExtLaunchKernelGGL((k_update_scan_mfma_u8<NG, KS>), dim3(cu_count() * per_cu), dim3(256), 0, st, nullptr,
+                          e_stop, 0, (const int8_t *)w.xs, R, keys, deg, w.lists + (size_t)(NG + 1) * N,
+                          &c->n_active[NG + 1], w.props, w.nprop, c);
 }
 
 // Fills w.xs for the uint8 MFMA scan (d = 32, 64 or 128; X is 16-byte aligned).
@@ -890,74 +899,81 @@ static size_t xs_bytes_for(long long N, int d, int variant) { return variant == 
 
 template <int KS>
 static void launch_mfma_scan_classes(const Workspace &w, const void *X, int R, u64 *keys, int *deg,
-                                     long long N, RoundCtr *c, hipStream_t st)
+                                     long long N, RoundCtr *c, hipStream_t st, const RoundEvents &re)
 {
-    launch_mfma_scan_packed<4, KS>(w, 0, R, keys, deg, N, c, st);
-    if (R > 8) launch_mfma_scan_packed<2, KS>(w, 1, R, keys, deg, N, c, st);
-    if (R > 16) launch_mfma_scan_packed<1, KS>(w, 2, R, keys, deg, N, c, st);
-    if (R > 32) launch_mfma_scan<2, KS>(w, X, R, keys, deg, N, c, st);
-    if (R > 64) launch_mfma_scan<3, KS>(w, X, R, keys, deg, N, c, st);
-    if (R > 96) launch_mfma_scan<4, KS>(w, X, R, keys, deg, N, c, st);
+    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_small<KS>, 5);
+    const int n_big = (R > 32) + (R > 64) + (R > 96);   // launches after the short-list kernel
+    const int ny = 1 + (R > 8) + (R > 16);
+    hipExtLaunchKernelGGL((k_update_scan_mfma_u8_small<KS>), dim3(cu_count() * per_cu, ny), dim3(256), 0, st,
+                          re.scan_start, n_big == 0 ? re.scan_stop : nullptr, 0, (const int8_t *)w.xs, R, keys, deg,
+                          w.lists, N, w.props, w.nprop, c);
+    if (R > 32) launch_mfma_scan<2, KS>(w, X, R, keys, deg, N, c, st, n_big == 1 ? re.scan_stop : nullptr);
+    if (R > 64) launch_mfma_scan<3, KS>(w, X, R, keys, deg, N, c, st, n_big == 2 ? re.scan_stop : nullptr);
+    if (R > 96) launch_mfma_scan<4, KS>(w, X, R, keys, deg, N, c, st, n_big == 3 ? re.scan_stop : nullptr);
 }
 
 template <int NG, int CH>
 static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, long long N,
-                            RoundCtr *c, hipStream_t st)
+                            RoundCtr *c, hipStream_t st, hipEvent_t e_start, hipEvent_t e_stop)
 {
     // wavefronts that fit per SIMD: about 4 for NG = 1, 2 for NG = 2, 1 for NG = 3 (21 accumulator tiles)
     const int per_cu = NG == 1 ? 4 : NG == 2 ? 2 : 1;
-    hipLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH>), dim3(cu_count() * per_cu), dim3(256), 0, st, (const float *)X,
-                       d, R, keys, deg, w.lists + (size_t)(NG + 1) * N, &c->n_active[NG + 1], w.props, w.nprop, c);
+    hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH>), dim3(cu_count() * per_cu), dim3(256), 0, st, e_start,
+                          e_stop, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)(NG + 1) * N,
+                          &c->n_active[NG + 1], w.props, w.nprop, c);
 }
 
 // One synchronous UpdateNeighbors round t (ctr[t] -> ctr[t+1]).
 static hipError_t launch_update_round(const Workspace &w, const void *X, long long N, int d, int dtype,
                                       int vec_ok, int variant, int R, u64 *keys, int *deg, int t,
-                                      hipStream_t st, hipEvent_t after_scan = nullptr)
+                                      hipStream_t st, const RoundEvents &re = RoundEvents())
 {
     const int pb = persistent_blocks();
     RoundCtr *c = w.ctr + t;
     const int use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
     if (variant == 2) {
-        if (d == 32) launch_mfma_scan_classes<1>(w, X, R, keys, deg, N, c, st);
-        else if (d == 64) launch_mfma_scan_classes<2>(w, X, R, keys, deg, N, c, st);
-        else launch_mfma_scan_classes<4>(w, X, R, keys, deg, N, c, st);
+        if (d == 32) launch_mfma_scan_classes<1>(w, X, R, keys, deg, N, c, st, re);
+        else if (d == 64) launch_mfma_scan_classes<2>(w, X, R, keys, deg, N, c, st, re);
+        else launch_mfma_scan_classes<4>(w, X, R, keys, deg, N, c, st, re);
     } else if (variant == 3) {
-        if (d % 32 == 0) launch_f32_scan<1, 2>(w, X, d, R, keys, deg, N, c, st);
-        else launch_f32_scan<1, 1>(w, X, d, R, keys, deg, N, c, st);
-        if (R > 32) launch_f32_scan<2, 1>(w, X, d, R, keys, deg, N, c, st);
-        if (R > 64) launch_f32_scan<3, 1>(w, X, d, R, keys, deg, N, c, st);
+        const int n_more = (R > 32) + (R > 64) + (R > 96);
+        if (d % 32 == 0) launch_f32_scan<1, 2>(w, X, d, R, keys, deg, N, c, st, re.scan_start, n_more == 0 ? re.scan_stop : nullptr);
+        else launch_f32_scan<1, 1>(w, X, d, R, keys, deg, N, c, st, re.scan_start, n_more == 0 ? re.scan_stop : nullptr);
+        if (R > 32) launch_f32_scan<2, 1>(w, X, d, R, keys, deg, N, c, st, nullptr, n_more == 1 ? re.scan_stop : nullptr);
+        if (R > 64) launch_f32_scan<3, 1>(w, X, d, R, keys, deg, N, c, st, nullptr, n_more == 2 ? re.scan_stop : nullptr);
         if (R > 96)   // lists of 97..128 entries: too many accumulator tiles, generic kernel
-            hipLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
-                               w.lists + (size_t)5 * N, &c->n_active[5], w.props, w.nprop, c);
+            hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, nullptr, re.scan_stop, 0, X, d,
+                                  vec_ok, R, keys, deg, w.lists + (size_t)5 * N, &c->n_active[5], w.props, w.nprop, c);
     } else if (dtype == RNND_U8) {
-        hipLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
-                           w.lists, &c->n_active[0], w.props, w.nprop, c);
+        hipExtLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
+                              vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);
     } else {
-        hipLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, X, d, vec_ok, R, keys, deg,
-                           w.lists, &c->n_active[0], w.props, w.nprop, c);
+        hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
+                              vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);
     }
-    if (after_scan) (void)hipEventRecord(after_scan, st);
     // from here on `fill` plays the role of the per-target count of this round
     const int ncl = use_classes ? NDEG : 1;
     hipLaunchKernelGGL(k_scatter, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop, w.fill,
                        w.inbox);
-    hipLaunchKernelGGL(k_touch_classify, dim3((unsigned)((N + 1023) / 1024)), dim3(1024), 0, st, N, w.fill, deg,
+    hipLaunchKernelGGL(k_touch_classify, dim3((unsigned)((N + 1024 * TC_TILES - 1) / (1024 * TC_TILES))), dim3(1024), 0, st, N, w.fill, deg,
                        w.binoff, c, w.touched);
     hipLaunchKernelGGL(k_scatter_surplus, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop,
                        w.binoff, w.bins);
     hipLaunchKernelGGL(k_merge, dim3(pb, NMRG), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
                        w.fill, w.inbox, w.binoff, w.bins, w.tcls, use_classes);
-    hipLaunchKernelGGL(k_compact_classes, dim3(128, NMRG), dim3(1024), 0, st, c->n_touched, 0u, w.touched, w.tcls,
-                       w.lists, N, (c + 1)->n_active);
+    hipExtLaunchKernelGGL(k_compact_classes, dim3(128, NMRG), dim3(1024), 0, st, nullptr, re.round_stop, 0,
+                          (const u32 *)c->n_touched, 0u, (const int *)w.touched, (const int8_t *)w.tcls, w.lists, N,
+                          (c + 1)->n_active);
     return hipGetLastError();
 }
 
 // vcls[] (class of every vertex holding a "new" entry) -> active lists of round t_next
-static void launch_compact_all(const Workspace &w, long long N, int t_next, hipStream_t st)
+static void launch_compact_all(const Workspace &w, long long N, int t_next, hipStream_t st,
+                               hipEvent_t e_stop = nullptr)
 {
-    hipLaunchKernelGGL(k_compact_classes, dim3(256, 1), dim3(1024), 0, st, (const u32 *)nullptr, (u32)N,
-                       (const int *)nullptr, w.vcls, w.lists, N, w.ctr[t_next].n_active);
+    hipExtLaunchKernelGGL(k_compact_classes, dim3(256, 1), dim3(1024), 0, st, nullptr, e_stop, 0,
+                          (const u32 *)nullptr, (u32)N, (const int *)nullptr, (const int8_t *)w.vcls, w.lists, N,
+                          w.ctr[t_next].n_active);
 }
 
 // AddReverseEdges; the active lists for round t_next are rebuilt from scratch.  Expects fill[] == 0
@@ -965,7 +981,7 @@ static void launch_compact_all(const Workspace &w, long long N, int t_next, hipS
 // count and the candidate marks.  misc: [0] bin cursor, [1] vertices with a bin (lines 1-5),
 // [2] bin cursor, [3] vertices with more than R incoming edges (lines 6-8).
 static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use_classes, u64 *keys, int *deg,
-                                 int t_next, hipStream_t st)
+                                 int t_next, hipStream_t st, hipEvent_t e_stop = nullptr)
 {
     const int vb = vertex_blocks(N), tb = (int)((N + 1023) / 1024);
     int *cnt_in = w.nprop;
@@ -989,7 +1005,7 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
                        cnt_in, w.binoff, w.bins, w.thr);
     hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, w.vcls, use_classes,
                        w.misc + 3);
-    launch_compact_all(w, N, t_next, st);
+    launch_compact_all(w, N, t_next, st, e_stop);
     return hipGetLastError();
 }
 
@@ -1033,8 +1049,9 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
     hipStream_t st = (hipStream_t)stream;
     const int rounds = T1 * T2, n_ctr = rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
     const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
-    // events: start, after init, (after scan, after round) per round, after each reverse, end
-    const int n_ev = 2 * rounds + T1 + 3;
+    // events (only when statistics are wanted): start, end of init, (scan start, scan stop, round
+    // stop) per round, end of each reverse call, end
+    const int n_ev = stats ? 3 * rounds + T1 + 3 : 0;
     Workspace w;
     hipEvent_t *ev = nullptr;
     RoundCtr *hctr = nullptr;
@@ -1042,13 +1059,15 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
     w.bytes = ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
     HIPCHK(hipMalloc((void **)&w.base, w.bytes));
     ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
-    ev = (hipEvent_t *)calloc(n_ev, sizeof(hipEvent_t));
+    ev = (hipEvent_t *)calloc(n_ev + 1, sizeof(hipEvent_t));
     hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
     if (!ev || !hctr) { rc = RNND_ERR_OOM; goto done; }
     for (; n_ev_made < n_ev; ++n_ev_made) HIPCHK(hipEventCreate(&ev[n_ev_made]));
     {
-        int e = 0, t = 0;
-        HIPCHK(hipEventRecord(ev[e++], st));
+        // event indices: 0 start, 1 end of init, 2 + 3t .. 4 + 3t round t, then the reverse calls, then the end
+        const int e_rev = 2 + 3 * rounds, e_end = e_rev + T1;
+        int t = 0;
+        if (stats) HIPCHK(hipEventRecord(ev[0], st));
         HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
         HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
         HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
@@ -1059,27 +1078,26 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
         else
             hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
                                vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
-        launch_compact_all(w, N, 0, st);
+        launch_compact_all(w, N, 0, st, stats ? ev[1] : nullptr);
         HIPCHK(hipGetLastError());
-        HIPCHK(hipEventRecord(ev[e++], st));
         for (int t1 = 0; t1 < T1; ++t1) {
             for (int t2 = 0; t2 < T2; ++t2, ++t) {
-                HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, w.keys, w.deg, t, st, ev[e]));
-                ++e;
-                HIPCHK(hipEventRecord(ev[e++], st));
+                RoundEvents re;
+                if (stats) { re.scan_start = ev[2 + 3 * t]; re.scan_stop = ev[3 + 3 * t]; re.round_stop = ev[4 + 3 * t]; }
+                HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, w.keys, w.deg, t, st, re));
             }
-            if (t1 != T1 - 1) {
-                HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, t, st));
-                HIPCHK(hipEventRecord(ev[e++], st));
-            }
+            if (t1 != T1 - 1)
+                HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, t, st, stats ? ev[e_rev + t1] : nullptr));
         }
         hipLaunchKernelGGL(k_export, dim3((unsigned)(((size_t)N * R + 255) / 256)), dim3(256), 0, st, (long long)N, R,
                            w.keys, w.deg, graph_out, degree_out);
         HIPCHK(hipGetLastError());
         if (keys_out)
             HIPCHK(hipMemcpyAsync(keys_out, w.keys, (size_t)N * R * 8, hipMemcpyDeviceToDevice, st));
-        HIPCHK(hipEventRecord(ev[e++], st));
-        HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
+        if (stats) {
+            HIPCHK(hipEventRecord(ev[e_end], st));
+            HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
+        }
         HIPCHK(hipStreamSynchronize(st));
         if (stats) {
             memset(stats, 0, sizeof *stats);
@@ -1089,20 +1107,20 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
             stats->kernel_variant = variant;
             float ms = 0;
             (void)hipEventElapsedTime(&ms, ev[0], ev[1]); stats->init_ms = ms;
-            int q = 1, tt = 0;   // ev[q] = end of the previous phase
+            int tt = 0;
             for (int t1 = 0; t1 < T1; ++t1) {
-                for (int t2 = 0; t2 < T2; ++t2, ++tt, q += 2) {
+                for (int t2 = 0; t2 < T2; ++t2, ++tt) {
                     if (tt >= RNND_MAX_ROUNDS) continue;
-                    (void)hipEventElapsedTime(&ms, ev[q], ev[q + 1]); stats->scan_ms[tt] = ms;
-                    (void)hipEventElapsedTime(&ms, ev[q], ev[q + 2]); stats->round_ms[tt] = ms;
+                    (void)hipEventElapsedTime(&ms, ev[2 + 3 * tt], ev[3 + 3 * tt]); stats->scan_ms[tt] = ms;
+                    (void)hipEventElapsedTime(&ms, ev[2 + 3 * tt], ev[4 + 3 * tt]); stats->round_ms[tt] = ms;
                 }
-                if (t1 != T1 - 1) {
-                    (void)hipEventElapsedTime(&ms, ev[q], ev[q + 1]);
-                    if (t1 < RNND_MAX_ROUNDS) stats->reverse_ms[t1] = ms;
-                    ++q;
+                if (t1 != T1 - 1 && t1 < RNND_MAX_ROUNDS) {
+                    // from the end of the last round before the call to the end of the call
+                    (void)hipEventElapsedTime(&ms, ev[4 + 3 * (tt - 1)], ev[e_rev + t1]);
+                    stats->reverse_ms[t1] = ms;
                 }
             }
-            (void)hipEventElapsedTime(&ms, ev[0], ev[e - 1]); stats->total_ms = ms;
+            (void)hipEventElapsedTime(&ms, ev[0], ev[e_end]); stats->total_ms = ms;
         }
     }
 done:

@@ -503,19 +503,17 @@ __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[K
 // Same two-deep software pipeline as k_update_scan_mfma_u8; trip g of a wavefront takes list entries
 // [P g, P g + P).
 template <int P, int KS>
-__global__ __launch_bounds__(256, 5) void k_update_scan_mfma_u8_packed(
-    const int8_t *__restrict__ X, int R, u64 *__restrict__ keys, int *__restrict__ deg,
-    const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
-    int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
+__device__ __forceinline__ void scan_packed_body(const int8_t *__restrict__ X, int R, u64 *__restrict__ keys,
+                                                 int *__restrict__ deg, const int *__restrict__ list,
+                                                 u32 n_active, Prop *__restrict__ props,
+                                                 int *__restrict__ nprop, RoundCtr *__restrict__ ctr,
+                                                 MfmaScanSmem<1> &sm)
 {
-    __shared__ MfmaScanSmem<1> smem[4];
     constexpr int W = 32 / P;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const int seg = l32 / W, pos = l32 % W;
     const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
-    const u32 n_active = *n_list;
     const u32 n_groups = (n_active + (u32)P - 1u) / (u32)P;
-    MfmaScanSmem<1> &sm = smem[wave];
     u64 tiles = 0, rows = 0, nprops_total = 0;
     u32 ev_lane = 0;
 
@@ -555,4 +553,22 @@ __global__ __launch_bounds__(256, 5) void k_update_scan_mfma_u8_packed(
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) evals_algo += shfl_xor_u64(evals_algo, o);
     if (lane == 0 && rows) add_round_stats(ctr, evals_algo, tiles * 1024ull, rows, nprops_total);
+}
+
+// The three short-list classes in one launch: blockIdx.y = degree class (lists of at most 8, 16, 32
+// entries: 4, 2, 1 vertices per wavefront).  Each class is walked by the gridDim.x blocks of its row.
+template <int KS>
+__global__ __launch_bounds__(256, 5) void k_update_scan_mfma_u8_small(
+    const int8_t *__restrict__ X, int R, u64 *__restrict__ keys, int *__restrict__ deg,
+    const int *__restrict__ lists, long long N, Prop *__restrict__ props, int *__restrict__ nprop,
+    RoundCtr *__restrict__ ctr)
+{
+    __shared__ MfmaScanSmem<1> smem[4];
+    MfmaScanSmem<1> &sm = smem[threadIdx.x >> 6];
+    const int y = blockIdx.y;
+    const int *list = lists + (size_t)y * N;
+    const u32 n = ctr->n_active[y];
+    if (y == 0) scan_packed_body<4, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm);
+    else if (y == 1) scan_packed_body<2, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm);
+    else scan_packed_body<1, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm);
 }
