@@ -318,12 +318,14 @@ __global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cn
     }
 }
 
+#define SURPLUS_MARK 0x40000000   // set in nprop[u]: some edge redirected by u arrived past its target's inbox
+
 // Every active vertex moves its redirected edges to their targets, 16 lanes per vertex.  Lanes of a
 // group that share a target take their arrival numbers with one atomic (a vertex usually redirects
 // several entries to the same kept neighbour).  Arrivals below INBOX_CAP go to the target's inbox;
 // later ones record their number in the edge and are placed by k_scatter_surplus once bins exist.
 __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int *lists, RoundCtr *ctr,
-                                                   Prop *props, const int *nprop, int *fill, u64 *inbox)
+                                                   Prop *props, int *nprop, int *fill, u64 *inbox)
 {
     const int lane = threadIdx.x & 63, sub = lane & 15, gbase = lane & ~15, c = blockIdx.y;
     const u32 g = (blockIdx.x * BLOCK + threadIdx.x) >> 4, ng = (gridDim.x * BLOCK) >> 4;
@@ -333,6 +335,7 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int
     for (u32 it = g; it < n; it += ng) {
         const int u = list[it];
         const int np = nprop[u];
+        bool mine_surplus = false;
         for (int p0 = 0; p0 < np; p0 += 16) {      // same trip count for the whole group
             const int p = p0 + sub;
             const bool have = p < np;
@@ -356,9 +359,15 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int
                     inbox[(size_t)pr.tgt * INBOX_CAP + s] = pr.key;
                 } else {
                     props[(size_t)u * R + p].arrival = (u32)s;
-                    surplus = true;
+                    mine_surplus = true;
                 }
             }
+        }
+        // mark u for the second pass (this group is the only one that touches nprop[u])
+        const u32 anyb = ((u32)(__builtin_amdgcn_ballot_w64(mine_surplus) >> gbase)) & 0xFFFFu;
+        if (anyb) {
+            if (sub == 0) nprop[u] = np | SURPLUS_MARK;
+            surplus = true;
         }
     }
     if (surplus) ctr->has_surplus = 1u;
@@ -376,7 +385,9 @@ __global__ __launch_bounds__(BLOCK) void k_scatter_surplus(long long N, int R, c
     const int *list = lists + (size_t)c * N;
     for (u32 it = g; it < n; it += ng) {
         const int u = list[it];
-        const int np = nprop[u];
+        int np = nprop[u];
+        if (!(np & SURPLUS_MARK)) continue;
+        np &= ~SURPLUS_MARK;
         for (int p = sub; p < np; p += 16) {
             const Prop pr = props[(size_t)u * R + p];
             if (pr.arrival >= (u32)INBOX_CAP)
@@ -455,27 +466,58 @@ __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int 
 
 // Merge of the touched vertices whose kept entries + received edges number at most G: one vertex per
 // group of G lanes.  list <- first R distinct keys; tcls[it] <- degree class if a "new" entry survives, else -1.
+// Lane `sub` of a group holds list slot `sub` and inbox slot G-1-sub, so what to load depends only on
+// the vertex; the loads of the next vertex and the list entry of the one after are issued before the
+// current vertex is sorted.
+struct MergeItem {
+    int x;        // vertex, -1 past the end of the list
+    int nb, c;    // kept entries, received entries
+    u64 kr, ki;   // list slot `sub`, inbox slot G-1-sub (either may be garbage: masked by nb, c)
+};
+
+template <int G>
+__device__ __forceinline__ MergeItem merge_item_load(int x, int R, const u64 *keys, const int *deg,
+                                                     const int *cnt, const u64 *inbox, int sub)
+{
+    MergeItem m;
+    m.x = x;
+    m.nb = m.c = 0;
+    m.kr = m.ki = KEY_PAD;
+    if (x >= 0) {
+        m.nb = deg[x];
+        m.c = cnt[x];
+        if (sub < R) m.kr = keys[(size_t)x * R + sub];
+        m.ki = inbox[(size_t)x * INBOX_CAP + (G - 1 - sub)];
+    }
+    return m;
+}
+
 template <int G>
 __device__ __forceinline__ void merge_group_body(int R, u64 *keys, int *deg, const int *tlist,
                                                  const u32 *n_ptr, int *cnt,
                                                  const u64 *inbox, const int *binoff, const u64 *bins,
                                                  int8_t *tcls, int use_classes)
 {
+    static_assert(G <= INBOX_CAP, "a group merge reads the received edges from the inbox only");
     const int lane = threadIdx.x & 63, sub = lane & (G - 1), shift = lane & ~(G - 1);
     const u64 gmask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull);
     const u32 gid = (blockIdx.x * BLOCK + threadIdx.x) / G, ngrp = (gridDim.x * BLOCK) / G;
     const u32 n = *n_ptr;
-    for (u32 it = gid; it < n; it += ngrp) {
-        const int x = tlist[it];
-        const int nb = deg[x], c = cnt[x];
+    if (gid >= n) return;
+    auto vertex_at = [&](unsigned long long i) -> int { return i < n ? tlist[i] : -1; };
+    MergeItem cur = merge_item_load<G>(vertex_at(gid), R, keys, deg, cnt, inbox, sub);
+    int x_next = vertex_at((unsigned long long)gid + ngrp);
+    int x_after = vertex_at((unsigned long long)gid + 2ull * ngrp);
+    for (unsigned long long it = gid; it < n; it += ngrp) {
+        const MergeItem nxt = merge_item_load<G>(x_next, R, keys, deg, cnt, inbox, sub);
+        x_next = x_after;
+        x_after = vertex_at(it + 3ull * ngrp);
+
+        const int x = cur.x, nb = cur.nb, c = cur.c;
         u64 *row = keys + (size_t)x * R;
         u64 k = KEY_PAD;
-        if (sub < nb) {
-            k = row[sub];
-        } else if (sub < nb + c) {
-            const int e = sub - nb;
-            k = e < INBOX_CAP ? inbox[(size_t)x * INBOX_CAP + e] : bins[(size_t)binoff[x] + (e - INBOX_CAP)];
-        }
+        if (sub < nb) k = cur.kr;
+        else if (G - 1 - sub < c) k = cur.ki;
         k = group_sort<G>(k, lane);
         u64 prev = shfl_up1_u64(k);
         if (sub == 0) prev = KEY_PAD;
@@ -492,6 +534,7 @@ __device__ __forceinline__ void merge_group_body(int R, u64 *keys, int *deg, con
             cnt[x] = 0;
             tcls[it] = nm ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
         }
+        cur = nxt;
     }
 }
 
@@ -1083,7 +1126,13 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
         for (int t1 = 0; t1 < T1; ++t1) {
             for (int t2 = 0; t2 < T2; ++t2, ++t) {
                 RoundEvents re;
-                if (stats) { re.scan_start = ev[2 + 3 * t]; re.scan_stop = ev[3 + 3 * t]; re.round_stop = ev[4 + 3 * t]; }
+                // a round ends where the next one starts; only the last round before a reverse call or
+                // the export needs an event of its own for that (every event costs a few microseconds)
+                if (stats) {
+                    re.scan_start = ev[2 + 3 * t];
+                    re.scan_stop = ev[3 + 3 * t];
+                    if (t2 == T2 - 1) re.round_stop = ev[4 + 3 * t];
+                }
                 HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, w.keys, w.deg, t, st, re));
             }
             if (t1 != T1 - 1)
@@ -1112,7 +1161,8 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
                 for (int t2 = 0; t2 < T2; ++t2, ++tt) {
                     if (tt >= RNND_MAX_ROUNDS) continue;
                     (void)hipEventElapsedTime(&ms, ev[2 + 3 * tt], ev[3 + 3 * tt]); stats->scan_ms[tt] = ms;
-                    (void)hipEventElapsedTime(&ms, ev[2 + 3 * tt], ev[4 + 3 * tt]); stats->round_ms[tt] = ms;
+                    (void)hipEventElapsedTime(&ms, ev[2 + 3 * tt], t2 == T2 - 1 ? ev[4 + 3 * tt] : ev[2 + 3 * (tt + 1)]);
+                    stats->round_ms[tt] = ms;
                 }
                 if (t1 != T1 - 1 && t1 < RNND_MAX_ROUNDS) {
                     // from the end of the last round before the call to the end of the call
