@@ -539,25 +539,70 @@ __device__ __forceinline__ void merge_group_body(int R, u64 *keys, int *deg, con
 }
 
 // General merge (any size): one touched vertex per wavefront; kept entries + inbox + surplus bin.
+// The common case (at most INBOX_CAP received, at most 128 keys in all) is sorted in registers from
+// loads issued one vertex ahead: lane l holds list slots l and l + 64 and inbox slot 63 - l.
+struct WideItem {
+    int x, nb, c;
+    u64 r0, r1, in;
+};
+
+__device__ __forceinline__ WideItem wide_item_load(int x, int R, const u64 *keys, const int *deg, const int *cnt,
+                                                   const u64 *inbox, int lane)
+{
+    WideItem m;
+    m.x = x;
+    m.nb = m.c = 0;
+    m.r0 = m.r1 = m.in = KEY_PAD;
+    if (x >= 0) {
+        m.nb = deg[x];
+        m.c = cnt[x];
+        if (lane < R) m.r0 = keys[(size_t)x * R + lane];
+        if (lane + 64 < R) m.r1 = keys[(size_t)x * R + lane + 64];
+        m.in = inbox[(size_t)x * INBOX_CAP + (INBOX_CAP - 1 - lane)];
+    }
+    return m;
+}
+
 __device__ __forceinline__ void merge_general_body(int R, u64 *keys, int *deg, const int *tlist,
                                                    const u32 *n_ptr, int *cnt, const u64 *inbox,
                                                    const int *binoff, const u64 *bins, int8_t *tcls,
                                                    int use_classes, u64 (*s_stage)[RNND_MAX_R])
 {
+    static_assert(INBOX_CAP == 64, "lane l prefetches inbox slot 63 - l");
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
     const u32 n = *n_ptr;
-    for (u32 it = gw; it < n; it += nw) {
-        const int x = tlist[it];
+    if (gw >= n) return;
+    auto vertex_at = [&](unsigned long long i) -> int { return i < n ? tlist[i] : -1; };
+    WideItem cur = wide_item_load(vertex_at(gw), R, keys, deg, cnt, inbox, lane);
+    int x_next = vertex_at((unsigned long long)gw + nw);
+    int x_after = vertex_at((unsigned long long)gw + 2ull * nw);
+    for (unsigned long long it = gw; it < n; it += nw) {
+        const WideItem nxt = wide_item_load(x_next, R, keys, deg, cnt, inbox, lane);
+        x_next = x_after;
+        x_after = vertex_at(it + 3ull * nw);
+
+        const int x = __builtin_amdgcn_readfirstlane(cur.x);
+        const int nb = __builtin_amdgcn_readfirstlane(cur.nb), c = __builtin_amdgcn_readfirstlane(cur.c);
         bool any_new = false;
-        const int c = cnt[x], ca = c < INBOX_CAP ? c : INBOX_CAP;
-        const int nd = wave_merge_row(keys + (size_t)x * R, deg[x], inbox + (size_t)x * INBOX_CAP, ca,
-                                      bins + (c > ca ? binoff[x] : 0), c - ca, R, s_stage[wave], lane, &any_new);
+        int nd;
+        if (c <= INBOX_CAP && nb + c <= 128) {
+            u64 k[2];
+            k[0] = lane < nb ? cur.r0 : KEY_PAD;
+            k[1] = lane + 64 < nb ? cur.r1 : (63 - lane < c ? cur.in : KEY_PAD);
+            wave_sort<2>(k, lane);
+            nd = wave_unique_prefix<2>(k, lane, R, keys + (size_t)x * R, &any_new);
+        } else {
+            const int ca = c < INBOX_CAP ? c : INBOX_CAP;
+            nd = wave_merge_row(keys + (size_t)x * R, nb, inbox + (size_t)x * INBOX_CAP, ca,
+                                bins + (c > ca ? binoff[x] : 0), c - ca, R, s_stage[wave], lane, &any_new);
+        }
         if (lane == 0) {
             deg[x] = nd;
             cnt[x] = 0;
             tcls[it] = any_new ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
         }
+        cur = nxt;
     }
 }
 
@@ -1002,7 +1047,8 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
                        w.binoff, c, w.touched);
     hipLaunchKernelGGL(k_scatter_surplus, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop,
                        w.binoff, w.bins);
-    hipLaunchKernelGGL(k_merge, dim3(pb, NMRG), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
+    static const int merge_per_cu = resident_blocks_per_cu(k_merge, 6);
+    hipLaunchKernelGGL(k_merge, dim3(cu_count() * merge_per_cu, NMRG), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
                        w.fill, w.inbox, w.binoff, w.bins, w.tcls, use_classes);
     hipExtLaunchKernelGGL(k_compact_classes, dim3(128, NMRG), dim3(1024), 0, st, nullptr, re.round_stop, 0,
                           (const u32 *)c->n_touched, 0u, (const int *)w.touched, (const int8_t *)w.tcls, w.lists, N,

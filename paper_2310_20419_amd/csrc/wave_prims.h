@@ -51,6 +51,41 @@ __device__ __forceinline__ u64 shfl_up1_u64(u64 v)
     return ((u64)hi << 32) | lo;
 }
 
+// Value of lane (l xor S), S a power of two below 64.  Within rows of 16 lanes the exchange is a
+// DPP move (no LDS round trip) where the ISA has one: quad permutations for S = 1, 2 and a rotation
+// by 8 for S = 8; S = 4 and 16 use the LDS swizzle unit, S = 32 the permute unit.
+template <int S>
+__device__ __forceinline__ u32 xor_lane_u32(u32 v)
+{
+    if constexpr (S == 1) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false);        // quad_perm [1,0,3,2]
+    else if constexpr (S == 2) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    else if constexpr (S == 8) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, false);  // row_ror:8
+    else if constexpr (S == 4) return (u32)__builtin_amdgcn_ds_swizzle((int)v, 0x101F);                     // xor 4, and 0x1F
+    else if constexpr (S == 16) return (u32)__builtin_amdgcn_ds_swizzle((int)v, 0x401F);                    // xor 16, and 0x1F
+    else return (u32)__shfl_xor((int)v, S);
+}
+
+__device__ __forceinline__ u64 xor_lane_u64(u64 v, int stride)
+{
+    u32 lo = (u32)v, hi = (u32)(v >> 32);
+    switch (stride) {   // constant after unrolling
+    case 1: lo = xor_lane_u32<1>(lo); hi = xor_lane_u32<1>(hi); break;
+    case 2: lo = xor_lane_u32<2>(lo); hi = xor_lane_u32<2>(hi); break;
+    case 4: lo = xor_lane_u32<4>(lo); hi = xor_lane_u32<4>(hi); break;
+    case 8: lo = xor_lane_u32<8>(lo); hi = xor_lane_u32<8>(hi); break;
+    case 16: lo = xor_lane_u32<16>(lo); hi = xor_lane_u32<16>(hi); break;
+    default: lo = xor_lane_u32<32>(lo); hi = xor_lane_u32<32>(hi); break;
+    }
+    return ((u64)hi << 32) | lo;
+}
+
+// One compare-exchange of a bitonic network from the point of view of one side: keeps the smaller
+// of (mine, other) if take_min, else the larger.
+__device__ __forceinline__ u64 keep_of_pair(u64 mine, u64 other, bool take_min)
+{
+    return ((mine < other) == take_min) ? mine : other;
+}
+
 // Ascending bitonic sort of 64*E keys held as k[r] in lane l  <->  element index r*64 + l.
 template <int E>
 __device__ __forceinline__ void wave_sort(u64 (&k)[E], int lane)
@@ -65,20 +100,18 @@ __device__ __forceinline__ void wave_sort(u64 (&k)[E], int lane)
                 for (int r = 0; r < E; ++r) {
                     if ((r & rs) == 0) {
                         const bool up = (((r * 64) & size) == 0);
-                        u64 a = k[r], b = k[r | rs];
-                        u64 lo = a < b ? a : b, hi = a < b ? b : a;
-                        k[r] = up ? lo : hi;
-                        k[r | rs] = up ? hi : lo;
+                        const u64 a = k[r], b = k[r | rs];
+                        const bool swap = (b < a) == up;      // up: smaller first
+                        k[r] = swap ? b : a;
+                        k[r | rs] = swap ? a : b;
                     }
                 }
             } else {
 #pragma unroll
                 for (int r = 0; r < E; ++r) {
                     const bool up = ((((r * 64) + lane) & size) == 0);
-                    u64 o = shfl_xor_u64(k[r], stride);
                     const bool lower = (lane & stride) == 0;
-                    u64 mn = k[r] < o ? k[r] : o, mx = k[r] < o ? o : k[r];
-                    k[r] = (lower == up) ? mn : mx;
+                    k[r] = keep_of_pair(k[r], xor_lane_u64(k[r], stride), lower == up);
                 }
             }
         }
@@ -95,10 +128,8 @@ __device__ __forceinline__ u64 group_sort(u64 k, int lane)
 #pragma unroll
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
             const bool up = (sub & size) == 0;      // for size == G: always ascending
-            const u64 o = shfl_xor_u64(k, stride);
             const bool lower = (lane & stride) == 0;
-            const u64 mn = k < o ? k : o, mx = k < o ? o : k;
-            k = (lower == up) ? mn : mx;
+            k = keep_of_pair(k, xor_lane_u64(k, stride), lower == up);
         }
     }
     return k;
