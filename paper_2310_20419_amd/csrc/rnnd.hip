@@ -332,16 +332,35 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int
     const u32 n = ctr->n_active[c];
     const int *list = lists + (size_t)c * N;
     bool surplus = false;
-    for (u32 it = g; it < n; it += ng) {
-        const int u = list[it];
-        const int np = nprop[u];
+    if (g >= n) return;
+    // the loads of the next vertex (its count and its first 16 edges) are issued before the atomics
+    // of the current one; the list entry of the vertex after that is fetched one trip earlier still
+    auto vertex_at = [&](unsigned long long i) -> int { return i < n ? list[i] : -1; };
+    auto first_edges = [&](int u, int &np, Prop &pr) {
+        np = 0;
+        pr.key = 0; pr.tgt = 0xFFFFFFFFu; pr.arrival = 0;
+        if (u >= 0) {
+            np = nprop[u];
+            if (sub < R) pr = props[(size_t)u * R + sub];   // slots past np exist; masked below
+        }
+    };
+    int u = vertex_at(g), np;
+    Prop pr0;
+    first_edges(u, np, pr0);
+    int u_next = vertex_at((unsigned long long)g + ng);
+    for (unsigned long long it = g; it < n; it += ng) {
+        int np_next;
+        Prop pr_next;
+        first_edges(u_next, np_next, pr_next);
+        const int u_after = vertex_at(it + 2ull * ng);
+
         bool mine_surplus = false;
         for (int p0 = 0; p0 < np; p0 += 16) {      // same trip count for the whole group
             const int p = p0 + sub;
             const bool have = p < np;
-            Prop pr;
-            pr.key = 0; pr.tgt = 0xFFFFFFFFu; pr.arrival = 0;
-            if (have) pr = props[(size_t)u * R + p];
+            Prop pr = pr0;
+            if (p0 > 0 && have) pr = props[(size_t)u * R + p];
+            if (!have) pr.tgt = 0xFFFFFFFFu;
             // lanes of my group with my target
             u32 same = 0;
 #pragma unroll
@@ -369,6 +388,8 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int
             if (sub == 0) nprop[u] = np | SURPLUS_MARK;
             surplus = true;
         }
+        u = u_next; np = np_next; pr0 = pr_next;
+        u_next = u_after;
     }
     if (surplus) ctr->has_surplus = 1u;
 }
@@ -989,7 +1010,7 @@ template <int KS>
 static void launch_mfma_scan_classes(const Workspace &w, const void *X, int R, u64 *keys, int *deg,
                                      long long N, RoundCtr *c, hipStream_t st, const RoundEvents &re)
 {
-    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_small<KS>, 5);
+    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_small<KS>, 4);
     const int n_big = (R > 32) + (R > 64) + (R > 96);   // launches after the short-list kernel
     const int ny = 1 + (R > 8) + (R > 16);
     hipExtLaunchKernelGGL((k_update_scan_mfma_u8_small<KS>), dim3(cu_count() * per_cu, ny), dim3(256), 0, st,

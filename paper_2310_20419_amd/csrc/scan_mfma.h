@@ -379,7 +379,7 @@ template <int P, int KS>
 __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[KS], MfmaScanSmem<1> &sm, int R,
                                                  u64 *__restrict__ keys, int *__restrict__ deg,
                                                  Prop *__restrict__ props, int *__restrict__ nprop, int lane,
-                                                 u64 &tiles, u64 &rows, u64 &nprops_total, u32 &ev_lane)
+                                                 u32 &tiles, u32 &rows, u32 &nprops_total, u32 &ev_lane)
 {
     constexpr int W = 32 / P;
     const int l32 = lane & 31, half = lane >> 5, seg = l32 / W, pos = l32 % W;
@@ -514,7 +514,7 @@ __device__ __forceinline__ void scan_packed_body(const int8_t *__restrict__ X, i
     const int seg = l32 / W, pos = l32 % W;
     const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
     const u32 n_groups = (n_active + (u32)P - 1u) / (u32)P;
-    u64 tiles = 0, rows = 0, nprops_total = 0;
+    u32 tiles = 0, rows = 0, nprops_total = 0;   // per wavefront: far below 2^32
     u32 ev_lane = 0;
 
     if (gw >= n_groups) return;
@@ -552,13 +552,13 @@ __device__ __forceinline__ void scan_packed_body(const int8_t *__restrict__ X, i
     u64 evals_algo = ev_lane;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) evals_algo += shfl_xor_u64(evals_algo, o);
-    if (lane == 0 && rows) add_round_stats(ctr, evals_algo, tiles * 1024ull, rows, nprops_total);
+    if (lane == 0 && rows) add_round_stats(ctr, evals_algo, (u64)tiles * 1024ull, rows, nprops_total);
 }
 
 // The three short-list classes in one launch: blockIdx.y = degree class (lists of at most 8, 16, 32
 // entries: 4, 2, 1 vertices per wavefront).  Each class is walked by the gridDim.x blocks of its row.
 template <int KS>
-__global__ __launch_bounds__(256, 5) void k_update_scan_mfma_u8_small(
+__global__ __launch_bounds__(256, 4) void k_update_scan_mfma_u8_small(
     const int8_t *__restrict__ X, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ lists, long long N, Prop *__restrict__ props, int *__restrict__ nprop,
     RoundCtr *__restrict__ ctr)
