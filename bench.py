@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per scan launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by
 # a plain 1 GiB copy in the same run); see profiles/update_scan_cfg3_hbm_traffic.txt.  Keyed by
 # (workload, kernel variant); None where it has not been measured.
-TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.176e9}
+TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.022e9}
 
 
 def cpu_baseline(cfg, X, sample_n):
@@ -134,7 +134,9 @@ def main():
     scan_ms = sum(s["scan_ms"])
     hbm_gbs = scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
     kv = s["kernel_variant"]
-    kname = {1: "k_update_scan", 2: "k_update_scan_mfma_u8<NG,%d> (NG = 1,2,3 back to back per round)" % (cfg.d // 32),
+    kname = {1: "k_update_scan",
+             2: "k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8<NG,%d>, NG = 2,3 (one round's scan launches, "
+                "back to back)" % (cfg.d // 32, cfg.d // 32),
              3: "k_update_scan_mfma_f32<NG,CH> (NG = 1,2,3 back to back per round)"}[kv]
     if kv == 3:
         # float rows: the Gram tiles run on the f64 matrix cores and bound the kernel for large d;
