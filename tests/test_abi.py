@@ -52,8 +52,13 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
 
 def test_workspace_bytes(lib):
     b = rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 96)
-    # graph (8 B) + overflow list (16 B) + bins (8 B) per slot, plus a 64-key inbox per vertex, dominate
-    assert 1_000_000 * (96 * 32 + 512) <= b < 1_000_000 * (96 * 32 + 512 + 128)
+    # graph (8 B) + redirected-edge slots (16 B) + bins (8 B) per list slot, a 64-key inbox per vertex, and
+    # (uint8 rows of 32/64/128 bytes) the int8 copy of X dominate; small per-vertex arrays on top
+    per_vertex = 96 * 32 + 512 + 128
+    assert 1_000_000 * per_vertex <= b < 1_000_000 * (per_vertex + 128)
+    # float rows have no int8 copy
+    bf = rn.rnnd_workspace_bytes(1_000_000, 96, rn.RNND_F32, 96)
+    assert 1_000_000 * (96 * 32 + 512) <= bf < 1_000_000 * (96 * 32 + 512 + 128)
     with pytest.raises(rn.RnndError):
         rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 500)
 
