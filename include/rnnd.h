@@ -120,6 +120,29 @@ int rnnd_add_reverse_edges(int64_t N, int32_t R, uint64_t *keys, int32_t *deg, v
 int rnnd_export_graph(int64_t N, int32_t R, const uint64_t *keys, const int32_t *deg,
                       int32_t *graph_out, int32_t *degree_out, void *stream);
 
+/* Search (Alg. 1) on a built graph, with the out-degree cap K of Eq. 4 (Sec. 5.2): for each of nq
+ * queries, the candidate list C of at most L points starts from min(L, N) distinct seeded random
+ * vertices (InitializeCandidates is not specified by the paper; the generator is the one RandomGraph
+ * uses, keyed by seed + 0x9E3779B97F4A7C15 * query index), the nearest unvisited member of C is
+ * expanded through its first min(degree, K) neighbours until C holds no unvisited point, and the k
+ * nearest members of C are written, nearest first, ties by id.
+ *   X          device, N x d row-major, as for rnnd_build; graph / degree: device, the output format of
+ *              rnnd_build (row u = neighbour ids nearest-first, degree[u] valid entries), rows
+ *              row_stride ints apart; entries that are not vertex ids are ignored.
+ *   Q          device, nq x d row-major, same dtype as X.
+ *   L, K, k    1 <= k <= L <= 128, K >= 1 (K >= row_stride: no cap).
+ *   out_ids    device, nq x k; -1 where C has fewer than k members.
+ *   out_dist_bits  device, nq x k, or NULL: delta(q, id) as for the build's keys (the int32 value for
+ *              uint8 data, the float's bit pattern for float32); 0xFFFFFFFF where out_ids is -1.
+ *   dist_evals host, or NULL: number of delta(q, .) evaluations over all queries.
+ * Work is enqueued on `stream` and the call returns after it has completed; a bitmap of N bits per
+ * wavefront in flight (at most 1 GiB in all) is allocated and freed inside the call.  Caller keeps
+ * ownership of every buffer.  Errors as for rnnd_build (RNND_ERR_BAD_PARAM for L, K, k, row_stride). */
+int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int metric, const int32_t *graph,
+                const int32_t *degree, int32_t row_stride, const void *Q, int64_t nq, int32_t L,
+                int32_t K, int32_t k, uint64_t seed, int32_t *out_ids, uint32_t *out_dist_bits,
+                int64_t *dist_evals, void *stream);
+
 /* Selects the UpdateNeighbors scan kernel: 0 = automatic (default), 1 = generic pair-at-a-time
  * kernel for every input.  Automatic uses the dense Gram-block kernels on the matrix cores where
  * they apply (uint8 with d = 32, 64 or 128: int8 MFMA; float32 with d a multiple of 16: f64 MFMA)

@@ -90,12 +90,14 @@ def load_library():
                                             c.POINTER(Stats), vp]
         L.rnnd_add_reverse_edges.argtypes = [i64, i32, vp, vp, vp]
         L.rnnd_export_graph.argtypes = [i64, i32, vp, vp, vp, vp, vp]
+        L.rnnd_search.argtypes = [vp, i64, i32, c.c_int, c.c_int, vp, vp, i32, vp, i64, i32, i32, i32, c.c_uint64,
+                                  vp, vp, c.POINTER(c.c_int64), vp]
         L.rnnd_set_kernel_variant.argtypes = [c.c_int]
         L.rnnd_strerror.argtypes = [c.c_int]
         L.rnnd_strerror.restype = c.c_char_p
         L.rnnd_version.restype = c.c_int
         for name in ("rnnd_build", "rnnd_build_ex", "rnnd_workspace_bytes", "rnnd_random_graph",
-                     "rnnd_update_neighbors", "rnnd_add_reverse_edges", "rnnd_export_graph",
+                     "rnnd_update_neighbors", "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search",
                      "rnnd_set_kernel_variant"):
             getattr(L, name).restype = c.c_int
         _lib = L
@@ -207,6 +209,24 @@ def rnnd_export_graph(keys, deg, R: int, stream=None):
     _check(load_library().rnnd_export_graph(N, R, keys.data_ptr(), deg.data_ptr(), graph.data_ptr(),
                                             degree.data_ptr(), _stream(stream)))
     return graph, degree
+
+
+def rnnd_search(X, graph, degree, Q, L: int, K: int, k: int, seed: int, want_dist: bool = False,
+                metric: int = RNND_L2SQ, stream=None):
+    """Alg. 1 with the cap K on the GPU.  Returns (ids int32 [nq, k], dist_bits int32 [nq, k] or None, evals)."""
+    torch = _torch()
+    ptr, N, d, dt = _data_args(X)
+    assert Q.is_cuda and Q.is_contiguous() and Q.dtype == X.dtype and Q.dim() == 2 and Q.shape[1] == d
+    assert graph.is_cuda and graph.is_contiguous() and graph.dtype == torch.int32 and graph.shape[0] == N
+    assert degree.is_cuda and degree.is_contiguous() and degree.dtype == torch.int32 and degree.shape == (N,)
+    nq = Q.shape[0]
+    ids = torch.empty((nq, k), dtype=torch.int32, device=X.device)
+    dist = torch.empty((nq, k), dtype=torch.int32, device=X.device) if want_dist else None
+    ev = ctypes.c_int64(0)
+    _check(load_library().rnnd_search(ptr, N, d, dt, metric, graph.data_ptr(), degree.data_ptr(), graph.shape[1],
+                                      Q.data_ptr(), nq, L, K, k, seed, ids.data_ptr(),
+                                      dist.data_ptr() if want_dist else None, ctypes.byref(ev), _stream(stream)))
+    return ids, dist, ev.value
 
 
 def rnnd_set_kernel_variant(variant: int):

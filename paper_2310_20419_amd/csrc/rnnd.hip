@@ -72,6 +72,7 @@ __device__ __forceinline__ void emit_redirect(u64 key, u32 tgt, Prop *slot)
 #include "dist.h"
 #include "scan_mfma.h"
 #include "scan_mfma_f32.h"
+#include "search.h"
 
 // Degree class of a list of m entries.  use_classes 0: one list for all (generic scan);
 // 1: lists 2..5 (up to 32, 64, 96, 128 entries: one, two, three, four 32-row blocks per wavefront);
@@ -84,16 +85,7 @@ __device__ __forceinline__ int degree_class(int m, int use_classes)
 }
 
 // ------------------------------------------------------------------ RandomGraph
-__device__ __forceinline__ u64 mix64(u64 z)
-{
-    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
-    z ^= z >> 27; z *= 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return z;
-}
-
-// Alg. 6 lines 1-2.  Draws are examined 64 at a time; a draw is accepted iff its id differs from
-// every earlier draw's id, which is the same set, in the same order, as accepting one by one.
+// Alg. 6 lines 1-2: S distinct random neighbours (wave_random_ids), their distances, sorted.
 template <int DT>
 __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long N, int d, int vec_ok,
                                                         int S, int R, u64 seed, u64 *keys, int *deg,
@@ -106,42 +98,7 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
     if (u >= N) return;
     int *ids = s_ids[wave];
     const size_t rowbytes = (size_t)d * (DT == DT_U8 ? 1 : 4);
-    const u64 hu = mix64(seed + GOLDEN64 * (u64)(u + 1));
-    const u64 jmax = 64ull * (u64)S + 1024ull;
-    int cnt = 0;
-    for (u64 j0 = 0; j0 < jmax && cnt < S;) {
-        // examine the next W draws (a few more than still needed; any W gives the same result)
-        const int W = (S - cnt) + 12 < 64 ? (S - cnt) + 12 : 64;
-        u64 j = j0 + lane;
-        u64 z = mix64(hu + GOLDEN64 * (j + 1));
-        u64 c = ((z >> 32) * (u64)(N - 1)) >> 32;
-        int id = (int)(c + (c >= (u64)u ? 1 : 0));
-        bool ok = lane < W && j < jmax;
-        for (int k = 0; k < cnt; ++k) ok = ok && (ids[k] != id);
-        for (int l = 0; l < W - 1; ++l) {
-            int o = __shfl(id, l);
-            if (l < lane && o == id) ok = false;
-        }
-        u64 m = __builtin_amdgcn_ballot_w64(ok);
-        int pos = cnt + __popcll(m & lanes_below(lane));
-        if (ok && pos < S) ids[pos] = id;
-        cnt += __popcll(m);
-        if (cnt > S) cnt = S;
-        j0 += W;
-        wave_sync();
-    }
-    if (cnt < S) {   // fallback, practically unreachable: smallest unused ids
-        for (long long id = 0; id < N && cnt < S; ++id) {
-            if (id == u) continue;
-            bool dup = false;
-            for (int k = 0; k < cnt; ++k) dup = dup || (ids[k] == (int)id);
-            if (!dup) {
-                if (lane == 0) ids[cnt] = (int)id;
-                ++cnt;
-                wave_sync();
-            }
-        }
-    }
+    wave_random_ids(seed, N, u, S, ids, lane);
     // delta(u, id): 8 rows at a time, 8 lanes per row
     const char *xu = (const char *)X + (size_t)u * rowbytes;
     for (int b = 0; b < S; b += 8) {
@@ -1353,9 +1310,60 @@ done:
     return rc;
 }
 
+extern "C" int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int metric, const int32_t *graph,
+                           const int32_t *degree, int32_t row_stride, const void *Q, int64_t nq, int32_t L,
+                           int32_t K, int32_t k, uint64_t seed, int32_t *out_ids, uint32_t *out_dist_bits,
+                           int64_t *dist_evals, void *stream)
+{
+    int rc = check_data_args(X, N, d, dtype, metric, 1);
+    if (rc) return rc;
+    if (nq < 0 || nq > 2147483646LL) return RNND_ERR_BAD_SHAPE;
+    if (row_stride < 1 || L < 1 || L > SEARCH_MAX_L || K < 1 || k < 1 || k > L) return RNND_ERR_BAD_PARAM;
+    if (!graph || !degree || ((!out_ids || !Q) && nq > 0)) return RNND_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (dist_evals) *dist_evals = 0;
+    if (nq == 0) return RNND_OK;
+    const size_t rowbytes = (size_t)d * (dtype == RNND_U8 ? 1 : 4);
+    const int vec_ok = (rowbytes % 16 == 0) && (((uintptr_t)X) % 16 == 0) && (((uintptr_t)Q) % 16 == 0);
+    // one bitmap of N bits per wavefront in flight; at most 1 GiB of them, at most 8 wavefronts per SIMD
+    const size_t bitmap_words = (((size_t)N + 31) / 32 + 63) / 64 * 64;
+    long long waves = (long long)cu_count() * 32;
+    const long long by_mem = (long long)((1ull << 30) / (bitmap_words * 4));
+    if (waves > by_mem) waves = by_mem;
+    if (waves > nq) waves = nq;
+    if (waves < 1) waves = 1;
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    const size_t bm_bytes = (size_t)blocks * 4 * bitmap_words * 4;
+    char *base = nullptr;
+    unsigned long long h_evals = 0;
+    HIPCHK(hipMalloc((void **)&base, bm_bytes + 256));
+    HIPCHK(hipMemsetAsync(base, 0, bm_bytes + 256, st));
+    {
+        u32 *bitmaps = (u32 *)base;
+        unsigned long long *d_evals = (unsigned long long *)(base + bm_bytes);
+#define RNND_SEARCH_LAUNCH(DT, E)                                                                            \
+    hipLaunchKernelGGL((k_search<DT, E>), dim3(blocks), dim3(256), 0, st, X, (long long)N, d, vec_ok, graph, \
+                       degree, row_stride, Q, (long long)nq, L, K, k, (u64)seed, bitmaps, bitmap_words,      \
+                       out_ids, out_dist_bits, d_evals)
+        if (dtype == RNND_U8) {
+            if (L <= 64) RNND_SEARCH_LAUNCH(DT_U8, 1); else RNND_SEARCH_LAUNCH(DT_U8, 2);
+        } else {
+            if (L <= 64) RNND_SEARCH_LAUNCH(DT_F32, 1); else RNND_SEARCH_LAUNCH(DT_F32, 2);
+        }
+#undef RNND_SEARCH_LAUNCH
+        HIPCHK(hipGetLastError());
+        HIPCHK(hipMemcpyAsync(&h_evals, d_evals, sizeof h_evals, hipMemcpyDeviceToHost, st));
+        HIPCHK(hipStreamSynchronize(st));
+        if (dist_evals) *dist_evals = (int64_t)h_evals;
+    }
+done:
+    if (base) (void)hipFree(base);
+    return rc;
+}
+
 extern "C" int rnnd_set_kernel_variant(int variant)
 {
-    if (variant < 0 || variant > 2) return RNND_ERR_BAD_PARAM;
+    if (variant < 0 || variant > 1) return RNND_ERR_BAD_PARAM;
     g_kernel_variant = variant;
     return RNND_OK;
 }
@@ -1374,4 +1382,4 @@ extern "C" const char *rnnd_strerror(int status)
     }
 }
 
-extern "C" int rnnd_version(void) { return 101; }
+extern "C" int rnnd_version(void) { return 102; }

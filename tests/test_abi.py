@@ -19,7 +19,7 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     names = rn.exported_symbols()
     assert {"rnnd_build", "rnnd_build_ex", "rnnd_random_graph", "rnnd_update_neighbors",
-            "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_workspace_bytes",
+            "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search", "rnnd_workspace_bytes",
             "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
