@@ -245,6 +245,13 @@ def test_cfg3_full_size_parity(rn, oracle_mod):
     assert (graph.cpu().numpy() == want.snap.ids).all()
     assert list(st.algo_evals[:60]) == want.round_evals.tolist()
     assert list(st.proposals[:60]) == want.round_props.tolist()
+    # search on the full-size graph: GPU search against the oracle's, 300 of the configuration's queries
+    Q = wl.make_queries(c, 300)
+    for L, K in ((64, 32), (128, 96)):
+        found, _, evals = rn.rnnd_search(cuda(X), graph, degree, cuda(Q), L, K, 10, 7)
+        wfound, wevals = oracle_mod.search(X, want.snap.ids, want.snap.deg, Q, L, K, 10, 7)
+        assert (found.cpu().numpy() == wfound).all() and evals == wevals
+        print("search parity ok: L %d K %d, %.0f evaluations per query" % (L, K, evals / 300), flush=True)
 
 
 FULL = os.environ.get("RNND_FULL_PARITY", "") == "1"
