@@ -642,33 +642,73 @@ __global__ __launch_bounds__(1024) void k_compact_classes(const u32 *n_ptr, u32 
 // ------------------------------------------------------------ AddReverseEdges
 // Alg. 5 lines 1-5 need, for every x, the edges that point to x.  Every edge (u, v) takes an arrival
 // number at v (one atomic on fill[v]); the first INBOX_CAP arrivals are written to v's inbox as
-// key(delta, u, new).  A vertex that receives more gets a bin afterwards and k_fill_bins places all of
-// its incoming edges there.
+// key(delta, u, new).  A later arrival is remembered with its edge (late[] holds its number, over[u]
+// one bit per list position of u, mark[u] says that u has any) and k_reverse_surplus places it in
+// v's bin once bins exist.
 __global__ __launch_bounds__(BLOCK) void k_reverse_scatter(long long N, int R, const u64 *keys, const int *deg,
-                                                           int *fill, u64 *inbox)
+                                                           int *fill, u64 *inbox, u32 *late, u64 *over,
+                                                           int8_t *mark)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
     if (u >= N) return;
     const int m = deg[u];
-    for (int e = lane; e < m; e += 64) {
-        const u64 k = keys[(size_t)u * R + e];
-        const u32 v = key_id(k);
-        const int a = atomicAdd(&fill[v], 1);
-        if (a < INBOX_CAP) inbox[(size_t)v * INBOX_CAP + a] = make_key(key_dist(k), (u32)u, 1u);
+    u64 ov[2] = {0ull, 0ull};
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int e = 64 * r + lane;
+        bool is_late = false;
+        if (e < m) {
+            const u64 k = keys[(size_t)u * R + e];
+            const u32 v = key_id(k);
+            const int a = atomicAdd(&fill[v], 1);
+            if (a < INBOX_CAP) {
+                inbox[(size_t)v * INBOX_CAP + a] = make_key(key_dist(k), (u32)u, 1u);
+            } else {
+                late[(size_t)u * R + e] = (u32)a;
+                is_late = true;
+            }
+        }
+        ov[r] = __builtin_amdgcn_ballot_w64(is_late);
+    }
+    if (lane == 0) {
+        const bool any = (ov[0] | ov[1]) != 0;
+        mark[u] = (int8_t)any;
+        if (any) { over[2 * u] = ov[0]; over[2 * u + 1] = ov[1]; }
     }
 }
 
-// For every edge (u, v) whose v owns a bin: bins[v] <- key(delta, u, flag).  Nothing to do when no
-// bin was handed out (*n_binned == 0).
-__global__ __launch_bounds__(BLOCK) void k_fill_bins(long long N, int R, const u64 *keys, const int *deg,
-                                                     const int *binoff, int *fill, u64 *bins, u32 flag,
-                                                     const u32 *n_binned)
+// The late arrivals of k_reverse_scatter go to their targets' bins (which hold arrivals INBOX_CAP, ...).
+__global__ __launch_bounds__(BLOCK) void k_reverse_surplus(long long N, int R, const u64 *keys, const u32 *late,
+                                                           const u64 *over, const int8_t *mark,
+                                                           const int *binoff, u64 *bins, const u32 *n_binned)
 {
     if (*n_binned == 0u) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
-    if (u >= N) return;
+    if (u >= N || !mark[u]) return;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const u64 ov = over[2 * u + r];
+        if ((ov >> lane) & 1ull) {
+            const int e = 64 * r + lane;
+            const u64 k = keys[(size_t)u * R + e];
+            const u32 v = key_id(k);
+            bins[(size_t)binoff[v] + (late[(size_t)u * R + e] - INBOX_CAP)] = make_key(key_dist(k), (u32)u, 1u);
+        }
+    }
+}
+
+// For every edge (u, v) of a flagged list whose v owns a bin: bins[v] <- key(delta, u, flag).  Nothing to
+// do when no bin was handed out (*n_binned == 0).
+__global__ __launch_bounds__(BLOCK) void k_fill_bins(long long N, int R, const u64 *keys, const int *deg,
+                                                     const int8_t *rowflag, const int *binoff, int *fill,
+                                                     u64 *bins, u32 flag, const u32 *n_binned)
+{
+    if (*n_binned == 0u) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
+    if (u >= N || !rowflag[u]) return;
     const int m = deg[u];
     for (int e = lane; e < m; e += 64) {
         const u64 k = keys[(size_t)u * R + e];
@@ -681,12 +721,12 @@ __global__ __launch_bounds__(BLOCK) void k_fill_bins(long long N, int R, const u
 // Alg. 5 lines 1-5: list(x) <- first R distinct of list(x) + reversed edges into x (flag new).
 // Then the edges of the new list are counted at those targets that can end up with more than R
 // incoming edges (cand[v]: |list(v)| + |edges into v| > R before the union; for every other vertex
-// the union itself bounds the in-degree by R).  vcls[x] <- degree class if the list holds a "new"
-// entry, else -1.
+// the union itself bounds the in-degree by R); rowflag[x] says whether the list has such an edge.
+// vcls[x] <- degree class if the list holds a "new" entry, else -1.
 __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64 *keys, int *deg, int *fill,
                                                          const u64 *inbox, const int *binoff, const u64 *bins,
-                                                         const int8_t *cand, int *cnt_in, int8_t *vcls,
-                                                         int use_classes)
+                                                         const int8_t *cand, int *cnt_in, int8_t *rowflag,
+                                                         int8_t *vcls, int use_classes)
 {
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -697,21 +737,26 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64
     int nd = deg[x];
     if (c > 0) {
         bool any_new;
-        const u64 *src = c <= INBOX_CAP ? inbox + (size_t)x * INBOX_CAP : bins + binoff[x];
-        nd = wave_merge_row(row, nd, src, c, src, 0, R, s_stage[wave], lane, &any_new);
+        const int ca = c < INBOX_CAP ? c : INBOX_CAP;
+        nd = wave_merge_row(row, nd, inbox + (size_t)x * INBOX_CAP, ca, bins + (c > ca ? binoff[x] : 0), c - ca, R,
+                            s_stage[wave], lane, &any_new);
         wave_sync();    // the list is read back below by other lanes of this wavefront
     }
-    bool nw = false;
+    bool nw = false, cd = false;
     for (int e = lane; e < nd; e += 64) {
         const u64 k = row[e];
         nw = nw || (k & 1ull);
         const u32 v = key_id(k);
-        if (cand[v]) atomicAdd(&cnt_in[v], 1);
+        if (cand[v]) {
+            atomicAdd(&cnt_in[v], 1);
+            cd = true;
+        }
     }
-    const u64 b = __builtin_amdgcn_ballot_w64(nw);
+    const u64 b = __builtin_amdgcn_ballot_w64(nw), bc = __builtin_amdgcn_ballot_w64(cd);
     if (lane == 0) {
         deg[x] = nd;
         fill[x] = 0;
+        rowflag[x] = (int8_t)(bc != 0);
         vcls[x] = b ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
     }
 }
@@ -740,13 +785,13 @@ __global__ __launch_bounds__(BLOCK) void k_incap_threshold(int R, const int *lis
 // Alg. 5 lines 6-8, second half: edge (u, v) survives iff (delta, u) <= thr[v]; vcls[u] follows the
 // new degree.  Nothing to do when no vertex has more than R incoming edges (*n_hubs == 0).
 __global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 *keys, int *deg,
-                                                        const u64 *thr, int8_t *vcls, int use_classes,
-                                                        const u32 *n_hubs)
+                                                        const u64 *thr, const int8_t *rowflag, int8_t *vcls,
+                                                        int use_classes, const u32 *n_hubs)
 {
     if (*n_hubs == 0u) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
-    if (u >= N) return;
+    if (u >= N || !rowflag[u]) return;   // a list without an edge to a candidate cannot lose one
     const int m = deg[u];
     u64 *row = keys + (size_t)u * R;
     u64 k[2];
@@ -1044,34 +1089,37 @@ static void launch_compact_all(const Workspace &w, long long N, int t_next, hipS
 }
 
 // AddReverseEdges; the active lists for round t_next are rebuilt from scratch.  Expects fill[] == 0
-// and leaves it so.  Between rounds nprop[] and tcls[] are free: they serve as the second in-edge
-// count and the candidate marks.  misc: [0] bin cursor, [1] vertices with a bin (lines 1-5),
+// and leaves it so.  Between rounds nprop[], tcls[], props[] and touched[] are free: they serve as the
+// second in-edge count, the per-vertex marks, the late arrival numbers and their position masks.  misc: [0] bin cursor, [1] vertices with a bin (lines 1-5),
 // [2] bin cursor, [3] vertices with more than R incoming edges (lines 6-8).
 static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use_classes, u64 *keys, int *deg,
                                  int t_next, hipStream_t st, hipEvent_t e_stop = nullptr)
 {
     const int vb = vertex_blocks(N), tb = (int)((N + 1023) / 1024);
     int *cnt_in = w.nprop;
-    int8_t *cand = w.tcls;
+    int8_t *cand = w.tcls, *rowflag = w.tcls + N, *mark = w.tcls + 2 * N;
+    u32 *late = (u32 *)w.props;          // one word per list slot (props is 16 bytes per slot)
+    u64 *over = (u64 *)w.touched;        // two words per vertex (touched is 16 bytes per vertex)
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, 8);
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NDEG);
     // lines 1-5: union with reversed edges, out-lists cut to R
-    hipLaunchKernelGGL(k_reverse_scatter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox);
-    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.fill, INBOX_CAP, INBOX_CAP, 0, w.binoff,
-                       w.misc + 0, w.hubs, w.misc + 1, w.cnt, cnt_in, (u64 *)nullptr, deg, R, cand);
-    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.cnt, w.bins, 1u,
-                       w.misc + 1);
+    hipLaunchKernelGGL(k_reverse_scatter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, late, over,
+                       mark);
+    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.fill, INBOX_CAP, INBOX_CAP, INBOX_CAP,
+                       w.binoff, w.misc + 0, w.hubs, w.misc + 1, w.cnt, cnt_in, (u64 *)nullptr, deg, R, cand);
+    hipLaunchKernelGGL(k_reverse_surplus, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, late, over, mark, w.binoff,
+                       w.bins, w.misc + 1);
     hipLaunchKernelGGL(k_reverse_merge, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, w.binoff,
-                       w.bins, cand, cnt_in, w.vcls, use_classes);
+                       w.bins, cand, cnt_in, rowflag, w.vcls, use_classes);
     // lines 6-8: in-lists cut to R; only vertices with more than R incoming edges need a bin
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, cnt_in, R, R, 0, w.binoff, w.misc + 2, w.hubs,
                        w.misc + 3, w.cnt, (int *)nullptr, w.thr, (const int *)nullptr, 0, (int8_t *)nullptr);
-    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.binoff, w.cnt, w.bins, 0u,
-                       w.misc + 3);
+    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, rowflag, w.binoff, w.cnt, w.bins,
+                       0u, w.misc + 3);
     hipLaunchKernelGGL(k_incap_threshold, dim3(persistent_blocks()), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 3,
                        cnt_in, w.binoff, w.bins, w.thr);
-    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, w.vcls, use_classes,
-                       w.misc + 3);
+    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, rowflag, w.vcls,
+                       use_classes, w.misc + 3);
     launch_compact_all(w, N, t_next, st, e_stop);
     return hipGetLastError();
 }
