@@ -1023,15 +1023,15 @@ static void launch_mfma_scan_classes(const Workspace &w, const void *X, int R, u
     if (R > 96) launch_mfma_scan<4, KS>(w, X, R, keys, deg, N, c, st, n_big == 3 ? re.scan_stop : nullptr);
 }
 
-template <int NG, int CH>
+template <int NG, int CH, int NRC>
 static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, long long N,
-                            RoundCtr *c, hipStream_t st, hipEvent_t e_start, hipEvent_t e_stop)
+                            RoundCtr *c, int cls, hipStream_t st, hipEvent_t e_start, hipEvent_t e_stop)
 {
     // wavefronts that fit per SIMD: about 4 for NG = 1, 2 for NG = 2, 1 for NG = 3 (21 accumulator tiles)
-    const int per_cu = NG == 1 ? 4 : NG == 2 ? 2 : 1;
-    hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH>), dim3(cu_count() * per_cu), dim3(256), 0, st, e_start,
-                          e_stop, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)(NG + 1) * N,
-                          &c->n_active[NG + 1], w.props, w.nprop, c);
+    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC>, NG == 1 ? 4 : NG == 2 ? 2 : 1);
+    hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC>), dim3(cu_count() * per_cu), dim3(256), 0, st, e_start,
+                          e_stop, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
+                          &c->n_active[cls], w.props, w.nprop, c);
 }
 
 // One synchronous UpdateNeighbors round t (ctr[t] -> ctr[t+1]).
@@ -1041,19 +1041,30 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
 {
     const int pb = persistent_blocks();
     RoundCtr *c = w.ctr + t;
-    const int use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
+    const int use_classes = variant >= 2 ? 2 : 0;
     if (variant == 2) {
         if (d == 32) launch_mfma_scan_classes<1>(w, X, R, keys, deg, N, c, st, re);
         else if (d == 64) launch_mfma_scan_classes<2>(w, X, R, keys, deg, N, c, st, re);
         else launch_mfma_scan_classes<4>(w, X, R, keys, deg, N, c, st, re);
     } else if (variant == 3) {
-        const int n_more = (R > 32) + (R > 64) + (R > 96);
-        if (d % 32 == 0) launch_f32_scan<1, 2>(w, X, d, R, keys, deg, N, c, st, re.scan_start, n_more == 0 ? re.scan_stop : nullptr);
-        else launch_f32_scan<1, 1>(w, X, d, R, keys, deg, N, c, st, re.scan_start, n_more == 0 ? re.scan_stop : nullptr);
-        if (R > 32) launch_f32_scan<2, 1>(w, X, d, R, keys, deg, N, c, st, nullptr, n_more == 1 ? re.scan_stop : nullptr);
-        if (R > 64) launch_f32_scan<3, 1>(w, X, d, R, keys, deg, N, c, st, nullptr, n_more == 2 ? re.scan_stop : nullptr);
+        // degree classes 0 (at most 8 entries) and 1 (at most 16): one 16-row group; 2: two; 3, 4: NG = 2, 3
+        const int n_more = (R > 8) + (R > 16) + (R > 32) + (R > 64) + (R > 96);
+        int k = 0;
+        auto stop_for = [&](void) { return k++ == n_more ? re.scan_stop : (hipEvent_t) nullptr; };
+        if (d % 32 == 0) launch_f32_scan<1, 2, 1>(w, X, d, R, keys, deg, N, c, 0, st, re.scan_start, stop_for());
+        else launch_f32_scan<1, 1, 1>(w, X, d, R, keys, deg, N, c, 0, st, re.scan_start, stop_for());
+        if (R > 8) {
+            if (d % 32 == 0) launch_f32_scan<1, 2, 1>(w, X, d, R, keys, deg, N, c, 1, st, nullptr, stop_for());
+            else launch_f32_scan<1, 1, 1>(w, X, d, R, keys, deg, N, c, 1, st, nullptr, stop_for());
+        }
+        if (R > 16) {
+            if (d % 32 == 0) launch_f32_scan<1, 2, 2>(w, X, d, R, keys, deg, N, c, 2, st, nullptr, stop_for());
+            else launch_f32_scan<1, 1, 2>(w, X, d, R, keys, deg, N, c, 2, st, nullptr, stop_for());
+        }
+        if (R > 32) launch_f32_scan<2, 1, 4>(w, X, d, R, keys, deg, N, c, 3, st, nullptr, stop_for());
+        if (R > 64) launch_f32_scan<3, 1, 6>(w, X, d, R, keys, deg, N, c, 4, st, nullptr, stop_for());
         if (R > 96)   // lists of 97..128 entries: too many accumulator tiles, generic kernel
-            hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, nullptr, re.scan_stop, 0, X, d,
+            hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, nullptr, stop_for(), 0, X, d,
                                   vec_ok, R, keys, deg, w.lists + (size_t)5 * N, &c->n_active[5], w.props, w.nprop, c);
     } else if (dtype == RNND_U8) {
         hipExtLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
@@ -1163,7 +1174,7 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
     if ((int64_t)T1 * T2 > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int rounds = T1 * T2, n_ctr = rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant >= 2 ? 2 : 0;
     // events (only when statistics are wanted): start, end of init, (scan start, scan stop, round
     // stop) per round, end of each reverse call, end
     const int n_ev = stats ? 3 * rounds + T1 + 3 : 0;
@@ -1292,7 +1303,7 @@ extern "C" int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dt
     if (n_rounds < 1 || n_rounds > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int n_ctr = n_rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant >= 2 ? 2 : 0;
     Workspace w;
     RoundCtr *hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
     if (!hctr) return RNND_ERR_OOM;

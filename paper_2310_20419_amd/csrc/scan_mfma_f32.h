@@ -101,14 +101,17 @@ __device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int 
 
 // CH = 16-dimension chunks fetched per loop iteration (d must be a multiple of 16*CH): a longer iteration
 // gives the prefetch of the next one more matrix work to hide behind.
-template <int NG, int CH>
+// NRC = 16-row groups whose rows are fetched and multiplied: 2 NG, or 1 for lists of at most 16 entries
+// (NG = 1), which then need a single tile.
+template <int NG, int CH, int NRC = 2 * NG>
 __global__ __launch_bounds__(64 * 4, (NG == 1 ? 4 : NG == 2 ? 2 : 1)) void k_update_scan_mfma_f32(
     const float *__restrict__ X, int d, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
     int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
 {
     constexpr int NR = 2 * NG;
-    constexpr int NT = NR * (NR + 1) / 2;
+    constexpr int NT = NRC * (NRC + 1) / 2;
+    static_assert(NRC == NR || (NG == 1 && NRC == 1), "only the one-block kernel has a half-size form");
     __shared__ F32ScanSmem<NG> smem[4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, q = lane >> 4, l32 = lane & 31, half = lane >> 5, sub = lane & 7, grp = lane >> 3;
@@ -133,7 +136,7 @@ __global__ __launch_bounds__(64 * 4, (NG == 1 ? 4 : NG == 2 ? 2 : 1)) void k_upd
 
         const int u = __builtin_amdgcn_readfirstlane(cur.u);      // same in every lane: keep it scalar
         int m = __builtin_amdgcn_readfirstlane(cur.m);
-        if (m > 32 * NG) m = 32 * NG;
+        if (m > 16 * NRC) m = 16 * NRC;   // cannot happen: the list is built per degree class
         if (m > R) m = R;
         u64 *row = keys + (size_t)u * R;
         u64 kreg[2];
@@ -155,37 +158,39 @@ __global__ __launch_bounds__(64 * 4, (NG == 1 ? 4 : NG == 2 ? 2 : 1)) void k_upd
 
             // ---- which 16x16 tiles hold a pair with a new entry (lines 8-9 skip the others)
             u32 new16[NR];
-            const float *rp[NR];
-            bool valid[NR];
+            const float *rp[NRC];
 #pragma unroll
             for (int g = 0; g < NR; ++g) {
                 const int p = 16 * g;   // positions p .. p+15
                 new16[g] = (u32)(newm[p >> 6] >> (p & 63)) & 0xFFFFu;
+            }
+#pragma unroll
+            for (int g = 0; g < NRC; ++g) {
+                const int p = 16 * g;
                 const u32 idr = key_id(kreg[p >> 6]);
                 const int id = __shfl((int)idr, (p & 63) + r16);
-                valid[g] = p + r16 < m;
-                rp[g] = X + (size_t)(valid[g] ? id : 0) * d + 4 * q;   // lanes without a row read row 0
+                rp[g] = X + (size_t)(p + r16 < m ? id : 0) * d + 4 * q;   // lanes without a row read row 0
             }
 
             // ---- Gram block over d in chunks of 16 dimensions
             v4d acc[NT];
 #pragma unroll
             for (int t = 0; t < NT; ++t) acc[t] = (v4d){0.0, 0.0, 0.0, 0.0};
-            double nr[NR];
+            double nr[NRC];
 #pragma unroll
-            for (int g = 0; g < NR; ++g) nr[g] = 0.0;
+            for (int g = 0; g < NRC; ++g) nr[g] = 0.0;
             // tiles worth computing: rows in use, and a new entry among the rows or the columns (lines 8-9)
             u32 need = 0;
 #pragma unroll
-            for (int I = 0; I < NR; ++I)
+            for (int I = 0; I < NRC; ++I)
 #pragma unroll
                 for (int J = 0; J <= I; ++J)
                     if (16 * I < m && (new16[I] | new16[J]) != 0) need |= 1u << (I * (I + 1) / 2 + J);
-            if (NR <= 2) need = (1u << NT) - 1u;
+            if (NRC <= 2) need = (1u << NT) - 1u;
             need = (u32)__builtin_amdgcn_readfirstlane((int)need);
-            gram_f64_loop<NR, CH>(rp, nchunk, acc, nr, need);
+            gram_f64_loop<NRC, CH>(rp, nchunk, acc, nr, need);
 #pragma unroll
-            for (int g = 0; g < NR; ++g) {
+            for (int g = 0; g < NRC; ++g) {
                 nr[g] += __shfl_xor(nr[g], 16);
                 nr[g] += __shfl_xor(nr[g], 32);     // n of row r16 of group g, in all four quarter-waves
                 if (q == 0) sm.nrm[16 * g + r16] = nr[g];
@@ -193,20 +198,21 @@ __global__ __launch_bounds__(64 * 4, (NG == 1 ? 4 : NG == 2 ? 2 : 1)) void k_upd
             wave_sync();
 
             // ---- line 11 for every computed pair; T[I][J]: lane r16 = row r16 of group I, bit c = column c of group J
-            u32 T[NT];
+            u32 T[NR * (NR + 1) / 2];
 #pragma unroll
             for (int I = 0; I < NR; ++I) {
 #pragma unroll
                 for (int J = 0; J <= I; ++J) {
                     const int t = I * (I + 1) / 2 + J;
                     T[t] = 0;
+                    if (I >= NRC) continue;   // rows past the list (half-size form)
                     if ((need >> t) & 1u) tiles += 1;
                     if (16 * I < m && (new16[I] | new16[J]) != 0) {
                         u32 ft = 0;   // lane = column r16 (row r16 of group J); accumulator v = row 4v + q of group I
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
                             const int rowpos = 16 * I + 4 * v + q;
-                            const float dvw = (float)(sm.nrm[rowpos] + nr[J] - 2.0 * acc[t][v]);
+                            const float dvw = (float)(sm.nrm[rowpos] + nr[J < NRC ? J : 0] - 2.0 * acc[t < NT ? t : 0][v]);
                             const float di = __uint_as_float(sm.dist[rowpos]);
                             ft |= (di >= dvw) ? (1u << (4 * v + q)) : 0u;
                         }
