@@ -48,7 +48,7 @@ typedef enum { RNND_L2SQ = 0 } rnnd_metric;
 typedef enum {
     RNND_OK = 0,
     RNND_ERR_NULL = -1,         /* a required pointer is NULL */
-    RNND_ERR_BAD_SHAPE = -2,    /* N < 2, N > 2^31-2, d < 1, or uint8 d > 33025 (int32 overflow) */
+    RNND_ERR_BAD_SHAPE = -2,    /* N < 2, N > 2^31-2, N*R >= 2^32-256, d < 1, or uint8 d > 33025 (int32 overflow) */
     RNND_ERR_BAD_PARAM = -3,    /* S < 1, S > R, S > N-1, R < 1, R > RNND_MAX_R, T1 < 1, T2 < 1 */
     RNND_ERR_UNSUPPORTED = -4,  /* unknown dtype or metric */
     RNND_ERR_OOM = -5,          /* workspace allocation failed */

@@ -930,6 +930,8 @@ static int check_data_args(const void *X, long long N, int d, int dtype, int met
     if (N < 2 || N > 2147483646LL || d < 1) return RNND_ERR_BAD_SHAPE;
     if (dtype == RNND_U8 && d > 33025) return RNND_ERR_BAD_SHAPE;
     if (R < 1 || R > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
+    // list slots are counted in 32-bit device counters (bin space handed out per round)
+    if ((unsigned long long)N * (unsigned long long)R > 0xFFFFFF00ull) return RNND_ERR_BAD_SHAPE;
     return RNND_OK;
 }
 
