@@ -23,7 +23,7 @@
 #define WAVES_PER_BLOCK 4
 #define BLOCK (64 * WAVES_PER_BLOCK)
 #define GOLDEN64 0x9E3779B97F4A7C15ull
-#define NDEG 6   // degree classes of the active lists: at most 8, 16, 32, 64, 96, 128 entries
+#define NDEG 8   // degree classes of the active lists (see degree_class)
 #define NMRG 4   // merge classes of the touched lists: kept + received at most 16, 32, 64, more
 #ifndef INBOX_CAP
 #define INBOX_CAP 64   // redirected edges a vertex can receive per round without the overflow path
@@ -37,7 +37,7 @@ struct RoundCtr {
     u32 n_touched[NMRG];  // distinct targets of the redirected edges, by size of the merge they need
     u32 bin_cursor;       // space handed out in the bin array
     u32 has_surplus;      // some vertex received more than INBOX_CAP edges this round
-    u32 pad[4];
+    u32 pad[2];
     // statistics, spread over STAT_SLOTS addresses so that the adds of many blocks do not queue up
     // on one: [slot][0..3] = algorithmic evals, executed evals, rows gathered, edges redirected
     u64 stat[STAT_SLOTS][4];
@@ -74,14 +74,17 @@ __device__ __forceinline__ void emit_redirect(u64 key, u32 tgt, Prop *slot)
 #include "scan_mfma_f32.h"
 #include "search.h"
 
-// Degree class of a list of m entries.  use_classes 0: one list for all (generic scan);
-// 1: lists 2..5 (up to 32, 64, 96, 128 entries: one, two, three, four 32-row blocks per wavefront);
-// 2: also lists 0 and 1 (up to 8 and 16 entries: four and two vertices share a wavefront).
+// Degree class of a list of m entries: which scan kernel takes it.  use_classes 0: one list for all
+// (generic scan).  2 (uint8 matrix-core scan): classes 0, 1, 2 = at most 8, 16, 32 entries (four, two,
+// one vertex per wavefront), 3, 4, 5 = at most 64, 96, 128 (two, three, four 32-row blocks).
+// 1 (float matrix-core scan, 16-row groups): classes 0..6 = at most 8, 16, 32, 48, 64, 80, 96 entries
+// (1, 1, 2, 3, 4, 5, 6 groups), 7 = more (generic scan).
 __device__ __forceinline__ int degree_class(int m, int use_classes)
 {
     if (!use_classes) return 0;
-    if (use_classes == 2 && m <= 16) return m <= 8 ? 0 : 1;
-    return m <= 32 ? 2 : 2 + ((m - 1) >> 5);
+    if (m <= 16) return m <= 8 ? 0 : 1;
+    if (use_classes == 2) return m <= 32 ? 2 : 2 + ((m - 1) >> 5);
+    return m <= 96 ? 1 + ((m - 1) >> 4) : 7;
 }
 
 // ------------------------------------------------------------------ RandomGraph
@@ -472,8 +475,7 @@ __device__ __forceinline__ MergeItem merge_item_load(int x, int R, const u64 *ke
 
 template <int G>
 __device__ __forceinline__ void merge_group_body(int R, u64 *keys, int *deg, const int *tlist,
-                                                 const u32 *n_ptr, int *cnt,
-                                                 const u64 *inbox, const int *binoff, const u64 *bins,
+                                                 const u32 *n_ptr, int *cnt, const u64 *inbox,
                                                  int8_t *tcls, int use_classes)
 {
     static_assert(G <= INBOX_CAP, "a group merge reads the received edges from the inbox only");
@@ -594,9 +596,9 @@ __global__ __launch_bounds__(BLOCK) void k_merge(long long N, int R, u64 *keys, 
     const int y = blockIdx.y;
     const int *tlist = tlists + (size_t)y * N;
     int8_t *tc = tcls + (size_t)y * N;
-    if (y == 0) merge_group_body<16>(R, keys, deg, tlist, n_touched + 0, cnt, inbox, binoff, bins, tc, use_classes);
-    else if (y == 1) merge_group_body<32>(R, keys, deg, tlist, n_touched + 1, cnt, inbox, binoff, bins, tc, use_classes);
-    else if (y == 2) merge_group_body<64>(R, keys, deg, tlist, n_touched + 2, cnt, inbox, binoff, bins, tc, use_classes);
+    if (y == 0) merge_group_body<16>(R, keys, deg, tlist, n_touched + 0, cnt, inbox, tc, use_classes);
+    else if (y == 1) merge_group_body<32>(R, keys, deg, tlist, n_touched + 1, cnt, inbox, tc, use_classes);
+    else if (y == 2) merge_group_body<64>(R, keys, deg, tlist, n_touched + 2, cnt, inbox, tc, use_classes);
     else merge_general_body(R, keys, deg, tlist, n_touched + 3, cnt, inbox, binoff, bins, tc, use_classes, s_stage);
 }
 
@@ -990,8 +992,8 @@ struct RoundEvents {
 };
 
 template <int NG, int KS>
-static void launch_mfma_scan(const Workspace &w, const void *X, int R, u64 *keys, int *deg, long long N,
-                             RoundCtr *c, hipStream_t st, hipEvent_t e_stop)
+static void launch_mfma_scan(const Workspace &w, int R, u64 *keys, int *deg, long long N, RoundCtr *c,
+                             hipStream_t st, hipEvent_t e_stop)
 {
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8<NG, KS>, NG == 2 ? 3 : 2);
     hipExtLaunchKernelGGL((k_update_scan_mfma_u8<NG, KS>), dim3(cu_count() * per_cu), dim3(256), 0, st, nullptr,
@@ -1011,8 +1013,8 @@ static void launch_prepare_u8(const Workspace &w, const void *X, long long N, in
 static size_t xs_bytes_for(long long N, int d, int variant) { return variant == 2 ? (size_t)N * d : 0; }
 
 template <int KS>
-static void launch_mfma_scan_classes(const Workspace &w, const void *X, int R, u64 *keys, int *deg,
-                                     long long N, RoundCtr *c, hipStream_t st, const RoundEvents &re)
+static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *deg, long long N, RoundCtr *c,
+                                     hipStream_t st, const RoundEvents &re)
 {
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_small<KS>, 4);
     const int n_big = (R > 32) + (R > 64) + (R > 96);   // launches after the short-list kernel
@@ -1020,9 +1022,9 @@ static void launch_mfma_scan_classes(const Workspace &w, const void *X, int R, u
     hipExtLaunchKernelGGL((k_update_scan_mfma_u8_small<KS>), dim3(cu_count() * per_cu, ny), dim3(256), 0, st,
                           re.scan_start, n_big == 0 ? re.scan_stop : nullptr, 0, (const int8_t *)w.xs, R, keys, deg,
                           w.lists, N, w.props, w.nprop, c);
-    if (R > 32) launch_mfma_scan<2, KS>(w, X, R, keys, deg, N, c, st, n_big == 1 ? re.scan_stop : nullptr);
-    if (R > 64) launch_mfma_scan<3, KS>(w, X, R, keys, deg, N, c, st, n_big == 2 ? re.scan_stop : nullptr);
-    if (R > 96) launch_mfma_scan<4, KS>(w, X, R, keys, deg, N, c, st, n_big == 3 ? re.scan_stop : nullptr);
+    if (R > 32) launch_mfma_scan<2, KS>(w, R, keys, deg, N, c, st, n_big == 1 ? re.scan_stop : nullptr);
+    if (R > 64) launch_mfma_scan<3, KS>(w, R, keys, deg, N, c, st, n_big == 2 ? re.scan_stop : nullptr);
+    if (R > 96) launch_mfma_scan<4, KS>(w, R, keys, deg, N, c, st, n_big == 3 ? re.scan_stop : nullptr);
 }
 
 template <int NG, int CH, int NRC>
@@ -1043,14 +1045,15 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
 {
     const int pb = persistent_blocks();
     RoundCtr *c = w.ctr + t;
-    const int use_classes = variant >= 2 ? 2 : 0;
+    const int use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
     if (variant == 2) {
-        if (d == 32) launch_mfma_scan_classes<1>(w, X, R, keys, deg, N, c, st, re);
-        else if (d == 64) launch_mfma_scan_classes<2>(w, X, R, keys, deg, N, c, st, re);
-        else launch_mfma_scan_classes<4>(w, X, R, keys, deg, N, c, st, re);
+        if (d == 32) launch_mfma_scan_classes<1>(w, R, keys, deg, N, c, st, re);
+        else if (d == 64) launch_mfma_scan_classes<2>(w, R, keys, deg, N, c, st, re);
+        else launch_mfma_scan_classes<4>(w, R, keys, deg, N, c, st, re);
     } else if (variant == 3) {
-        // degree classes 0 (at most 8 entries) and 1 (at most 16): one 16-row group; 2: two; 3, 4: NG = 2, 3
-        const int n_more = (R > 8) + (R > 16) + (R > 32) + (R > 64) + (R > 96);
+        // degree classes 0..6: lists of at most 8, 16, 32, 48, 64, 80, 96 entries = 1, 1, 2, 3, 4, 5, 6 groups of 16
+        // rows; class 7 (97..128 entries: too many accumulator tiles) goes to the generic kernel
+        const int n_more = (R > 8) + (R > 16) + (R > 32) + (R > 48) + (R > 64) + (R > 80) + (R > 96);
         int k = 0;
         auto stop_for = [&](void) { return k++ == n_more ? re.scan_stop : (hipEvent_t) nullptr; };
         if (d % 32 == 0) launch_f32_scan<1, 2, 1>(w, X, d, R, keys, deg, N, c, 0, st, re.scan_start, stop_for());
@@ -1063,11 +1066,13 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
             if (d % 32 == 0) launch_f32_scan<1, 2, 2>(w, X, d, R, keys, deg, N, c, 2, st, nullptr, stop_for());
             else launch_f32_scan<1, 1, 2>(w, X, d, R, keys, deg, N, c, 2, st, nullptr, stop_for());
         }
-        if (R > 32) launch_f32_scan<2, 1, 4>(w, X, d, R, keys, deg, N, c, 3, st, nullptr, stop_for());
-        if (R > 64) launch_f32_scan<3, 1, 6>(w, X, d, R, keys, deg, N, c, 4, st, nullptr, stop_for());
-        if (R > 96)   // lists of 97..128 entries: too many accumulator tiles, generic kernel
+        if (R > 32) launch_f32_scan<2, 1, 3>(w, X, d, R, keys, deg, N, c, 3, st, nullptr, stop_for());
+        if (R > 48) launch_f32_scan<2, 1, 4>(w, X, d, R, keys, deg, N, c, 4, st, nullptr, stop_for());
+        if (R > 64) launch_f32_scan<3, 1, 5>(w, X, d, R, keys, deg, N, c, 5, st, nullptr, stop_for());
+        if (R > 80) launch_f32_scan<3, 1, 6>(w, X, d, R, keys, deg, N, c, 6, st, nullptr, stop_for());
+        if (R > 96)
             hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, nullptr, stop_for(), 0, X, d,
-                                  vec_ok, R, keys, deg, w.lists + (size_t)5 * N, &c->n_active[5], w.props, w.nprop, c);
+                                  vec_ok, R, keys, deg, w.lists + (size_t)7 * N, &c->n_active[7], w.props, w.nprop, c);
     } else if (dtype == RNND_U8) {
         hipExtLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
                               vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);
@@ -1176,7 +1181,7 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
     if ((int64_t)T1 * T2 > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int rounds = T1 * T2, n_ctr = rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant >= 2 ? 2 : 0;
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
     // events (only when statistics are wanted): start, end of init, (scan start, scan stop, round
     // stop) per round, end of each reverse call, end
     const int n_ev = stats ? 3 * rounds + T1 + 3 : 0;
@@ -1305,7 +1310,7 @@ extern "C" int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dt
     if (n_rounds < 1 || n_rounds > 1000000) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const int n_ctr = n_rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant >= 2 ? 2 : 0;
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
     Workspace w;
     RoundCtr *hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
     if (!hctr) return RNND_ERR_OOM;

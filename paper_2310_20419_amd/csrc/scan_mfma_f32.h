@@ -101,17 +101,17 @@ __device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int 
 
 // CH = 16-dimension chunks fetched per loop iteration (d must be a multiple of 16*CH): a longer iteration
 // gives the prefetch of the next one more matrix work to hide behind.
-// NRC = 16-row groups whose rows are fetched and multiplied: 2 NG, or 1 for lists of at most 16 entries
-// (NG = 1), which then need a single tile.
+// NRC = 16-row groups whose rows are fetched and multiplied: 2 NG - 1 or 2 NG (lists of at most 16 NRC
+// entries).
 template <int NG, int CH, int NRC = 2 * NG>
-__global__ __launch_bounds__(64 * 4, (NG == 1 ? 4 : NG == 2 ? 2 : 1)) void k_update_scan_mfma_f32(
+__global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_update_scan_mfma_f32(
     const float *__restrict__ X, int d, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
     int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
 {
     constexpr int NR = 2 * NG;
     constexpr int NT = NRC * (NRC + 1) / 2;
-    static_assert(NRC == NR || (NG == 1 && NRC == 1), "only the one-block kernel has a half-size form");
+    static_assert(NRC == NR || NRC == NR - 1, "a list of at most 16 NRC entries spans NG 32-row blocks");
     __shared__ F32ScanSmem<NG> smem[4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, q = lane >> 4, l32 = lane & 31, half = lane >> 5, sub = lane & 7, grp = lane >> 3;
