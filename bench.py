@@ -63,12 +63,13 @@ def search_quality(cfg, rn, Xd, graph, degree, nq, L=64, K=32):
     Xf = Xd.double()
     xn = (Xf * Xf).sum(1)
     hit = 0
-    for q0 in range(0, nq, 500):
-        Qf = Qd[q0:q0 + 500].double()
+    step = max(1, min(500, int(2e9 // Xd.shape[0])))     # the distance matrix of one chunk stays below 16 GB
+    for q0 in range(0, nq, step):
+        Qf = Qd[q0:q0 + step].double()
         d2 = (Qf * Qf).sum(1)[:, None] + xn[None, :] - 2.0 * (Qf @ Xf.T)
         cand = torch.topk(d2, 32, dim=1, largest=False)
         cv, ci = cand.values.cpu().numpy(), cand.indices.cpu().numpy()
-        got = ids[q0:q0 + 500].cpu().numpy()
+        got = ids[q0:q0 + step].cpu().numpy()
         for q in range(cv.shape[0]):
             order = np.lexsort((ci[q], cv[q]))
             hit += len(set(ci[q][order][:10].tolist()) & set(got[q].tolist()))
@@ -87,6 +88,7 @@ def main():
     ap.add_argument("--queries", type=int, default=10000, help="queries of the search-quality leg (at most the config's)")
     ap.add_argument("--variant", type=int, default=0, help="UpdateNeighbors kernel: 0 auto, 1 generic, 2 MFMA")
     ap.add_argument("--cpu-sample", type=int, default=0)
+    ap.add_argument("--n", type=int, default=0, help="override the workload's N (same generator; scale checks)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -104,6 +106,9 @@ def main():
     rn.load_library()
     rn.rnnd_set_kernel_variant(args.variant)
     cfg = wl.CONFIGS[args.workload]
+    if args.n:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, N=args.n, name="%s_n%d" % (cfg.name, args.n))
     t0 = time.perf_counter()
     X = wl.make_data(cfg)
     gen_s = time.perf_counter() - t0
