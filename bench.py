@@ -174,7 +174,9 @@ def main():
         "value": ms_per_step / 1000.0, "unit": "s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8 (int8 MFMA, int32 distances)" if cfg.dtype == "u8" else "f32 (f64 MFMA / f64 accumulation, float distances)",
+        "dtype": "u8" if cfg.dtype == "u8" else "f32",
+        "arithmetic": ("uint8 rows, int8 MFMA Gram tiles, exact int32 distances" if cfg.dtype == "u8" else
+                       "float32 rows, f64 MFMA Gram tiles / f64 accumulation, distances rounded once to float32"),
         "data": "synthetic",
         "config": {"workload": "%s: N=%d d=%d %s, S=%d R=%d T1=%d T2=%d, seeded %s mixture"
                                % (cfg.name, cfg.N, cfg.d, cfg.dtype, cfg.S, cfg.R, cfg.T1, cfg.T2, cfg.kind),
