@@ -80,12 +80,43 @@ struct SearchSmem {
     u32 dist[SEARCH_MAX_L];    // their delta(q, .) bits
 };
 
-// delta(q, ids[0..cnt)) -> dist[0..cnt), 8 vertices at a time.
+// delta(q, ids[0..cnt)) -> dist[0..cnt), 8 vertices at a time (8 lanes per vertex).  uint8 rows of at
+// most 128 bytes that can be read 16 bytes at a time take one load per lane and vertex: the loads of up
+// to 32 vertices are issued together, so their latency is paid once.  (Same arithmetic as the general
+// routine: three byte dot products per word, xor-tree sum.)
 template <int DT>
 __device__ __forceinline__ void search_eval(const void *X, const void *qv, int d, int vec_ok, size_t rowbytes,
                                             SearchSmem &sm, int cnt, int lane)
 {
     const int sub = lane & 7, grp = lane >> 3;
+    if (DT == DT_U8 && vec_ok && d <= 128) {
+        const bool mine = 16 * sub < d;     // d is a multiple of 16 here
+        uint4 q4 = make_uint4(0u, 0u, 0u, 0u);
+        if (mine) q4 = ((const uint4 *)qv)[sub];
+        for (int b = 0; b < cnt; b += 32) {
+            uint4 x4[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int p = b + 8 * j + grp;
+                x4[j] = make_uint4(0u, 0u, 0u, 0u);
+                if (p < cnt && mine) x4[j] = ((const uint4 *)((const char *)X + (size_t)sm.id[p] * rowbytes))[sub];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int p = b + 8 * j + grp;
+                int acc = 0;
+                acc = sqdiff_word_u8(q4.x, x4[j].x, acc);
+                acc = sqdiff_word_u8(q4.y, x4[j].y, acc);
+                acc = sqdiff_word_u8(q4.z, x4[j].z, acc);
+                acc = sqdiff_word_u8(q4.w, x4[j].w, acc);
+                acc += __shfl_xor(acc, 1);
+                acc += __shfl_xor(acc, 2);
+                acc += __shfl_xor(acc, 4);
+                if (p < cnt && sub == 0) sm.dist[p] = (u32)acc;
+            }
+        }
+        return;
+    }
     for (int b = 0; b < cnt; b += 8) {
         const int p = b + grp;
         const int id = sm.id[p < cnt ? p : cnt - 1];
@@ -130,9 +161,13 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
     u32 *seen = bitmaps + (size_t)gw * bitmap_words;   // all zero on entry, and again after every query
     const size_t rowbytes = (size_t)d * (DT == DT_U8 ? 1 : 4);
     const int L0 = (long long)L < N ? L : (int)N;
+    // uint8 rows of at most 128 bytes, readable 16 bytes at a time: one load per lane and vertex
+    const bool short_rows = DT == DT_U8 && vec_ok && d <= 128;
     unsigned long long ev = 0;
     for (long long q = gw; q < nq; q += nw) {
         const void *qv = (const char *)Q + (size_t)q * rowbytes;
+        uint4 q4 = make_uint4(0u, 0u, 0u, 0u);      // short uint8 rows: this lane's 16 bytes of the query
+        if (short_rows && 16 * (lane & 7) < d) q4 = ((const uint4 *)qv)[lane & 7];
         // ---- line 1
         if ((long long)L0 == N) {
             for (int t = lane; t < L0; t += 64) sm.id[t] = t;
@@ -167,6 +202,9 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
             if (iu < 0) break;
             const int u = (int)key_id(shfl_u64(C[iu >> 6], iu & 63));
             if (lane == (iu & 63)) C[iu >> 6] &= ~1ull;
+            // the first 64 entries of u's row are read without waiting for its degree (rows are W wide)
+            int v0 = -1;
+            if (lane < W && lane < K) v0 = graph[(size_t)u * W + lane];
             int du = degree[u];
             if (du > K) du = K;     // Eq. 4: rows are nearest-first
             if (du > W) du = W;
@@ -175,26 +213,65 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
                 // lines 5-6
                 const int t = t0 + lane;
                 int v = -1;
-                bool fresh = false;
-                if (t < du) {
-                    v = graph[(size_t)u * W + t];
-                    if (v >= 0 && (long long)v < N) {   // anything else is not a vertex: ignored
+                if (t < du) v = t0 == 0 ? v0 : graph[(size_t)u * W + t];
+                const bool isv = v >= 0 && (long long)v < N;   // anything else is not a vertex: ignored
+                u64 kn;
+                if (short_rows) {
+                    // line 7 for every neighbour, while the bitmap answers which of them are new to this
+                    // query: short rows cost less to read than a second round trip; lane p keeps candidate p
+                    const int sub = lane & 7, grp = lane >> 3;
+                    const int np = du - t0 < 64 ? du - t0 : 64;
+                    u32 old = 0xFFFFFFFFu;
+                    const u32 bit = 1u << (v & 31);
+                    if (isv) old = atomicOr(&seen[v >> 5], bit);
+                    wave_sync();
+                    for (int b = 0; b < np; b += 32) {
+                        uint4 x4[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int p = b + 8 * j + grp;
+                            const int idp = __shfl(v, p & 63);
+                            x4[j] = make_uint4(0u, 0u, 0u, 0u);
+                            if (p < np && idp >= 0 && (long long)idp < N && 16 * sub < d)
+                                x4[j] = ((const uint4 *)((const char *)X + (size_t)idp * rowbytes))[sub];
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int p = b + 8 * j + grp;
+                            int acc = 0;
+                            acc = sqdiff_word_u8(q4.x, x4[j].x, acc);
+                            acc = sqdiff_word_u8(q4.y, x4[j].y, acc);
+                            acc = sqdiff_word_u8(q4.z, x4[j].z, acc);
+                            acc = sqdiff_word_u8(q4.w, x4[j].w, acc);
+                            acc += __shfl_xor(acc, 1);
+                            acc += __shfl_xor(acc, 2);
+                            acc += __shfl_xor(acc, 4);
+                            if (p < np && sub == 0) sm.dist[p] = (u32)acc;
+                        }
+                    }
+                    wave_sync();
+                    const bool fresh = isv && (old & bit) == 0u;
+                    ev += (unsigned long long)__popcll(__builtin_amdgcn_ballot_w64(fresh));
+                    kn = fresh ? make_key(sm.dist[lane], (u32)v, 1u) : KEY_PAD;
+                } else {
+                    bool fresh = false;
+                    if (isv) {
                         const u32 bit = 1u << (v & 31);
                         fresh = (atomicOr(&seen[v >> 5], bit) & bit) == 0u;
                     }
+                    const u64 fm = __builtin_amdgcn_ballot_w64(fresh);
+                    const int nf = __popcll(fm);
+                    if (nf == 0) continue;
+                    wave_sync();
+                    if (fresh) sm.id[__popcll(fm & lanes_below(lane))] = v;
+                    wave_sync();
+                    // line 7
+                    search_eval<DT>(X, qv, d, vec_ok, rowbytes, sm, nf, lane);
+                    ev += (unsigned long long)nf;
+                    wave_sync();
+                    kn = lane < nf ? make_key(sm.dist[lane], (u32)sm.id[lane], 1u) : KEY_PAD;
                 }
-                const u64 fm = __builtin_amdgcn_ballot_w64(fresh);
-                const int nf = __popcll(fm);
-                if (nf == 0) continue;
-                wave_sync();
-                if (fresh) sm.id[__popcll(fm & lanes_below(lane))] = v;
-                wave_sync();
-                // line 7
-                search_eval<DT>(X, qv, d, vec_ok, rowbytes, sm, nf, lane);
-                ev += (unsigned long long)nf;
-                wave_sync();
                 // lines 8-9
-                u64 kn = lane < nf ? make_key(sm.dist[lane], (u32)sm.id[lane], 1u) : KEY_PAD;
                 if (m == L) {
                     const u64 last = shfl_u64(C[(L - 1) >> 6], (L - 1) & 63);
                     if ((kn >> 1) >= (last >> 1)) kn = KEY_PAD;
