@@ -1,0 +1,44 @@
+"""Method-behaviour regression checks on the GPU path (Sec. 5.4 of the paper): at a constant number of
+UpdateNeighbors rounds T1*T2, a build without any AddReverseEdges call (T1 = 1) searches clearly worse
+than the paper's T1 = 4, T2 = 15, and the in-degree bound of Alg. 5 holds on the final graph."""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rn():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2310_20419_amd as m
+    m.load_library()
+    return m
+
+
+def test_reverse_edges_matter_cfg2(rn, oracle_mod):
+    import torch
+    c = wl.CONFIGS["cfg2"]
+    X = wl.make_data(c)
+    Q = wl.make_queries(c, 200)
+    Xd, Qd = torch.from_numpy(X).cuda(), torch.from_numpy(Q).cuda()
+    truth = oracle_mod.bruteforce_knn(X, Q, 10)
+    recall = {}
+    for T1, T2 in ((1, 60), (4, 15)):
+        graph, degree = rn.rnnd_build(Xd, c.S, c.R, T1, T2, wl.BUILD_SEED)
+        ids, _, _ = rn.rnnd_search(Xd, graph, degree, Qd, 32, 32, 10, 7)
+        recall[T1] = oracle_mod.recall_at_k(ids.cpu().numpy(), truth)
+        g, dg = graph.cpu().numpy(), degree.cpu().numpy()
+        assert dg.max() <= c.R
+        if T1 == 1:
+            assert dg.min() >= 1      # the nearest entry of a list is never pruned; only Alg. 5 can empty a list
+        if T1 > 1:
+            # Alg. 5 lines 6-8 bound the in-degree after each call; UpdateNeighbors never raises a vertex's
+            # in-degree above what it was (a redirected edge replaces an edge into the same vertex)
+            indeg = np.bincount(g[g >= 0], minlength=c.N)
+            assert indeg.max() <= c.R
+    print("recall@10 at L=32, K=32: T1=1 %.4f, T1=4 %.4f" % (recall[1], recall[4]))
+    assert recall[4] > 0.93
+    assert recall[4] > recall[1] + 0.03
