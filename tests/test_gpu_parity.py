@@ -225,6 +225,10 @@ def test_cfg2_full_parity(rn, oracle_mod, variant):
     graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
     assert_snapshot_equal(want.snap, False, keys, degree, "cfg2")
     assert list(st.algo_evals[:60]) == want.round_evals.tolist()
+    # the plain entry point (no statistics, no timing events) builds the same graph
+    g1, d1 = rn.rnnd_build(cuda(X), c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    assert (g1 == graph).all() and (d1 == degree).all()
+    assert (g1.cpu().numpy() == want.snap.ids).all()
 
 
 @pytest.mark.slow
