@@ -1,6 +1,7 @@
 // librnnd: Relative NN-Descent graph construction (arXiv 2310.20419, Alg. 4-6) on gfx950.
 //
-// One wavefront owns one vertex in every per-vertex kernel.  A round is synchronous:
+// A wavefront, or a group of 16, 32 or 64 of its lanes, owns one vertex in every per-vertex kernel.
+// A round is synchronous:
 //   scan     every active vertex (one holding a "new" entry) runs Alg. 4 lines 2-15 on its own list,
 //            writes its kept entries back in place and leaves its redirected edges in its slot of `props`
 //   scatter  every redirected edge takes an arrival number at its target (the round's only atomic per
@@ -9,8 +10,10 @@
 //            those that received more than INBOX_CAP get a bin, which a second scatter pass fills
 //   merge    every touched list becomes the first R distinct keys of (kept entries + inbox + bin)
 //   compact  touched vertices whose new list holds a "new" entry form the next active lists,
-//            one per degree class (lists of up to 32, 64, 96, 128 entries)
+//            one per degree class (see degree_class)
+// Between outer rounds AddReverseEdges (Alg. 5) uses the same inboxes and bins (launch_reverse).
 // Counters that many wavefronts would hit at one address are aggregated per block first.
+// search.h holds the graph search of Alg. 1 (rnnd_search).
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <stdint.h>
