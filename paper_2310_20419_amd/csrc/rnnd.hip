@@ -570,26 +570,10 @@ __device__ __forceinline__ void merge_general_body(int R, u64 *keys, int *deg, c
         bool any_new = false;
         int nd;
         if (c <= INBOX_CAP && nb + c <= 128) {
-            // the list is sorted already: sort the received keys alone, lay them out descending above the
-            // list (ascending, then padding, then descending = bitonic) and finish with one bitonic merge
-            u64 a[1];
-            a[0] = 63 - lane < c ? cur.in : KEY_PAD;
-            wave_sort<1>(a, lane);                          // ascending, padding last
-            const u64 desc = shfl_u64(a[0], 63 - lane);     // padding first, then descending
             u64 k[2];
             k[0] = lane < nb ? cur.r0 : KEY_PAD;
-            k[1] = lane + 64 < nb ? cur.r1 : desc;          // nb + c <= 128: the two parts do not overlap
-            {
-                const u64 lo = k[0] < k[1] ? k[0] : k[1], hi = k[0] < k[1] ? k[1] : k[0];
-                k[0] = lo;
-                k[1] = hi;
-            }
-#pragma unroll
-            for (int stride = 32; stride > 0; stride >>= 1) {
-                const bool lower = (lane & stride) == 0;
-                k[0] = keep_of_pair(k[0], xor_lane_u64(k[0], stride), lower);
-                k[1] = keep_of_pair(k[1], xor_lane_u64(k[1], stride), lower);
-            }
+            k[1] = lane + 64 < nb ? cur.r1 : (63 - lane < c ? cur.in : KEY_PAD);
+            wave_sort<2>(k, lane);
             nd = wave_unique_prefix<2>(k, lane, R, keys + (size_t)x * R, &any_new);
         } else {
             const int ca = c < INBOX_CAP ? c : INBOX_CAP;

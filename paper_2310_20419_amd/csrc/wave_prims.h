@@ -179,28 +179,6 @@ __device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *binA,
         k[0] = lane < nb ? row[lane] : (lane < total ? bin_at(lane - nb) : KEY_PAD);
         wave_sort<1>(k, lane);
         n = wave_unique_prefix<1>(k, lane, R, row, any_new);
-    } else if (total <= 128 && c <= 64) {
-        // the row is sorted already: sort the c other keys alone, lay them out descending above the row
-        // (ascending, padding, descending = bitonic) and finish with one bitonic merge of 128
-        u64 a[1];
-        a[0] = lane < c ? bin_at(lane) : KEY_PAD;
-        wave_sort<1>(a, lane);                          // ascending, padding last
-        const u64 desc = shfl_u64(a[0], 63 - lane);     // padding first, then descending
-        u64 k[2];
-        k[0] = lane < nb ? row[lane] : KEY_PAD;
-        k[1] = lane + 64 < nb ? row[lane + 64] : desc;  // nb + c <= 128: the two parts do not overlap
-        {
-            const u64 lo = k[0] < k[1] ? k[0] : k[1], hi = k[0] < k[1] ? k[1] : k[0];
-            k[0] = lo;
-            k[1] = hi;
-        }
-#pragma unroll
-        for (int stride = 32; stride > 0; stride >>= 1) {
-            const bool lower = (lane & stride) == 0;
-            k[0] = keep_of_pair(k[0], xor_lane_u64(k[0], stride), lower);
-            k[1] = keep_of_pair(k[1], xor_lane_u64(k[1], stride), lower);
-        }
-        n = wave_unique_prefix<2>(k, lane, R, row, any_new);
     } else if (total <= 128) {
         u64 k[2];
 #pragma unroll
