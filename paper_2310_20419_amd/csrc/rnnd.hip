@@ -734,35 +734,81 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64
                                                          int8_t *vcls, int use_classes)
 {
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const long long x = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
-    if (x >= N) return;
-    u64 *row = keys + (size_t)x * R;
-    const int c = fill[x];
-    int nd = deg[x];
-    if (c > 0) {
-        bool any_new;
-        const int ca = c < INBOX_CAP ? c : INBOX_CAP;
-        nd = wave_merge_row(row, nd, inbox + (size_t)x * INBOX_CAP, ca, bins + (c > ca ? binoff[x] : 0), c - ca, R,
-                            s_stage[wave], lane, &any_new);
-        wave_sync();    // the list is read back below by other lanes of this wavefront
-    }
-    bool nw = false, cd = false;
-    for (int e = lane; e < nd; e += 64) {
-        const u64 k = row[e];
-        nw = nw || (k & 1ull);
-        const u32 v = key_id(k);
-        if (cand[v]) {
-            atomicAdd(&cnt_in[v], 1);
-            cd = true;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+    // a wavefront takes two vertices, one per half: lists are short on average, and when both unions have
+    // at most 32 keys they are formed side by side (32-lane sorts); otherwise one after the other
+    const long long x0 = ((long long)blockIdx.x * WAVES_PER_BLOCK + wave) * 2;
+    if (x0 >= N) return;
+    const long long xh = x0 + half;
+    const bool have = xh < N;
+    const int ch = have ? fill[xh] : 0, nbh = have ? deg[xh] : 0;
+    const bool small = __builtin_amdgcn_ballot_w64(nbh + ch > 32) == 0;
+    if (small) {
+        u64 *row = keys + (size_t)xh * R;
+        u64 k = KEY_PAD;
+        if (have) {
+            if (l32 < nbh) k = row[l32];
+            else if (31 - l32 < ch) k = inbox[(size_t)xh * INBOX_CAP + (31 - l32)];
         }
+        k = group_sort<32>(k, lane);
+        u64 prev = shfl_up1_u64(k);
+        if (l32 == 0) prev = KEY_PAD;
+        const bool keep = (k != KEY_PAD) && ((k >> 1) != (prev >> 1));
+        const u32 m = (u32)(__builtin_amdgcn_ballot_w64(keep) >> (32 * half));
+        const int pos = __popc(m & ((1u << l32) - 1u));
+        const bool w = keep && pos < R;
+        if (w) row[pos] = k;
+        bool cd = false;
+        if (w) {
+            const u32 v = key_id(k);
+            if (cand[v]) {
+                atomicAdd(&cnt_in[v], 1);
+                cd = true;
+            }
+        }
+        const u32 nm = (u32)(__builtin_amdgcn_ballot_w64(w && (k & 1ull)) >> (32 * half));
+        const u32 cm = (u32)(__builtin_amdgcn_ballot_w64(cd) >> (32 * half));
+        if (have && l32 == 0) {
+            int nd = __popc(m);
+            if (nd > R) nd = R;
+            deg[xh] = nd;
+            fill[xh] = 0;
+            rowflag[xh] = (int8_t)(cm != 0);
+            vcls[xh] = nm ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
+        }
+        return;
     }
-    const u64 b = __builtin_amdgcn_ballot_w64(nw), bc = __builtin_amdgcn_ballot_w64(cd);
-    if (lane == 0) {
-        deg[x] = nd;
-        fill[x] = 0;
-        rowflag[x] = (int8_t)(bc != 0);
-        vcls[x] = b ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
+    for (int h = 0; h < 2; ++h) {
+        const long long x = x0 + h;
+        if (x >= N) break;
+        u64 *row = keys + (size_t)x * R;
+        const int c = fill[x];
+        int nd = deg[x];
+        if (c > 0) {
+            bool any_new;
+            const int ca = c < INBOX_CAP ? c : INBOX_CAP;
+            wave_sync();    // the staging area may still be read by the previous vertex
+            nd = wave_merge_row(row, nd, inbox + (size_t)x * INBOX_CAP, ca, bins + (c > ca ? binoff[x] : 0), c - ca, R,
+                                s_stage[wave], lane, &any_new);
+            wave_sync();    // the list is read back below by other lanes of this wavefront
+        }
+        bool nw = false, cd = false;
+        for (int e = lane; e < nd; e += 64) {
+            const u64 k = row[e];
+            nw = nw || (k & 1ull);
+            const u32 v = key_id(k);
+            if (cand[v]) {
+                atomicAdd(&cnt_in[v], 1);
+                cd = true;
+            }
+        }
+        const u64 b = __builtin_amdgcn_ballot_w64(nw), bc = __builtin_amdgcn_ballot_w64(cd);
+        if (lane == 0) {
+            deg[x] = nd;
+            fill[x] = 0;
+            rowflag[x] = (int8_t)(bc != 0);
+            vcls[x] = b ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
+        }
     }
 }
 
@@ -1130,7 +1176,7 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
                        w.binoff, w.misc + 0, w.hubs, w.misc + 1, w.cnt, cnt_in, (u64 *)nullptr, deg, R, cand);
     hipLaunchKernelGGL(k_reverse_surplus, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, late, over, mark, w.binoff,
                        w.bins, w.misc + 1);
-    hipLaunchKernelGGL(k_reverse_merge, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, w.binoff,
+    hipLaunchKernelGGL(k_reverse_merge, dim3((vb + 1) / 2), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, w.binoff,
                        w.bins, cand, cnt_in, rowflag, w.vcls, use_classes);
     // lines 6-8: in-lists cut to R; only vertices with more than R incoming edges need a bin
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, cnt_in, R, R, 0, w.binoff, w.misc + 2, w.hubs,
