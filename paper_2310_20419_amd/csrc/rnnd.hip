@@ -1452,7 +1452,7 @@ extern "C" int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int m
     char *base = nullptr;
     unsigned long long h_evals = 0;
     HIPCHK(hipMalloc((void **)&base, bm_bytes + 256));
-    HIPCHK(hipMemsetAsync(base, 0, bm_bytes + 256, st));
+    HIPCHK(hipMemsetAsync(base + bm_bytes, 0, 256, st));     // the evaluation counter; bitmaps are cleared per query
     {
         u32 *bitmaps = (u32 *)base;
         unsigned long long *d_evals = (unsigned long long *)(base + bm_bytes);

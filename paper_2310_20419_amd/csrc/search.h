@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long gw = (long long)blockIdx.x * 4 + wave, nw = (long long)gridDim.x * 4;
     SearchSmem &sm = smem[wave];
-    u32 *seen = bitmaps + (size_t)gw * bitmap_words;   // all zero on entry, and again after every query
+    u32 *seen = bitmaps + (size_t)gw * bitmap_words;   // cleared by this wavefront before every query
     const size_t rowbytes = (size_t)d * (DT == DT_U8 ? 1 : 4);
     const int L0 = (long long)L < N ? L : (int)N;
     // uint8 rows of at most 128 bytes, readable 16 bytes at a time: one load per lane and vertex
@@ -168,6 +168,10 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
         const void *qv = (const char *)Q + (size_t)q * rowbytes;
         uint4 q4 = make_uint4(0u, 0u, 0u, 0u);      // short uint8 rows: this lane's 16 bytes of the query
         if (short_rows && 16 * (lane & 7) < d) q4 = ((const uint4 *)qv)[lane & 7];
+        // ---- nothing has been evaluated for this query yet (the memory arrives uninitialised)
+        for (size_t w4 = (size_t)lane * 4; w4 < bitmap_words; w4 += 256)
+            *(uint4 *)(seen + w4) = make_uint4(0u, 0u, 0u, 0u);
+        wave_sync();
         // ---- line 1
         if ((long long)L0 == N) {
             for (int t = lane; t < L0; t += 64) sm.id[t] = t;
@@ -297,11 +301,6 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
                 if (out_dist) out_dist[(size_t)q * k + t] = t < m ? key_dist(C[r]) : 0xFFFFFFFFu;
             }
         }
-        // ---- leave the bitmap clean for the next query of this wavefront
-        wave_sync();
-        for (size_t w4 = (size_t)lane * 4; w4 < bitmap_words; w4 += 256)
-            *(uint4 *)(seen + w4) = make_uint4(0u, 0u, 0u, 0u);
-        wave_sync();
     }
     if (lane == 0 && evals && ev) atomicAdd(evals, ev);
 }
