@@ -3,7 +3,7 @@
 
 A "step" is one complete rnnd_build (RandomGraph + T1*T2 UpdateNeighbors rounds + T1-1
 AddReverseEdges) over one synthetic database that is already resident in HBM.  The default
-workload is BASELINE configuration 3 (N = 1,000,000, d = 128, uint8, S=20 R=96 T1=4 T2=15), the
+workload is cfg3 of workloads.py (N = 1,000,000, d = 128, uint8, S=20 R=96 T1=4 T2=15), the
 one the "1M-vector graph build time" metric is quoted on.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu-baseline]

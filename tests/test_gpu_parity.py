@@ -218,7 +218,7 @@ def test_argument_errors_on_device(rn):
 
 
 def test_cfg2_full_parity(rn, oracle_mod, variant):
-    """BASELINE configuration 2 (N = 100,000, d = 128 uint8, paper parameters): ~20 s of oracle."""
+    """Workload cfg2 (N = 100,000, d = 128 uint8, paper parameters): ~20 s of oracle."""
     c = wl.CONFIGS["cfg2"]
     X = wl.make_data(c)
     want = oracle_mod.build_sync(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
@@ -233,7 +233,7 @@ def test_cfg2_full_parity(rn, oracle_mod, variant):
 
 @pytest.mark.slow
 def test_cfg3_full_size_parity(rn, oracle_mod):
-    """BASELINE configuration 3 -- the benchmark's workload (N = 1,000,000, d = 128 uint8, S=20 R=96
+    """Workload cfg3 -- the benchmark's workload (N = 1,000,000, d = 128 uint8, S=20 R=96
     T1=4 T2=15) in the launch configuration bench.py times: the whole graph, every distance, flag,
     degree and per-round evaluation count against a full oracle run (about a minute of CPU)."""
     import time
@@ -264,7 +264,7 @@ FULL = os.environ.get("RNND_FULL_PARITY", "") == "1"
 @pytest.mark.slow
 @pytest.mark.skipif(not FULL, reason="set RNND_FULL_PARITY=1: several minutes of single-threaded oracle")
 def test_cfg4_full_size_parity(rn, oracle_mod):
-    """BASELINE configuration 4 (N = 1,000,000, d = 96 float32, unit vectors) against a full oracle run."""
+    """Workload cfg4 (N = 1,000,000, d = 96 float32, unit vectors) against a full oracle run."""
     import time
     c = wl.CONFIGS["cfg4"]
     X = wl.make_data(c)
@@ -283,7 +283,7 @@ def test_cfg4_full_size_parity(rn, oracle_mod):
 
 @pytest.mark.slow
 def test_cfg5_full_size_sampled_parity(rn, oracle_mod):
-    """BASELINE configuration 5 (N = 1,000,000, d = 960 float32) in the launch configuration bench.py
+    """Workload cfg5 (N = 1,000,000, d = 960 float32) in the launch configuration bench.py
     times.  A full oracle run would take hours, so outputs are sampled: after the GPU has run RandomGraph
     and k rounds, one more round is run on the GPU, and for 2,000 sampled vertices the oracle computes
     that round one vertex at a time (a snapshot in which only the sampled lists are non-empty).  The
