@@ -354,6 +354,53 @@ def test_search_with_full_candidate_list_is_exact(oracle_mod):
     assert (found == oracle_mod.bruteforce_knn(X, Q, 10)).all()
 
 
+def _search_model(X, ids, deg, q, start, L, K, k):
+    """Alg. 1 with the cap of Eq. 4, written on Python sets and dicts (a different shape from the C
+    routine: no sorted array, no insertion): C maps vertex -> distance, `visited` are the expanded members
+    of C, `evaluated` every vertex whose distance to q was ever computed."""
+    Xl = X.astype(np.int64)
+    dist = lambda v: int(((Xl[v] - q.astype(np.int64)) ** 2).sum())
+    C = {int(v): dist(int(v)) for v in start}
+    evaluated, visited = set(C), set()
+    evals = len(C)
+    while True:
+        pending = [v for v in C if v not in visited]
+        if not pending:
+            break
+        u = min(pending, key=lambda v: (C[v], v))                        # line 3
+        visited.add(u)
+        for v in ids[u][:min(int(deg[u]), K)].tolist():                  # line 5 with Eq. 4
+            if v in evaluated:                                           # line 6
+                continue
+            evaluated.add(v)
+            C[v] = dist(v)                                               # line 7
+            evals += 1
+            if len(C) > L:                                               # lines 8-9
+                worst = max(C, key=lambda w: (C[w], w))
+                del C[worst]
+                visited.discard(worst)
+    best = sorted(C, key=lambda v: (C[v], v))[:k]
+    return best + [-1] * (k - len(best)), evals
+
+
+@pytest.mark.parametrize("L,K,k", [(8, 4, 5), (16, 100, 10), (40, 6, 10), (5, 3, 5)])
+def test_search_matches_a_setwise_model_on_small_inputs(oracle_mod, L, K, k):
+    """The search routine against an independent model of Alg. 1 + Eq. 4 (only the seeded start set, which
+    the paper leaves open, is taken from the generator that has its own pins)."""
+    X = small_u8(300, 12, 61)
+    Q = small_u8(15, 12, 62)
+    g = oracle_mod.build_sync(X, 6, 16, 2, 3, 9).snap
+    seed = 77
+    found, evals = oracle_mod.search(X, g.ids, g.deg, Q, L, K, k, seed)
+    total = 0
+    for qi in range(len(Q)):
+        start = oracle_mod.random_ids(len(X) + 1, len(X), min(L, len(X)), (seed + 0x9E3779B97F4A7C15 * qi) % 2 ** 64)
+        want, ev = _search_model(X, g.ids, g.deg, Q[qi], start, L, K, k)
+        assert found[qi].tolist() == want, "query %d" % qi
+        total += ev
+    assert evals == total
+
+
 def test_search_quality_sync_vs_paper_order_vs_no_reverse_edges(oracle_mod):
     c = wl.CONFIGS["cfg1"]
     X, Q = wl.make_data(c), wl.make_queries(c)
