@@ -47,7 +47,19 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert call(S=0) == -3 and call(S=9) == -3 and call(R=0) == -3 and call(R=129) == -3
     assert call(T1=0) == -3 and call(T2=0) == -3 and call(N=5, S=5, R=8) == -3
     assert call(dtype=2) == -4 and call(metric=1) == -4
-    assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(0) == 0
+    assert call(N=50_000_000, R=128, S=4) == -2          # N*R does not fit the 32-bit slot counters
+    assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(2) == -3
+    assert lib.rnnd_set_kernel_variant(0) == 0
+    # rnnd_search: parameters are checked before pointers, pointers before any GPU call
+    def search(**kw):
+        a = dict(dict(X=one, N=100, d=16, dtype=0, metric=0, g=one, dg=one, W=8, Q=one, nq=3, L=16, K=8, k=5,
+                      out=one), **kw)
+        return lib.rnnd_search(a["X"], a["N"], a["d"], a["dtype"], a["metric"], a["g"], a["dg"], a["W"], a["Q"],
+                               a["nq"], a["L"], a["K"], a["k"], 1, a["out"], None, None, None)
+    assert search(L=0) == -3 and search(L=129) == -3 and search(K=0) == -3 and search(k=0) == -3
+    assert search(k=17) == -3 and search(W=0) == -3 and search(nq=-1) == -2
+    assert search(X=None) == -1 and search(g=None) == -1 and search(dg=None) == -1 and search(Q=None) == -1
+    assert search(out=None) == -1 and search(dtype=3) == -4
 
 
 def test_workspace_bytes(lib):
