@@ -187,6 +187,11 @@ def main():
         "gpu_ms": {"total": s["total_ms"], "init": s["init_ms"], "rounds": sum(s["round_ms"]),
                    "scan": scan_ms, "reverse": sum(s["reverse_ms"])},
         "mean_degree": float(degree.float().mean().item()), "max_degree": int(degree.max().item()),
+        # out-degrees 0, 1-8, 9-16, 17-32, 33-64, 65-96, 97-128
+        "degree_histogram": torch.histc(degree.float(), bins=1, min=-0.5, max=0.5).int().tolist()
+        + [int(((degree > lo) & (degree <= hi)).sum().item()) for lo, hi in
+           ((0, 8), (8, 16), (16, 32), (32, 64), (64, 96), (96, 128))],
+        "data_stats": dict(wl.describe(X), sha256=wl.sha256_of(X)[:16]),
         "roofline": roof,
         "data_gen_s": gen_s,
     }
