@@ -62,3 +62,30 @@ def test_random_config(rn, oracle_mod, i, kind, N, d, S, R, T1, T2):
     found, _, evals = rn.rnnd_search(Xd, graph, degree, torch.from_numpy(Q).cuda(), L, K, k, 99 + i)
     wfound, wevals = oracle_mod.search(X, want.snap.ids, want.snap.deg, Q, L, K, k, 99 + i)
     assert (found.cpu().numpy() == wfound).all() and evals == wevals
+
+
+def _mid_configs():
+    g = np.random.default_rng(31415)
+    out = []
+    for i in range(16):
+        N = int(g.choice([5000, 12000, 20000]))
+        kind, d = [("heavy_u8", 128), ("heavy_u8", 64), ("gauss_u8", 32), ("gauss_u8", 48), ("unit_f32", 96),
+                   ("unit_f32", 32), ("ties_u8", 16), ("lattice_f32", 16)][i % 8]
+        R = int(g.choice([8, 16, 32, 64, 96]))
+        S = int(g.integers(max(1, R // 4), R + 1))
+        out.append((i, kind, N, d, S, R, int(g.integers(2, 4)), int(g.integers(2, 6))))
+    return out
+
+
+@pytest.mark.parametrize("i,kind,N,d,S,R,T1,T2", _mid_configs())
+def test_mid_size_config(rn, oracle_mod, i, kind, N, d, S, R, T1, T2):
+    """Tens of thousands of vertices with small degree caps: hubs overflow the inboxes, Alg. 5's in-degree cap
+    bites, lists fill up to R."""
+    import torch
+    X = _data(kind, N, d, 3000 + i) if kind != "heavy_u8" else wl.custom(kind, N, d, 3000 + i)
+    isf = X.dtype == np.float32
+    want = oracle_mod.build_sync(X, S, R, T1, T2, 50 + i)
+    graph, degree, keys, st = rn.rnnd_build_ex(torch.from_numpy(X).cuda(), S, R, T1, T2, 50 + i)
+    assert_snapshot_equal(want.snap, isf, keys, degree, "mid config %d" % i)
+    assert list(st.algo_evals[:T1 * T2]) == want.round_evals.tolist()
+    assert list(st.proposals[:T1 * T2]) == want.round_props.tolist()
