@@ -1,18 +1,27 @@
 // UpdateNeighbors scan (Alg. 4 lines 2-15) for float32 rows on the double-precision matrix cores.
 //
-// One wavefront owns one vertex u with m <= 32*NG list entries, handled as NR = 2*NG groups of 16 rows.
-// The rows of the whole list are streamed through registers 16 dimensions (64 bytes per row) at a time:
-// lane l loads 4 floats of row l%16 of every group, widens them to double, and for each of the 4 it feeds
-// v_mfma_f64_16x16x4_f64 for every 16x16 tile (I >= J) of the Gram block G = A A^T.  The A and B operand
-// of a tile come from the same loads with the same lane -> dimension mapping, so the products pair up
-// whatever that mapping is.  Products of floats are exact in double, so with n_i = sum_k x_ik^2
+// One wavefront owns one vertex u with m <= 16*NRC list entries, handled as NRC groups of 16 rows.
+// The rows are streamed through registers 16 dimensions (64 bytes per row) at a time: lane l loads 4
+// floats of row l%16 of every group, widens them to double, and for each of the 4 it feeds
+// v_mfma_f64_16x16x4_f64 for every needed 16x16 tile (I >= J) of the Gram block G = A A^T.  The A and B
+// operand of a tile come from the same loads with the same lane -> dimension mapping, so the products
+// pair up whatever that mapping is.  Products of floats are exact in double, so with n_i = sum_k x_ik^2
 //     delta(v_i, v_j) ~= float(n_i + n_j - 2 G_ij)
 // differs from the reference value (double accumulation of (a-b)^2, rounded once) only when the two
 // doubles straddle a rounding boundary of float, about 1e-8 of the time; it is used for the DECISION of
 // line 11 only.  Every distance that is STORED (the delta(v,w) of a redirected edge) is recomputed by
 // the one routine all stored distances come from (dist.h), so equal edges always carry equal keys.
-// The outcomes are packed and transposed into one 32-bit row word per lane and 32-row block exactly as
-// in the uint8 kernel, and lines 5-18 run on those masks.
+//
+// Lines 8-9 never test two old entries against each other, so only pairs with a new member need a
+// distance.  The list is therefore laid out in SLOTS: its new entries first, then its old ones, each in
+// list order.  A tile is needed only if its column group J holds a new slot, i.e. J < ceil(#new / 16):
+// with few new entries a list of 6 groups costs 6 tiles instead of 21.  Everything after the tiles
+// works on slots; list order is carried by masks: before(s) = the slots whose entry precedes s's in
+// the list = a prefix of the new slots and a prefix of the old slots.  Row s fails against column t
+// (t before s, one of them new) iff delta(u, s) >= delta(s, t); the kept set is the fixed point of
+//     K_s = not exists t in before(s): F_st and K_t ,
+// found by sweeps over the whole list at once (row s is final after rank(s)+1 sweeps); the redirect
+// target of a pruned row is its failing kept column that comes first in the list.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -21,13 +30,13 @@
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
-template <int NG>
+template <int NRC>
 struct alignas(16) F32ScanSmem {
-    double nrm[32 * NG];   // n_j by list position
-    u32 dist[32 * NG];     // delta(u, v_j) as float bits
-    int id[32 * NG];       // vertex id by list position
-    u32 ppos[32 * NG];     // redirected entries: list position of v ...
-    u32 ptgt[32 * NG];     // ... and of the w it failed against
+    u64 key[16 * NRC];      // list entry by slot
+    double nrm[16 * NRC];   // n by slot
+    int pos[16 * NRC];      // list position by slot
+    u32 pv[16 * NRC];       // redirected entries: slot of v ...
+    u32 pw[16 * NRC];       // ... and of the w it failed against
 };
 
 template <int SH, u32 M>
@@ -101,23 +110,41 @@ __device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int 
 
 // CH = 16-dimension chunks fetched per loop iteration (d must be a multiple of 16*CH): a longer iteration
 // gives the prefetch of the next one more matrix work to hide behind.
-// NRC = 16-row groups whose rows are fetched and multiplied: 2 NG - 1 or 2 NG (lists of at most 16 NRC
-// entries).
+// bits [lo, hi) of a 96-bit mask, as word c (bits 32c .. 32c+31)
+__device__ __forceinline__ u32 range_word(int lo, int hi, int c)
+{
+    const int a = lo - 32 * c, b = hi - 32 * c;
+    const u32 below_b = b >= 32 ? 0xFFFFFFFFu : (b <= 0 ? 0u : ((1u << b) - 1u));
+    const u32 below_a = a >= 32 ? 0xFFFFFFFFu : (a <= 0 ? 0u : ((1u << a) - 1u));
+    return below_b & ~below_a;
+}
+
+__device__ __forceinline__ int popc_below(u64 m0, u64 m1, int p)   // set bits of the 128-bit (m0, m1) below p
+{
+    if (p <= 0) return 0;
+    if (p < 64) return __popcll(m0 & ((1ull << p) - 1ull));
+    if (p == 64) return __popcll(m0);
+    return __popcll(m0) + __popcll(m1 & ((p >= 128) ? ~0ull : ((1ull << (p - 64)) - 1ull)));
+}
+
+// NRC = 16-row groups of the list (lists of at most 16 NRC entries); NG = ceil(NRC / 2) names the
+// degree class family; CH = 16-dimension chunks fetched per loop iteration (d a multiple of 16*CH).
 template <int NG, int CH, int NRC = 2 * NG>
 __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_update_scan_mfma_f32(
     const float *__restrict__ X, int d, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
     int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
 {
-    constexpr int NR = 2 * NG;
     constexpr int NT = NRC * (NRC + 1) / 2;
-    static_assert(NRC == NR || NRC == NR - 1, "a list of at most 16 NRC entries spans NG 32-row blocks");
-    __shared__ F32ScanSmem<NG> smem[4];
+    constexpr int NWD = (NRC + 1) / 2;        // 32-bit words of a mask over slots
+    constexpr int NSET = NRC > 4 ? 2 : 1;     // lane (r16, q) owns rows 16 q + r16 and, if NRC > 4, 64 + 16 q + r16
+    static_assert(NRC >= 1 && NRC <= 6 && (NRC == 2 * NG || NRC == 2 * NG - 1), "lists of at most 96 entries");
+    __shared__ F32ScanSmem<NRC> smem[4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int r16 = lane & 15, q = lane >> 4, l32 = lane & 31, half = lane >> 5, sub = lane & 7, grp = lane >> 3;
+    const int r16 = lane & 15, q = lane >> 4, sub = lane & 7, grp = lane >> 3;
     const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
     const u32 n_active = *n_list;
-    F32ScanSmem<NG> &sm = smem[wave];
+    F32ScanSmem<NRC> &sm = smem[wave];
     const int nchunk = d / (16 * CH);
     u64 tiles = 0, rows = 0, nprops_total = 0;
     u32 ev_lane = 0;
@@ -141,166 +168,223 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
         u64 *row = keys + (size_t)u * R;
         u64 kreg[2];
         kreg[0] = lane < m ? cur.k[0] : KEY_PAD;
-        kreg[1] = (NG > 2 && lane + 64 < m) ? cur.k[1] : KEY_PAD;
-        u64 newm[2];
-        newm[0] = __builtin_amdgcn_ballot_w64(lane < m && (kreg[0] & 1ull));
-        newm[1] = __builtin_amdgcn_ballot_w64(NG > 2 && lane + 64 < m && (kreg[1] & 1ull));
-        if ((newm[0] | newm[1]) == 0) {
+        kreg[1] = (NRC > 4 && lane + 64 < m) ? cur.k[1] : KEY_PAD;
+        // by list position: which entries are new, which old
+        const u64 new0 = __builtin_amdgcn_ballot_w64(lane < m && (kreg[0] & 1ull));
+        const u64 new1 = __builtin_amdgcn_ballot_w64(NRC > 4 && lane + 64 < m && (kreg[1] & 1ull));
+        if ((new0 | new1) == 0) {
             if (lane == 0) nprop[u] = 0;
         } else {
+            const u64 val0 = m >= 64 ? ~0ull : ((1ull << m) - 1ull);
+            const u64 val1 = m > 64 ? ((1ull << (m - 64)) - 1ull) : 0ull;
+            const u64 old0 = val0 & ~new0, old1 = val1 & ~new1;
+            const int n_new = __popcll(new0) + __popcll(new1);
+            const int g_new = (n_new + 15) >> 4;          // column groups that hold a new slot
+            // ---- slots: new entries first, then old ones, each in list order
             wave_sync();
-            if (lane < 32 * NG) { sm.id[lane] = (int)key_id(kreg[0]); sm.dist[lane] = key_dist(kreg[0]); }
-            if (NG > 2 && lane + 64 < 32 * NG) {
-                sm.id[64 + lane] = (int)key_id(kreg[1]);
-                sm.dist[64 + lane] = key_dist(kreg[1]);
+#pragma unroll
+            for (int h = 0; h < (NRC > 4 ? 2 : 1); ++h) {
+                const int p = 64 * h + lane;
+                if (p < m) {
+                    const bool isnew = kreg[h] & 1ull;
+                    const int s = isnew ? popc_below(new0, new1, p) : n_new + popc_below(old0, old1, p);
+                    sm.key[s] = kreg[h];
+                    sm.pos[s] = p;
+                } else if (p < 16 * NRC) {
+                    sm.key[p] = 0;      // slots past the list: vertex 0, never tested
+                    sm.pos[p] = p;
+                }
             }
             rows += m;
+            wave_sync();
 
-            // ---- which 16x16 tiles hold a pair with a new entry (lines 8-9 skip the others)
-            u32 new16[NR];
+            // ---- rows of the slots, 16 per group
             const float *rp[NRC];
 #pragma unroll
-            for (int g = 0; g < NR; ++g) {
-                const int p = 16 * g;   // positions p .. p+15
-                new16[g] = (u32)(newm[p >> 6] >> (p & 63)) & 0xFFFFu;
-            }
-#pragma unroll
             for (int g = 0; g < NRC; ++g) {
-                const int p = 16 * g;
-                const u32 idr = key_id(kreg[p >> 6]);
-                const int id = __shfl((int)idr, (p & 63) + r16);
-                rp[g] = X + (size_t)(p + r16 < m ? id : 0) * d + 4 * q;   // lanes without a row read row 0
+                const int s = 16 * g + r16;
+                const int id = s < m ? (int)key_id(sm.key[s]) : 0;      // lanes without a row read row 0
+                rp[g] = X + (size_t)id * d + 4 * q;
             }
-
-            // ---- Gram block over d in chunks of 16 dimensions
+            // ---- Gram block over d in chunks of 16 dimensions: the tiles whose column group holds a new slot
             v4d acc[NT];
 #pragma unroll
             for (int t = 0; t < NT; ++t) acc[t] = (v4d){0.0, 0.0, 0.0, 0.0};
             double nr[NRC];
 #pragma unroll
             for (int g = 0; g < NRC; ++g) nr[g] = 0.0;
-            // tiles worth computing: rows in use, and a new entry among the rows or the columns (lines 8-9)
             u32 need = 0;
 #pragma unroll
             for (int I = 0; I < NRC; ++I)
 #pragma unroll
                 for (int J = 0; J <= I; ++J)
-                    if (16 * I < m && (new16[I] | new16[J]) != 0) need |= 1u << (I * (I + 1) / 2 + J);
-            if (NRC <= 2) need = (1u << NT) - 1u;
+                    if (16 * I < m && J < g_new) need |= 1u << (I * (I + 1) / 2 + J);
             need = (u32)__builtin_amdgcn_readfirstlane((int)need);
             gram_f64_loop<NRC, CH>(rp, nchunk, acc, nr, need);
 #pragma unroll
             for (int g = 0; g < NRC; ++g) {
                 nr[g] += __shfl_xor(nr[g], 16);
-                nr[g] += __shfl_xor(nr[g], 32);     // n of row r16 of group g, in all four quarter-waves
+                nr[g] += __shfl_xor(nr[g], 32);     // n of slot 16 g + r16, in all four quarter-waves
                 if (q == 0) sm.nrm[16 * g + r16] = nr[g];
             }
             wave_sync();
 
-            // ---- line 11 for every computed pair; T[I][J]: lane r16 = row r16 of group I, bit c = column c of group J
-            u32 T[NR * (NR + 1) / 2];
+            // ---- line 11 for every pair of a computed tile, both ways round.  FA[t]: lane r16 = slot r16 of
+            // group I as the tested row, bit c = column slot c of group J.  FB[t] (I != J): lane r16 = slot r16
+            // of group J as the tested row, bit c = column slot c of group I.  (Same in all quarter-waves.)
+            u32 FA[NT], FB[NT];
 #pragma unroll
-            for (int I = 0; I < NR; ++I) {
+            for (int I = 0; I < NRC; ++I) {
 #pragma unroll
                 for (int J = 0; J <= I; ++J) {
                     const int t = I * (I + 1) / 2 + J;
-                    T[t] = 0;
-                    if (I >= NRC) continue;   // rows past the list (half-size form)
-                    if ((need >> t) & 1u) tiles += 1;
-                    if (16 * I < m && (new16[I] | new16[J]) != 0) {
-                        u32 ft = 0;   // lane = column r16 (row r16 of group J); accumulator v = row 4v + q of group I
+                    FA[t] = FB[t] = 0;
+                    if (NRC <= 2 || ((need >> t) & 1u)) tiles += 1;      // what the loop above computed
+                    if ((need >> t) & 1u) {     // wave-uniform
+                        // lane = slot r16 of group J; accumulator v = slot 4v + q of group I
+                        const float dj = __uint_as_float(key_dist(sm.key[16 * J + r16]));
+                        u32 fa = 0, fb = 0;
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
-                            const int rowpos = 16 * I + 4 * v + q;
-                            const float dvw = (float)(sm.nrm[rowpos] + nr[J < NRC ? J : 0] - 2.0 * acc[t < NT ? t : 0][v]);
-                            const float di = __uint_as_float(sm.dist[rowpos]);
-                            ft |= (di >= dvw) ? (1u << (4 * v + q)) : 0u;
+                            const int si = 16 * I + 4 * v + q;
+                            const float dvw = (float)(sm.nrm[si] + nr[J] - 2.0 * acc[t][v]);
+                            const float di = __uint_as_float(key_dist(sm.key[si]));
+                            fa |= (di >= dvw) ? (1u << (4 * v + q)) : 0u;
+                            fb |= (dj >= dvw) ? (1u << (4 * v + q)) : 0u;
                         }
-                        ft |= (u32)__shfl_xor((int)ft, 16);
-                        ft |= (u32)__shfl_xor((int)ft, 32);
-                        T[t] = transpose16_bits(ft, lane);
+                        fa |= (u32)__shfl_xor((int)fa, 16);
+                        fa |= (u32)__shfl_xor((int)fa, 32);
+                        FA[t] = transpose16_bits(fa, lane);
+                        if (I != J) {
+                            fb |= (u32)__shfl_xor((int)fb, 16);
+                            fb |= (u32)__shfl_xor((int)fb, 32);
+                            FB[t] = fb & 0xFFFFu;
+                        }
                     }
                 }
             }
 
-            // ---- lines 5-18 on masks, one 32-row block at a time (same as the uint8 kernel)
-            u32 Kw[NG];
-            int np_base = 0;
-            wave_sync();
+            // ---- per lane: the rows it owns (slot 16 q + r16 of set 0, slot 64 + 16 q + r16 of set 1) as masks
+            // over all column slots, restricted to the pairs Alg. 4 tests
+            u32 Fw[NSET][NWD], Ew[NSET][NWD], Bw[NSET][NWD];
+            bool valid[NSET];
+            int mypos[NSET];
 #pragma unroll
-            for (int I = 0; I < NG; ++I) {
-                Kw[I] = 0;
-                if (32 * I < m) {
-                    const u64 kb = shfl_u64(kreg[I >> 1], 32 * (I & 1) + l32);
-                    const int posi = 32 * I + l32;
-                    const bool validi = posi < m;
-                    const bool newi = kb & 1ull;
-                    const bool upper = (l32 & 16) != 0;   // my row is in 16-row group 2I+1 (else 2I)
-                    u32 F[NG], E[NG];
+            for (int e = 0; e < NSET; ++e) {
+                const int rg = 4 * e + q;                 // my row group in this set
+                const int s = 16 * rg + r16;
+                valid[e] = rg < NRC && s < m;
+                mypos[e] = valid[e] ? sm.pos[s] : 0;
+                const bool snew = s < n_new;
+                const int a = popc_below(new0, new1, mypos[e]);     // new entries before mine in the list
+                const int b = popc_below(old0, old1, mypos[e]);     // old entries before mine
 #pragma unroll
-                    for (int J = 0; J < NG; ++J) {
-                        u32 f = 0;
-                        if (J <= I) {
-                            // row group a = 2I or 2I+1, column groups 2J and 2J+1 (only tiles with column group <= row group exist)
-                            const int a0 = 2 * I, a1 = 2 * I + 1;
-                            const u32 lo0 = T[a0 * (a0 + 1) / 2 + 2 * J];
-                            const u32 lo1 = T[a1 * (a1 + 1) / 2 + 2 * J];
-                            const u32 hi0 = (2 * J + 1 <= a0) ? T[a0 * (a0 + 1) / 2 + (2 * J + 1 <= a0 ? 2 * J + 1 : 0)] : 0u;
-                            const u32 hi1 = T[a1 * (a1 + 1) / 2 + 2 * J + 1];
-                            f = upper ? (lo1 | (hi1 << 16)) : (lo0 | (hi0 << 16));
+                for (int c = 0; c < NWD; ++c) {
+                    // column groups 2c and 2c + 1
+                    u32 w = 0;
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        const int Jc = 2 * c + hh;
+                        if (Jc >= NRC) continue;
+                        u32 w16 = 0;
+#pragma unroll
+                        for (int Ir = 4 * e; Ir < 4 * e + 4 && Ir < NRC; ++Ir) {
+                            const u32 cand = Jc <= Ir ? FA[Ir * (Ir + 1) / 2 + Jc] : FB[Jc * (Jc + 1) / 2 + Ir];
+                            w16 = (rg == Ir) ? cand : w16;
                         }
-                        const u32 neww = (u32)(newm[J >> 1] >> (32 * (J & 1)));
-                        u32 e = newi ? 0xFFFFFFFFu : neww;
-                        if (J == I) e &= (1u << l32) - 1u;
-                        if (J > I || !validi) e = 0;
-                        E[J] = e;
-                        F[J] = f & e;
+                        w |= w16 << (16 * hh);
                     }
-                    bool pre = false;
-#pragma unroll
-                    for (int J = 0; J < I; ++J) pre = pre || ((F[J] & Kw[J]) != 0);
-                    u32 Kcur = (u32)__builtin_amdgcn_ballot_w64(validi && half == 0);
-                    for (int sweep = 0; sweep < 33; ++sweep) {
-                        const bool keep = validi && !pre && ((F[I] & Kcur) == 0);
-                        const u32 Knew = (u32)__builtin_amdgcn_ballot_w64(keep && half == 0);
-                        if (Knew == Kcur) break;
-                        Kcur = Knew;
-                    }
-                    Kw[I] = Kcur;
-                    const bool kept = (Kcur >> l32) & 1u;
-                    const bool pruned = validi && !kept && half == 0;
-                    int tgt = -1, ev = 0;
-#pragma unroll
-                    for (int J = 0; J <= I; ++J) {
-                        const u32 fk = F[J] & Kw[J], ek = E[J] & Kw[J];
-                        if (tgt < 0) {
-                            if (fk) {
-                                const int b = __builtin_ctz(fk);
-                                tgt = 32 * J + b;
-                                ev += __popc(ek & (0xFFFFFFFFu >> (31 - b)));
-                            } else {
-                                ev += __popc(ek);
-                            }
-                        }
-                    }
-                    if (half == 0) ev_lane += (u32)ev;
-                    const u64 pm = __builtin_amdgcn_ballot_w64(pruned);
-                    if (pruned) {
-                        const int p = np_base + __popcll(pm & lanes_below(lane));
-                        sm.ppos[p] = (u32)posi;
-                        sm.ptgt[p] = (u32)tgt;
-                    }
-                    np_base += __popcll(pm);
+                    const u32 bnew = range_word(0, a, c), bold = range_word(n_new, n_new + b, c);
+                    Bw[e][c] = bnew | bold;
+                    Ew[e][c] = valid[e] ? (snew ? (bnew | bold) : bnew) : 0u;
+                    Fw[e][c] = w & Ew[e][c];
                 }
             }
-            // line 15 + compaction: kept entries, flag old, back into the row
-            const u64 K0 = (u64)Kw[0] | (NG > 1 ? ((u64)Kw[NG > 1 ? 1 : 0] << 32) : 0ull);
-            const u64 K1 = NG > 2 ? ((u64)Kw[NG > 2 ? 2 : 0] | (NG > 3 ? ((u64)Kw[NG > 3 ? 3 : 0] << 32) : 0ull)) : 0ull;
-            const int nk0 = __popcll(K0);
-            if ((K0 >> lane) & 1ull) row[__popcll(K0 & lanes_below(lane))] = kreg[0] & ~1ull;
-            if (NG > 2 && ((K1 >> lane) & 1ull)) row[nk0 + __popcll(K1 & lanes_below(lane))] = kreg[1] & ~1ull;
+
+            // ---- lines 5-18: the kept set as the fixed point, all rows at once
+            u32 Kw[3] = {0u, 0u, 0u};
+            u64 Kset[2] = {0ull, 0ull};       // bit lane of Kset[e]: my row of set e is kept
+            {
+                const u64 v0 = val0, v1 = val1;     // slots in use: 0 .. m-1 (same masks as positions)
+                u64 K0 = v0;
+                u32 K1 = (u32)v1;
+                for (int sweep = 0; sweep < 16 * NRC + 1; ++sweep) {
+                    bool hit0 = false, hit1 = false;
+#pragma unroll
+                    for (int c = 0; c < NWD; ++c) {
+                        const u32 kc = c == 0 ? (u32)K0 : c == 1 ? (u32)(K0 >> 32) : K1;
+                        hit0 = hit0 || ((Fw[0][c] & kc) != 0);
+                        if (NSET > 1) hit1 = hit1 || ((Fw[NSET - 1][c] & kc) != 0);
+                    }
+                    const u64 b0 = __builtin_amdgcn_ballot_w64(hit0);
+                    const u64 b1 = NSET > 1 ? __builtin_amdgcn_ballot_w64(hit1) : 0ull;
+                    const u64 K0n = v0 & ~b0;
+                    const u32 K1n = (u32)v1 & ~(u32)b1;
+                    if (K0n == K0 && K1n == K1) break;
+                    K0 = K0n;
+                    K1 = K1n;
+                }
+                Kw[0] = (u32)K0;
+                Kw[1] = (u32)(K0 >> 32);
+                Kw[2] = K1;
+                Kset[0] = K0;
+                Kset[1] = (u64)K1;
+            }
+
+            // ---- kept rows go back to the list in list order; pruned rows name their target
+            int np_base = 0;
+            int nkept = 0;
+#pragma unroll
+            for (int c = 0; c < 3; ++c) nkept += __popc(Kw[c]);
+            wave_sync();
+#pragma unroll
+            for (int e = 0; e < NSET; ++e) {
+                const int s = 16 * (4 * e + q) + r16;
+                const bool kept = valid[e] && ((Kset[e] >> lane) & 1ull);
+                const bool pruned = valid[e] && !kept;
+                int tgt = -1, ev = 0;
+                if (valid[e]) {
+                    // failing kept columns: the first new one and the first old one are the list-first of their kind
+                    int tn = -1, to = -1;
+#pragma unroll
+                    for (int c = NWD - 1; c >= 0; --c) {
+                        const u32 fk = Fw[e][c] & Kw[c];
+                        const u32 fn = fk & range_word(0, n_new, c), fo = fk & ~range_word(0, n_new, c);
+                        if (fn) tn = 32 * c + __builtin_ctz(fn);
+                        if (fo) to = 32 * c + __builtin_ctz(fo);
+                    }
+                    if (tn >= 0 && to >= 0) tgt = sm.pos[tn] < sm.pos[to] ? tn : to;
+                    else tgt = tn >= 0 ? tn : to;
+                    // the evaluations Alg. 4 makes for this row: tested kept candidates up to and including w
+                    int ta = 16 * NRC, tb = 16 * NRC;      // no target: everything before me
+                    if (tgt >= 0) {
+                        const int pt = sm.pos[tgt];
+                        ta = popc_below(new0, new1, pt) + (tgt < n_new ? 1 : 0);
+                        tb = popc_below(old0, old1, pt) + (tgt < n_new ? 0 : 1);
+                    }
+#pragma unroll
+                    for (int c = 0; c < NWD; ++c) {
+                        const u32 upto = range_word(0, ta, c) | range_word(n_new, n_new + tb, c);
+                        ev += __popc(Ew[e][c] & Kw[c] & upto);
+                    }
+                }
+                ev_lane += (u32)ev;
+                if (kept) {
+                    int rank = 0;
+#pragma unroll
+                    for (int c = 0; c < NWD; ++c) rank += __popc(Kw[c] & Bw[e][c]);
+                    row[rank] = sm.key[s] & ~1ull;      // line 15: flag old
+                }
+                const u64 pm = __builtin_amdgcn_ballot_w64(pruned);
+                if (pruned) {
+                    const int p = np_base + __popcll(pm & lanes_below(lane));
+                    sm.pv[p] = (u32)s;
+                    sm.pw[p] = (u32)tgt;
+                }
+                np_base += __popcll(pm);
+            }
             if (lane == 0) {
-                deg[u] = nk0 + __popcll(K1);
+                deg[u] = nkept;
                 nprop[u] = np_base;
             }
             nprops_total += np_base;
@@ -309,8 +393,9 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
             for (int b = 0; b < np_base; b += 8) {
                 const int p = b + grp;
                 const bool have = p < np_base;
-                const int pi = (int)sm.ppos[have ? p : 0], pt = (int)sm.ptgt[have ? p : 0];
-                const int idv = sm.id[pi], idw = sm.id[pt];
+                const u32 sv = sm.pv[have ? p : 0], sw0 = sm.pw[have ? p : 0];
+                const u32 sw = sw0 < 16u * NRC ? sw0 : 0u;     // a pruned row always has a target
+                const int idv = (int)key_id(sm.key[sv]), idw = (int)key_id(sm.key[sw]);
                 u32 db = 0;
                 if (have) db = group8_dist_bits<DT_F32>(X + (size_t)idv * d, X + (size_t)idw * d, d, 1, sub);
                 if (have && sub == 0) emit_redirect(make_key(db, (u32)idv, 1u), (u32)idw, props + (size_t)u * R + p);
