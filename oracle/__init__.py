@@ -173,6 +173,42 @@ def build_sync(X: np.ndarray, S: int, R: int, T1: int, T2: int, seed: int,
     return BuildResult(s, rev, rpr, ie.value)
 
 
+def update_neighbors_blocks(X: np.ndarray, snap: Snapshot, R: int, nblocks: int):
+    """One block-sequential UpdateNeighbors pass (nblocks runs of consecutive ids in turn; 1 = the
+    synchronous round, n = Alg. 4's vertex order); returns (new snapshot, evals, proposals)."""
+    _chk(X)
+    n, d = X.shape
+    s = snap.copy()
+    W = s.ids.shape[1]
+    ev = ctypes.c_int64(0)
+    npr = ctypes.c_int64(0)
+    rc = _load().orc_update_neighbors_blocks(
+        _p(X), ctypes.c_int64(n), ctypes.c_int32(d), ctypes.c_int(_dt(X)), ctypes.c_int32(R),
+        ctypes.c_int32(W), ctypes.c_int64(nblocks), _p(s.ids), _p(s.dist), _p(s.flags), _p(s.deg),
+        ctypes.byref(ev), ctypes.byref(npr))
+    assert rc == 0, rc
+    return s, ev.value, npr.value
+
+
+def build_blocks(X: np.ndarray, S: int, R: int, T1: int, T2: int, seed: int, nblocks: int,
+                 W: int | None = None, progress: bool = False) -> BuildResult:
+    """Alg. 6 with block-sequential passes (see update_neighbors_blocks)."""
+    _chk(X)
+    _load().orc_set_progress(ctypes.c_int(1 if progress else 0))
+    n, d = X.shape
+    W = R if W is None else W
+    s = Snapshot.empty(n, W)
+    rev = np.zeros(T1 * T2, np.int64)
+    rpr = np.zeros(T1 * T2, np.int64)
+    rc = _load().orc_build_blocks(
+        _p(X), ctypes.c_int64(n), ctypes.c_int32(d), ctypes.c_int(_dt(X)), ctypes.c_int32(S),
+        ctypes.c_int32(R), ctypes.c_int32(T1), ctypes.c_int32(T2), ctypes.c_uint64(seed),
+        ctypes.c_int64(nblocks), ctypes.c_int32(W), _p(s.ids), _p(s.dist), _p(s.flags), _p(s.deg),
+        _p(rev), _p(rpr))
+    assert rc == 0, rc
+    return BuildResult(s, rev, rpr, n * S)
+
+
 def build_paper_order(X: np.ndarray, S: int, R: int, T1: int, T2: int, seed: int, W: int):
     """Alg. 6 in the paper's in-place vertex order; returns (ids, deg, evals, max_degree)."""
     _chk(X)

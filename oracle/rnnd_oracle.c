@@ -11,8 +11,8 @@
  * The method is a heuristic iteration, so this file takes the algorithm's
  * steps in the paper's order and notation:
  *
- *   Alg. 6 (RNN-Descent)      -> orc_build_sync / orc_build_paper_order
- *   Alg. 4 (UpdateNeighbors)  -> orc_update_neighbors_sync / update_paper_order
+ *   Alg. 6 (RNN-Descent)      -> orc_build_sync / orc_build_blocks / orc_build_paper_order
+ *   Alg. 4 (UpdateNeighbors)  -> orc_update_neighbors_sync / _blocks / update_paper_order
  *   Alg. 5 (AddReverseEdges)  -> orc_add_reverse_edges
  *   Alg. 3 (RNGStrategy)      -> orc_rng_strategy
  *   Alg. 1 (Search) + Eq. 4   -> orc_search
@@ -334,6 +334,49 @@ static void update_neighbors_sync(const data_t *D, list_t *G, int32_t R, int use
     free(P.p);
 }
 
+/* Block-sequential pass (between the synchronous round and the paper's in-place order): the
+ * vertices are cut into nblocks runs of consecutive ids, ceil(n / nblocks) each, which take their
+ * turn in id order.  Every vertex of a run is scanned against the graph as it stands when the run
+ * starts; the run's redirected edges enter their targets' lists (any vertex; lists cut to R as in
+ * the synchronous round) before the next run starts, so later runs of the same pass see them, as
+ * later vertices do in Alg. 4's own loop.  nblocks = 1 is the synchronous round; nblocks = n is
+ * Alg. 4's vertex order. */
+static void update_neighbors_blocks(const data_t *D, list_t *G, int32_t R, int64_t nblocks,
+                                    int64_t *evals, int64_t *nprops)
+{
+    int64_t n = D->n, bs = (n + nblocks - 1) / nblocks;
+    plist_t P = {0, 0, 0};
+    char *dirty = (char *)calloc((size_t)n, 1);
+    for (int64_t lo = 0; lo < n; lo += bs) {
+        int64_t hi = lo + bs < n ? lo + bs : n;
+        list_t *K = graph_alloc(hi - lo);
+        P.len = 0;
+        for (int64_t u = lo; u < hi; ++u) {
+            scan_vertex(D, &G[u], 1, &K[u - lo], &P, evals);
+            for (int32_t k = 0; k < K[u - lo].len; ++k) K[u - lo].e[k].is_new = 0;   /* L15 */
+        }
+        for (int64_t u = lo; u < hi; ++u) {
+            free(G[u].e);
+            G[u] = K[u - lo];
+        }
+        free(K);
+        *nprops += P.len;
+        for (int64_t i = 0; i < P.len; ++i) {            /* L13: v enters w's list, flagged new */
+            entry_t x;
+            x.id = P.p[i].id; x.dist = P.p[i].dist; x.is_new = 1;
+            list_push(&G[P.p[i].target], x);
+            dirty[P.p[i].target] = 1;
+        }
+        for (int64_t i = 0; i < P.len; ++i)
+            if (dirty[P.p[i].target]) {
+                list_canonicalise(&G[P.p[i].target], R);
+                dirty[P.p[i].target] = 0;
+            }
+    }
+    free(dirty);
+    free(P.p);
+}
+
 /* Paper order: vertices in index order, every redirect applied at once to w's
  * list (no cap on the list length, Sec. 4.4), flags exactly as in Alg. 4. */
 static void update_neighbors_paper_order(const data_t *D, list_t *G, int64_t *evals)
@@ -475,6 +518,52 @@ int orc_build_sync(const void *X, int64_t n, int32_t d, int dtype, int32_t S, in
             if (round_props) round_props[t1 * T2 + t2] = np;
             if (g_progress) {
                 fprintf(stderr, "oracle: round %d of %d done, %lld evaluations\n",
+                        (int)(t1 * T2 + t2 + 1), (int)(T1 * T2), (long long)ev);
+                fflush(stderr);
+            }
+        }
+        if (t1 != T1 - 1) add_reverse_edges(G, n, R);           /* L6-7 */
+    }
+    graph_to_flat(G, n, W, ids, dist, flags, deg);
+    graph_free(G, n);
+    return 0;
+}
+
+/* One block-sequential pass on a flat snapshot. */
+int orc_update_neighbors_blocks(const void *X, int64_t n, int32_t d, int dtype, int32_t R, int32_t W,
+                                int64_t nblocks, int32_t *ids, double *dist, uint8_t *flags,
+                                int32_t *deg, int64_t *evals, int64_t *nprops)
+{
+    if (R > W || nblocks < 1 || nblocks > n) return -1;
+    data_t D = {X, n, d, dtype};
+    list_t *G = graph_from_flat(n, W, ids, dist, flags, deg);
+    int64_t ev = 0, np = 0;
+    update_neighbors_blocks(&D, G, R, nblocks, &ev, &np);
+    graph_to_flat(G, n, W, ids, dist, flags, deg);
+    graph_free(G, n);
+    if (evals) *evals = ev;
+    if (nprops) *nprops = np;
+    return 0;
+}
+
+/* Alg. 6 with block-sequential passes. */
+int orc_build_blocks(const void *X, int64_t n, int32_t d, int dtype, int32_t S, int32_t R,
+                     int32_t T1, int32_t T2, uint64_t seed, int64_t nblocks, int32_t W,
+                     int32_t *ids, double *dist, uint8_t *flags, int32_t *deg,
+                     int64_t *round_evals, int64_t *round_props)
+{
+    if (S < 1 || S > R || R > W || (int64_t)S > n - 1 || T1 < 1 || T2 < 1) return -1;
+    if (nblocks < 1 || nblocks > n) return -1;
+    data_t D = {X, n, d, dtype};
+    list_t *G = random_graph(&D, S, seed);                      /* L1-2 */
+    for (int32_t t1 = 0; t1 < T1; ++t1) {                       /* L3 */
+        for (int32_t t2 = 0; t2 < T2; ++t2) {                   /* L4 */
+            int64_t ev = 0, np = 0;
+            update_neighbors_blocks(&D, G, R, nblocks, &ev, &np);       /* L5 */
+            if (round_evals) round_evals[t1 * T2 + t2] = ev;
+            if (round_props) round_props[t1 * T2 + t2] = np;
+            if (g_progress) {
+                fprintf(stderr, "oracle: pass %d of %d done, %lld evaluations\n",
                         (int)(t1 * T2 + t2 + 1), (int)(T1 * T2), (long long)ev);
                 fflush(stderr);
             }

@@ -7,6 +7,8 @@ mathematics fixes, never against itself.  (CPU only.)
   Eq. 2 on kept neighbours, degree bounds    -> Eq. 2, Alg. 5, Sec. 5.3
   flag skip changes cost, not results        -> Sec. 4.2 last paragraph
   set-wise brute-force models on tiny inputs -> Alg. 4, Alg. 5 written a second way
+  block-sequential passes: worked example of the vertex order, one block = synchronous round,
+  n blocks = the in-place order of Alg. 4 line 1  -> Alg. 4
 """
 import numpy as np
 import pytest
@@ -336,6 +338,106 @@ def test_against_setwise_model_on_tiny_inputs(oracle_mod, seed, R):
 
 
 # ----------------------------------------------------------- search tooling
+# ------------------------------- block-sequential passes (order of Alg. 4's vertex loop)
+def test_vertex_order_worked_example(oracle_mod):
+    g = read_golden("vertex_order_example.txt")
+    X = np.array(g["points"], np.uint8)
+    n = len(X)
+    lists = [list(r) for r in g["initial_lists"]] + [[] for _ in range(n - len(g["initial_lists"]))]
+    s0 = snapshot_from_lists(oracle_mod, X, lists, 8)
+
+    def rows(s):
+        got = [[i for _, i, _ in rows_of(s, u)] for u in range(n)]
+        while got and not got[-1]:
+            got.pop()
+        return got
+
+    s_in_place, ev, _ = oracle_mod.update_neighbors_blocks(X, s0, 8, n)
+    assert rows(s_in_place) == g["in_place_rows_after"] and ev == g["in_place_evaluations"][0][0]
+    assert rows_of(s_in_place, 2) == [(13.0, 3, 0)]             # received before its own turn: scanned, old
+    assert rows_of(s_in_place, 1) == [(2.0, 2, 0)]
+    s_sync, ev, _ = oracle_mod.update_neighbors_blocks(X, s0, 8, 1)
+    assert rows(s_sync) == g["synchronous_rows_after"] and ev == g["synchronous_evaluations"][0][0]
+    assert rows_of(s_sync, 1) == [(2.0, 2, 1), (13.0, 3, 0)]    # received after its scan: still new
+    s_ref, ev_ref, _ = oracle_mod.update_neighbors_sync(X, s0, 8)
+    assert rows(s_ref) == g["synchronous_rows_after"] and ev_ref == ev
+
+
+def py_block_pass(D, lists, R, nblocks):
+    """The pass in runs of consecutive ids, written with dicts: a run is scanned on the lists as they
+    stand when it starts; its redirected edges are merged (existing entry wins, cut to R) before the next."""
+    n = len(lists)
+    bs = -(-n // nblocks)
+    lists = [dict(l) for l in lists]
+    evals = 0
+    for lo in range(0, n, bs):
+        incoming = {}
+        kept = {}
+        for u in range(lo, min(n, lo + bs)):
+            sel = []
+            for v in sorted(lists[u], key=lambda v: (D[u, v], v)):
+                ok = True
+                for w in sel:
+                    if lists[u][v] == 0 and lists[u][w] == 0:
+                        continue
+                    evals += 1
+                    if D[u, v] >= D[v, w]:
+                        incoming.setdefault(w, set()).add(v)
+                        ok = False
+                        break
+                if ok:
+                    sel.append(v)
+            kept[u] = {v: 0 for v in sel}
+        for u, k in kept.items():
+            lists[u] = k
+        for x, vs in incoming.items():
+            cand = {v: 1 for v in vs}
+            cand.update(lists[x])
+            order = sorted(cand, key=lambda v: (D[x, v], v))[:R]
+            lists[x] = {v: cand[v] for v in order}
+    return lists, evals
+
+
+@pytest.mark.parametrize("seed,R,nblocks", [(1, 4, 1), (2, 6, 3), (3, 3, 7), (4, 10, 30), (5, 5, 4), (6, 8, 29)])
+def test_block_passes_against_setwise_model(oracle_mod, seed, R, nblocks):
+    n, S = 30, 3
+    X = small_u8(n, 2, 200 + seed, 0, 12)                       # dense ties
+    D = sqdist_matrix(X)
+    snap = oracle_mod.random_graph(X, S, seed, R)
+    model = lists_of(snap, n)
+    for step in ["u", "u", "u", "r", "u", "u", "r", "u", "u"]:
+        if step == "u":
+            snap, evals, _ = oracle_mod.update_neighbors_blocks(X, snap, R, nblocks)
+            model, mevals = py_block_pass(D, model, R, nblocks)
+            assert evals == mevals
+        else:
+            snap = oracle_mod.add_reverse_edges(snap, R)
+            model = py_add_reverse(D, model, R)
+        assert lists_of(snap, n) == model
+
+
+@pytest.mark.parametrize("kind", ["u8", "f32"])
+def test_one_block_is_the_synchronous_round_and_n_blocks_the_in_place_order(oracle_mod, kind):
+    n, S, T1, T2 = 150, 6, 3, 4
+    X = small_u8(n, 8, 31, 0, 40) if kind == "u8" else small_f32(n, 8, 32)
+    R = 40
+    a = oracle_mod.build_blocks(X, S, R, T1, T2, 9, 1)
+    b = oracle_mod.build_sync(X, S, R, T1, T2, 9)
+    assert (a.snap.ids == b.snap.ids).all() and (a.snap.dist == b.snap.dist).all()
+    assert (a.snap.flags == b.snap.flags).all() and (a.snap.deg == b.snap.deg).all()
+    assert (a.round_evals == b.round_evals).all() and (a.round_props == b.round_props).all()
+    # with lists that never reach the cut (R = n - 1) the n-block form is Alg. 4 as printed
+    R = n - 1
+    c = oracle_mod.build_blocks(X, S, R, T1, T2, 9, n)
+    ids, deg, evals, mx = oracle_mod.build_paper_order(X, S, R, T1, T2, 9, R)
+    assert mx <= R
+    assert (c.snap.deg == deg).all() and (c.snap.ids == ids).all()
+    assert int(c.round_evals.sum()) == evals
+    # and the order matters: the two ends differ on the same input
+    d = oracle_mod.build_blocks(X, S, R, T1, T2, 9, 1)
+    assert (d.snap.ids != c.snap.ids).any()
+
+
 def test_bruteforce_knn_matches_numpy(oracle_mod):
     X = small_u8(500, 16, 41)
     Q = small_u8(20, 16, 42)
