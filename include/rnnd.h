@@ -95,6 +95,28 @@ int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int metric, in
                   int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out, int32_t *degree_out,
                   uint64_t *keys_out, rnnd_stats *stats, void *stream);
 
+/* Alg. 6 with block-sequential passes: a variant between the synchronous round and the in-place
+ * vertex loop of Alg. 4 (line 1 visits the vertices one after the other and line 13 changes the
+ * edge set at once, so a vertex visited later in the same pass already sees the edges redirected
+ * to it).  The vertices are cut into runs of ceil(N / blocks) consecutive ids; the runs take their
+ * turn in id order; every vertex of a run is scanned against the graph as it stands when the run
+ * starts, and the run's redirected edges are merged into their targets' lists (any vertex; first R
+ * entries as in rnnd_build) before the next run starts.  blocks = 1 gives the graph of rnnd_build;
+ * blocks = N visits the vertices in Alg. 4's own order.  Every value of blocks defines one graph
+ * per seed, bit for bit.
+ *   blocks     1 <= blocks <= N, and T1 * T2 * (runs per pass) <= 131072
+ *   keys_out   device uint64 [N*R] or NULL; stats: host or NULL (per-pass sums; scan_ms is not measured)
+ * Other arguments, ownership and errors as for rnnd_build_ex. */
+int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+                      int32_t T1, int32_t T2, uint64_t seed, int64_t blocks, int32_t *graph_out,
+                      int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream);
+
+/* n_passes block-sequential UpdateNeighbors passes (see rnnd_build_blocks) applied in place to a
+ * snapshot.  stats (host, may be NULL) receives the per-pass counters. */
+int rnnd_update_neighbors_blocks(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t R,
+                                 uint64_t *keys, int32_t *deg, int32_t n_passes, int64_t blocks,
+                                 rnnd_stats *stats, void *stream);
+
 /* Bytes of device workspace rnnd_build allocates (and frees) internally for these sizes. */
 int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, size_t *bytes);
 

@@ -84,6 +84,10 @@ def load_library():
         L.rnnd_build.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, i32, i32, u64, vp, vp, vp]
         L.rnnd_build_ex.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, i32, i32, u64, vp, vp, vp,
                                     c.POINTER(Stats), vp]
+        L.rnnd_build_blocks.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, i32, i32, u64, i64, vp, vp, vp,
+                                        c.POINTER(Stats), vp]
+        L.rnnd_update_neighbors_blocks.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, vp, vp, i32, i64,
+                                                   c.POINTER(Stats), vp]
         L.rnnd_workspace_bytes.argtypes = [i64, i32, c.c_int, i32, c.POINTER(c.c_size_t)]
         L.rnnd_random_graph.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, u64, vp, vp, vp]
         L.rnnd_update_neighbors.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, vp, vp, i32,
@@ -98,7 +102,7 @@ def load_library():
         L.rnnd_version.restype = c.c_int
         for name in ("rnnd_build", "rnnd_build_ex", "rnnd_workspace_bytes", "rnnd_random_graph",
                      "rnnd_update_neighbors", "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search",
-                     "rnnd_set_kernel_variant"):
+                     "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks"):
             getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -173,6 +177,21 @@ def rnnd_build_ex(X, S: int, R: int, T1: int, T2: int, seed: int, metric: int = 
     return graph, degree, keys, st
 
 
+def rnnd_build_blocks(X, S: int, R: int, T1: int, T2: int, seed: int, blocks: int, metric: int = RNND_L2SQ,
+                      stream=None, want_keys: bool = True):
+    """rnnd_build_blocks: returns (graph, degree, keys [N, R] int64-typed uint64 or None, Stats)."""
+    torch = _torch()
+    ptr, N, d, dt = _data_args(X)
+    graph = torch.empty((N, R), dtype=torch.int32, device=X.device)
+    degree = torch.empty((N,), dtype=torch.int32, device=X.device)
+    keys = torch.empty((N, R), dtype=torch.int64, device=X.device) if want_keys else None
+    st = Stats()
+    _check(load_library().rnnd_build_blocks(ptr, N, d, dt, metric, S, R, T1, T2, seed, blocks, graph.data_ptr(),
+                                            degree.data_ptr(), keys.data_ptr() if want_keys else None,
+                                            ctypes.byref(st), _stream(stream)))
+    return graph, degree, keys, st
+
+
 def rnnd_random_graph(X, S: int, R: int, seed: int, metric: int = RNND_L2SQ, stream=None):
     torch = _torch()
     ptr, N, d, dt = _data_args(X)
@@ -191,6 +210,18 @@ def rnnd_update_neighbors(X, keys, deg, R: int, n_rounds: int = 1, metric: int =
     st = Stats()
     _check(load_library().rnnd_update_neighbors(ptr, N, d, dt, metric, R, keys.data_ptr(), deg.data_ptr(),
                                                 n_rounds, ctypes.byref(st), _stream(stream)))
+    return st
+
+
+def rnnd_update_neighbors_blocks(X, keys, deg, R: int, blocks: int, n_passes: int = 1, metric: int = RNND_L2SQ,
+                                 stream=None):
+    """In place on (keys, deg); returns Stats."""
+    ptr, N, d, dt = _data_args(X)
+    assert keys.is_cuda and keys.is_contiguous() and keys.shape == (N, R) and keys.element_size() == 8
+    assert deg.is_cuda and deg.is_contiguous() and deg.shape == (N,) and deg.element_size() == 4
+    st = Stats()
+    _check(load_library().rnnd_update_neighbors_blocks(ptr, N, d, dt, metric, R, keys.data_ptr(), deg.data_ptr(),
+                                                       n_passes, blocks, ctypes.byref(st), _stream(stream)))
     return st
 
 

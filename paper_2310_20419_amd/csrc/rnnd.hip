@@ -605,11 +605,12 @@ __global__ __launch_bounds__(BLOCK) void k_merge(long long N, int R, u64 *keys, 
     else merge_general_body(R, keys, deg, tlist, n_touched + 3, cnt, inbox, binoff, bins, tc, use_classes, s_stage);
 }
 
-// Items i < n with cls[i] >= 0 are appended to list cls[i]; item i stands for vertex idx[i] (or i).
-// blockIdx.y = s selects source list s: n_ptr[s], idx + s*N, cls + s*N.  One atomic per class per 1024 items.
+// Items i < n with cls[first + i] >= 0 are appended to list cls[first + i]; item i stands for vertex idx[i]
+// (or first + i).  blockIdx.y = s selects source list s: n_ptr[s], idx + s*N, cls + s*N.  One atomic per class
+// per 1024 items.  With `taken`, the class of every listed item is then cleared there (taken may be cls).
 __global__ __launch_bounds__(1024) void k_compact_classes(const u32 *n_ptr, u32 n_fixed, const int *idx,
                                                           const int8_t *cls, int *lists, long long N,
-                                                          u32 *n_out)
+                                                          u32 *n_out, u32 first, int8_t *taken)
 {
     __shared__ u32 s_cnt[16][NDEG], s_base[NDEG];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -618,7 +619,7 @@ __global__ __launch_bounds__(1024) void k_compact_classes(const u32 *n_ptr, u32 
     cls += (size_t)blockIdx.y * N;
     for (u32 base = blockIdx.x * 1024u; base < n; base += gridDim.x * 1024u) {
         const u32 i = base + threadIdx.x;
-        const int c = i < n ? (int)cls[i] : -1;
+        const int c = i < n ? (int)cls[first + i] : -1;
         u64 b[NDEG];
 #pragma unroll
         for (int k = 0; k < NDEG; ++k) b[k] = __builtin_amdgcn_ballot_w64(c == k);
@@ -638,10 +639,22 @@ __global__ __launch_bounds__(1024) void k_compact_classes(const u32 *n_ptr, u32 
 #pragma unroll
             for (int k = 1; k < NDEG; ++k) mine = (c == k) ? b[k] : mine;
             const u32 off = s_base[c] + s_cnt[wave][c] + (u32)__popcll(mine & lanes_below(lane));
-            lists[(size_t)c * N + off] = idx ? idx[i] : (int)i;
+            lists[(size_t)c * N + off] = idx ? idx[i] : (int)(first + i);
+            if (taken) taken[first + i] = (int8_t)-1;
         }
         __syncthreads();
     }
+}
+
+// Block-sequential passes keep the class of every vertex that holds a "new" entry in vcls[] between runs:
+// after a run's merge, vcls[x] <- tcls of every touched vertex x (blockIdx.y = merge class).
+__global__ __launch_bounds__(256) void k_store_classes(const u32 *n_touched, const int *tlists, const int8_t *tcls,
+                                                       long long N, int8_t *vcls)
+{
+    const u32 n = n_touched[blockIdx.y];
+    const int *tl = tlists + (size_t)blockIdx.y * N;
+    const int8_t *tc = tcls + (size_t)blockIdx.y * N;
+    for (u32 i = blockIdx.x * 256u + threadIdx.x; i < n; i += gridDim.x * 256u) vcls[tl[i]] = tc[i];
 }
 
 // ------------------------------------------------------------ AddReverseEdges
@@ -1088,13 +1101,28 @@ static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64
 }
 
 // One synchronous UpdateNeighbors round t (ctr[t] -> ctr[t+1]).
+// One run of consecutive vertex ids of a block-sequential pass: ids first .. first + count - 1.
+struct VertexRun {
+    u32 first = 0, count = 0;
+};
+
+// One synchronous round over the active lists of counter slot t (run == nullptr), or one run of a
+// block-sequential pass: the run's active lists are taken from vcls[] first, and the classes of the
+// vertices its merge touched go back to vcls[] instead of into the next slot's lists.
 static hipError_t launch_update_round(const Workspace &w, const void *X, long long N, int d, int dtype,
                                       int vec_ok, int variant, int R, u64 *keys, int *deg, int t,
-                                      hipStream_t st, const RoundEvents &re = RoundEvents())
+                                      hipStream_t st, const RoundEvents &re = RoundEvents(),
+                                      const VertexRun *run = nullptr)
 {
     const int pb = persistent_blocks();
     RoundCtr *c = w.ctr + t;
     const int use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
+    if (run) {
+        const unsigned cb = (run->count + 1023u) / 1024u;
+        hipLaunchKernelGGL(k_compact_classes, dim3(cb < 256u ? cb : 256u, 1), dim3(1024), 0, st, (const u32 *)nullptr,
+                           run->count, (const int *)nullptr, (const int8_t *)w.vcls, w.lists, N, c->n_active,
+                           run->first, w.vcls);
+    }
     if (variant == 2) {
         if (d == 32) launch_mfma_scan_classes<1>(w, R, keys, deg, N, c, st, re);
         else if (d == 64) launch_mfma_scan_classes<2>(w, R, keys, deg, N, c, st, re);
@@ -1140,10 +1168,41 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
     static const int merge_per_cu = resident_blocks_per_cu(k_merge, 6);
     hipLaunchKernelGGL(k_merge, dim3(cu_count() * merge_per_cu, NMRG), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
                        w.fill, w.inbox, w.binoff, w.bins, w.tcls, use_classes);
-    hipExtLaunchKernelGGL(k_compact_classes, dim3(128, NMRG), dim3(1024), 0, st, nullptr, re.round_stop, 0,
-                          (const u32 *)c->n_touched, 0u, (const int *)w.touched, (const int8_t *)w.tcls, w.lists, N,
-                          (c + 1)->n_active);
+    if (run)
+        hipLaunchKernelGGL(k_store_classes, dim3(64, NMRG), dim3(256), 0, st, (const u32 *)c->n_touched,
+                           (const int *)w.touched, (const int8_t *)w.tcls, N, w.vcls);
+    else
+        hipExtLaunchKernelGGL(k_compact_classes, dim3(128, NMRG), dim3(1024), 0, st, nullptr, re.round_stop, 0,
+                              (const u32 *)c->n_touched, 0u, (const int *)w.touched, (const int8_t *)w.tcls, w.lists,
+                              N, (c + 1)->n_active, 0u, (int8_t *)nullptr);
     return hipGetLastError();
+}
+
+// One block-sequential pass: `blocks` runs of ceil(N / blocks) consecutive ids, in id order, counter slots
+// t0, t0 + 1, ...  Returns the number of slots used through *used.
+static hipError_t launch_update_pass_blocks(const Workspace &w, const void *X, long long N, int d, int dtype,
+                                            int vec_ok, int variant, int R, u64 *keys, int *deg, int t0,
+                                            long long blocks, hipStream_t st, int *used)
+{
+    const long long bs = (N + blocks - 1) / blocks;
+    int k = 0;
+    for (long long lo = 0; lo < N; lo += bs, ++k) {
+        VertexRun run;
+        run.first = (u32)lo;
+        run.count = (u32)(lo + bs < N ? bs : N - lo);
+        hipError_t e = launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, keys, deg, t0 + k, st, RoundEvents(),
+                                           &run);
+        if (e != hipSuccess) return e;
+    }
+    *used = k;
+    return hipSuccess;
+}
+
+// slots a pass of `blocks` runs uses
+static long long runs_per_pass(long long N, long long blocks)
+{
+    const long long bs = (N + blocks - 1) / blocks;
+    return (N + bs - 1) / bs;
 }
 
 // vcls[] (class of every vertex holding a "new" entry) -> active lists of round t_next
@@ -1152,10 +1211,11 @@ static void launch_compact_all(const Workspace &w, long long N, int t_next, hipS
 {
     hipExtLaunchKernelGGL(k_compact_classes, dim3(256, 1), dim3(1024), 0, st, nullptr, e_stop, 0,
                           (const u32 *)nullptr, (u32)N, (const int *)nullptr, (const int8_t *)w.vcls, w.lists, N,
-                          w.ctr[t_next].n_active);
+                          w.ctr[t_next].n_active, 0u, (int8_t *)nullptr);
 }
 
-// AddReverseEdges; the active lists for round t_next are rebuilt from scratch.  Expects fill[] == 0
+// AddReverseEdges; the active lists for round t_next are rebuilt from scratch (t_next < 0: only vcls[], the
+// class of every vertex that holds a "new" entry, is written).  Expects fill[] == 0
 // and leaves it so.  Between rounds nprop[], tcls[], props[] and touched[] are free: they serve as the
 // second in-edge count, the per-vertex marks, the late arrival numbers and their position masks.  misc: [0] bin cursor, [1] vertices with a bin (lines 1-5),
 // [2] bin cursor, [3] vertices with more than R incoming edges (lines 6-8).
@@ -1168,7 +1228,7 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     u32 *late = (u32 *)w.props;          // one word per list slot (props is 16 bytes per slot)
     u64 *over = (u64 *)w.touched;        // two words per vertex (touched is 16 bytes per vertex)
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, 8);
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NDEG);
+    if (t_next >= 0) hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NDEG);
     // lines 1-5: union with reversed edges, out-lists cut to R
     hipLaunchKernelGGL(k_reverse_scatter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, late, over,
                        mark);
@@ -1187,7 +1247,8 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
                        cnt_in, w.binoff, w.bins, w.thr);
     hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, rowflag, w.vcls,
                        use_classes, w.misc + 3);
-    launch_compact_all(w, N, t_next, st, e_stop);
+    if (t_next >= 0) launch_compact_all(w, N, t_next, st, e_stop);
+    else if (e_stop) (void)hipEventRecord(e_stop, st);
     return hipGetLastError();
 }
 
@@ -1328,6 +1389,122 @@ extern "C" int rnnd_build(const void *X, int64_t N, int32_t d, int dtype, int me
                          stream);
 }
 
+// per-pass statistics of a block-sequential run: slot sums of the runs of each pass
+static void fill_pass_stats(rnnd_stats *s, const RoundCtr *h, int passes, int per_pass)
+{
+    rnnd_stats one;
+    s->rounds = passes;
+    for (int p = 0; p < passes && p < RNND_MAX_ROUNDS; ++p) {
+        for (int k = 0; k < per_pass; ++k) {
+            memset(&one, 0, sizeof one);
+            fill_round_stats(&one, h + (size_t)p * per_pass + k, 1);
+            s->active[p] += one.active[0];
+            s->algo_evals[p] += one.algo_evals[0];
+            s->exec_evals[p] += one.exec_evals[0];
+            s->gathered_rows[p] += one.gathered_rows[0];
+            s->proposals[p] += one.proposals[0];
+        }
+    }
+}
+
+#define RNND_MAX_RUN_SLOTS 131072   // passes x runs per pass: one small counter block each
+
+extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
+                                 int32_t R, int32_t T1, int32_t T2, uint64_t seed, int64_t blocks,
+                                 int32_t *graph_out, int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats,
+                                 void *stream)
+{
+    int rc = check_data_args(X, N, d, dtype, metric, R);
+    if (rc) return rc;
+    if (!graph_out || !degree_out) return RNND_ERR_NULL;
+    if (S < 1 || S > R || (int64_t)S > N - 1 || T1 < 1 || T2 < 1) return RNND_ERR_BAD_PARAM;
+    if ((int64_t)T1 * T2 > 1000000 || blocks < 1 || blocks > N) return RNND_ERR_BAD_PARAM;
+    const long long per_pass = runs_per_pass(N, blocks);
+    if ((long long)T1 * T2 * per_pass > RNND_MAX_RUN_SLOTS) return RNND_ERR_BAD_PARAM;
+    hipStream_t st = (hipStream_t)stream;
+    const int passes = T1 * T2, n_ctr = (int)(passes * per_pass) + 2, vec_ok = vec_ok_for(X, d, dtype);
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
+    // events (only when statistics are wanted): 0 start, 1 end of init, 2 + p end of pass p, then the end of
+    // each AddReverseEdges call, then the end
+    const int e_rev = 2 + passes, e_end = e_rev + T1, n_ev = stats ? e_end + 1 : 0;
+    Workspace w;
+    hipEvent_t *ev = nullptr;
+    RoundCtr *hctr = nullptr;
+    int n_ev_made = 0;
+    w.bytes = ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
+    HIPCHK(hipMalloc((void **)&w.base, w.bytes));
+    ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
+    ev = (hipEvent_t *)calloc(n_ev + 1, sizeof(hipEvent_t));
+    hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
+    if (!ev || !hctr) { rc = RNND_ERR_OOM; goto done; }
+    for (; n_ev_made < n_ev; ++n_ev_made) HIPCHK(hipEventCreate(&ev[n_ev_made]));
+    {
+        int p = 0;
+        if (stats) HIPCHK(hipEventRecord(ev[0], st));
+        HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
+        HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
+        HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
+        if (variant == 2) launch_prepare_u8(w, X, N, d, st);
+        if (dtype == RNND_U8)
+            hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
+                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+        else
+            hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
+                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+        HIPCHK(hipGetLastError());
+        if (stats) HIPCHK(hipEventRecord(ev[1], st));
+        for (int t1 = 0; t1 < T1; ++t1) {
+            for (int t2 = 0; t2 < T2; ++t2, ++p) {
+                int used = 0;
+                HIPCHK(launch_update_pass_blocks(w, X, N, d, dtype, vec_ok, variant, R, w.keys, w.deg,
+                                                 (int)(p * per_pass), blocks, st, &used));
+                if (stats) HIPCHK(hipEventRecord(ev[2 + p], st));
+            }
+            if (t1 != T1 - 1)
+                HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, -1, st, stats ? ev[e_rev + t1] : nullptr));
+        }
+        hipLaunchKernelGGL(k_export, dim3((unsigned)(((size_t)N * R + 255) / 256)), dim3(256), 0, st, (long long)N, R,
+                           w.keys, w.deg, graph_out, degree_out);
+        HIPCHK(hipGetLastError());
+        if (keys_out)
+            HIPCHK(hipMemcpyAsync(keys_out, w.keys, (size_t)N * R * 8, hipMemcpyDeviceToDevice, st));
+        if (stats) {
+            HIPCHK(hipEventRecord(ev[e_end], st));
+            HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
+        }
+        HIPCHK(hipStreamSynchronize(st));
+        if (stats) {
+            memset(stats, 0, sizeof *stats);
+            fill_pass_stats(stats, hctr, passes, (int)per_pass);
+            stats->reverse_calls = T1 - 1;
+            stats->init_evals = (int64_t)N * S;
+            stats->kernel_variant = variant;
+            float ms = 0;
+            (void)hipEventElapsedTime(&ms, ev[0], ev[1]); stats->init_ms = ms;
+            int pp = 0;
+            for (int t1 = 0; t1 < T1; ++t1) {
+                for (int t2 = 0; t2 < T2; ++t2, ++pp) {
+                    if (pp >= RNND_MAX_ROUNDS) continue;
+                    // a pass starts where the one before it, the init or the reverse call ended
+                    hipEvent_t from = t2 > 0 ? ev[2 + pp - 1] : (t1 == 0 ? ev[1] : ev[e_rev + t1 - 1]);
+                    (void)hipEventElapsedTime(&ms, from, ev[2 + pp]); stats->round_ms[pp] = ms;
+                }
+                if (t1 != T1 - 1 && t1 < RNND_MAX_ROUNDS) {
+                    (void)hipEventElapsedTime(&ms, ev[2 + pp - 1], ev[e_rev + t1]);
+                    stats->reverse_ms[t1] = ms;
+                }
+            }
+            (void)hipEventElapsedTime(&ms, ev[0], ev[e_end]); stats->total_ms = ms;
+        }
+    }
+done:
+    for (int i = 0; i < n_ev_made; ++i) (void)hipEventDestroy(ev[i]);
+    free(ev);
+    free(hctr);
+    if (w.base) (void)hipFree(w.base);
+    return rc;
+}
+
 extern "C" int rnnd_random_graph(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
                                  int32_t R, uint64_t seed, uint64_t *keys, int32_t *deg, void *stream)
 {
@@ -1381,6 +1558,50 @@ extern "C" int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dt
     if (stats) {
         memset(stats, 0, sizeof *stats);
         fill_round_stats(stats, hctr, n_rounds);
+        stats->kernel_variant = variant;
+    }
+done:
+    free(hctr);
+    if (w.base) (void)hipFree(w.base);
+    return rc;
+}
+
+extern "C" int rnnd_update_neighbors_blocks(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t R,
+                                           uint64_t *keys, int32_t *deg, int32_t n_passes, int64_t blocks,
+                                           rnnd_stats *stats, void *stream)
+{
+    int rc = check_data_args(X, N, d, dtype, metric, R);
+    if (rc) return rc;
+    if (!keys || !deg) return RNND_ERR_NULL;
+    if (n_passes < 1 || n_passes > 1000000 || blocks < 1 || blocks > N) return RNND_ERR_BAD_PARAM;
+    const long long per_pass = runs_per_pass(N, blocks);
+    if ((long long)n_passes * per_pass > RNND_MAX_RUN_SLOTS) return RNND_ERR_BAD_PARAM;
+    hipStream_t st = (hipStream_t)stream;
+    const int n_ctr = (int)(n_passes * per_pass) + 2, vec_ok = vec_ok_for(X, d, dtype);
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
+    Workspace w;
+    RoundCtr *hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
+    if (!hctr) return RNND_ERR_OOM;
+    w.bytes = ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
+    HIPCHK(hipMalloc((void **)&w.base, w.bytes));
+    ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
+    HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
+    HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
+    HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
+    if (variant == 2) launch_prepare_u8(w, X, N, d, st);
+    hipLaunchKernelGGL(k_classify, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, (long long)N, R, (const u64 *)keys,
+                       deg, w.vcls, use_classes);
+    HIPCHK(hipGetLastError());
+    for (int p = 0; p < n_passes; ++p) {
+        int used = 0;
+        HIPCHK(launch_update_pass_blocks(w, X, N, d, dtype, vec_ok, variant, R, (u64 *)keys, deg, (int)(p * per_pass),
+                                         blocks, st, &used));
+    }
+    HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
+    HIPCHK(hipStreamSynchronize(st));
+    if (stats) {
+        memset(stats, 0, sizeof *stats);
+        fill_pass_stats(stats, hctr, n_passes, (int)per_pass);
         stats->kernel_variant = variant;
     }
 done:
@@ -1497,4 +1718,4 @@ extern "C" const char *rnnd_strerror(int status)
     }
 }
 
-extern "C" int rnnd_version(void) { return 102; }
+extern "C" int rnnd_version(void) { return 103; }

@@ -20,7 +20,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = rn.exported_symbols()
     assert {"rnnd_build", "rnnd_build_ex", "rnnd_random_graph", "rnnd_update_neighbors",
             "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search", "rnnd_workspace_bytes",
-            "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant"} <= set(names)
+            "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant", "rnnd_build_blocks",
+            "rnnd_update_neighbors_blocks"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -50,6 +51,17 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert call(N=50_000_000, R=128, S=4) == -2          # N*R does not fit the 32-bit slot counters
     assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(2) == -3
     assert lib.rnnd_set_kernel_variant(0) == 0
+    # block-sequential entry points: same checks, plus the number of runs
+    def blocks(**kw):
+        a = dict(ok, **kw)
+        return lib.rnnd_build_blocks(a["X"], a["N"], a["d"], a["dtype"], a["metric"], a["S"], a["R"], a["T1"],
+                                     a["T2"], 0, a.get("blocks", 4), a.get("g", one), a.get("deg", one), None, None,
+                                     None)
+    assert blocks(blocks=0) == -3 and blocks(blocks=101) == -3 and blocks(X=None) == -1 and blocks(g=None) == -1
+    assert blocks(T1=400, T2=400, blocks=100) == -3 and blocks(S=0) == -3 and blocks(dtype=2) == -4
+    assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, one, one, 1, 0, None, None) == -3
+    assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, None, one, 1, 4, None, None) == -1
+    assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, one, one, 0, 4, None, None) == -3
     # rnnd_search: parameters are checked before pointers, pointers before any GPU call
     def search(**kw):
         a = dict(dict(X=one, N=100, d=16, dtype=0, metric=0, g=one, dg=one, W=8, Q=one, nq=3, L=16, K=8, k=5,
