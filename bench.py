@@ -44,37 +44,54 @@ def cpu_baseline(cfg, X, sample_n):
     }
 
 
-def search_quality(cfg, rn, Xd, graph, degree, nq, L=64, K=32):
+def exact_top10(Xd, Qd):
+    """Exact 10 nearest neighbours of every query (ties by id): test tooling, a double-precision matmul on
+    the GPU in chunks whose distance matrix stays below 16 GB."""
+    import numpy as np
+    import torch
+    Xf = Xd.double()
+    xn = (Xf * Xf).sum(1)
+    nq = Qd.shape[0]
+    out = np.zeros((nq, 10), np.int64)
+    step = max(1, min(500, int(2e9 // Xd.shape[0])))
+    for q0 in range(0, nq, step):
+        Qf = Qd[q0:q0 + step].double()
+        d2 = (Qf * Qf).sum(1)[:, None] + xn[None, :] - 2.0 * (Qf @ Xf.T)
+        cand = torch.topk(d2, 32, dim=1, largest=False)
+        cv, ci = cand.values.cpu().numpy(), cand.indices.cpu().numpy()
+        for q in range(cv.shape[0]):
+            out[q0 + q] = ci[q][np.lexsort((ci[q], cv[q]))][:10]
+    return out
+
+
+def search_quality(cfg, rn, Xd, graph, degree, nq, L=64, K=32, sweep=False):
     """Search on the graph just built, by the library's own GPU search (Alg. 1 with the cap K): queries per
-    second and recall@10 against the exact top-10 (ties by id), which is test tooling computed here by a
-    double-precision matmul on the GPU."""
+    second, recall@10 and R@1 against the exact neighbours.  sweep: also the grid of L and K of Sec. 5.2."""
     import time
     import numpy as np
     import torch
     import workloads as wl
     Q = wl.make_queries(cfg, nq)
     Qd = torch.from_numpy(Q).cuda()
-    rn.rnnd_search(Xd, graph, degree, Qd[:64].contiguous(), L, K, 10, 7)      # warm-up
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ids, _, evals = rn.rnnd_search(Xd, graph, degree, Qd, L, K, 10, 7)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    Xf = Xd.double()
-    xn = (Xf * Xf).sum(1)
-    hit = 0
-    step = max(1, min(500, int(2e9 // Xd.shape[0])))     # the distance matrix of one chunk stays below 16 GB
-    for q0 in range(0, nq, step):
-        Qf = Qd[q0:q0 + step].double()
-        d2 = (Qf * Qf).sum(1)[:, None] + xn[None, :] - 2.0 * (Qf @ Xf.T)
-        cand = torch.topk(d2, 32, dim=1, largest=False)
-        cv, ci = cand.values.cpu().numpy(), cand.indices.cpu().numpy()
-        got = ids[q0:q0 + step].cpu().numpy()
-        for q in range(cv.shape[0]):
-            order = np.lexsort((ci[q], cv[q]))
-            hit += len(set(ci[q][order][:10].tolist()) & set(got[q].tolist()))
-    return {"queries": nq, "L": L, "K": K, "k": 10, "seconds": dt, "queries_per_s": nq / dt,
-            "recall_at_10": hit / (10.0 * nq), "distance_evals_per_query": evals / nq}
+    truth = exact_top10(Xd, Qd)
+
+    def one(L, K):
+        rn.rnnd_search(Xd, graph, degree, Qd[:64].contiguous(), L, K, min(10, L), 7)      # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ids, _, evals = rn.rnnd_search(Xd, graph, degree, Qd, L, K, min(10, L), 7)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        got = ids.cpu().numpy()
+        hit = sum(len(set(truth[q].tolist()) & set(got[q].tolist())) for q in range(nq))
+        return {"queries": nq, "L": L, "K": K, "k": min(10, L), "seconds": dt, "queries_per_s": nq / dt,
+                "recall_at_10": hit / (10.0 * nq), "r_at_1": float((got[:, 0] == truth[:, 0]).mean()),
+                "distance_evals_per_query": evals / nq}
+
+    res = one(L, K)
+    if sweep:
+        res["sweep"] = [one(l, k) for l in (16, 32, 64, 128) for k in (16, 32, 48, 64, 96, 128)]
+    return res
 
 
 def main():
@@ -89,6 +106,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="UpdateNeighbors kernel: 0 auto, 1 generic, 2 MFMA")
     ap.add_argument("--cpu-sample", type=int, default=0)
     ap.add_argument("--n", type=int, default=0, help="override the workload's N (same generator; scale checks)")
+    ap.add_argument("--search-sweep", action="store_true",
+                    help="search-quality leg over L in {16,32,64,128} x K in {16,...,96, no cap} (Sec. 5.2)")
     ap.add_argument("--blocks", type=int, default=0,
                     help="block-sequential passes with this many runs of consecutive ids per pass "
                          "(rnnd_build_blocks; 0 = the synchronous build the metric is quoted on)")
@@ -207,7 +226,7 @@ def main():
     }
     if not args.no_recall:
         try:
-            sq = search_quality(cfg, rn, Xd, graph, degree, min(cfg.n_queries, args.queries))
+            sq = search_quality(cfg, rn, Xd, graph, degree, min(cfg.n_queries, args.queries), sweep=args.search_sweep)
             out["recall_at_10"] = sq["recall_at_10"]
             out["search"] = sq
         except Exception as e:  # reporting only; never hides the build measurement

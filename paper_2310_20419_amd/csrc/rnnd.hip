@@ -1100,7 +1100,6 @@ static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64
                           &c->n_active[cls], w.props, w.nprop, c);
 }
 
-// One synchronous UpdateNeighbors round t (ctr[t] -> ctr[t+1]).
 // One run of consecutive vertex ids of a block-sequential pass: ids first .. first + count - 1.
 struct VertexRun {
     u32 first = 0, count = 0;

@@ -63,7 +63,8 @@ __device__ __forceinline__ u32 transpose16_bits(u32 w, int lane)
 // the matrix instructions on the doubles -- the next chunk travels while the matrix cores work.  The
 // body is straight-line: loads are unconditional (lanes without a row read row 0 of X; what they
 // produce is masked later) and the last iteration re-reads the last chunk.
-template <int NR, int CH>
+// TM != 0: the tiles to compute are fixed at compile time (bit I(I+1)/2 + J of TM); TM == 0: bit of `need`.
+template <int NR, int CH, u32 TM = 0>
 __device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int nchunk, v4d (&acc)[NR * (NR + 1) / 2],
                                               double (&nr)[NR], u32 need)
 {
@@ -101,7 +102,7 @@ __device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int 
                 for (int I = 0; I < NR; ++I)
 #pragma unroll
                     for (int J = 0; J <= I; ++J)
-                        if (NR <= 2 || ((need >> (I * (I + 1) / 2 + J)) & 1u))   // wave-uniform
+                        if (TM ? ((TM >> (I * (I + 1) / 2 + J)) & 1u) != 0 : ((need >> (I * (I + 1) / 2 + J)) & 1u) != 0)   // wave-uniform
                             acc[I * (I + 1) / 2 + J] = __builtin_amdgcn_mfma_f64_16x16x4f64(
                                 a[I][j][t], a[J][j][t], acc[I * (I + 1) / 2 + J], 0, 0, 0);
             }
@@ -220,7 +221,16 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
                 for (int J = 0; J <= I; ++J)
                     if (16 * I < m && J < g_new) need |= 1u << (I * (I + 1) / 2 + J);
             need = (u32)__builtin_amdgcn_readfirstlane((int)need);
-            gram_f64_loop<NRC, CH>(rp, nchunk, acc, nr, need);
+            if (NRC == 1) {
+                gram_f64_loop<NRC, CH, 1u>(rp, nchunk, acc, nr, need);
+            } else if (NRC == 2) {
+                // two straight-line loops instead of per-tile branches: all three tiles, or (new entries in
+                // the first group only) the two tiles of column group 0
+                if (need == 7u) gram_f64_loop<NRC, CH, 7u>(rp, nchunk, acc, nr, need);
+                else gram_f64_loop<NRC, CH, 3u>(rp, nchunk, acc, nr, need);
+            } else {
+                gram_f64_loop<NRC, CH>(rp, nchunk, acc, nr, need);
+            }
 #pragma unroll
             for (int g = 0; g < NRC; ++g) {
                 nr[g] += __shfl_xor(nr[g], 16);
@@ -239,7 +249,7 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
                 for (int J = 0; J <= I; ++J) {
                     const int t = I * (I + 1) / 2 + J;
                     FA[t] = FB[t] = 0;
-                    if (NRC <= 2 || ((need >> t) & 1u)) tiles += 1;      // what the loop above computed
+                    if (NRC == 1 || (NRC == 2 && need != 7u && t < 2) || ((need >> t) & 1u)) tiles += 1;   // what the loop above computed
                     if ((need >> t) & 1u) {     // wave-uniform
                         // lane = slot r16 of group J; accumulator v = slot 4v + q of group I
                         const float dj = __uint_as_float(key_dist(sm.key[16 * J + r16]));
