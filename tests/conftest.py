@@ -56,3 +56,20 @@ def snapshot_from_lists(oracle, X, lists, W):
             s.ids[u, k], s.dist[u, k], s.flags[u, k] = v, dd, 1
         s.deg[u] = len(ent)
     return s
+
+
+def live(test):
+    """Decorator for the cases that run for minutes: their progress lines (Python's and the oracle's own,
+    written by C code to stderr) reach the real stdout/stderr even when pytest captures output, so a watcher
+    of the run sees that it is alive."""
+    import functools
+
+    @functools.wraps(test)
+    def wrapper(*args, capfd, **kwargs):
+        with capfd.disabled():
+            return test(*args, **kwargs)
+    import inspect
+    sig = inspect.signature(test)
+    params = list(sig.parameters.values()) + [inspect.Parameter("capfd", inspect.Parameter.KEYWORD_ONLY)]
+    wrapper.__signature__ = sig.replace(parameters=params)
+    return wrapper

@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 import workloads as wl
+from conftest import live
 from gpu_util import assert_snapshot_equal, snapshot_to_device
 
 pytestmark = pytest.mark.gpu
@@ -105,6 +106,7 @@ def test_stepwise_passes_from_an_oracle_snapshot(rn, oracle_mod):
             assert st.algo_evals[0] == evals and st.proposals[0] == props
 
 
+@live
 def test_cfg2_build_blocks_and_search_quality(rn, oracle_mod):
     """Workload cfg2 (100,000 x 128 uint8) in 16 runs per pass: identical to the oracle's 16-run build, and
     the graph searches as well as the synchronous one (statistical: recall@10 within 0.01)."""

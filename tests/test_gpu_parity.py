@@ -10,6 +10,7 @@ import numpy as np
 import pytest
 
 import workloads as wl
+from conftest import live
 from gpu_util import assert_snapshot_equal, device_to_arrays, dist_bits_of, snapshot_to_device
 
 pytestmark = pytest.mark.gpu
@@ -232,6 +233,7 @@ def test_cfg2_full_parity(rn, oracle_mod, variant):
 
 
 @pytest.mark.slow
+@live
 def test_cfg3_full_size_parity(rn, oracle_mod):
     """Workload cfg3 -- the benchmark's workload (N = 1,000,000, d = 128 uint8, S=20 R=96
     T1=4 T2=15) in the launch configuration bench.py times: the whole graph, every distance, flag,
@@ -263,6 +265,7 @@ FULL = os.environ.get("RNND_FULL_PARITY", "") == "1"
 
 @pytest.mark.slow
 @pytest.mark.skipif(not FULL, reason="set RNND_FULL_PARITY=1: several minutes of single-threaded oracle")
+@live
 def test_cfg4_full_size_parity(rn, oracle_mod):
     """Workload cfg4 (N = 1,000,000, d = 96 float32, unit vectors) against a full oracle run."""
     import time
@@ -282,6 +285,7 @@ def test_cfg4_full_size_parity(rn, oracle_mod):
 
 
 @pytest.mark.slow
+@live
 def test_cfg5_full_size_sampled_parity(rn, oracle_mod):
     """Workload cfg5 (N = 1,000,000, d = 960 float32) in the launch configuration bench.py
     times.  A full oracle run would take hours, so outputs are sampled: after the GPU has run RandomGraph
