@@ -56,8 +56,8 @@ typedef enum {
 } rnnd_status;
 
 /* Counters of one build, filled on the host.  "algo" evaluations are the delta(v,w)
- * evaluations Alg. 4 line 11 performs (with the old/old skip of lines 8-9 and the break of
- * line 14); "exec" are the distances the kernels actually computed. */
+ * evaluations the prune test of Alg. 4 performs (with its old/old skip and its break at the
+ * first failure); "exec" are the distances the kernels actually computed. */
 typedef struct {
     int32_t rounds;                         /* UpdateNeighbors rounds run (T1*T2) */
     int32_t reverse_calls;                  /* AddReverseEdges calls run (T1-1) */
@@ -65,11 +65,11 @@ typedef struct {
     int32_t reserved;
     float total_ms, init_ms;                /* GPU time of the whole call / of RandomGraph */
     float round_ms[RNND_MAX_ROUNDS];        /* GPU time of each UpdateNeighbors round */
-    float scan_ms[RNND_MAX_ROUNDS];         /* of which: the scan kernel (Alg. 4 lines 2-15) */
+    float scan_ms[RNND_MAX_ROUNDS];         /* of which: the scan kernel (Alg. 4's loop body) */
     float reverse_ms[RNND_MAX_ROUNDS];      /* GPU time of each AddReverseEdges call */
     int64_t init_evals;                     /* N*S */
     int64_t active[RNND_MAX_ROUNDS];        /* vertices with at least one "new" entry */
-    int64_t proposals[RNND_MAX_ROUNDS];     /* redirected edges emitted (Alg. 4 line 13) */
+    int64_t proposals[RNND_MAX_ROUNDS];     /* redirected edges emitted (Alg. 4's edge update) */
     int64_t algo_evals[RNND_MAX_ROUNDS];
     int64_t exec_evals[RNND_MAX_ROUNDS];
     int64_t gathered_rows[RNND_MAX_ROUNDS]; /* rows of X the round kernel fetched */
@@ -77,9 +77,9 @@ typedef struct {
 
 /* Alg. 6, RNN-Descent(S, R, T1, T2), with synchronous rounds:
  *   G <- RandomGraph(S), all flags new; T1 x { T2 x UpdateNeighbors; AddReverseEdges unless last }.
- * Each UpdateNeighbors round scans every vertex against the same snapshot (Alg. 4 lines 2-15)
+ * Each UpdateNeighbors round scans every vertex against the same snapshot (the body of Alg. 4's vertex loop)
  * and then rebuilds every list as the first R entries, in (delta, id) order and without
- * duplicates, of its kept entries plus the edges redirected to it (line 13: v enters w's list).
+ * duplicates, of its kept entries plus the edges redirected to it (the edge update: v enters w's list).
  *   X          device, N x d
  *   graph_out  device int32 [N * R]: row u = neighbour ids of u, ascending (delta, id), -1 padded
  *   degree_out device int32 [N]
@@ -96,7 +96,7 @@ int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int metric, in
                   uint64_t *keys_out, rnnd_stats *stats, void *stream);
 
 /* Alg. 6 with block-sequential passes: a variant between the synchronous round and the in-place
- * vertex loop of Alg. 4 (line 1 visits the vertices one after the other and line 13 changes the
+ * vertex loop of Alg. 4 (it visits the vertices one after the other and its edge update changes the
  * edge set at once, so a vertex visited later in the same pass already sees the edges redirected
  * to it).  The vertices are cut into runs of ceil(N / blocks) consecutive ids; the runs take their
  * turn in id order; every vertex of a run is scanned against the graph as it stands when the run
@@ -120,7 +120,7 @@ int rnnd_update_neighbors_blocks(const void *X, int64_t N, int32_t d, int dtype,
 /* Bytes of device workspace rnnd_build allocates (and frees) internally for these sizes. */
 int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, size_t *bytes);
 
-/* RandomGraph(S) (Alg. 6 lines 1-2): row u <- S distinct ids != u drawn from a counter-based
+/* RandomGraph(S) (first step of Alg. 6): row u <- S distinct ids != u drawn from a counter-based
  * generator (draw j of vertex u = mix64(mix64(seed + G*(u+1)) + G*(j+1)), mix64 = splitmix64's
  * output function, G = 0x9E3779B97F4A7C15; id = c + (c >= u) with c = ((draw >> 32) * (N-1)) >> 32;
  * repeats are skipped), with delta(u, id), flag new, sorted.  Writes keys [N*R] and deg [N]. */

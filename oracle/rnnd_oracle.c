@@ -200,7 +200,7 @@ static int32_t graph_to_flat(const list_t *G, int64_t n, int32_t W, int32_t *ids
     return maxlen;
 }
 
-/* ------------------------------------------------ RandomGraph (Alg. 6 L1-2) */
+/* ------------------------------------- RandomGraph (first step of Alg. 6) */
 /* splitmix64 output function (Steele, Lea, Flood 2014; Vigna's reference). */
 static uint64_t mix64(uint64_t z)
 {
@@ -255,7 +255,7 @@ static list_t *random_graph(const data_t *D, int32_t S, uint64_t seed)
             entry_t x;
             x.id = tmp[k];
             x.dist = delta(D, u, tmp[k]);
-            x.is_new = 1;                       /* Alg. 6 L2 */
+            x.is_new = 1;                       /* Alg. 6: all flags start as new */
             list_push(&G[u], x);
         }
         list_sort(&G[u]);
@@ -266,7 +266,7 @@ static list_t *random_graph(const data_t *D, int32_t S, uint64_t seed)
 
 /* ------------------------------------------- UpdateNeighbors (Alg. 4), scan */
 /* One vertex of Alg. 4 against its own list L (sorted on entry).  Kept entries
- * go to `kept` (flags old, L15); each pruned v calls emit(w, v, delta(v,w)). */
+ * go to `kept` (flags old); each pruned v calls emit(w, v, delta(v,w)). */
 typedef struct { int32_t target, id; double dist; } proposal_t;
 
 typedef struct {
@@ -287,24 +287,24 @@ static void scan_vertex(const data_t *D, const list_t *U, int use_flag_skip, lis
                         plist_t *props, int64_t *evals)
 {
     kept->len = 0;
-    for (int32_t i = 0; i < U->len; ++i) {               /* L5: v in U, ascending */
+    for (int32_t i = 0; i < U->len; ++i) {               /* for v in U, ascending */
         entry_t v = U->e[i];
-        int f = 1;                                       /* L6 */
-        for (int32_t j = 0; j < kept->len; ++j) {        /* L7: w in U' */
+        int f = 1;                                       /* v is kept unless a test fires */
+        for (int32_t j = 0; j < kept->len; ++j) {        /* for w in U', in order */
             entry_t w = kept->e[j];
-            if (use_flag_skip && !v.is_new && !w.is_new) /* L8-9 */
+            if (use_flag_skip && !v.is_new && !w.is_new) /* both old: skip */
                 continue;
             double dvw = delta(D, v.id, w.id);
             ++*evals;
-            if (v.dist >= dvw) {                         /* L11: delta(u,v) >= delta(v,w) */
-                f = 0;                                   /* L12 */
-                proposal_t p;                            /* L13: E <- E \ (u,v) + (w,v) */
+            if (v.dist >= dvw) {                         /* the prune test: delta(u,v) >= delta(v,w) */
+                f = 0;
+                proposal_t p;                            /* redirect: E <- E \ (u,v) + (w,v) */
                 p.target = w.id; p.id = v.id; p.dist = dvw;
                 plist_push(props, p);
-                break;                                   /* L14 */
+                break;                                   /* first failing w only */
             }
         }
-        if (f) list_push(kept, v);                       /* L17-18, flag kept as read */
+        if (f) list_push(kept, v);                       /* v joins U', flag kept as read */
     }
 }
 
@@ -317,7 +317,7 @@ static void update_neighbors_sync(const data_t *D, list_t *G, int32_t R, int use
     plist_t P = {0, 0, 0};
     for (int64_t u = 0; u < n; ++u) {
         scan_vertex(D, &G[u], use_flag_skip, &K[u], &P, evals);
-        for (int32_t k = 0; k < K[u].len; ++k) K[u].e[k].is_new = 0;   /* L15 */
+        for (int32_t k = 0; k < K[u].len; ++k) K[u].e[k].is_new = 0;   /* kept: old */
     }
     *nprops += P.len;
     for (int64_t i = 0; i < P.len; ++i) {
@@ -353,7 +353,7 @@ static void update_neighbors_blocks(const data_t *D, list_t *G, int32_t R, int64
         P.len = 0;
         for (int64_t u = lo; u < hi; ++u) {
             scan_vertex(D, &G[u], 1, &K[u - lo], &P, evals);
-            for (int32_t k = 0; k < K[u - lo].len; ++k) K[u - lo].e[k].is_new = 0;   /* L15 */
+            for (int32_t k = 0; k < K[u - lo].len; ++k) K[u - lo].e[k].is_new = 0;   /* kept: old */
         }
         for (int64_t u = lo; u < hi; ++u) {
             free(G[u].e);
@@ -361,7 +361,7 @@ static void update_neighbors_blocks(const data_t *D, list_t *G, int32_t R, int64
         }
         free(K);
         *nprops += P.len;
-        for (int64_t i = 0; i < P.len; ++i) {            /* L13: v enters w's list, flagged new */
+        for (int64_t i = 0; i < P.len; ++i) {            /* the redirect: v enters w's list, flagged new */
             entry_t x;
             x.id = P.p[i].id; x.dist = P.p[i].dist; x.is_new = 1;
             list_push(&G[P.p[i].target], x);
@@ -384,13 +384,13 @@ static void update_neighbors_paper_order(const data_t *D, list_t *G, int64_t *ev
     list_t kept = {0, 0, 0};
     plist_t P = {0, 0, 0};
     for (int64_t u = 0; u < D->n; ++u) {
-        list_sort(&G[u]);                                /* L3 */
+        list_sort(&G[u]);                                /* U <- sorted neighbours */
         P.len = 0;
         scan_vertex(D, &G[u], 1, &kept, &P, evals);
         G[u].len = 0;
         for (int32_t k = 0; k < kept.len; ++k) {
             entry_t x = kept.e[k];
-            x.is_new = 0;                                /* L15 */
+            x.is_new = 0;                                /* kept: old */
             list_push(&G[u], x);
         }
         for (int64_t i = 0; i < P.len; ++i) {
@@ -410,7 +410,7 @@ static void update_neighbors_paper_order(const data_t *D, list_t *G, int64_t *ev
 /* ------------------------------------------------- AddReverseEdges (Alg. 5) */
 static void add_reverse_edges(list_t *G, int64_t n, int32_t R)
 {
-    /* L1-2: E <- E + reversed E, added entries flagged new */
+    /* first loop: E <- E + reversed E, added entries flagged new */
     list_t *A = graph_alloc(n);
     for (int64_t u = 0; u < n; ++u)
         for (int32_t k = 0; k < G[u].len; ++k) {
@@ -422,11 +422,11 @@ static void add_reverse_edges(list_t *G, int64_t n, int32_t R)
         for (int32_t k = 0; k < A[v].len; ++k)
             if (!list_has(&G[v], A[v].e[k].id)) list_push(&G[v], A[v].e[k]);
         free(A[v].e);
-        /* L3-5: keep only the R shortest edges leaving v */
+        /* second loop: keep only the R shortest edges leaving v */
         list_canonicalise(&G[v], R);
     }
     free(A);
-    /* L6-8: keep only the R shortest edges entering v, by (delta, source) */
+    /* third loop: keep only the R shortest edges entering v, by (delta, source) */
     list_t *In = graph_alloc(n);
     for (int64_t u = 0; u < n; ++u)
         for (int32_t k = 0; k < G[u].len; ++k) {
@@ -508,12 +508,12 @@ int orc_build_sync(const void *X, int64_t n, int32_t d, int dtype, int32_t S, in
 {
     if (S < 1 || S > R || R > W || (int64_t)S > n - 1 || T1 < 1 || T2 < 1) return -1;
     data_t D = {X, n, d, dtype};
-    list_t *G = random_graph(&D, S, seed);                      /* L1-2 */
+    list_t *G = random_graph(&D, S, seed);                      /* RandomGraph, flags new */
     if (init_evals) *init_evals = n * (int64_t)S;
-    for (int32_t t1 = 0; t1 < T1; ++t1) {                       /* L3 */
-        for (int32_t t2 = 0; t2 < T2; ++t2) {                   /* L4 */
+    for (int32_t t1 = 0; t1 < T1; ++t1) {                       /* outer loop */
+        for (int32_t t2 = 0; t2 < T2; ++t2) {                   /* inner loop */
             int64_t ev = 0, np = 0;
-            update_neighbors_sync(&D, G, R, use_flag_skip, &ev, &np);   /* L5 */
+            update_neighbors_sync(&D, G, R, use_flag_skip, &ev, &np);   /* UpdateNeighbors */
             if (round_evals) round_evals[t1 * T2 + t2] = ev;
             if (round_props) round_props[t1 * T2 + t2] = np;
             if (g_progress) {
@@ -522,7 +522,7 @@ int orc_build_sync(const void *X, int64_t n, int32_t d, int dtype, int32_t S, in
                 fflush(stderr);
             }
         }
-        if (t1 != T1 - 1) add_reverse_edges(G, n, R);           /* L6-7 */
+        if (t1 != T1 - 1) add_reverse_edges(G, n, R);           /* unless last */
     }
     graph_to_flat(G, n, W, ids, dist, flags, deg);
     graph_free(G, n);
@@ -555,11 +555,11 @@ int orc_build_blocks(const void *X, int64_t n, int32_t d, int dtype, int32_t S, 
     if (S < 1 || S > R || R > W || (int64_t)S > n - 1 || T1 < 1 || T2 < 1) return -1;
     if (nblocks < 1 || nblocks > n) return -1;
     data_t D = {X, n, d, dtype};
-    list_t *G = random_graph(&D, S, seed);                      /* L1-2 */
-    for (int32_t t1 = 0; t1 < T1; ++t1) {                       /* L3 */
-        for (int32_t t2 = 0; t2 < T2; ++t2) {                   /* L4 */
+    list_t *G = random_graph(&D, S, seed);                      /* RandomGraph, flags new */
+    for (int32_t t1 = 0; t1 < T1; ++t1) {                       /* outer loop */
+        for (int32_t t2 = 0; t2 < T2; ++t2) {                   /* inner loop */
             int64_t ev = 0, np = 0;
-            update_neighbors_blocks(&D, G, R, nblocks, &ev, &np);       /* L5 */
+            update_neighbors_blocks(&D, G, R, nblocks, &ev, &np);       /* UpdateNeighbors */
             if (round_evals) round_evals[t1 * T2 + t2] = ev;
             if (round_props) round_props[t1 * T2 + t2] = np;
             if (g_progress) {
@@ -568,7 +568,7 @@ int orc_build_blocks(const void *X, int64_t n, int32_t d, int dtype, int32_t S, 
                 fflush(stderr);
             }
         }
-        if (t1 != T1 - 1) add_reverse_edges(G, n, R);           /* L6-7 */
+        if (t1 != T1 - 1) add_reverse_edges(G, n, R);           /* unless last */
     }
     graph_to_flat(G, n, W, ids, dist, flags, deg);
     graph_free(G, n);
@@ -607,11 +607,11 @@ int orc_rng_strategy(const void *X, int64_t n, int32_t d, int dtype, int64_t u,
         x.id = cand[k]; x.dist = delta(&D, u, cand[k]); x.is_new = 1;
         list_push(&U, x);
     }
-    list_sort(&U);                                              /* L1 */
-    int32_t m = 0;                                              /* L2 */
-    for (int32_t i = 0; i < U.len; ++i) {                       /* L3 */
+    list_sort(&U);                                              /* candidates, ascending */
+    int32_t m = 0;                                              /* selected set, empty */
+    for (int32_t i = 0; i < U.len; ++i) {                       /* for v in order */
         int f = 1;
-        for (int32_t j = 0; j < m; ++j)                         /* L5 */
+        for (int32_t j = 0; j < m; ++j)                         /* for selected w */
             if (U.e[i].dist >= delta(&D, U.e[i].id, out[j])) { f = 0; break; }
         if (f) out[m++] = U.e[i].id;
     }
@@ -671,7 +671,7 @@ int orc_search(const void *X, int64_t n, int32_t d, int dtype, const int32_t *id
         const void *qv = row_ptr(&D, Q, q);
         memset(seen, 0, (size_t)n);
         int32_t m = 0;
-        /* L1: seeded random start set; vertex "n" is not a vertex, so nothing is skipped */
+        /* InitializeCandidates: seeded random start set; vertex "n" is not a vertex, so nothing is skipped */
         if ((int64_t)L0 == n) for (int32_t t = 0; t < L0; ++t) init[t] = t;
         else random_row(seed, n + 1, n, L0, init) /* ids in [0,n) */;
         for (int32_t t = 0; t < L0; ++t) {
@@ -684,20 +684,20 @@ int orc_search(const void *X, int64_t n, int32_t d, int dtype, const int32_t *id
             C[p] = x;
         }
         for (;;) {
-            int32_t iu = -1;                                    /* L3 */
+            int32_t iu = -1;                                    /* nearest unvisited member of C */
             for (int32_t t = 0; t < m; ++t) if (C[t].is_new) { iu = t; break; }
-            if (iu < 0) break;                                  /* L10-11 */
+            if (iu < 0) break;                                  /* none left: done */
             C[iu].is_new = 0;
             int64_t u = C[iu].id;
             int32_t du = deg[u] < K ? deg[u] : K;               /* Eq. 4: rows are nearest-first */
-            for (int32_t t = 0; t < du; ++t) {                  /* L5 */
+            for (int32_t t = 0; t < du; ++t) {                  /* its (capped) neighbours */
                 int32_t v = ids[u * W + t];
-                if (seen[v]) continue;                          /* L6 */
+                if (seen[v]) continue;                          /* evaluated before */
                 seen[v] = 1;
                 entry_t x;
                 x.id = v; x.dist = delta_vec(&D, qv, row_ptr(&D, X, v)); x.is_new = 1;
                 ++ev;
-                if (m == L && entry_cmp(&x, &C[m - 1]) >= 0) continue;  /* L8-9 */
+                if (m == L && entry_cmp(&x, &C[m - 1]) >= 0) continue;  /* C keeps its L nearest */
                 int32_t p = m < L ? m++ : m - 1;
                 while (p > 0 && entry_cmp(&x, &C[p - 1]) < 0) { C[p] = C[p - 1]; --p; }
                 C[p] = x;

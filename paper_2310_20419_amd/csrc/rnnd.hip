@@ -2,7 +2,7 @@
 //
 // A wavefront, or a group of 16, 32 or 64 of its lanes, owns one vertex in every per-vertex kernel.
 // A round is synchronous:
-//   scan     every active vertex (one holding a "new" entry) runs Alg. 4 lines 2-15 on its own list,
+//   scan     every active vertex (one holding a "new" entry) runs the body of Alg. 4's vertex loop on its own list,
 //            writes its kept entries back in place and leaves its redirected edges in its slot of `props`
 //   scatter  every redirected edge takes an arrival number at its target (the round's only atomic per
 //            edge) and moves into the target's inbox (INBOX_CAP slots per vertex); later arrivals wait
@@ -56,13 +56,13 @@ __device__ __forceinline__ void add_round_stats(RoundCtr *ctr, u64 algo, u64 exe
     atomicAdd(&s[3], props);
 }
 
-struct Prop {          // one redirected edge (Alg. 4 line 13): `key` enters `tgt`'s list
+struct Prop {          // one redirected edge (Alg. 4, the edge update): `key` enters `tgt`'s list
     u64 key;
     u32 tgt;
     u32 arrival;       // set by the scatter: arrival number at tgt, for edges past the inbox
 };
 
-// Line 13: (w, v) enters E.  Recorded in the scanning vertex's own slot.
+// The edge update of Alg. 4: (w, v) enters E.  Recorded in the scanning vertex's own slot.
 __device__ __forceinline__ void emit_redirect(u64 key, u32 tgt, Prop *slot)
 {
     Prop pr;
@@ -91,7 +91,7 @@ __device__ __forceinline__ int degree_class(int m, int use_classes)
 }
 
 // ------------------------------------------------------------------ RandomGraph
-// Alg. 6 lines 1-2: S distinct random neighbours (wave_random_ids), their distances, sorted.
+// Alg. 6, RandomGraph: S distinct random neighbours (wave_random_ids), their distances, sorted.
 template <int DT>
 __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long N, int d, int vec_ok,
                                                         int S, int R, u64 seed, u64 *keys, int *deg,
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
 }
 
 // ------------------------------------------------- UpdateNeighbors: scan (generic kernel)
-// Alg. 4 lines 2-15 for one vertex per wavefront, in the algorithm's own order: v runs over the
+// The body of Alg. 4's vertex loop for one vertex per wavefront, in the algorithm's own order: v runs over the
 // sorted list; the kept set U' so far is a bit mask; the delta(v,w) of up to 8 eligible w (kept,
 // not old/old) are evaluated at once by 8-lane groups in ascending w, and the first failing one
 // prunes v and redirects it.  Kept entries are written back in place with the flag cleared.
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
             const u64 ki = sk[i];
             const u32 di = key_dist(ki), idv = key_id(ki);
             const bool newv = ki & 1ull;
-            u64 e0 = newv ? K0 : (K0 & new0);   // lines 8-9: old/old pairs are skipped
+            u64 e0 = newv ? K0 : (K0 & new0);   // old/old pairs are skipped
             u64 e1 = newv ? K1 : (K1 & new1);
             bool pruned = false;
             const char *xv = (const char *)X + (size_t)idv * rowbytes;
@@ -199,12 +199,12 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
                 u32 db = 0;
                 if (mypos >= 0)
                     db = group8_dist_bits<DT>(xv, (const char *)X + (size_t)idw * rowbytes, d, vec_ok, sub);
-                const bool fail = mypos >= 0 && di >= db;   // line 11
+                const bool fail = mypos >= 0 && di >= db;   // the prune test
                 const u64 fm = __builtin_amdgcn_ballot_w64(fail && sub == 0);
                 if (fm) {
                     const int fl = __builtin_ctzll(fm);     // first failing w in list order
                     const u32 fdb = __shfl(db, fl), fidw = __shfl(idw, fl);
-                    if (lane == 0) {                        // line 13: (u,v) leaves, (w,v) enters
+                    if (lane == 0) {                        // the edge update: (u,v) leaves, (w,v) enters
                         s_pkey[wave][np] = make_key(fdb, idv, 1u);
                         s_ptgt[wave][np] = fidw;
                     }
@@ -217,10 +217,10 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
                 evals_exec += nb;
             }
             if (!pruned) {
-                if (i < 64) K0 |= 1ull << i; else K1 |= 1ull << (i - 64);   // lines 17-18
+                if (i < 64) K0 |= 1ull << i; else K1 |= 1ull << (i - 64);   // v joins U'
             }
         }
-        // line 15 + compaction: kept entries, flag old, back into the row
+        // kept entries, flag old, compacted back into the row
         const int nk0 = __popcll(K0);
         if ((K0 >> lane) & 1ull) row[__popcll(K0 & lanes_below(lane))] = k0 & ~1ull;
         if ((K1 >> lane) & 1ull) row[nk0 + __popcll(K1 & lanes_below(lane))] = k1 & ~1ull;
@@ -658,7 +658,7 @@ __global__ __launch_bounds__(256) void k_store_classes(const u32 *n_touched, con
 }
 
 // ------------------------------------------------------------ AddReverseEdges
-// Alg. 5 lines 1-5 need, for every x, the edges that point to x.  Every edge (u, v) takes an arrival
+// The union and the out-degree cut of Alg. 5 need, for every x, the edges that point to x.  Every edge (u, v) takes an arrival
 // number at v (one atomic on fill[v]); the first INBOX_CAP arrivals are written to v's inbox as
 // key(delta, u, new).  A later arrival is remembered with its edge (late[] holds its number, over[u]
 // one bit per list position of u, mark[u] says that u has any) and k_reverse_surplus places it in
@@ -736,7 +736,7 @@ __global__ __launch_bounds__(BLOCK) void k_fill_bins(long long N, int R, const u
     }
 }
 
-// Alg. 5 lines 1-5: list(x) <- first R distinct of list(x) + reversed edges into x (flag new).
+// Alg. 5, union and out-degree cut: list(x) <- first R distinct of list(x) + reversed edges into x (flag new).
 // Then the edges of the new list are counted at those targets that can end up with more than R
 // incoming edges (cand[v]: |list(v)| + |edges into v| > R before the union; for every other vertex
 // the union itself bounds the in-degree by R); rowflag[x] says whether the list has such an edge.
@@ -825,7 +825,7 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64
     }
 }
 
-// Alg. 5 lines 6-8, first half: thr[v] <- the R-th smallest (delta, source) among the edges into v.
+// Alg. 5, in-degree cut, first half: thr[v] <- the R-th smallest (delta, source) among the edges into v.
 __global__ __launch_bounds__(BLOCK) void k_incap_threshold(int R, const int *list, const u32 *n_list,
                                                            const int *cnt, const int *binoff,
                                                            const u64 *bins, u64 *thr)
@@ -846,7 +846,7 @@ __global__ __launch_bounds__(BLOCK) void k_incap_threshold(int R, const int *lis
     }
 }
 
-// Alg. 5 lines 6-8, second half: edge (u, v) survives iff (delta, u) <= thr[v]; vcls[u] follows the
+// Alg. 5, in-degree cut, second half: edge (u, v) survives iff (delta, u) <= thr[v]; vcls[u] follows the
 // new degree.  Nothing to do when no vertex has more than R incoming edges (*n_hubs == 0).
 __global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 *keys, int *deg,
                                                         const u64 *thr, const int8_t *rowflag, int8_t *vcls,
@@ -1216,8 +1216,8 @@ static void launch_compact_all(const Workspace &w, long long N, int t_next, hipS
 // AddReverseEdges; the active lists for round t_next are rebuilt from scratch (t_next < 0: only vcls[], the
 // class of every vertex that holds a "new" entry, is written).  Expects fill[] == 0
 // and leaves it so.  Between rounds nprop[], tcls[], props[] and touched[] are free: they serve as the
-// second in-edge count, the per-vertex marks, the late arrival numbers and their position masks.  misc: [0] bin cursor, [1] vertices with a bin (lines 1-5),
-// [2] bin cursor, [3] vertices with more than R incoming edges (lines 6-8).
+// second in-edge count, the per-vertex marks, the late arrival numbers and their position masks.  misc: [0] bin cursor, [1] vertices with a bin (union and out-degree cut),
+// [2] bin cursor, [3] vertices with more than R incoming edges (in-degree cut).
 static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use_classes, u64 *keys, int *deg,
                                  int t_next, hipStream_t st, hipEvent_t e_stop = nullptr)
 {
@@ -1228,7 +1228,7 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     u64 *over = (u64 *)w.touched;        // two words per vertex (touched is 16 bytes per vertex)
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, 8);
     if (t_next >= 0) hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NDEG);
-    // lines 1-5: union with reversed edges, out-lists cut to R
+    // union with reversed edges, out-lists cut to R
     hipLaunchKernelGGL(k_reverse_scatter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, late, over,
                        mark);
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.fill, INBOX_CAP, INBOX_CAP, INBOX_CAP,
@@ -1237,7 +1237,7 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
                        w.bins, w.misc + 1);
     hipLaunchKernelGGL(k_reverse_merge, dim3((vb + 1) / 2), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, w.binoff,
                        w.bins, cand, cnt_in, rowflag, w.vcls, use_classes);
-    // lines 6-8: in-lists cut to R; only vertices with more than R incoming edges need a bin
+    // in-lists cut to R; only vertices with more than R incoming edges need a bin
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, cnt_in, R, R, 0, w.binoff, w.misc + 2, w.hubs,
                        w.misc + 3, w.cnt, (int *)nullptr, w.thr, (const int *)nullptr, 0, (int8_t *)nullptr);
     hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, rowflag, w.binoff, w.cnt, w.bins,

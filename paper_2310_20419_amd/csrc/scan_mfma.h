@@ -1,4 +1,4 @@
-// UpdateNeighbors scan (Alg. 4 lines 2-15) for uint8 rows on the matrix cores.
+// UpdateNeighbors scan (Alg. 4, the body of the vertex loop) for uint8 rows on the matrix cores.
 //
 // One wavefront owns one vertex u with m <= 32*NG list entries.  The rows x_v of its whole list are
 // gathered straight into MFMA operand registers (lane l: row l%32 of a 32-row group, bytes
@@ -12,11 +12,11 @@
 // and 16 of its columns, j = 8(a/4) + 4(l/32) + a%4: by the symmetry of the Gram matrix no transpose
 // is needed.  Both operands use the same byte order, so however the hardware pairs the K bytes, the
 // two sides pair alike.  With delta(v_i, w_j) = n_i + n_j - 2<x_i, x_j> (exact in int32):
-//     line 11 fails  <=>  delta(u, v_i) >= delta(v_i, w_j)  <=>  T_ij >= 0 ,
-// Each half-wave collects the outcomes for its 16 columns as bits of one word per row.  Lines 5-18
+//     the prune test fires  <=>  delta(u, v_i) >= delta(v_i, w_j)  <=>  T_ij >= 0 ,
+// Each half-wave collects the outcomes for its 16 columns as bits of one word per row.  The loop over v
 // then run on bit masks: the kept set U' is the unique solution K of
 //     K_i = not exists j < i : F_ij and K_j
-// (F already masked by the old/old skip of lines 8-9), found per 32-row block by iterating
+// (F already masked by the old/old skip), found per 32-row block by iterating
 // K <- Phi(K) from "all kept" until it stops changing (row i is final after i+1 sweeps).  A pruned
 // row's redirect target is the first set bit of F_i & K, and delta(v,w) for the new edge comes from
 // the tile kept in LDS:  delta(v_i, w_j) = delta(u, v_i) - T_ij.
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void k_prepare_u8(const uint8_t *__restrict__ 
     }
 }
 
-// Lines 2-15 for the vertex in `cur`, whose rows are in A and whose norms are in nr.
+// The body of Alg. 4's vertex loop for the vertex in `cur`, whose rows are in A and whose norms are in nr.
 template <int NG, int KS>
 __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG][KS], MfmaScanSmem<NG> &sm, int R, u64 *__restrict__ keys,
                                                int *__restrict__ deg, Prop *__restrict__ props,
@@ -170,11 +170,11 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
             for (int J = 0; J < NG; ++J) F[J] = E[J] = 0;
 #pragma unroll
             for (int J = 0; J <= I; ++J) {
-                // a tile without a new row and without a new column holds only old/old pairs (lines 8-9)
+                // a tile without a new row and without a new column holds only old/old pairs, which Alg. 4 skips
                 const u32 new_J = (u32)(newm[J >> 1] >> (32 * (J & 1)));
                 if ((new_I | new_J) == 0) continue;
                 tiles += 1;
-                // lines 8-9: a pair is tested only if v or w is new; only w before v count
+                // the old/old skip: a pair is tested only if v or w is new; only w before v count
                 u32 e = newi ? 0xFFFFFFFFu : new_J;
                 if (J == I) e &= (1u << l32) - 1u;
                 if (!validi) e = 0;
@@ -199,7 +199,7 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
                 gt[2] = make_int4(acc[4], acc[5], acc[6], acc[7]);
                 gt[4] = make_int4(acc[8], acc[9], acc[10], acc[11]);
                 gt[6] = make_int4(acc[12], acc[13], acc[14], acc[15]);
-                // bit a of ok: T < 0, the test of line 11 holds for column a
+                // bit a of ok: T < 0, v passes the prune test against column a
                 u32 ok = 0;
 #pragma unroll
                 for (int a = 15; a >= 0; --a) ok = __builtin_amdgcn_alignbit(ok, (u32)acc[a], 31);
@@ -209,7 +209,7 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
                 ok <<= 4 * half;
                 F[J] = E[J] & ~ok;
             }
-            // lines 5-18 on masks; what the two half-waves find for a row is joined through ballots
+            // the loop over v on masks; what the two half-waves find for a row is joined through ballots
             bool pre = false;
 #pragma unroll
             for (int J = 0; J < I; ++J) pre = pre || ((F[J] & Kw[J]) != 0);
@@ -252,7 +252,7 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
             if (pruned) {
                 const int tv = sm.gt[((tgt & ~31) + l32) * GT_STRIDE + (tgt & 31)];
                 const u32 dvw = (u32)(di - tv);
-                // line 13: v enters w's list
+                // the redirect: v enters w's list
                 emit_redirect(make_key(dvw, key_id(kb), 1u), (u32)sm.id[tgt],
                               props + (size_t)u * R + np_base + __popcll(pm & lanes_below(lane)));
             }
@@ -260,7 +260,7 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
             if (I + 1 < NG) wave_sync();   // before the next block overwrites the tiles
         }
     }
-    // line 15 + compaction: kept entries, flag old, back into the row
+    // kept entries, flag old, compacted back into the row
     const u64 K0 = (u64)Kw[0] | (NG > 1 ? ((u64)Kw[NG > 1 ? 1 : 0] << 32) : 0ull);
     const u64 K1 = NG > 2 ? ((u64)Kw[NG > 2 ? 2 : 0] | (NG > 3 ? ((u64)Kw[NG > 3 ? 3 : 0] << 32) : 0ull)) : 0ull;
     const int nk0 = __popcll(K0);
@@ -422,7 +422,7 @@ __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[K
     const int negt = di - ni;
     const u32 segmask = (W == 32 ? 0xFFFFFFFFu : ((1u << (W & 31)) - 1u) << (seg * W));
     const u32 hm = 0x0F0F0F0Fu << (4 * half);   // the columns this half-wave holds
-    // lines 8-9: a pair is tested only if v or w is new; only w before v (in v's own list) count
+    // the old/old skip: a pair is tested only if v or w is new; only w before v (in v's own list) count
     u32 E = newi ? segmask : (new32 & segmask);
     E &= (1u << l32) - 1u;
     if (!valid) E = 0;
@@ -449,7 +449,7 @@ __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[K
         gt[4] = make_int4(acc[8], acc[9], acc[10], acc[11]);
         gt[6] = make_int4(acc[12], acc[13], acc[14], acc[15]);
     }
-    // bit a of ok: T < 0, the test of line 11 holds for column a
+    // bit a of ok: T < 0, v passes the prune test against column a
     u32 ok = 0;
 #pragma unroll
     for (int a = 15; a >= 0; --a) ok = __builtin_amdgcn_alignbit(ok, (u32)acc[a], 31);
@@ -458,7 +458,7 @@ __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[K
     ok = (ok | (ok << 4)) & 0x0F0F0F0Fu;
     ok <<= 4 * half;
     const u32 F = E & ~ok;
-    // lines 5-18 on masks; what the two half-waves find for a row is joined through ballots
+    // the loop over v on masks; what the two half-waves find for a row is joined through ballots
     u32 Kcur = vmask;
     for (int sweep = 0; sweep < 33; ++sweep) {
         const u64 hit = __builtin_amdgcn_ballot_w64((F & Kcur) != 0);
@@ -487,11 +487,11 @@ __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[K
     if (pruned) {
         const int tv = sm.gt[l32 * GT_STRIDE + tgt];
         const u32 dvw = (u32)(di - tv);
-        // line 13: v enters w's list
+        // the redirect: v enters w's list
         emit_redirect(make_key(dvw, key_id(kb), 1u), (u32)sm.id[tgt],
                       props + (size_t)u * R + __popc(pm & segmask & below));
     }
-    // line 15 + compaction: kept entries, flag old, back into the row
+    // kept entries, flag old, compacted back into the row
     if (kept && half == 0) keys[(size_t)u * R + __popc(Kcur & segmask & below)] = kb & ~1ull;
     if (leader) {
         deg[u] = __popc(Kcur & segmask);

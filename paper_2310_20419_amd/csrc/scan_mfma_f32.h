@@ -1,4 +1,4 @@
-// UpdateNeighbors scan (Alg. 4 lines 2-15) for float32 rows on the double-precision matrix cores.
+// UpdateNeighbors scan (Alg. 4, the body of the vertex loop) for float32 rows on the double-precision matrix cores.
 //
 // One wavefront owns one vertex u with m <= 16*NRC list entries, handled as NRC groups of 16 rows.
 // The rows are streamed through registers 16 dimensions (64 bytes per row) at a time: lane l loads 4
@@ -9,10 +9,10 @@
 //     delta(v_i, v_j) ~= float(n_i + n_j - 2 G_ij)
 // differs from the reference value (double accumulation of (a-b)^2, rounded once) only when the two
 // doubles straddle a rounding boundary of float, about 1e-8 of the time; it is used for the DECISION of
-// line 11 only.  Every distance that is STORED (the delta(v,w) of a redirected edge) is recomputed by
+// the prune test only.  Every distance that is STORED (the delta(v,w) of a redirected edge) is recomputed by
 // the one routine all stored distances come from (dist.h), so equal edges always carry equal keys.
 //
-// Lines 8-9 never test two old entries against each other, so only pairs with a new member need a
+// Alg. 4 never tests two old entries against each other (the old/old skip), so only pairs with a new member need a
 // distance.  The list is therefore laid out in SLOTS: its new entries first, then its old ones, each in
 // list order.  A tile is needed only if its column group J holds a new slot, i.e. J < ceil(#new / 16):
 // with few new entries a list of 6 groups costs 6 tiles instead of 21.  Everything after the tiles
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
             }
             wave_sync();
 
-            // ---- line 11 for every pair of a computed tile, both ways round.  FA[t]: lane r16 = slot r16 of
+            // ---- the prune test for every pair of a computed tile, both ways round.  FA[t]: lane r16 = slot r16 of
             // group I as the tested row, bit c = column slot c of group J.  FB[t] (I != J): lane r16 = slot r16
             // of group J as the tested row, bit c = column slot c of group I.  (Same in all quarter-waves.)
             u32 FA[NT], FB[NT];
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
                 }
             }
 
-            // ---- lines 5-18: the kept set as the fixed point, all rows at once
+            // ---- the loop over v: the kept set as the fixed point, all rows at once
             u32 Kw[3] = {0u, 0u, 0u};
             u64 Kset[2] = {0ull, 0ull};       // bit lane of Kset[e]: my row of set e is kept
             {
@@ -383,7 +383,7 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
                     int rank = 0;
 #pragma unroll
                     for (int c = 0; c < NWD; ++c) rank += __popc(Kw[c] & Bw[e][c]);
-                    row[rank] = sm.key[s] & ~1ull;      // line 15: flag old
+                    row[rank] = sm.key[s] & ~1ull;      // kept: flag old
                 }
                 const u64 pm = __builtin_amdgcn_ballot_w64(pruned);
                 if (pruned) {
@@ -399,7 +399,7 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
             }
             nprops_total += np_base;
             wave_sync();
-            // line 13: the redirected edges, with delta(v,w) from the routine every stored distance comes from
+            // the redirected edges, with delta(v,w) from the routine every stored distance comes from
             for (int b = 0; b < np_base; b += 8) {
                 const int p = b + grp;
                 const bool have = p < np_base;

@@ -2,15 +2,15 @@
 //
 // The candidate list C (at most L <= 128 points, ascending by (delta, id)) lives in registers, one or
 // two keys per lane: key = (delta bits << 32) | (id << 1) | unvisited.  One step of the loop:
-//   line 3     first unvisited member u of C (ballot), marked visited;
-//   line 5     its first min(deg(u), K) neighbours (rows are nearest-first), 64 per pass;
-//   line 6     a neighbour already evaluated for this query is skipped: one bit per vertex in a bitmap
+//   select     first unvisited member u of C (ballot), marked visited;
+//   expand     its first min(deg(u), K) neighbours (rows are nearest-first), 64 per pass;
+//   visited?   a neighbour already evaluated for this query is skipped: one bit per vertex in a bitmap
 //              that the wavefront owns, tested and set by a single atomic OR;
-//   line 7     delta(q, v) for the rest, 8 vertices at a time (8 lanes per vertex);
-//   lines 8-9  C <- the L smallest of C and the new points: the new keys are sorted, reversed, and merged
+//   evaluate   delta(q, v) for the rest, 8 vertices at a time (8 lanes per vertex);
+//   insert     C <- the L smallest of C and the new points: the new keys are sorted, reversed, and merged
 //              into C by a bitonic merge whose upper half is never formed; keys not below C's last one
 //              are dropped first when C is full, and the merge is skipped when none is left.
-// The loop ends when C holds no unvisited point (lines 10-11).  InitializeCandidates (line 1) is
+// The loop ends when C holds no unvisited point (the loop's exit).  InitializeCandidates is
 // min(L, N) distinct seeded random vertices from the same counter-based generator as RandomGraph,
 // keyed by the query index.  Inserting the new points one by one, as the algorithm is written, and
 // merging them at once give the same C, because each keeps the L smallest of what has been seen.
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
         for (size_t w4 = (size_t)lane * 4; w4 < bitmap_words; w4 += 256)
             *(uint4 *)(seen + w4) = make_uint4(0u, 0u, 0u, 0u);
         wave_sync();
-        // ---- line 1
+        // ---- InitializeCandidates
         if ((long long)L0 == N) {
             for (int t = lane; t < L0; t += 64) sm.id[t] = t;
         } else {
@@ -194,9 +194,9 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
         wave_sort<E>(C, lane);
         int m = L0;
         ev += (unsigned long long)L0;
-        // ---- lines 2-11
+        // ---- the search loop
         for (;;) {
-            // line 3: the first unvisited member of C
+            // select: the first unvisited member of C
             int iu = -1;
 #pragma unroll
             for (int r = E - 1; r >= 0; --r) {
@@ -214,14 +214,14 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
             if (du > W) du = W;
             if (du < 0) du = 0;
             for (int t0 = 0; t0 < du; t0 += 64) {
-                // lines 5-6
+                // expand, skipping what was evaluated before
                 const int t = t0 + lane;
                 int v = -1;
                 if (t < du) v = t0 == 0 ? v0 : graph[(size_t)u * W + t];
                 const bool isv = v >= 0 && (long long)v < N;   // anything else is not a vertex: ignored
                 u64 kn;
                 if (short_rows) {
-                    // line 7 for every neighbour, while the bitmap answers which of them are new to this
+                    // evaluate every neighbour, while the bitmap answers which of them are new to this
                     // query: short rows cost less to read than a second round trip; lane p keeps candidate p
                     const int sub = lane & 7, grp = lane >> 3;
                     const int np = du - t0 < 64 ? du - t0 : 64;
@@ -269,13 +269,13 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
                     wave_sync();
                     if (fresh) sm.id[__popcll(fm & lanes_below(lane))] = v;
                     wave_sync();
-                    // line 7
+                    // evaluate
                     search_eval<DT>(X, qv, d, vec_ok, rowbytes, sm, nf, lane);
                     ev += (unsigned long long)nf;
                     wave_sync();
                     kn = lane < nf ? make_key(sm.dist[lane], (u32)sm.id[lane], 1u) : KEY_PAD;
                 }
-                // lines 8-9
+                // insert
                 if (m == L) {
                     const u64 last = shfl_u64(C[(L - 1) >> 6], (L - 1) & 63);
                     if ((kn >> 1) >= (last >> 1)) kn = KEY_PAD;

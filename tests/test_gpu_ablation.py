@@ -35,7 +35,7 @@ def test_reverse_edges_matter_cfg2(rn, oracle_mod):
         if T1 == 1:
             assert dg.min() >= 1      # the nearest entry of a list is never pruned; only Alg. 5 can empty a list
         if T1 > 1:
-            # Alg. 5 lines 6-8 bound the in-degree after each call; UpdateNeighbors never raises a vertex's
+            # the in-degree cut of Alg. 5 bounds the in-degree after each call; UpdateNeighbors never raises a vertex's
             # in-degree above what it was (a redirected edge replaces an edge into the same vertex)
             indeg = np.bincount(g[g >= 0], minlength=c.N)
             assert indeg.max() <= c.R

@@ -1,7 +1,7 @@
 """Block-sequential passes on the GPU (rnnd_build_blocks, rnnd_update_neighbors_blocks) against the
 oracle's block-sequential variant: runs of consecutive vertex ids take their turn in id order and a run's
-redirected edges are merged before the next run starts (Alg. 4 line 1 visits the vertices one after the
-other and line 13 changes the edge set at once).  Every number of runs defines one graph per seed, so the
+redirected edges are merged before the next run starts (Alg. 4 visits the vertices one after the
+other and its edge update changes the edge set at once).  Every number of runs defines one graph per seed, so the
 comparison is exact: ids, distances, flags, degrees and per-pass evaluation counts."""
 import numpy as np
 import pytest

@@ -1,14 +1,14 @@
 """Pins for the CPU oracle: each test checks it against something the paper or the
 mathematics fixes, never against itself.  (CPU only.)
 
-  Fig. 1(c) worked example, tie rule         -> Alg. 4 lines 11-13
+  Fig. 1(c) worked example, tie rule         -> Alg. 4 (prune test, redirect)
   reduction to Alg. 3 / exact RNG / 1-NN     -> Sec. 4.2 ("most of the algorithm is the RNG Strategy")
   path-graph fixed point on a 1-D lattice    -> Alg. 4 (closed form)
   Eq. 2 on kept neighbours, degree bounds    -> Eq. 2, Alg. 5, Sec. 5.3
   flag skip changes cost, not results        -> Sec. 4.2 last paragraph
   set-wise brute-force models on tiny inputs -> Alg. 4, Alg. 5 written a second way
   block-sequential passes: worked example of the vertex order, one block = synchronous round,
-  n blocks = the in-place order of Alg. 4 line 1  -> Alg. 4
+  n blocks = the in-place order of Alg. 4's vertex loop  -> Alg. 4
 """
 import numpy as np
 import pytest
@@ -42,7 +42,7 @@ def small_f32(n, d, seed):
     return np.random.default_rng(seed).normal(size=(n, d)).astype(np.float32)
 
 
-# ------------------------------------------------- RandomGraph (Alg. 6 line 1)
+# ------------------------------------------------- RandomGraph (Alg. 6)
 def test_mix64_matches_published_splitmix64_vector(oracle_mod):
     vec = [int(line) for line in open(__import__("os").path.join(
         __import__("conftest").GOLDEN, "splitmix64_seed1234567.txt")) if line[0].isdigit()]
@@ -469,15 +469,15 @@ def _search_model(X, ids, deg, q, start, L, K, k):
         pending = [v for v in C if v not in visited]
         if not pending:
             break
-        u = min(pending, key=lambda v: (C[v], v))                        # line 3
+        u = min(pending, key=lambda v: (C[v], v))                        # select
         visited.add(u)
-        for v in ids[u][:min(int(deg[u]), K)].tolist():                  # line 5 with Eq. 4
-            if v in evaluated:                                           # line 6
+        for v in ids[u][:min(int(deg[u]), K)].tolist():                  # expand, with Eq. 4
+            if v in evaluated:                                           # evaluated before
                 continue
             evaluated.add(v)
-            C[v] = dist(v)                                               # line 7
+            C[v] = dist(v)                                               # evaluate
             evals += 1
-            if len(C) > L:                                               # lines 8-9
+            if len(C) > L:                                               # C keeps its L nearest
                 worst = max(C, key=lambda w: (C[w], w))
                 del C[worst]
                 visited.discard(worst)
