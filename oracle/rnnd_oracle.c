@@ -395,7 +395,7 @@ static void update_neighbors_paper_order(const data_t *D, list_t *G, int64_t *ev
         }
         for (int64_t i = 0; i < P.len; ++i) {
             list_t *Lw = &G[P.p[i].target];
-            if (!list_has(Lw, P.p[i].id)) {              /* no edge added if it exists */
+            if (!list_has(Lw, P.p[i].id)) {              /* an edge already present is not added again */
                 entry_t x;
                 x.id = P.p[i].id; x.dist = P.p[i].dist; x.is_new = 1;
                 list_push(Lw, x);

@@ -2,7 +2,7 @@
 mathematics fixes, never against itself.  (CPU only.)
 
   Fig. 1(c) worked example, tie rule         -> Alg. 4 (prune test, redirect)
-  reduction to Alg. 3 / exact RNG / 1-NN     -> Sec. 4.2 ("most of the algorithm is the RNG Strategy")
+  reduction to Alg. 3 / exact RNG / 1-NN     -> Sec. 4.2 (Alg. 4 is Alg. 3 applied to the current neighbours)
   path-graph fixed point on a 1-D lattice    -> Alg. 4 (closed form)
   Eq. 2 on kept neighbours, degree bounds    -> Eq. 2, Alg. 5, Sec. 5.3
   flag skip changes cost, not results        -> Sec. 4.2 last paragraph
