@@ -166,10 +166,12 @@ int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int metric, cons
                 int64_t *dist_evals, void *stream);
 
 /* Selects the UpdateNeighbors scan kernel: 0 = automatic (default), 1 = generic pair-at-a-time
- * kernel for every input.  Automatic uses the dense Gram-block kernels on the matrix cores where
- * they apply (uint8 with d = 32, 64 or 128: int8 MFMA; float32 with d a multiple of 16: f64 MFMA)
- * and the generic kernel otherwise.  All give identical graphs; this exists for testing and
- * profiling.  Process-wide, not thread-safe. */
+ * kernel for every input, 2 = automatic, but the float32 matrix-core scan works in double precision
+ * throughout.  Automatic uses the dense Gram-block kernels on the matrix cores where they apply
+ * (uint8 with d = 32, 64 or 128: int8 MFMA; float32 with d a multiple of 16: fp32 MFMA first, every
+ * pair whose outcome lies within that block's error bound decided by the exact distance, and
+ * vertices with very many such pairs redone on the f64 MFMA) and the generic kernel otherwise.
+ * All give identical graphs; this exists for testing and profiling.  Process-wide, not thread-safe. */
 int rnnd_set_kernel_variant(int variant);
 
 const char *rnnd_strerror(int status);

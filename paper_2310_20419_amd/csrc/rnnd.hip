@@ -41,6 +41,7 @@ struct RoundCtr {
     u32 bin_cursor;       // space handed out in the bin array
     u32 has_surplus;      // some vertex received more than INBOX_CAP edges this round
     u32 pad[2];
+    u32 n_redo[NDEG];     // float scan: vertices the single-precision form left to the double-precision one
     // statistics, spread over STAT_SLOTS addresses so that the adds of many blocks do not queue up
     // on one: [slot][0..3] = algorithmic evals, executed evals, rows gathered, edges redirected
     u64 stat[STAT_SLOTS][4];
@@ -1089,15 +1090,28 @@ static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *
     if (R > 96) launch_mfma_scan<4, KS>(w, R, keys, deg, N, c, st, n_big == 3 ? re.scan_stop : nullptr);
 }
 
+// Float scan of degree class cls: the single-precision form over the class's active list, then the
+// double-precision form over the (normally empty) list of vertices the first one left alone.  The redo
+// lists live in the bin array, which nothing else uses until the scatter that follows the scans.
 template <int NG, int CH, int NRC>
 static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, long long N,
                             RoundCtr *c, int cls, hipStream_t st, hipEvent_t e_start, hipEvent_t e_stop)
 {
     // wavefronts that fit per SIMD: about 4 for NG = 1, 2 for NG = 2, 1 for NG = 3 (21 accumulator tiles)
-    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC>, NG == 1 ? 4 : NG == 2 ? 2 : 1);
-    hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC>), dim3(cu_count() * per_cu), dim3(256), 0, st, e_start,
-                          e_stop, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
-                          &c->n_active[cls], w.props, w.nprop, c);
+    static const int per_cu_fast = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, true>, NG == 1 ? 4 : 2);
+    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, false>, NG == 1 ? 4 : NG == 2 ? 2 : 1);
+    int *redo = (int *)w.bins + (size_t)cls * N;
+    if (g_kernel_variant != 2)
+        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, true>), dim3(cu_count() * per_cu_fast), dim3(256), 0, st,
+                              e_start, nullptr, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
+                              &c->n_active[cls], w.props, w.nprop, c, redo, &c->n_redo[cls]);
+    else
+        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, false>), dim3(cu_count() * per_cu), dim3(256), 0, st,
+                              e_start, nullptr, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
+                              &c->n_active[cls], w.props, w.nprop, c, (int *)nullptr, (u32 *)nullptr);
+    hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, false>), dim3(cu_count() * per_cu), dim3(256), 0, st,
+                          nullptr, e_stop, 0, (const float *)X, d, R, keys, deg, (const int *)redo,
+                          (const u32 *)&c->n_redo[cls], w.props, w.nprop, c, (int *)nullptr, (u32 *)nullptr);
 }
 
 // One run of consecutive vertex ids of a block-sequential pass: ids first .. first + count - 1.
@@ -1696,9 +1710,11 @@ done:
     return rc;
 }
 
+// 0: automatic; 1: generic scan for every input; 2: automatic, but the float matrix-core scan runs in
+// double precision only (no single-precision first pass)
 extern "C" int rnnd_set_kernel_variant(int variant)
 {
-    if (variant < 0 || variant > 1) return RNND_ERR_BAD_PARAM;
+    if (variant < 0 || variant > 2) return RNND_ERR_BAD_PARAM;
     g_kernel_variant = variant;
     return RNND_OK;
 }

@@ -29,6 +29,9 @@
 #include "wave_prims.h"
 
 typedef double v4d __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+#define F32_AMB_CAP 256   // pairs of one vertex that the single-precision form may leave undecided
 
 template <int NRC>
 struct alignas(16) F32ScanSmem {
@@ -37,6 +40,7 @@ struct alignas(16) F32ScanSmem {
     int pos[16 * NRC];      // list position by slot
     u32 pv[16 * NRC];       // redirected entries: slot of v ...
     u32 pw[16 * NRC];       // ... and of the w it failed against
+    uint16_t amb[F32_AMB_CAP];   // undecided pairs: row slot << 8 | column slot; bit 15 <- the exact outcome
 };
 
 template <int SH, u32 M>
@@ -57,6 +61,28 @@ __device__ __forceinline__ u32 transpose16_bits(u32 w, int lane)
     w = transpose_step16<1, 0x5555u>(w, lane);
     return w & 0xFFFFu;
 }
+
+// The same for two 16x16 bit matrices at once, one in the low and one in the high half of the word.
+template <int SH, u32 M>
+__device__ __forceinline__ u32 transpose_step16x2(u32 w, int lane)
+{
+    constexpr u32 M2 = M | (M << 16);
+    const u32 p = (u32)__shfl_xor((int)w, SH);
+    const u32 lo = (w & M2) | ((p & M2) << SH);
+    const u32 hi = ((p >> SH) & M2) | (w & ~M2);
+    return (lane & SH) ? hi : lo;
+}
+__device__ __forceinline__ u32 transpose16_bits_x2(u32 w, int lane)
+{
+    w = transpose_step16x2<8, 0x00FFu>(w, lane);
+    w = transpose_step16x2<4, 0x0F0Fu>(w, lane);
+    w = transpose_step16x2<2, 0x3333u>(w, lane);
+    w = transpose_step16x2<1, 0x5555u>(w, lane);
+    return w;
+}
+
+template <bool FAST> struct GramAcc { typedef v4d type; };
+template <> struct GramAcc<true> { typedef v4f type; };
 
 // The Gram block of all NR 16-row groups over all d dimensions.  Per iteration: wait for the chunk,
 // widen it to double, immediately issue the loads of the next chunk into the same registers, then run
@@ -109,6 +135,75 @@ __device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int 
     }
 }
 
+// Single-precision form of the same loop: the rows go to v_mfma_f32_16x16x4_f32 as they are (twice the
+// rate of the double-precision instruction, half the accumulator registers).  That instruction adds its
+// four products one after the other, each product exact and each sum rounded to nearest, so after d
+// dimensions |G - G_exact| <= d 2^-24 sum_k |x_ik x_jk| (1 + 2 d 2^-24) <= 1.01 d 2^-24 sqrt(n_i n_j).
+// The norms stay in double.
+template <int NR, int CH, u32 TM>
+__device__ __forceinline__ void gram_f32_chunk(const float4 (&x)[NR][CH], v4f (&acc)[NR * (NR + 1) / 2], double (&nr)[NR],
+                                               u32 need)
+{
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            float a[NR];
+#pragma unroll
+            for (int g = 0; g < NR; ++g) {
+                a[g] = t == 0 ? x[g][j].x : t == 1 ? x[g][j].y : t == 2 ? x[g][j].z : x[g][j].w;
+                const double ad = (double)a[g];
+                nr[g] = fma(ad, ad, nr[g]);
+            }
+#pragma unroll
+            for (int I = 0; I < NR; ++I)
+#pragma unroll
+                for (int J = 0; J <= I; ++J)
+                    if (TM ? ((TM >> (I * (I + 1) / 2 + J)) & 1u) != 0 : ((need >> (I * (I + 1) / 2 + J)) & 1u) != 0)   // wave-uniform
+                        acc[I * (I + 1) / 2 + J] =
+                            __builtin_amdgcn_mfma_f32_16x16x4f32(a[I], a[J], acc[I * (I + 1) / 2 + J], 0, 0, 0);
+        }
+}
+
+// Three buffers in rotation: while the matrix cores work on one chunk, the loads of the next two are in
+// flight (the single-precision instruction is fast enough that one chunk of lead does not cover the
+// latency of the gathers).  Loads past the end re-read the last chunk.
+template <int NR, int CH, u32 TM = 0>
+__device__ __forceinline__ void gram_f32_loop(const float *const (&rp)[NR], int nchunk, v4f (&acc)[NR * (NR + 1) / 2],
+                                              double (&nr)[NR], u32 need)
+{
+    float4 x0[NR][CH], x1[NR][CH], x2[NR][CH];
+    const int last = nchunk - 1;
+    auto fetch = [&](float4 (&x)[NR][CH], int c) {
+        const int cc = c < last ? c : last;
+#pragma unroll
+        for (int g = 0; g < NR; ++g)
+#pragma unroll
+            for (int j = 0; j < CH; ++j) x[g][j] = *(const float4 *)(rp[g] + 16 * (CH * cc + j));
+    };
+    fetch(x0, 0);
+    fetch(x1, 1);
+#pragma unroll 1
+    for (int c = 0; c < nchunk; c += 3) {
+        fetch(x2, c + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        gram_f32_chunk<NR, CH, TM>(x0, acc, nr, need);
+        __builtin_amdgcn_sched_barrier(0);
+        if (c + 1 < nchunk) {
+            fetch(x0, c + 3);
+            __builtin_amdgcn_sched_barrier(0);
+            gram_f32_chunk<NR, CH, TM>(x1, acc, nr, need);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (c + 2 < nchunk) {
+            fetch(x1, c + 4);
+            __builtin_amdgcn_sched_barrier(0);
+            gram_f32_chunk<NR, CH, TM>(x2, acc, nr, need);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
 // CH = 16-dimension chunks fetched per loop iteration (d must be a multiple of 16*CH): a longer iteration
 // gives the prefetch of the next one more matrix work to hide behind.
 // bits [lo, hi) of a 96-bit mask, as word c (bits 32c .. 32c+31)
@@ -130,12 +225,22 @@ __device__ __forceinline__ int popc_below(u64 m0, u64 m1, int p)   // set bits o
 
 // NRC = 16-row groups of the list (lists of at most 16 NRC entries); NG = ceil(NRC / 2) names the
 // degree class family; CH = 16-dimension chunks fetched per loop iteration (d a multiple of 16*CH).
-template <int NG, int CH, int NRC = 2 * NG>
-__global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_update_scan_mfma_f32(
+// FAST: the Gram block in single precision (gram_f32_loop).  A pair is then decided only if the outcome of
+// the prune test is beyond the error bound of that block, eps_ij = (1.25 d + 8) 2^-24 (n_i + n_j), which
+// covers the accumulation (2 x 1.01 d 2^-24 sqrt(n_i n_j) <= 1.01 d 2^-24 (n_i + n_j)) and the roundings of
+// delta(v,w) to float on either side (delta <= 2 (n_i + n_j)); the few undecided pairs get the exact
+// delta(v,w) from the routine every stored distance comes from, so the decisions are those of the
+// reference arithmetic.  A vertex with more than F32_AMB_CAP undecided pairs (ties in bulk: duplicates,
+// lattices) is left untouched and appended to `redo`, which the double-precision form (FAST = false)
+// takes afterwards.
+template <int NG, int CH, int NRC = 2 * NG, bool FAST = false>
+__global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) : (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1))) void k_update_scan_mfma_f32(
     const float *__restrict__ X, int d, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
-    int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
+    int *__restrict__ nprop, RoundCtr *__restrict__ ctr, int *__restrict__ redo, u32 *__restrict__ n_redo)
 {
+    typedef typename GramAcc<FAST>::type acc_t;
+    const double epsk = (1.25 * (double)d + 8.0) * 5.9604644775390625e-08;
     constexpr int NT = NRC * (NRC + 1) / 2;
     constexpr int NWD = (NRC + 1) / 2;        // 32-bit words of a mask over slots
     constexpr int NSET = NRC > 4 ? 2 : 1;     // lane (r16, q) owns rows 16 q + r16 and, if NRC > 4, 64 + 16 q + r16
@@ -208,9 +313,9 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
                 rp[g] = X + (size_t)id * d + 4 * q;
             }
             // ---- Gram block over d in chunks of 16 dimensions: the tiles whose column group holds a new slot
-            v4d acc[NT];
+            acc_t acc[NT];
 #pragma unroll
-            for (int t = 0; t < NT; ++t) acc[t] = (v4d){0.0, 0.0, 0.0, 0.0};
+            for (int t = 0; t < NT; ++t) acc[t] = (acc_t)(0);
             double nr[NRC];
 #pragma unroll
             for (int g = 0; g < NRC; ++g) nr[g] = 0.0;
@@ -221,15 +326,26 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
                 for (int J = 0; J <= I; ++J)
                     if (16 * I < m && J < g_new) need |= 1u << (I * (I + 1) / 2 + J);
             need = (u32)__builtin_amdgcn_readfirstlane((int)need);
-            if (NRC == 1) {
-                gram_f64_loop<NRC, CH, 1u>(rp, nchunk, acc, nr, need);
-            } else if (NRC == 2) {
-                // two straight-line loops instead of per-tile branches: all three tiles, or (new entries in
-                // the first group only) the two tiles of column group 0
-                if (need == 7u) gram_f64_loop<NRC, CH, 7u>(rp, nchunk, acc, nr, need);
-                else gram_f64_loop<NRC, CH, 3u>(rp, nchunk, acc, nr, need);
+            if constexpr (FAST) {
+                if (NRC == 1) {
+                    gram_f32_loop<NRC, CH, 1u>(rp, nchunk, acc, nr, need);
+                } else if (NRC == 2) {
+                    if (need == 7u) gram_f32_loop<NRC, CH, 7u>(rp, nchunk, acc, nr, need);
+                    else gram_f32_loop<NRC, CH, 3u>(rp, nchunk, acc, nr, need);
+                } else {
+                    gram_f32_loop<NRC, CH>(rp, nchunk, acc, nr, need);
+                }
             } else {
-                gram_f64_loop<NRC, CH>(rp, nchunk, acc, nr, need);
+                if (NRC == 1) {
+                    gram_f64_loop<NRC, CH, 1u>(rp, nchunk, acc, nr, need);
+                } else if (NRC == 2) {
+                    // two straight-line loops instead of per-tile branches: all three tiles, or (new entries in
+                    // the first group only) the two tiles of column group 0
+                    if (need == 7u) gram_f64_loop<NRC, CH, 7u>(rp, nchunk, acc, nr, need);
+                    else gram_f64_loop<NRC, CH, 3u>(rp, nchunk, acc, nr, need);
+                } else {
+                    gram_f64_loop<NRC, CH>(rp, nchunk, acc, nr, need);
+                }
             }
 #pragma unroll
             for (int g = 0; g < NRC; ++g) {
@@ -251,24 +367,33 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
                     FA[t] = FB[t] = 0;
                     if (NRC == 1 || (NRC == 2 && need != 7u && t < 2) || ((need >> t) & 1u)) tiles += 1;   // what the loop above computed
                     if ((need >> t) & 1u) {     // wave-uniform
-                        // lane = slot r16 of group J; accumulator v = slot 4v + q of group I
+                        // lane = slot r16 of group J; accumulator v = slot 4v + q of group I (4q + v in the
+                        // single-precision instruction).  Low half of a word: the test fires; high half: undecided.
                         const float dj = __uint_as_float(key_dist(sm.key[16 * J + r16]));
                         u32 fa = 0, fb = 0;
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
-                            const int si = 16 * I + 4 * v + q;
-                            const float dvw = (float)(sm.nrm[si] + nr[J] - 2.0 * acc[t][v]);
+                            const int rsel = FAST ? 4 * q + v : 4 * v + q;
+                            const int si = 16 * I + rsel;
+                            const double nsum = sm.nrm[si] + nr[J];
+                            const double dvwd = nsum - 2.0 * (double)acc[t][v];
+                            const float dvw = (float)dvwd;
                             const float di = __uint_as_float(key_dist(sm.key[si]));
-                            fa |= (di >= dvw) ? (1u << (4 * v + q)) : 0u;
-                            fb |= (dj >= dvw) ? (1u << (4 * v + q)) : 0u;
+                            fa |= (di >= dvw) ? (1u << rsel) : 0u;
+                            fb |= (dj >= dvw) ? (1u << rsel) : 0u;
+                            if (FAST) {
+                                const double tol = epsk * nsum;
+                                fa |= !(fabs((double)di - dvwd) > tol) ? (0x10000u << rsel) : 0u;      // also when not finite
+                                fb |= !(fabs((double)dj - dvwd) > tol) ? (0x10000u << rsel) : 0u;
+                            }
                         }
                         fa |= (u32)__shfl_xor((int)fa, 16);
                         fa |= (u32)__shfl_xor((int)fa, 32);
-                        FA[t] = transpose16_bits(fa, lane);
+                        FA[t] = FAST ? transpose16_bits_x2(fa, lane) : transpose16_bits(fa, lane);
                         if (I != J) {
                             fb |= (u32)__shfl_xor((int)fb, 16);
                             fb |= (u32)__shfl_xor((int)fb, 32);
-                            FB[t] = fb & 0xFFFFu;
+                            FB[t] = FAST ? fb : (fb & 0xFFFFu);
                         }
                     }
                 }
@@ -276,7 +401,7 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
 
             // ---- per lane: the rows it owns (slot 16 q + r16 of set 0, slot 64 + 16 q + r16 of set 1) as masks
             // over all column slots, restricted to the pairs Alg. 4 tests
-            u32 Fw[NSET][NWD], Ew[NSET][NWD], Bw[NSET][NWD];
+            u32 Fw[NSET][NWD], Ew[NSET][NWD], Bw[NSET][NWD], Aw[NSET][NWD];
             bool valid[NSET];
             int mypos[NSET];
 #pragma unroll
@@ -291,7 +416,7 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
 #pragma unroll
                 for (int c = 0; c < NWD; ++c) {
                     // column groups 2c and 2c + 1
-                    u32 w = 0;
+                    u32 w = 0, wa = 0;
 #pragma unroll
                     for (int hh = 0; hh < 2; ++hh) {
                         const int Jc = 2 * c + hh;
@@ -302,14 +427,82 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
                             const u32 cand = Jc <= Ir ? FA[Ir * (Ir + 1) / 2 + Jc] : FB[Jc * (Jc + 1) / 2 + Ir];
                             w16 = (rg == Ir) ? cand : w16;
                         }
-                        w |= w16 << (16 * hh);
+                        w |= (w16 & 0xFFFFu) << (16 * hh);
+                        wa |= (w16 >> 16) << (16 * hh);
                     }
                     const u32 bnew = range_word(0, a, c), bold = range_word(n_new, n_new + b, c);
                     Bw[e][c] = bnew | bold;
                     Ew[e][c] = valid[e] ? (snew ? (bnew | bold) : bnew) : 0u;
-                    Fw[e][c] = w & Ew[e][c];
+                    Aw[e][c] = FAST ? (wa & Ew[e][c]) : 0u;
+                    Fw[e][c] = w & Ew[e][c] & ~Aw[e][c];
                 }
             }
+
+            // ---- single precision only: the undecided pairs get the exact delta(v,w)
+            bool defer = false;
+            if (FAST) {
+                int mine = 0;
+#pragma unroll
+                for (int e = 0; e < NSET; ++e)
+#pragma unroll
+                    for (int c = 0; c < NWD; ++c) mine += __popc(Aw[e][c]);
+                int incl = mine;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const int up = __shfl_up(incl, o);
+                    if (lane >= o) incl += up;
+                }
+                const int total = __shfl(incl, 63);
+                if (total > F32_AMB_CAP) {
+                    defer = true;
+                    if (lane == 0) redo[atomicAdd(n_redo, 1u)] = u;
+                } else if (total > 0) {
+                    wave_sync();
+                    int o = incl - mine;
+#pragma unroll
+                    for (int e = 0; e < NSET; ++e) {
+                        const int s = 16 * (4 * e + q) + r16;
+#pragma unroll
+                        for (int c = 0; c < NWD; ++c) {
+                            u32 bits = Aw[e][c];
+                            while (bits) {
+                                const int b = __builtin_ctz(bits);
+                                bits &= bits - 1u;
+                                sm.amb[o++] = (uint16_t)((s << 8) | (32 * c + b));
+                            }
+                        }
+                    }
+                    wave_sync();
+                    for (int base = 0; base < total; base += 8) {
+                        const int p = base + grp;
+                        const bool have = p < total;
+                        const u32 pair = sm.amb[have ? p : 0];
+                        const u32 sv0 = (pair >> 8) & 0x7Fu, sw0 = pair & 0xFFu;
+                        const u32 sv = sv0 < 16u * NRC ? sv0 : 0u, sw = sw0 < 16u * NRC ? sw0 : 0u;
+                        const int idv = (int)key_id(sm.key[sv]), idw = (int)key_id(sm.key[sw]);
+                        u32 db = 0;
+                        if (have) db = group8_dist_bits<DT_F32>(X + (size_t)idv * d, X + (size_t)idw * d, d, 1, sub);
+                        if (have && sub == 0) {
+                            const bool fails = __uint_as_float(key_dist(sm.key[sv])) >= __uint_as_float(db);
+                            sm.amb[p] = (uint16_t)(pair | (fails ? 0x8000u : 0u));
+                        }
+                    }
+                    wave_sync();
+                    o = incl - mine;
+#pragma unroll
+                    for (int e = 0; e < NSET; ++e)
+#pragma unroll
+                        for (int c = 0; c < NWD; ++c) {
+                            u32 bits = Aw[e][c];
+                            while (bits) {
+                                const int b = __builtin_ctz(bits);
+                                bits &= bits - 1u;
+                                if (sm.amb[o++] & 0x8000u) Fw[e][c] |= 1u << b;
+                            }
+                        }
+                }
+            }
+            if (!defer) {
 
             // ---- the loop over v: the kept set as the fixed point, all rows at once
             u32 Kw[3] = {0u, 0u, 0u};
@@ -410,6 +603,7 @@ __global__ __launch_bounds__(64 * 4, (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1)) void k_u
                 if (have) db = group8_dist_bits<DT_F32>(X + (size_t)idv * d, X + (size_t)idw * d, d, 1, sub);
                 if (have && sub == 0) emit_redirect(make_key(db, (u32)idv, 1u), (u32)idw, props + (size_t)u * R + p);
             }
+            }   // !defer
         }
         cur = nxt;
         nxt = aft;

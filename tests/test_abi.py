@@ -49,7 +49,7 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert call(T1=0) == -3 and call(T2=0) == -3 and call(N=5, S=5, R=8) == -3
     assert call(dtype=2) == -4 and call(metric=1) == -4
     assert call(N=50_000_000, R=128, S=4) == -2          # N*R does not fit the 32-bit slot counters
-    assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(2) == -3
+    assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(3) == -3
     assert lib.rnnd_set_kernel_variant(0) == 0
     # block-sequential entry points: same checks, plus the number of runs
     def blocks(**kw):
