@@ -21,9 +21,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 # HBM bytes per scan launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by
-# a plain 1 GiB copy in the same run); see profiles/update_scan_cfg3_hbm_traffic.txt.  Keyed by
-# (workload, kernel variant); None where it has not been measured.
-TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.022e9}
+# a plain 1 GiB copy in the same run); see profiles/update_scan_cfg3_hbm_traffic.txt and
+# profiles/update_scan_cfg5_hbm_traffic.txt.  Keyed by (workload, kernel variant); None where it has
+# not been measured.
+TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.022e9, ("cfg5", 3): 8.233e10}
 
 
 def cpu_baseline(cfg, X, sample_n):
@@ -103,7 +104,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--queries", type=int, default=10000, help="queries of the search-quality leg (at most the config's)")
-    ap.add_argument("--variant", type=int, default=0, help="UpdateNeighbors kernel: 0 auto, 1 generic, 2 MFMA")
+    ap.add_argument("--variant", type=int, default=0, help="UpdateNeighbors kernel: 0 auto, 1 generic, 2 auto with the float scan in double precision")
     ap.add_argument("--cpu-sample", type=int, default=0)
     ap.add_argument("--n", type=int, default=0, help="override the workload's N (same generator; scale checks)")
     ap.add_argument("--search-sweep", action="store_true",
@@ -177,17 +178,24 @@ def main():
     kname = {1: "k_update_scan",
              2: "k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8<NG,%d>, NG = 2,3 (one round's scan launches, "
                 "back to back)" % (cfg.d // 32, cfg.d // 32),
-             3: "k_update_scan_mfma_f32<NG,CH> (NG = 1,2,3 back to back per round)"}[kv]
+             3: "k_update_scan_mfma_f32<NG,CH,NRC,fast> (one launch per degree class, back to back per round; "
+                "fp32 MFMA Gram tiles, undecided pairs by exact distances)"}[kv]
     if kv == 3:
-        # float rows: the Gram tiles run on the f64 matrix cores and bound the kernel for large d;
+        # float rows: the Gram tiles run on the fp32 matrix cores (157.3 TFLOP/s dense), the rows are
+        # gathered from HBM; the kernel is reported against whichever of the two it sits closer to.
         # executed flops = computed pair distances * 2 d
         flops = sum(s["exec_evals"]) * 2.0 * cfg.d
-        achieved = flops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0
-        roof = {"bound": "mfma", "kernel": kname, "achieved": achieved, "peak": 78.6, "unit": "TFLOP/s",
-                "frac": achieved / 78.6, "traffic": None, "launches": rounds,
-                "avg_launch_ms": scan_ms / max(1, rounds), "flops_per_launch": flops / max(1, rounds),
-                "hbm_algorithmic_GBps": hbm_gbs, "hbm_frac": hbm_gbs / HBM_PEAK_GBS,
-                "algorithmic_bytes_per_launch": scan_bytes / max(1, rounds)}
+        tflops = flops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0
+        extra = {"launches": rounds, "avg_launch_ms": scan_ms / max(1, rounds),
+                 "flops_per_launch": flops / max(1, rounds), "mfma_fp32_TFLOPs": tflops,
+                 "mfma_fp32_frac": tflops / 157.3, "hbm_algorithmic_GBps": hbm_gbs,
+                 "hbm_frac": hbm_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": scan_bytes / max(1, rounds)}
+        if hbm_gbs / HBM_PEAK_GBS >= tflops / 157.3:
+            roof = dict({"bound": "hbm", "kernel": kname, "achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC_PER_LAUNCH.get((cfg.name, kv))}, **extra)
+        else:
+            roof = dict({"bound": "mfma", "kernel": kname, "achieved": tflops, "peak": 157.3, "unit": "TFLOP/s",
+                         "frac": tflops / 157.3, "traffic": None}, **extra)
     else:
         roof = {"bound": "hbm", "kernel": kname, "achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC_PER_LAUNCH.get((cfg.name, kv)),
@@ -203,7 +211,8 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8" if cfg.dtype == "u8" else "f32",
         "arithmetic": ("uint8 rows, int8 MFMA Gram tiles, exact int32 distances" if cfg.dtype == "u8" else
-                       "float32 rows, f64 MFMA Gram tiles / f64 accumulation, distances rounded once to float32"),
+                       "float32 rows; decisions from fp32 MFMA Gram tiles with an error bound, exact f64-accumulated distances "
+                       "for undecided pairs and for every stored distance (rounded once to float32)"),
         "data": "synthetic",
         "config": {"workload": "%s: N=%d d=%d %s, S=%d R=%d T1=%d T2=%d, seeded %s mixture"
                                % (cfg.name, cfg.N, cfg.d, cfg.dtype, cfg.S, cfg.R, cfg.T1, cfg.T2, cfg.kind),

@@ -23,7 +23,9 @@ __device__ __forceinline__ int sqdiff_word_u8(uint32_t a, uint32_t b, int acc)
     return acc + (int)(aa + bb - 2u * ab);
 }
 
-template <int DT>
+// UF (float rows): 16-byte chunks per lane whose loads are issued together before the (ordered)
+// accumulation; it changes how many loads are in flight, never the order of the arithmetic.
+template <int DT, int UF = 4>
 __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void *pb, int d,
                                                      int vec_ok, int sub)
 {
@@ -56,13 +58,13 @@ __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void 
             const int nchunk = d >> 2;
             const float4 *pa4 = (const float4 *)a, *pb4 = (const float4 *)b;
             int c = sub;
-            // four chunks per trip, all eight loads issued before the (ordered) accumulation
-            for (; c + 24 < nchunk; c += 32) {
-                float4 va[4], vb[4];
+            // UF chunks per trip, all 2 UF loads issued before the (ordered) accumulation
+            for (; c + 8 * (UF - 1) < nchunk; c += 8 * UF) {
+                float4 va[UF], vb[UF];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) { va[k] = pa4[c + 8 * k]; vb[k] = pb4[c + 8 * k]; }
+                for (int k = 0; k < UF; ++k) { va[k] = pa4[c + 8 * k]; vb[k] = pb4[c + 8 * k]; }
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
+                for (int k = 0; k < UF; ++k) {
                     double t;
                     t = (double)va[k].x - (double)vb[k].x; acc = fma(t, t, acc);
                     t = (double)va[k].y - (double)vb[k].y; acc = fma(t, t, acc);

@@ -600,7 +600,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                 const u32 sw = sw0 < 16u * NRC ? sw0 : 0u;     // a pruned row always has a target
                 const int idv = (int)key_id(sm.key[sv]), idw = (int)key_id(sm.key[sw]);
                 u32 db = 0;
-                if (have) db = group8_dist_bits<DT_F32>(X + (size_t)idv * d, X + (size_t)idw * d, d, 1, sub);
+                if (have) db = group8_dist_bits<DT_F32, (NRC <= 2 ? 6 : 8)>(X + (size_t)idv * d, X + (size_t)idw * d, d, 1, sub);
                 if (have && sub == 0) emit_redirect(make_key(db, (u32)idv, 1u), (u32)idw, props + (size_t)u * R + p);
             }
             }   // !defer
