@@ -25,12 +25,21 @@ def rn():
     return m
 
 
-@pytest.fixture(params=[0, 1], ids=["auto", "generic"])
+@pytest.fixture(params=[0, 1, 2], ids=["auto", "generic", "f64"])
 def variant(request, rn):
-    """0 = automatic choice (matrix-core Gram kernels where they apply), 1 = generic kernel."""
+    """0 = automatic choice (matrix-core Gram kernels where they apply), 1 = generic kernel, 2 = automatic
+    with the float matrix-core scan in double precision throughout (no single-precision first pass)."""
     rn.rnnd_set_kernel_variant(request.param)
     yield request.param
     rn.rnnd_set_kernel_variant(0)
+
+
+def skip_if_nothing_new(variant, X):
+    """Variants 1 and 2 only differ from the automatic choice where a matrix-core kernel applies."""
+    if variant == 1 and not mfma_applies(X):
+        pytest.skip("automatic choice already is the generic kernel")
+    if variant == 2 and mfma_applies(X) != 3:
+        pytest.skip("the double-precision form only exists for the float matrix-core scan")
 
 
 def mfma_applies(X):
@@ -68,6 +77,9 @@ DATASETS = {
     "f32_d32_dense": lambda: (clustered_u8(900, 32, 13, k=3, spread=9).astype(np.float32) / 7.0),   # long lists, ties
     "f32_d960": lambda: wl.custom("beta_f32", 1200, 960, 11),
     "f32_d7": lambda: gauss_f32(1000, 7, 5),
+    # quarter-integer lattice: exact ties in bulk, far more undecided pairs per vertex than the
+    # single-precision pass resolves itself, so its vertices go through the double-precision second pass
+    "f32_d16_lattice": lambda: (np.random.default_rng(17).integers(-2, 3, size=(2000, 16)) * 0.25).astype(np.float32),
 }
 
 
@@ -84,12 +96,12 @@ def test_random_graph(rn, oracle_mod, name, S, R):
 @pytest.mark.parametrize("name,S,R", [("cfg1", 10, 32), ("u8_d128", 20, 96), ("u8_d33_ties", 6, 16),
                                       ("u8_dups", 8, 12), ("f32_d96", 20, 96), ("f32_d960", 8, 24),
                                       ("f32_d7", 100, 128), ("u8_d64_dense", 100, 128), ("u8_d128", 70, 70),
-                                      ("f32_d32_dense", 90, 96), ("f32_d32_dense", 100, 128)])
+                                      ("f32_d32_dense", 90, 96), ("f32_d32_dense", 100, 128),
+                                      ("f32_d16_lattice", 60, 96)])
 def test_rounds_from_shared_snapshots(rn, oracle_mod, variant, name, S, R):
     """Every step starts from the oracle's snapshot, so one divergence cannot hide the next."""
     X = DATASETS[name]()
-    if variant == 1 and not mfma_applies(X):
-        pytest.skip("automatic choice already is the generic kernel")
+    skip_if_nothing_new(variant, X)
     isf = X.dtype == np.float32
     Xd = cuda(X)
     snap = oracle_mod.random_graph(X, S, 99, R)
@@ -98,7 +110,7 @@ def test_rounds_from_shared_snapshots(rn, oracle_mod, variant, name, S, R):
         if step == "u":
             snap, evals, props = oracle_mod.update_neighbors_sync(X, snap, R)
             st = rn.rnnd_update_neighbors(Xd, keys, deg, R, 1)
-            assert st.kernel_variant == (mfma_applies(X) if variant == 0 and mfma_applies(X) else 1)
+            assert st.kernel_variant == (mfma_applies(X) if variant != 1 and mfma_applies(X) else 1)
             assert st.algo_evals[0] == evals and st.proposals[0] == props
         else:
             snap = oracle_mod.add_reverse_edges(snap, R)
@@ -110,11 +122,10 @@ def test_rounds_from_shared_snapshots(rn, oracle_mod, variant, name, S, R):
     ("cfg1", 10, 32, 2, 4), ("u8_d128", 20, 96, 3, 5), ("u8_d33_ties", 6, 16, 3, 4),
     ("u8_dups", 8, 12, 3, 4), ("u8_d64_dense", 40, 128, 3, 4), ("u8_d128", 60, 64, 2, 3),
     ("f32_d96", 20, 96, 3, 5), ("f32_d960", 8, 24, 2, 4), ("f32_d7", 16, 128, 2, 6),
-    ("f32_d32_dense", 40, 96, 3, 4), ("f32_d32_dense", 40, 128, 2, 3)])
+    ("f32_d32_dense", 40, 96, 3, 4), ("f32_d32_dense", 40, 128, 2, 3), ("f32_d16_lattice", 30, 96, 2, 3)])
 def test_full_build(rn, oracle_mod, variant, name, S, R, T1, T2):
     X = DATASETS[name]()
-    if variant == 1 and not mfma_applies(X):
-        pytest.skip("automatic choice already is the generic kernel")
+    skip_if_nothing_new(variant, X)
     isf = X.dtype == np.float32
     want = oracle_mod.build_sync(X, S, R, T1, T2, wl.BUILD_SEED)
     graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), S, R, T1, T2, wl.BUILD_SEED)
@@ -151,6 +162,8 @@ def test_hub_vertex_streams_through_the_merge(rn, oracle_mod, variant):
     """A star: vertex 0 sits at the centre of everything, so hundreds of edges are redirected to
     it in one round and hundreds of reverse edges enter it (the > 128-key path of the merge and
     the in-degree cap of Alg. 5)."""
+    if variant == 2:
+        pytest.skip("uint8 data: variant 2 is the automatic choice")
     g = np.random.default_rng(8)
     n, d, R = 2500, 32, 16
     X = np.clip(128 + g.normal(0, 40, size=(n, d)), 0, 255).astype(np.uint8)
@@ -178,6 +191,8 @@ def test_hub_vertex_streams_through_the_merge(rn, oracle_mod, variant):
 
 
 def test_tiny_and_degenerate_inputs(rn, oracle_mod, variant):
+    if variant == 2:
+        pytest.skip("uint8 data: variant 2 is the automatic choice")
     # N = 2: the only possible graph
     X = np.array([[0, 0], [3, 4]], np.uint8)
     g, d = rn.rnnd_build(cuda(X), 1, 1, 2, 2, 0)
@@ -220,6 +235,8 @@ def test_argument_errors_on_device(rn):
 
 def test_cfg2_full_parity(rn, oracle_mod, variant):
     """Workload cfg2 (N = 100,000, d = 128 uint8, paper parameters): ~20 s of oracle."""
+    if variant == 2:
+        pytest.skip("uint8 data: variant 2 is the automatic choice")
     c = wl.CONFIGS["cfg2"]
     X = wl.make_data(c)
     want = oracle_mod.build_sync(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
