@@ -1090,9 +1090,10 @@ static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *
     if (R > 96) launch_mfma_scan<4, KS>(w, R, keys, deg, N, c, st, n_big == 3 ? re.scan_stop : nullptr);
 }
 
-// Float scan of degree class cls: the single-precision form over the class's active list, then the
-// double-precision form over the (normally empty) list of vertices the first one left alone.  The redo
-// lists live in the bin array, which nothing else uses until the scatter that follows the scans.
+// Float scan of degree class cls: the single-precision form over the class's active list.  Vertices it
+// leaves alone (ties in bulk) go to one redo list for all classes, which launch_f32_redo hands to the
+// double-precision form.  The redo list lives in the bin array, which nothing else uses until the
+// scatter that follows the scans.  Kernel variant 2: the double-precision form on the active list itself.
 template <int NG, int CH, int NRC>
 static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, long long N,
                             RoundCtr *c, int cls, hipStream_t st, hipEvent_t e_start, hipEvent_t e_stop)
@@ -1100,18 +1101,24 @@ static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64
     // wavefronts that fit per SIMD: about 4 for NG = 1, 2 for NG = 2, 1 for NG = 3 (21 accumulator tiles)
     static const int per_cu_fast = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, true>, NG == 1 ? 4 : 2);
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, false>, NG == 1 ? 4 : NG == 2 ? 2 : 1);
-    int *redo = (int *)w.bins + (size_t)cls * N;
     if (g_kernel_variant != 2)
         hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, true>), dim3(cu_count() * per_cu_fast), dim3(256), 0, st,
-                              e_start, nullptr, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
-                              &c->n_active[cls], w.props, w.nprop, c, redo, &c->n_redo[cls]);
+                              e_start, e_stop, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
+                              &c->n_active[cls], w.props, w.nprop, c, (int *)w.bins, &c->n_redo[0]);
     else
         hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, false>), dim3(cu_count() * per_cu), dim3(256), 0, st,
-                              e_start, nullptr, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
+                              e_start, e_stop, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
                               &c->n_active[cls], w.props, w.nprop, c, (int *)nullptr, (u32 *)nullptr);
-    hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, false>), dim3(cu_count() * per_cu), dim3(256), 0, st,
-                          nullptr, e_stop, 0, (const float *)X, d, R, keys, deg, (const int *)redo,
-                          (const u32 *)&c->n_redo[cls], w.props, w.nprop, c, (int *)nullptr, (u32 *)nullptr);
+}
+
+// The double-precision form (in its widest shape: lists of up to 96 entries) over the round's redo list.
+static void launch_f32_redo(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, RoundCtr *c,
+                            hipStream_t st, hipEvent_t e_stop)
+{
+    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<3, 1, 6, false>, 1);
+    hipExtLaunchKernelGGL((k_update_scan_mfma_f32<3, 1, 6, false>), dim3(cu_count() * per_cu), dim3(256), 0, st, nullptr,
+                          e_stop, 0, (const float *)X, d, R, keys, deg, (const int *)w.bins,
+                          (const u32 *)&c->n_redo[0], w.props, w.nprop, c, (int *)nullptr, (u32 *)nullptr);
 }
 
 // One run of consecutive vertex ids of a block-sequential pass: ids first .. first + count - 1.
@@ -1144,8 +1151,13 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
         // degree classes 0..6: lists of at most 8, 16, 32, 48, 64, 80, 96 entries = 1, 1, 2, 3, 4, 5, 6 groups of 16
         // rows; class 7 (97..128 entries: too many accumulator tiles) goes to the generic kernel
         const int n_more = (R > 8) + (R > 16) + (R > 32) + (R > 48) + (R > 64) + (R > 80) + (R > 96);
+        // the round's scan ends with its last launch: the redo pass, or the generic kernel when R > 96
+        const bool redo_pass = g_kernel_variant != 2, generic_tail = R > 96;
         int k = 0;
-        auto stop_for = [&](void) { return k++ == n_more ? re.scan_stop : (hipEvent_t) nullptr; };
+        auto stop_for = [&](void) {
+            const bool last = k++ == n_more;
+            return (last && (generic_tail || !redo_pass)) ? re.scan_stop : (hipEvent_t) nullptr;
+        };
         if (d % 32 == 0) launch_f32_scan<1, 2, 1>(w, X, d, R, keys, deg, N, c, 0, st, re.scan_start, stop_for());
         else launch_f32_scan<1, 1, 1>(w, X, d, R, keys, deg, N, c, 0, st, re.scan_start, stop_for());
         if (R > 8) {
@@ -1160,6 +1172,7 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
         if (R > 48) launch_f32_scan<2, 1, 4>(w, X, d, R, keys, deg, N, c, 4, st, nullptr, stop_for());
         if (R > 64) launch_f32_scan<3, 1, 5>(w, X, d, R, keys, deg, N, c, 5, st, nullptr, stop_for());
         if (R > 80) launch_f32_scan<3, 1, 6>(w, X, d, R, keys, deg, N, c, 6, st, nullptr, stop_for());
+        if (redo_pass) launch_f32_redo(w, X, d, R, keys, deg, c, st, generic_tail ? (hipEvent_t) nullptr : re.scan_stop);
         if (R > 96)
             hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, nullptr, stop_for(), 0, X, d,
                                   vec_ok, R, keys, deg, w.lists + (size_t)7 * N, &c->n_active[7], w.props, w.nprop, c);
