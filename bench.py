@@ -201,6 +201,10 @@ def main():
                 "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC_PER_LAUNCH.get((cfg.name, kv)),
                 "launches": rounds, "avg_launch_ms": scan_ms / max(1, rounds),
                 "algorithmic_bytes_per_launch": scan_bytes / max(1, rounds)}
+    # what a kernel that only gathers random whole rows of X reaches on this GPU (same access pattern)
+    ceiling = rn.rnnd_probe_gather(Xd, max(1, int(8e9 // (cfg.d * esz))))
+    roof["gather_ceiling_GBps"] = ceiling
+    roof["frac_of_gather_ceiling"] = (hbm_gbs / ceiling) if ceiling > 0 else None
     if args.blocks:      # the scan launches of a run are not timed one by one
         roof = dict(roof, achieved=None, frac=None, avg_launch_ms=None, traffic=None,
                     note="per-launch scan times are measured for the synchronous build only")

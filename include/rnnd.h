@@ -165,6 +165,17 @@ int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int metric, cons
                 int32_t K, int32_t k, uint64_t seed, int32_t *out_ids, uint32_t *out_dist_bits,
                 int64_t *dist_evals, void *stream);
 
+/* Measurement aid, not a step of the method: the rate at which this GPU delivers random whole rows
+ * when a kernel does nothing but gather them with the scan kernels' access pattern (16 bytes per
+ * lane, up to 8 lanes per row, row numbers from the counter generator), i.e. the ceiling that the
+ * gather-bound UpdateNeighbors scan is compared with besides the HBM peak.
+ *   X           device, n_rows rows of row_bytes bytes (a multiple of 16, at most 1 MiB), 16-byte aligned
+ *   n_gather    rows to read in the timed pass (rounded up to a whole number of wavefront trips)
+ *   gbytes_per_s  host: rows read x row_bytes / time of the second of two passes, in GB/s
+ * Returns after the work has completed; allocates and frees a few MB of device memory. */
+int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t n_gather, uint64_t seed,
+                      double *gbytes_per_s, void *stream);
+
 /* Selects the UpdateNeighbors scan kernel: 0 = automatic (default), 1 = generic pair-at-a-time
  * kernel for every input, 2 = automatic, but the float32 matrix-core scan works in double precision
  * throughout.  Automatic uses the dense Gram-block kernels on the matrix cores where they apply

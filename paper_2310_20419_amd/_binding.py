@@ -96,13 +96,15 @@ def load_library():
         L.rnnd_export_graph.argtypes = [i64, i32, vp, vp, vp, vp, vp]
         L.rnnd_search.argtypes = [vp, i64, i32, c.c_int, c.c_int, vp, vp, i32, vp, i64, i32, i32, i32, c.c_uint64,
                                   vp, vp, c.POINTER(c.c_int64), vp]
+        L.rnnd_probe_gather.argtypes = [vp, i64, i64, i64, u64, c.POINTER(c.c_double), vp]
         L.rnnd_set_kernel_variant.argtypes = [c.c_int]
         L.rnnd_strerror.argtypes = [c.c_int]
         L.rnnd_strerror.restype = c.c_char_p
         L.rnnd_version.restype = c.c_int
         for name in ("rnnd_build", "rnnd_build_ex", "rnnd_workspace_bytes", "rnnd_random_graph",
                      "rnnd_update_neighbors", "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search",
-                     "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks"):
+                     "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks",
+                     "rnnd_probe_gather"):
             getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -223,6 +225,15 @@ def rnnd_update_neighbors_blocks(X, keys, deg, R: int, blocks: int, n_passes: in
     _check(load_library().rnnd_update_neighbors_blocks(ptr, N, d, dt, metric, R, keys.data_ptr(), deg.data_ptr(),
                                                        n_passes, blocks, ctypes.byref(st), _stream(stream)))
     return st
+
+
+def rnnd_probe_gather(X, n_gather: int, seed: int = 1, stream=None) -> float:
+    """GB/s of random whole-row gathers from X (measurement aid)."""
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2
+    out = ctypes.c_double(0.0)
+    _check(load_library().rnnd_probe_gather(X.data_ptr(), X.shape[0], X.shape[1] * X.element_size(), n_gather, seed,
+                                            ctypes.byref(out), _stream(stream)))
+    return out.value
 
 
 def rnnd_add_reverse_edges(keys, deg, R: int, stream=None):

@@ -913,6 +913,36 @@ __global__ void k_export(long long N, int R, const u64 *keys, const int *deg, in
     if (e == 0) degree_out[u] = m;
 }
 
+// Measurement aid: random row gathers and nothing else.  Every wavefront draws row numbers from the
+// counter generator and reads whole rows, LPR lanes per row with 16 bytes per lane and piece, four
+// rows' worth of loads per lane in flight; the values are folded into one word per thread so that
+// the loads cannot be dropped.  This is the access pattern of the scan kernels without their work.
+template <int LPR>
+__global__ __launch_bounds__(256) void k_probe_gather(const uint4 *X, u32 n_rows, u32 pieces, u64 trips, u64 seed, u32 *sink)
+{
+    constexpr int RPI = 64 / LPR;       // rows per load instruction
+    const int lane = threadIdx.x & 63, r = lane / LPR, q = lane % LPR;
+    const u64 gw = ((u64)blockIdx.x * 256 + threadIdx.x) >> 6, nw = ((u64)gridDim.x * 256) >> 6;
+    u32 acc = 0;
+    for (u64 t = gw; t < trips; t += nw) {
+        const uint4 *p[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const u64 z = splitmix_finish(seed + 0x9E3779B97F4A7C15ull * (t * (4 * RPI) + (u64)(k * RPI + r) + 1));
+            const u32 row = (u32)(((z >> 32) * (u64)n_rows) >> 32);
+            p[k] = X + (size_t)row * pieces + q;
+        }
+        for (u32 c = 0; c < pieces; c += LPR) {
+            uint4 v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = p[k][c];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc ^= v[k].x + v[k].y + v[k].z + v[k].w;
+        }
+    }
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc;
+}
+
 // ===================================================================== host side
 #define HIPCHK(x)                                                                  \
     do {                                                                           \
@@ -1723,6 +1753,54 @@ done:
     return rc;
 }
 
+template <int LPR>
+static void launch_probe_gather(const void *X, u32 n_rows, u32 pieces, u64 trips, u64 seed, u32 *sink, int blocks,
+                                hipStream_t st)
+{
+    hipLaunchKernelGGL(k_probe_gather<LPR>, dim3(blocks), dim3(256), 0, st, (const uint4 *)X, n_rows, pieces, trips,
+                       seed, sink);
+}
+
+extern "C" int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t n_gather, uint64_t seed,
+                                 double *gbytes_per_s, void *stream)
+{
+    int rc = RNND_OK;
+    if (!X || !gbytes_per_s) return RNND_ERR_NULL;
+    if (n_rows < 1 || n_rows > 2147483646LL || n_gather < 1) return RNND_ERR_BAD_SHAPE;
+    if (row_bytes < 16 || row_bytes % 16 != 0 || row_bytes > (1 << 20) || ((uintptr_t)X & 15) != 0)
+        return RNND_ERR_BAD_PARAM;
+    hipStream_t st = (hipStream_t)stream;
+    const u32 pieces = (u32)(row_bytes / 16);
+    // lanes per row: the largest power of two that divides the number of 16-byte pieces, at most 8
+    const int lpr = pieces % 8 == 0 ? 8 : pieces % 4 == 0 ? 4 : pieces % 2 == 0 ? 2 : 1;
+    const int rows_per_trip = 4 * (64 / lpr);
+    const u64 trips = ((u64)n_gather + rows_per_trip - 1) / rows_per_trip;
+    const int blocks = persistent_blocks();
+    u32 *sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    float ms = 0;
+    HIPCHK(hipMalloc((void **)&sink, (size_t)blocks * 256 * 4));
+    HIPCHK(hipEventCreate(&e0));
+    HIPCHK(hipEventCreate(&e1));
+    for (int rep = 0; rep < 2; ++rep) {     // the second pass is the one that is timed
+        HIPCHK(hipEventRecord(e0, st));
+        if (lpr == 8) launch_probe_gather<8>(X, (u32)n_rows, pieces, trips, seed + rep, sink, blocks, st);
+        else if (lpr == 4) launch_probe_gather<4>(X, (u32)n_rows, pieces, trips, seed + rep, sink, blocks, st);
+        else if (lpr == 2) launch_probe_gather<2>(X, (u32)n_rows, pieces, trips, seed + rep, sink, blocks, st);
+        else launch_probe_gather<1>(X, (u32)n_rows, pieces, trips, seed + rep, sink, blocks, st);
+        HIPCHK(hipGetLastError());
+        HIPCHK(hipEventRecord(e1, st));
+        HIPCHK(hipStreamSynchronize(st));
+    }
+    HIPCHK(hipEventElapsedTime(&ms, e0, e1));
+    *gbytes_per_s = ms > 0 ? (double)trips * rows_per_trip * (double)row_bytes / (ms * 1e-3) / 1e9 : 0.0;
+done:
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (sink) (void)hipFree(sink);
+    return rc;
+}
+
 // 0: automatic; 1: generic scan for every input; 2: automatic, but the float matrix-core scan runs in
 // double precision only (no single-precision first pass)
 extern "C" int rnnd_set_kernel_variant(int variant)
@@ -1746,4 +1824,4 @@ extern "C" const char *rnnd_strerror(int status)
     }
 }
 
-extern "C" int rnnd_version(void) { return 103; }
+extern "C" int rnnd_version(void) { return 104; }

@@ -21,7 +21,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"rnnd_build", "rnnd_build_ex", "rnnd_random_graph", "rnnd_update_neighbors",
             "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search", "rnnd_workspace_bytes",
             "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant", "rnnd_build_blocks",
-            "rnnd_update_neighbors_blocks"} <= set(names)
+            "rnnd_update_neighbors_blocks", "rnnd_probe_gather"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -62,6 +62,14 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, one, one, 1, 0, None, None) == -3
     assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, None, one, 1, 4, None, None) == -1
     assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, one, one, 0, 4, None, None) == -3
+    # the gather probe
+    import ctypes as c
+    out = c.c_double(0)
+    assert lib.rnnd_probe_gather(None, 10, 128, 100, 1, c.byref(out), None) == -1
+    assert lib.rnnd_probe_gather(one, 10, 128, 100, 1, None, None) == -1
+    assert lib.rnnd_probe_gather(c.c_void_p(16), 0, 128, 100, 1, c.byref(out), None) == -2
+    assert lib.rnnd_probe_gather(c.c_void_p(16), 10, 100, 100, 1, c.byref(out), None) == -3      # not a multiple of 16
+    assert lib.rnnd_probe_gather(c.c_void_p(8), 10, 128, 100, 1, c.byref(out), None) == -3       # misaligned
     # rnnd_search: parameters are checked before pointers, pointers before any GPU call
     def search(**kw):
         a = dict(dict(X=one, N=100, d=16, dtype=0, metric=0, g=one, dg=one, W=8, Q=one, nq=3, L=16, K=8, k=5,

@@ -364,3 +364,14 @@ def test_cfg5_full_size_sampled_parity(rn, oracle_mod):
         assert (bits[u, :m].view(np.float32) == ref).all()
         key = list(zip(bits[u, :m].tolist(), row.tolist()))
         assert key == sorted(key)
+
+
+def test_gather_probe_reports_a_plausible_rate(rn):
+    """The measurement aid behind the 'gather ceiling' of the benchmark line: it must run on rows of any
+    multiple of 16 bytes and report something between a trickle and the HBM peak times the cache effect."""
+    import torch
+    for rows, width, dtype in ((200_000, 128, torch.uint8), (50_000, 96, torch.float32), (3_000, 48, torch.uint8),
+                               (1, 16, torch.uint8)):
+        X = torch.zeros((rows, width), dtype=dtype, device="cuda")
+        rate = rn.rnnd_probe_gather(X, 2_000_000)
+        assert 1.0 < rate < 100_000.0, (rows, width, rate)
