@@ -42,7 +42,7 @@ extern "C" {
 #define RNND_MAX_R 128          /* largest supported degree cap R */
 #define RNND_MAX_ROUNDS 256     /* per-round statistics are kept for the first 256 rounds */
 
-typedef enum { RNND_U8 = 0, RNND_F32 = 1 } rnnd_dtype;
+typedef enum { RNND_U8 = 0, RNND_F32 = 1, RNND_F16 = 2 } rnnd_dtype;
 typedef enum { RNND_L2SQ = 0 } rnnd_metric;
 
 typedef enum {

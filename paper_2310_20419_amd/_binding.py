@@ -5,7 +5,7 @@ import ctypes
 import os
 import re
 
-RNND_U8, RNND_F32 = 0, 1
+RNND_U8, RNND_F32, RNND_F16 = 0, 1, 2
 RNND_L2SQ = 0
 RNND_MAX_R = 128
 RNND_MAX_ROUNDS = 256
@@ -136,8 +136,10 @@ def _data_args(X):
         dt = RNND_U8
     elif X.dtype == torch.float32:
         dt = RNND_F32
+    elif X.dtype == torch.float16:
+        dt = RNND_F16
     else:
-        raise ValueError("X must be uint8 or float32")
+        raise ValueError("X must be uint8, float32 or float16")
     return X.data_ptr(), X.shape[0], X.shape[1], dt
 
 

@@ -104,7 +104,7 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
     if (u >= N) return;
     int *ids = s_ids[wave];
-    const size_t rowbytes = (size_t)d * (DT == DT_U8 ? 1 : 4);
+    const size_t rowbytes = (size_t)d * dt_size(DT);
     wave_random_ids(seed, N, u, S, ids, lane);
     // delta(u, id): 8 rows at a time, 8 lanes per row
     const char *xu = (const char *)X + (size_t)u * rowbytes;
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, sub = lane & 7, grp = lane >> 3;
     const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
     const u32 n_active = *n_list;
-    const size_t rowbytes = (size_t)d * (DT == DT_U8 ? 1 : 4);
+    const size_t rowbytes = (size_t)d * dt_size(DT);
     u64 *sk = s_key[wave];
     u64 evals_algo = 0, evals_exec = 0, rows = 0, nprops_total = 0;
     for (u32 it = gw; it < n_active; it += nw) {
@@ -1020,7 +1020,7 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
 static int check_data_args(const void *X, long long N, int d, int dtype, int metric, int R)
 {
     if (!X) return RNND_ERR_NULL;
-    if (dtype != RNND_U8 && dtype != RNND_F32) return RNND_ERR_UNSUPPORTED;
+    if (dtype != RNND_U8 && dtype != RNND_F32 && dtype != RNND_F16) return RNND_ERR_UNSUPPORTED;
     if (metric != RNND_L2SQ) return RNND_ERR_UNSUPPORTED;
     if (N < 2 || N > 2147483646LL || d < 1) return RNND_ERR_BAD_SHAPE;
     if (dtype == RNND_U8 && d > 33025) return RNND_ERR_BAD_SHAPE;
@@ -1032,7 +1032,7 @@ static int check_data_args(const void *X, long long N, int d, int dtype, int met
 
 static int vec_ok_for(const void *X, int d, int dtype)
 {
-    size_t rowbytes = (size_t)d * (dtype == RNND_U8 ? 1 : 4);
+    size_t rowbytes = (size_t)d * dt_size(dtype);
     return (rowbytes % 16 == 0) && (((uintptr_t)X) % 16 == 0);
 }
 
@@ -1209,6 +1209,9 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
     } else if (dtype == RNND_U8) {
         hipExtLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
                               vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);
+    } else if (dtype == RNND_F16) {
+        hipExtLaunchKernelGGL(k_update_scan<DT_F16>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
+                              vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);
     } else {
         hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
                               vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);
@@ -1326,7 +1329,7 @@ static void fill_round_stats(rnnd_stats *s, const RoundCtr *h, int rounds)
 extern "C" int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, size_t *bytes)
 {
     if (!bytes) return RNND_ERR_NULL;
-    if (dtype != RNND_U8 && dtype != RNND_F32) return RNND_ERR_UNSUPPORTED;
+    if (dtype != RNND_U8 && dtype != RNND_F32 && dtype != RNND_F16) return RNND_ERR_UNSUPPORTED;
     if (N < 2 || N > 2147483646LL || d < 1) return RNND_ERR_BAD_SHAPE;
     if (R < 1 || R > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
     Workspace w;
@@ -1373,6 +1376,9 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
         if (variant == 2) launch_prepare_u8(w, X, N, d, st);
         if (dtype == RNND_U8)
             hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
+                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+        else if (dtype == RNND_F16)
+            hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
                                vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
         else
             hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
@@ -1504,6 +1510,9 @@ extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype,
         if (dtype == RNND_U8)
             hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
                                vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+        else if (dtype == RNND_F16)
+            hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
+                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
         else
             hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
                                vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
@@ -1572,6 +1581,9 @@ extern "C" int rnnd_random_graph(const void *X, int64_t N, int32_t d, int dtype,
     const int vec_ok = vec_ok_for(X, d, dtype);
     if (dtype == RNND_U8)
         hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
+                           S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
+    else if (dtype == RNND_F16)
+        hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
                            S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
     else
         hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
@@ -1715,7 +1727,7 @@ extern "C" int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int m
     hipStream_t st = (hipStream_t)stream;
     if (dist_evals) *dist_evals = 0;
     if (nq == 0) return RNND_OK;
-    const size_t rowbytes = (size_t)d * (dtype == RNND_U8 ? 1 : 4);
+    const size_t rowbytes = (size_t)d * dt_size(dtype);
     const int vec_ok = (rowbytes % 16 == 0) && (((uintptr_t)X) % 16 == 0) && (((uintptr_t)Q) % 16 == 0);
     // one bitmap of N bits per wavefront in flight; at most 1 GiB of them, at most 8 wavefronts per SIMD
     const size_t bitmap_words = (((size_t)N + 31) / 32 + 63) / 64 * 64;
@@ -1739,6 +1751,8 @@ extern "C" int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int m
                        out_ids, out_dist_bits, d_evals)
         if (dtype == RNND_U8) {
             if (L <= 64) RNND_SEARCH_LAUNCH(DT_U8, 1); else RNND_SEARCH_LAUNCH(DT_U8, 2);
+        } else if (dtype == RNND_F16) {
+            if (L <= 64) RNND_SEARCH_LAUNCH(DT_F16, 1); else RNND_SEARCH_LAUNCH(DT_F16, 2);
         } else {
             if (L <= 64) RNND_SEARCH_LAUNCH(DT_F32, 1); else RNND_SEARCH_LAUNCH(DT_F32, 2);
         }

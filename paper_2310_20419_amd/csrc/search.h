@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void k_search(const void *X, long long N, int 
     const long long gw = (long long)blockIdx.x * 4 + wave, nw = (long long)gridDim.x * 4;
     SearchSmem &sm = smem[wave];
     u32 *seen = bitmaps + (size_t)gw * bitmap_words;   // cleared by this wavefront before every query
-    const size_t rowbytes = (size_t)d * (DT == DT_U8 ? 1 : 4);
+    const size_t rowbytes = (size_t)d * dt_size(DT);
     const int L0 = (long long)L < N ? L : (int)N;
     // uint8 rows of at most 128 bytes, readable 16 bytes at a time: one load per lane and vertex
     const bool short_rows = DT == DT_U8 && vec_ok && d <= 128;
