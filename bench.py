@@ -32,6 +32,8 @@ def cpu_baseline(cfg, X, sample_n):
     import oracle
     oracle.build()
     Xs = X[:sample_n].copy()
+    if Xs.dtype.itemsize == 2:      # half-precision storage: the oracle works on the floats the halves stand for
+        Xs = Xs.astype("float32")
     t0 = time.perf_counter()
     res = oracle.build_sync(Xs, cfg.S, cfg.R, cfg.T1, cfg.T2, 2310)
     dt = time.perf_counter() - t0
@@ -73,7 +75,7 @@ def search_quality(cfg, rn, Xd, graph, degree, nq, L=64, K=32, sweep=False):
     import torch
     import workloads as wl
     Q = wl.make_queries(cfg, nq)
-    Qd = torch.from_numpy(Q).cuda()
+    Qd = torch.from_numpy(Q).cuda().to(Xd.dtype).contiguous()
     truth = exact_top10(Xd, Qd)
 
     def one(L, K):
@@ -107,6 +109,9 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="UpdateNeighbors kernel: 0 auto, 1 generic, 2 auto with the float scan in double precision")
     ap.add_argument("--cpu-sample", type=int, default=0)
     ap.add_argument("--n", type=int, default=0, help="override the workload's N (same generator; scale checks)")
+    ap.add_argument("--storage", choices=["native", "f16"], default="native",
+                    help="f16: float workloads are stored as IEEE half precision (RNND_F16); the graph is the one "
+                         "of the rounded data")
     ap.add_argument("--search-sweep", action="store_true",
                     help="search-quality leg over L in {16,32,64,128} x K in {16,...,96, no cap} (Sec. 5.2)")
     ap.add_argument("--blocks", type=int, default=0,
@@ -135,8 +140,11 @@ def main():
     t0 = time.perf_counter()
     X = wl.make_data(cfg)
     gen_s = time.perf_counter() - t0
+    half = args.storage == "f16" and cfg.dtype != "u8"
+    if half:
+        X = X.astype(np.float16)
     Xd = torch.from_numpy(X).cuda()
-    esz = 1 if cfg.dtype == "u8" else 4
+    esz = 1 if cfg.dtype == "u8" else 2 if half else 4
     torch.cuda.synchronize()
 
     if args.copy_calibration:
@@ -214,6 +222,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8" if cfg.dtype == "u8" else "f32",
+        "storage": "f16" if half else cfg.dtype,
         "arithmetic": ("uint8 rows, int8 MFMA Gram tiles, exact int32 distances" if cfg.dtype == "u8" else
                        "float32 rows; decisions from fp32 MFMA Gram tiles with an error bound, exact f64-accumulated distances "
                        "for undecided pairs and for every stored distance (rounded once to float32)"),

@@ -8,7 +8,10 @@
  * Conventions
  *   - "device" pointers are HIP device memory owned by the caller; the library
  *     never keeps a pointer after a call returns.
- *   - X is row-major N x d, contiguous, uint8 or float32.
+ *   - X is row-major N x d, contiguous: uint8, float32, or (RNND_F16) IEEE binary16 as a
+ *     storage format for float data -- every coordinate stands for the float32 value it
+ *     converts to exactly, all arithmetic is that of float data, and the graph is the one
+ *     rnnd_build gives for that float32 matrix; it halves the bytes the rounds gather.
  *   - vertex ids are 0-based (the paper's V = {1..n}, Sec. 2.2, shifted by one).
  *   - delta(u,v) is the squared Euclidean distance of x_u and x_v (Eq. 3 with
  *     dist = squared L2; every comparison of Alg. 3-5 is monotone in it).

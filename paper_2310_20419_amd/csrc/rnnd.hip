@@ -1044,6 +1044,7 @@ static int scan_variant_for(const void *X, int d, int dtype)
     if (g_kernel_variant == 1 || !aligned) return 1;
     if (dtype == RNND_U8 && (d == 32 || d == 64 || d == 128)) return 2;
     if (dtype == RNND_F32 && d % 16 == 0) return 3;
+    if (dtype == RNND_F16 && d % 32 == 0) return 3;      // rows of a multiple of 64 bytes
     return 1;
 }
 
@@ -1124,31 +1125,51 @@ static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *
 // leaves alone (ties in bulk) go to one redo list for all classes, which launch_f32_redo hands to the
 // double-precision form.  The redo list lives in the bin array, which nothing else uses until the
 // scatter that follows the scans.  Kernel variant 2: the double-precision form on the active list itself.
-template <int NG, int CH, int NRC>
-static void launch_f32_scan(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, long long N,
-                            RoundCtr *c, int cls, hipStream_t st, hipEvent_t e_start, hipEvent_t e_stop)
+template <int NG, int CH, int NRC, int DT>
+static void launch_f32_scan_dt(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, long long N,
+                               RoundCtr *c, int cls, hipStream_t st, hipEvent_t e_start, hipEvent_t e_stop)
 {
     // wavefronts that fit per SIMD: about 4 for NG = 1, 2 for NG = 2, 1 for NG = 3 (21 accumulator tiles)
-    static const int per_cu_fast = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, true>, NG == 1 ? 4 : 2);
-    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, false>, NG == 1 ? 4 : NG == 2 ? 2 : 1);
+    static const int per_cu_fast = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, true, DT>, NG == 1 ? 4 : 2);
+    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, false, DT>, NG == 1 ? 4 : NG == 2 ? 2 : 1);
     if (g_kernel_variant != 2)
-        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, true>), dim3(cu_count() * per_cu_fast), dim3(256), 0, st,
-                              e_start, e_stop, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
+        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, true, DT>), dim3(cu_count() * per_cu_fast), dim3(256), 0,
+                              st, e_start, e_stop, 0, (const char *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
                               &c->n_active[cls], w.props, w.nprop, c, (int *)w.bins, &c->n_redo[0]);
     else
-        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, false>), dim3(cu_count() * per_cu), dim3(256), 0, st,
-                              e_start, e_stop, 0, (const float *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
+        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, false, DT>), dim3(cu_count() * per_cu), dim3(256), 0,
+                              st, e_start, e_stop, 0, (const char *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
                               &c->n_active[cls], w.props, w.nprop, c, (int *)nullptr, (u32 *)nullptr);
 }
 
-// The double-precision form (in its widest shape: lists of up to 96 entries) over the round's redo list.
-static void launch_f32_redo(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, RoundCtr *c,
-                            hipStream_t st, hipEvent_t e_stop)
+template <int NG, int CH, int NRC>
+static void launch_f32_scan(const Workspace &w, const void *X, int d, int dtype, int R, u64 *keys, int *deg,
+                            long long N, RoundCtr *c, int cls, hipStream_t st, hipEvent_t e_start, hipEvent_t e_stop)
 {
-    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<3, 1, 6, false>, 1);
-    hipExtLaunchKernelGGL((k_update_scan_mfma_f32<3, 1, 6, false>), dim3(cu_count() * per_cu), dim3(256), 0, st, nullptr,
-                          e_stop, 0, (const float *)X, d, R, keys, deg, (const int *)w.bins,
+    // (half rows: the three-group shape compiles badly -- thousands of spilled registers -- so lists of 33..48
+    // entries take the four-group kernel, which skips the tiles of the empty group)
+    if (dtype == RNND_F16)
+        launch_f32_scan_dt<NG, CH, (NRC == 3 ? 4 : NRC), DT_F16>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
+    else
+        launch_f32_scan_dt<NG, CH, NRC, DT_F32>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
+}
+
+// The double-precision form (in its widest shape: lists of up to 96 entries) over the round's redo list.
+template <int DT>
+static void launch_f32_redo_dt(const Workspace &w, const void *X, int d, int R, u64 *keys, int *deg, RoundCtr *c,
+                               hipStream_t st, hipEvent_t e_stop)
+{
+    static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<3, 1, 6, false, DT>, 1);
+    hipExtLaunchKernelGGL((k_update_scan_mfma_f32<3, 1, 6, false, DT>), dim3(cu_count() * per_cu), dim3(256), 0, st,
+                          nullptr, e_stop, 0, (const char *)X, d, R, keys, deg, (const int *)w.bins,
                           (const u32 *)&c->n_redo[0], w.props, w.nprop, c, (int *)nullptr, (u32 *)nullptr);
+}
+
+static void launch_f32_redo(const Workspace &w, const void *X, int d, int dtype, int R, u64 *keys, int *deg,
+                            RoundCtr *c, hipStream_t st, hipEvent_t e_stop)
+{
+    if (dtype == RNND_F16) launch_f32_redo_dt<DT_F16>(w, X, d, R, keys, deg, c, st, e_stop);
+    else launch_f32_redo_dt<DT_F32>(w, X, d, R, keys, deg, c, st, e_stop);
 }
 
 // One run of consecutive vertex ids of a block-sequential pass: ids first .. first + count - 1.
@@ -1188,24 +1209,30 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
             const bool last = k++ == n_more;
             return (last && (generic_tail || !redo_pass)) ? re.scan_stop : (hipEvent_t) nullptr;
         };
-        if (d % 32 == 0) launch_f32_scan<1, 2, 1>(w, X, d, R, keys, deg, N, c, 0, st, re.scan_start, stop_for());
-        else launch_f32_scan<1, 1, 1>(w, X, d, R, keys, deg, N, c, 0, st, re.scan_start, stop_for());
+        const bool wide = ((size_t)d * dt_size(dtype)) % 128 == 0;     // two 64-byte chunks per iteration
+        if (wide) launch_f32_scan<1, 2, 1>(w, X, d, dtype, R, keys, deg, N, c, 0, st, re.scan_start, stop_for());
+        else launch_f32_scan<1, 1, 1>(w, X, d, dtype, R, keys, deg, N, c, 0, st, re.scan_start, stop_for());
         if (R > 8) {
-            if (d % 32 == 0) launch_f32_scan<1, 2, 1>(w, X, d, R, keys, deg, N, c, 1, st, nullptr, stop_for());
-            else launch_f32_scan<1, 1, 1>(w, X, d, R, keys, deg, N, c, 1, st, nullptr, stop_for());
+            if (wide) launch_f32_scan<1, 2, 1>(w, X, d, dtype, R, keys, deg, N, c, 1, st, nullptr, stop_for());
+            else launch_f32_scan<1, 1, 1>(w, X, d, dtype, R, keys, deg, N, c, 1, st, nullptr, stop_for());
         }
         if (R > 16) {
-            if (d % 32 == 0) launch_f32_scan<1, 2, 2>(w, X, d, R, keys, deg, N, c, 2, st, nullptr, stop_for());
-            else launch_f32_scan<1, 1, 2>(w, X, d, R, keys, deg, N, c, 2, st, nullptr, stop_for());
+            if (wide) launch_f32_scan<1, 2, 2>(w, X, d, dtype, R, keys, deg, N, c, 2, st, nullptr, stop_for());
+            else launch_f32_scan<1, 1, 2>(w, X, d, dtype, R, keys, deg, N, c, 2, st, nullptr, stop_for());
         }
-        if (R > 32) launch_f32_scan<2, 1, 3>(w, X, d, R, keys, deg, N, c, 3, st, nullptr, stop_for());
-        if (R > 48) launch_f32_scan<2, 1, 4>(w, X, d, R, keys, deg, N, c, 4, st, nullptr, stop_for());
-        if (R > 64) launch_f32_scan<3, 1, 5>(w, X, d, R, keys, deg, N, c, 5, st, nullptr, stop_for());
-        if (R > 80) launch_f32_scan<3, 1, 6>(w, X, d, R, keys, deg, N, c, 6, st, nullptr, stop_for());
-        if (redo_pass) launch_f32_redo(w, X, d, R, keys, deg, c, st, generic_tail ? (hipEvent_t) nullptr : re.scan_stop);
-        if (R > 96)
-            hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, nullptr, stop_for(), 0, X, d,
-                                  vec_ok, R, keys, deg, w.lists + (size_t)7 * N, &c->n_active[7], w.props, w.nprop, c);
+        if (R > 32) launch_f32_scan<2, 1, 3>(w, X, d, dtype, R, keys, deg, N, c, 3, st, nullptr, stop_for());
+        if (R > 48) launch_f32_scan<2, 1, 4>(w, X, d, dtype, R, keys, deg, N, c, 4, st, nullptr, stop_for());
+        if (R > 64) launch_f32_scan<3, 1, 5>(w, X, d, dtype, R, keys, deg, N, c, 5, st, nullptr, stop_for());
+        if (R > 80) launch_f32_scan<3, 1, 6>(w, X, d, dtype, R, keys, deg, N, c, 6, st, nullptr, stop_for());
+        if (redo_pass) launch_f32_redo(w, X, d, dtype, R, keys, deg, c, st, generic_tail ? (hipEvent_t) nullptr : re.scan_stop);
+        if (R > 96) {
+            if (dtype == RNND_F16)
+                hipExtLaunchKernelGGL(k_update_scan<DT_F16>, dim3(pb), dim3(BLOCK), 0, st, nullptr, stop_for(), 0, X, d,
+                                      vec_ok, R, keys, deg, w.lists + (size_t)7 * N, &c->n_active[7], w.props, w.nprop, c);
+            else
+                hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, nullptr, stop_for(), 0, X, d,
+                                      vec_ok, R, keys, deg, w.lists + (size_t)7 * N, &c->n_active[7], w.props, w.nprop, c);
+        }
     } else if (dtype == RNND_U8) {
         hipExtLaunchKernelGGL(k_update_scan<DT_U8>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
                               vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);

@@ -84,102 +84,118 @@ __device__ __forceinline__ u32 transpose16_bits_x2(u32 w, int lane)
 template <bool FAST> struct GramAcc { typedef v4d type; };
 template <> struct GramAcc<true> { typedef v4f type; };
 
-// The Gram block of all NR 16-row groups over all d dimensions.  Per iteration: wait for the chunk,
-// widen it to double, immediately issue the loads of the next chunk into the same registers, then run
-// the matrix instructions on the doubles -- the next chunk travels while the matrix cores work.  The
-// body is straight-line: loads are unconditional (lanes without a row read row 0 of X; what they
-// produce is masked later) and the last iteration re-reads the last chunk.
-// TM != 0: the tiles to compute are fixed at compile time (bit I(I+1)/2 + J of TM); TM == 0: bit of `need`.
-template <int NR, int CH, u32 TM = 0>
-__device__ __forceinline__ void gram_f64_loop(const float *const (&rp)[NR], int nchunk, v4d (&acc)[NR * (NR + 1) / 2],
-                                              double (&nr)[NR], u32 need)
+// A lane's load is 16 bytes of a row: 4 float coordinates, or 8 half coordinates (DT_F16: IEEE binary16
+// storage, each coordinate standing for the float it converts to exactly).  Coordinate t of such a load:
+template <int DT>
+__device__ __forceinline__ float chunk_coord(const uint4 &raw, int t)
 {
-    float4 x[NR][CH];
+    if (DT == DT_F16) {
+        const u32 w = (t >> 1) == 0 ? raw.x : (t >> 1) == 1 ? raw.y : (t >> 1) == 2 ? raw.z : raw.w;
+        return (float)__builtin_bit_cast(_Float16, (unsigned short)((t & 1) ? (w >> 16) : (w & 0xFFFFu)));
+    }
+    return __uint_as_float(t == 0 ? raw.x : t == 1 ? raw.y : t == 2 ? raw.z : raw.w);
+}
+template <int DT> struct ChunkCoords { static constexpr int n = DT == DT_F16 ? 8 : 4; };
+
+// One chunk (64 bytes of every row: lane (r16, q) holds bytes 16 q .. 16 q + 15 of row r16 of every group)
+// into the norms and the Gram tiles.  The matrix instruction multiplies, for each of its 4 k slots, what
+// lane quarter q supplies for the row with what it supplies for the column: the same coordinate of both,
+// whichever coordinate that is.  ACC = v4f: v_mfma_f32_16x16x4_f32 on the floats; v4d: the f64 instruction.
+// TM != 0: the tiles to compute are fixed at compile time (bit I(I+1)/2 + J of TM); TM == 0: bit of `need`.
+template <int NR, int CH, u32 TM, int DT, typename ACC>
+__device__ __forceinline__ void gram_chunk(const uint4 (&x)[NR][CH], ACC (&acc)[NR * (NR + 1) / 2], double (&nr)[NR], u32 need)
+{
 #pragma unroll
-    for (int g = 0; g < NR; ++g)
+    for (int j = 0; j < CH; ++j)
 #pragma unroll
-        for (int j = 0; j < CH; ++j) x[g][j] = *(const float4 *)(rp[g] + 16 * j);
-#pragma unroll 1
-    for (int c = 0; c < nchunk; ++c) {
-        double a[NR][CH][4];
+        for (int t = 0; t < ChunkCoords<DT>::n; ++t) {
+            if constexpr (sizeof(acc[0][0]) == 4) {
+                float a[NR];
 #pragma unroll
-        for (int g = 0; g < NR; ++g)
-#pragma unroll
-            for (int j = 0; j < CH; ++j) {
-                a[g][j][0] = (double)x[g][j].x;
-                a[g][j][1] = (double)x[g][j].y;
-                a[g][j][2] = (double)x[g][j].z;
-                a[g][j][3] = (double)x[g][j].w;
-            }
-        const int cn = c + 1 < nchunk ? c + 1 : c;
-        __builtin_amdgcn_sched_barrier(0);   // keep the three phases in this order
-#pragma unroll
-        for (int g = 0; g < NR; ++g)
-#pragma unroll
-            for (int j = 0; j < CH; ++j) x[g][j] = *(const float4 *)(rp[g] + 16 * (CH * cn + j));
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < CH; ++j)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-#pragma unroll
-                for (int g = 0; g < NR; ++g) nr[g] = fma(a[g][j][t], a[g][j][t], nr[g]);
+                for (int g = 0; g < NR; ++g) {
+                    a[g] = chunk_coord<DT>(x[g][j], t);
+                    const double ad = (double)a[g];
+                    nr[g] = fma(ad, ad, nr[g]);
+                }
 #pragma unroll
                 for (int I = 0; I < NR; ++I)
 #pragma unroll
                     for (int J = 0; J <= I; ++J)
                         if (TM ? ((TM >> (I * (I + 1) / 2 + J)) & 1u) != 0 : ((need >> (I * (I + 1) / 2 + J)) & 1u) != 0)   // wave-uniform
-                            acc[I * (I + 1) / 2 + J] = __builtin_amdgcn_mfma_f64_16x16x4f64(
-                                a[I][j][t], a[J][j][t], acc[I * (I + 1) / 2 + J], 0, 0, 0);
+                            acc[I * (I + 1) / 2 + J] =
+                                __builtin_amdgcn_mfma_f32_16x16x4f32(a[I], a[J], acc[I * (I + 1) / 2 + J], 0, 0, 0);
+            } else {
+                double ad[NR];
+#pragma unroll
+                for (int g = 0; g < NR; ++g) {
+                    ad[g] = (double)chunk_coord<DT>(x[g][j], t);
+                    nr[g] = fma(ad[g], ad[g], nr[g]);
+                }
+#pragma unroll
+                for (int I = 0; I < NR; ++I)
+#pragma unroll
+                    for (int J = 0; J <= I; ++J)
+                        if (TM ? ((TM >> (I * (I + 1) / 2 + J)) & 1u) != 0 : ((need >> (I * (I + 1) / 2 + J)) & 1u) != 0)   // wave-uniform
+                            acc[I * (I + 1) / 2 + J] =
+                                __builtin_amdgcn_mfma_f64_16x16x4f64(ad[I], ad[J], acc[I * (I + 1) / 2 + J], 0, 0, 0);
             }
-    }
-}
-
-// Single-precision form of the same loop: the rows go to v_mfma_f32_16x16x4_f32 as they are (twice the
-// rate of the double-precision instruction, half the accumulator registers).  That instruction adds its
-// four products one after the other, each product exact and each sum rounded to nearest, so after d
-// dimensions |G - G_exact| <= d 2^-24 sum_k |x_ik x_jk| (1 + 2 d 2^-24) <= 1.01 d 2^-24 sqrt(n_i n_j).
-// The norms stay in double.
-template <int NR, int CH, u32 TM>
-__device__ __forceinline__ void gram_f32_chunk(const float4 (&x)[NR][CH], v4f (&acc)[NR * (NR + 1) / 2], double (&nr)[NR],
-                                               u32 need)
-{
-#pragma unroll
-    for (int j = 0; j < CH; ++j)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            float a[NR];
-#pragma unroll
-            for (int g = 0; g < NR; ++g) {
-                a[g] = t == 0 ? x[g][j].x : t == 1 ? x[g][j].y : t == 2 ? x[g][j].z : x[g][j].w;
-                const double ad = (double)a[g];
-                nr[g] = fma(ad, ad, nr[g]);
-            }
-#pragma unroll
-            for (int I = 0; I < NR; ++I)
-#pragma unroll
-                for (int J = 0; J <= I; ++J)
-                    if (TM ? ((TM >> (I * (I + 1) / 2 + J)) & 1u) != 0 : ((need >> (I * (I + 1) / 2 + J)) & 1u) != 0)   // wave-uniform
-                        acc[I * (I + 1) / 2 + J] =
-                            __builtin_amdgcn_mfma_f32_16x16x4f32(a[I], a[J], acc[I * (I + 1) / 2 + J], 0, 0, 0);
+            // half rows: eight coordinates per load; keep the conversions of one step next to its matrix
+            // instructions instead of letting all eight steps' worth pile up in registers
+            if (DT == DT_F16) __builtin_amdgcn_sched_barrier(0);
         }
 }
 
-// Three buffers in rotation: while the matrix cores work on one chunk, the loads of the next two are in
-// flight (the single-precision instruction is fast enough that one chunk of lead does not cover the
-// latency of the gathers).  Loads past the end re-read the last chunk.
-template <int NR, int CH, u32 TM = 0>
-__device__ __forceinline__ void gram_f32_loop(const float *const (&rp)[NR], int nchunk, v4f (&acc)[NR * (NR + 1) / 2],
+// The Gram block of all NR 16-row groups over the whole rows, double precision.  Per iteration: wait for
+// the chunk, set it aside, immediately issue the loads of the next chunk into the same registers, then run
+// the matrix instructions -- the next chunk travels while the matrix cores work.  The body is
+// straight-line: loads are unconditional (lanes without a row read row 0 of X; what they produce is
+// masked later) and the last iteration re-reads the last chunk.  rp: byte pointers, 16 q into each row.
+template <int NR, int CH, u32 TM, int DT>
+__device__ __forceinline__ void gram_f64_loop(const char *const (&rp)[NR], int nchunk, v4d (&acc)[NR * (NR + 1) / 2],
                                               double (&nr)[NR], u32 need)
 {
-    float4 x0[NR][CH], x1[NR][CH], x2[NR][CH];
+    uint4 x[NR][CH];
+#pragma unroll
+    for (int g = 0; g < NR; ++g)
+#pragma unroll
+        for (int j = 0; j < CH; ++j) x[g][j] = *(const uint4 *)(rp[g] + 64 * j);
+#pragma unroll 1
+    for (int c = 0; c < nchunk; ++c) {
+        uint4 xc[NR][CH];
+#pragma unroll
+        for (int g = 0; g < NR; ++g)
+#pragma unroll
+            for (int j = 0; j < CH; ++j) xc[g][j] = x[g][j];
+        const int cn = c + 1 < nchunk ? c + 1 : c;
+        __builtin_amdgcn_sched_barrier(0);   // keep the three phases in this order
+#pragma unroll
+        for (int g = 0; g < NR; ++g)
+#pragma unroll
+            for (int j = 0; j < CH; ++j) x[g][j] = *(const uint4 *)(rp[g] + 64 * (CH * cn + j));
+        __builtin_amdgcn_sched_barrier(0);
+        gram_chunk<NR, CH, TM, DT, v4d>(xc, acc, nr, need);
+    }
+}
+
+// Single-precision form: the coordinates go to v_mfma_f32_16x16x4_f32 as floats (twice the rate of the
+// double-precision instruction, half the accumulator registers).  That instruction adds its four products
+// one after the other, each product exact and each sum rounded to nearest, so after d dimensions
+// |G - G_exact| <= d 2^-24 sum_k |x_ik x_jk| (1 + 2 d 2^-24) <= 1.01 d 2^-24 sqrt(n_i n_j).  The norms stay
+// in double.  Three buffers in rotation: while the matrix cores work on one chunk, the loads of the next
+// two are in flight (the instruction is fast enough that one chunk of lead does not cover the latency of
+// the gathers).  Loads past the end re-read the last chunk.
+template <int NR, int CH, u32 TM, int DT>
+__device__ __forceinline__ void gram_f32_loop(const char *const (&rp)[NR], int nchunk, v4f (&acc)[NR * (NR + 1) / 2],
+                                              double (&nr)[NR], u32 need)
+{
+    uint4 x0[NR][CH], x1[NR][CH], x2[NR][CH];
     const int last = nchunk - 1;
-    auto fetch = [&](float4 (&x)[NR][CH], int c) {
+    auto fetch = [&](uint4 (&x)[NR][CH], int c) {
         const int cc = c < last ? c : last;
 #pragma unroll
         for (int g = 0; g < NR; ++g)
 #pragma unroll
-            for (int j = 0; j < CH; ++j) x[g][j] = *(const float4 *)(rp[g] + 16 * (CH * cc + j));
+            for (int j = 0; j < CH; ++j) x[g][j] = *(const uint4 *)(rp[g] + 64 * (CH * cc + j));
     };
     fetch(x0, 0);
     fetch(x1, 1);
@@ -187,25 +203,23 @@ __device__ __forceinline__ void gram_f32_loop(const float *const (&rp)[NR], int 
     for (int c = 0; c < nchunk; c += 3) {
         fetch(x2, c + 2);
         __builtin_amdgcn_sched_barrier(0);
-        gram_f32_chunk<NR, CH, TM>(x0, acc, nr, need);
+        gram_chunk<NR, CH, TM, DT, v4f>(x0, acc, nr, need);
         __builtin_amdgcn_sched_barrier(0);
         if (c + 1 < nchunk) {
             fetch(x0, c + 3);
             __builtin_amdgcn_sched_barrier(0);
-            gram_f32_chunk<NR, CH, TM>(x1, acc, nr, need);
+            gram_chunk<NR, CH, TM, DT, v4f>(x1, acc, nr, need);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (c + 2 < nchunk) {
             fetch(x1, c + 4);
             __builtin_amdgcn_sched_barrier(0);
-            gram_f32_chunk<NR, CH, TM>(x2, acc, nr, need);
+            gram_chunk<NR, CH, TM, DT, v4f>(x2, acc, nr, need);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
 
-// CH = 16-dimension chunks fetched per loop iteration (d must be a multiple of 16*CH): a longer iteration
-// gives the prefetch of the next one more matrix work to hide behind.
 // bits [lo, hi) of a 96-bit mask, as word c (bits 32c .. 32c+31)
 __device__ __forceinline__ u32 range_word(int lo, int hi, int c)
 {
@@ -224,7 +238,9 @@ __device__ __forceinline__ int popc_below(u64 m0, u64 m1, int p)   // set bits o
 }
 
 // NRC = 16-row groups of the list (lists of at most 16 NRC entries); NG = ceil(NRC / 2) names the
-// degree class family; CH = 16-dimension chunks fetched per loop iteration (d a multiple of 16*CH).
+// degree class family; CH = 64-byte chunks of every row fetched per loop iteration (rows a multiple of
+// 64 CH bytes: a longer iteration gives the prefetch more matrix work to hide behind); DT = DT_F32 or
+// DT_F16 (half-precision storage of the same kind of rows).
 // FAST: the Gram block in single precision (gram_f32_loop).  A pair is then decided only if the outcome of
 // the prune test is beyond the error bound of that block, eps_ij = (1.25 d + 8) 2^-24 (n_i + n_j), which
 // covers the accumulation (2 x 1.01 d 2^-24 sqrt(n_i n_j) <= 1.01 d 2^-24 (n_i + n_j)) and the roundings of
@@ -233,9 +249,9 @@ __device__ __forceinline__ int popc_below(u64 m0, u64 m1, int p)   // set bits o
 // reference arithmetic.  A vertex with more than F32_AMB_CAP undecided pairs (ties in bulk: duplicates,
 // lattices) is left untouched and appended to `redo`, which the double-precision form (FAST = false)
 // takes afterwards.
-template <int NG, int CH, int NRC = 2 * NG, bool FAST = false>
-__global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) : (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1))) void k_update_scan_mfma_f32(
-    const float *__restrict__ X, int d, int R, u64 *__restrict__ keys, int *__restrict__ deg,
+template <int NG, int CH, int NRC = 2 * NG, bool FAST = false, int DT = DT_F32>
+__global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == DT_F32) ? 3 : 2) : (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1))) void k_update_scan_mfma_f32(
+    const char *__restrict__ X, int d, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
     int *__restrict__ nprop, RoundCtr *__restrict__ ctr, int *__restrict__ redo, u32 *__restrict__ n_redo)
 {
@@ -251,7 +267,8 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
     const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
     const u32 n_active = *n_list;
     F32ScanSmem<NRC> &sm = smem[wave];
-    const int nchunk = d / (16 * CH);
+    const size_t rowbytes = (size_t)d * dt_size(DT);
+    const int nchunk = (int)(rowbytes / (64 * CH));
     u64 tiles = 0, rows = 0, nprops_total = 0;
     u32 ev_lane = 0;
 
@@ -305,12 +322,12 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
             wave_sync();
 
             // ---- rows of the slots, 16 per group
-            const float *rp[NRC];
+            const char *rp[NRC];
 #pragma unroll
             for (int g = 0; g < NRC; ++g) {
                 const int s = 16 * g + r16;
                 const int id = s < m ? (int)key_id(sm.key[s]) : 0;      // lanes without a row read row 0
-                rp[g] = X + (size_t)id * d + 4 * q;
+                rp[g] = X + (size_t)id * rowbytes + 16 * q;
             }
             // ---- Gram block over d in chunks of 16 dimensions: the tiles whose column group holds a new slot
             acc_t acc[NT];
@@ -328,23 +345,23 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
             need = (u32)__builtin_amdgcn_readfirstlane((int)need);
             if constexpr (FAST) {
                 if (NRC == 1) {
-                    gram_f32_loop<NRC, CH, 1u>(rp, nchunk, acc, nr, need);
+                    gram_f32_loop<NRC, CH, 1u, DT>(rp, nchunk, acc, nr, need);
                 } else if (NRC == 2) {
-                    if (need == 7u) gram_f32_loop<NRC, CH, 7u>(rp, nchunk, acc, nr, need);
-                    else gram_f32_loop<NRC, CH, 3u>(rp, nchunk, acc, nr, need);
+                    if (need == 7u) gram_f32_loop<NRC, CH, 7u, DT>(rp, nchunk, acc, nr, need);
+                    else gram_f32_loop<NRC, CH, 3u, DT>(rp, nchunk, acc, nr, need);
                 } else {
-                    gram_f32_loop<NRC, CH>(rp, nchunk, acc, nr, need);
+                    gram_f32_loop<NRC, CH, 0u, DT>(rp, nchunk, acc, nr, need);
                 }
             } else {
                 if (NRC == 1) {
-                    gram_f64_loop<NRC, CH, 1u>(rp, nchunk, acc, nr, need);
+                    gram_f64_loop<NRC, CH, 1u, DT>(rp, nchunk, acc, nr, need);
                 } else if (NRC == 2) {
                     // two straight-line loops instead of per-tile branches: all three tiles, or (new entries in
                     // the first group only) the two tiles of column group 0
-                    if (need == 7u) gram_f64_loop<NRC, CH, 7u>(rp, nchunk, acc, nr, need);
-                    else gram_f64_loop<NRC, CH, 3u>(rp, nchunk, acc, nr, need);
+                    if (need == 7u) gram_f64_loop<NRC, CH, 7u, DT>(rp, nchunk, acc, nr, need);
+                    else gram_f64_loop<NRC, CH, 3u, DT>(rp, nchunk, acc, nr, need);
                 } else {
-                    gram_f64_loop<NRC, CH>(rp, nchunk, acc, nr, need);
+                    gram_f64_loop<NRC, CH, 0u, DT>(rp, nchunk, acc, nr, need);
                 }
             }
 #pragma unroll
@@ -481,7 +498,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                         const u32 sv = sv0 < 16u * NRC ? sv0 : 0u, sw = sw0 < 16u * NRC ? sw0 : 0u;
                         const int idv = (int)key_id(sm.key[sv]), idw = (int)key_id(sm.key[sw]);
                         u32 db = 0;
-                        if (have) db = group8_dist_bits<DT_F32>(X + (size_t)idv * d, X + (size_t)idw * d, d, 1, sub);
+                        if (have) db = group8_dist_bits<DT>(X + (size_t)idv * rowbytes, X + (size_t)idw * rowbytes, d, 1, sub);
                         if (have && sub == 0) {
                             const bool fails = __uint_as_float(key_dist(sm.key[sv])) >= __uint_as_float(db);
                             sm.amb[p] = (uint16_t)(pair | (fails ? 0x8000u : 0u));
@@ -600,7 +617,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                 const u32 sw = sw0 < 16u * NRC ? sw0 : 0u;     // a pruned row always has a target
                 const int idv = (int)key_id(sm.key[sv]), idw = (int)key_id(sm.key[sw]);
                 u32 db = 0;
-                if (have) db = group8_dist_bits<DT_F32, (NRC <= 2 ? 6 : 8)>(X + (size_t)idv * d, X + (size_t)idw * d, d, 1, sub);
+                if (have) db = group8_dist_bits<DT, (NRC <= 2 ? 6 : 8)>(X + (size_t)idv * rowbytes, X + (size_t)idw * rowbytes, d, 1, sub);
                 if (have && sub == 0) emit_redirect(make_key(db, (u32)idv, 1u), (u32)idw, props + (size_t)u * R + p);
             }
             }   // !defer
