@@ -267,8 +267,8 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
     const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
     const u32 n_active = *n_list;
     F32ScanSmem<NRC> &sm = smem[wave];
-    const size_t rowbytes = (size_t)d * dt_size(DT);
-    const int nchunk = (int)(rowbytes / (64 * CH));
+    const u32 rowbytes = (u32)d * (u32)dt_size(DT);     // at most a few hundred KB
+    const int nchunk = (int)(rowbytes / (64u * CH));
     u64 tiles = 0, rows = 0, nprops_total = 0;
     u32 ev_lane = 0;
 
@@ -617,7 +617,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
                 const u32 sw = sw0 < 16u * NRC ? sw0 : 0u;     // a pruned row always has a target
                 const int idv = (int)key_id(sm.key[sv]), idw = (int)key_id(sm.key[sw]);
                 u32 db = 0;
-                if (have) db = group8_dist_bits<DT, (NRC <= 2 ? 6 : 8)>(X + (size_t)idv * rowbytes, X + (size_t)idw * rowbytes, d, 1, sub);
+                if (have) db = group8_dist_bits<DT, (NRC <= 2 ? 5 : 8)>(X + (size_t)idv * rowbytes, X + (size_t)idw * rowbytes, d, 1, sub);
                 if (have && sub == 0) emit_redirect(make_key(db, (u32)idv, 1u), (u32)idw, props + (size_t)u * R + p);
             }
             }   // !defer
