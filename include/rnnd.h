@@ -64,7 +64,7 @@ typedef enum {
 typedef struct {
     int32_t rounds;                         /* UpdateNeighbors rounds run (T1*T2) */
     int32_t reverse_calls;                  /* AddReverseEdges calls run (T1-1) */
-    int32_t kernel_variant;                 /* UpdateNeighbors scan kernel used: 1 generic, 2 int8 MFMA, 3 f64 MFMA */
+    int32_t kernel_variant;                 /* UpdateNeighbors scan kernel used: 1 generic, 2 int8 MFMA, 3 float MFMA (fp32, then f64) */
     int32_t reserved;
     float total_ms, init_ms;                /* GPU time of the whole call / of RandomGraph */
     float round_ms[RNND_MAX_ROUNDS];        /* GPU time of each UpdateNeighbors round */
@@ -180,11 +180,13 @@ int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t 
                       double *gbytes_per_s, void *stream);
 
 /* Selects the UpdateNeighbors scan kernel: 0 = automatic (default), 1 = generic pair-at-a-time
- * kernel for every input, 2 = automatic, but the float32 matrix-core scan works in double precision
+ * kernel for every input, 2 = automatic, but the float matrix-core scan works in double precision
  * throughout.  Automatic uses the dense Gram-block kernels on the matrix cores where they apply
- * (uint8 with d = 32, 64 or 128: int8 MFMA; float32 with d a multiple of 16: fp32 MFMA first, every
- * pair whose outcome lies within that block's error bound decided by the exact distance, and
- * vertices with very many such pairs redone on the f64 MFMA) and the generic kernel otherwise.
+ * and the generic kernel otherwise:
+ *   uint8 rows with d = 32, 64 or 128: int8 MFMA;
+ *   float32 rows with d a multiple of 16, half rows with d a multiple of 32: fp32 MFMA first,
+ *   every pair whose outcome lies within that block's error bound decided by the exact distance,
+ *   and vertices with very many such pairs redone on the f64 MFMA.
  * All give identical graphs; this exists for testing and profiling.  Process-wide, not thread-safe. */
 int rnnd_set_kernel_variant(int variant);
 

@@ -1037,7 +1037,7 @@ static int vec_ok_for(const void *X, int d, int dtype)
 }
 
 // How UpdateNeighbors scans for this input: 1 = generic kernel, 2 = int8 MFMA Gram kernel (uint8 rows),
-// 3 = double-precision MFMA Gram kernel (float rows).
+// 3 = matrix-core Gram kernel for float or half rows (fp32 MFMA first, f64 MFMA for what it leaves).
 static int scan_variant_for(const void *X, int d, int dtype)
 {
     const bool aligned = (((uintptr_t)X) % 16 == 0);
