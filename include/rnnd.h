@@ -98,6 +98,17 @@ int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int metric, in
                   int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out, int32_t *degree_out,
                   uint64_t *keys_out, rnnd_stats *stats, void *stream);
 
+/* Alg. 6 with synchronous rounds whose merges cut a list to M >= R entries instead of R: in the
+ * paper UpdateNeighbors never drops an edge for lack of room and only AddReverseEdges bounds the
+ * degrees by R (Sec. 5.1 reports out-degrees above R in the finished graphs), whereas rnnd_build
+ * keeps rows of fixed width R throughout.  Here rows are M slots wide, 1 <= R <= M <= RNND_MAX_R:
+ * between two AddReverseEdges calls, and in the result, a list may hold up to M entries.
+ *   graph_out  device int32 [N * M], keys_out device uint64 [N * M] or NULL
+ * M = R gives the graph of rnnd_build.  Other arguments, ownership and errors as for rnnd_build_ex. */
+int rnnd_build_wide(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+                    int32_t M, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
+                    int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream);
+
 /* Alg. 6 with block-sequential passes: a variant between the synchronous round and the in-place
  * vertex loop of Alg. 4 (it visits the vertices one after the other and its edge update changes the
  * edge set at once, so a vertex visited later in the same pass already sees the edges redirected

@@ -209,6 +209,22 @@ def build_blocks(X: np.ndarray, S: int, R: int, T1: int, T2: int, seed: int, nbl
     return BuildResult(s, rev, rpr, n * S)
 
 
+def build_wide(X: np.ndarray, S: int, R: int, M: int, T1: int, T2: int, seed: int) -> BuildResult:
+    """Alg. 6 with synchronous rounds whose merges cut to M >= R entries; AddReverseEdges cuts to R.
+    Rows of the result are M wide."""
+    _chk(X)
+    n, d = X.shape
+    s = Snapshot.empty(n, M)
+    rev = np.zeros(T1 * T2, np.int64)
+    rpr = np.zeros(T1 * T2, np.int64)
+    rc = _load().orc_build_wide(
+        _p(X), ctypes.c_int64(n), ctypes.c_int32(d), ctypes.c_int(_dt(X)), ctypes.c_int32(S),
+        ctypes.c_int32(R), ctypes.c_int32(M), ctypes.c_int32(T1), ctypes.c_int32(T2), ctypes.c_uint64(seed),
+        ctypes.c_int32(M), _p(s.ids), _p(s.dist), _p(s.flags), _p(s.deg), _p(rev), _p(rpr))
+    assert rc == 0, rc
+    return BuildResult(s, rev, rpr, n * S)
+
+
 def build_paper_order(X: np.ndarray, S: int, R: int, T1: int, T2: int, seed: int, W: int):
     """Alg. 6 in the paper's in-place vertex order; returns (ids, deg, evals, max_degree)."""
     _chk(X)

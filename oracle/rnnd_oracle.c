@@ -529,6 +529,30 @@ int orc_build_sync(const void *X, int64_t n, int32_t d, int dtype, int32_t S, in
     return 0;
 }
 
+/* Alg. 6 with synchronous rounds whose merges cut a list to M >= R entries; only AddReverseEdges
+ * bounds the degrees by R, as in the paper, where UpdateNeighbors itself never drops an edge for
+ * lack of room (Sec. 5.1 reports out-degrees above R at the end).  M = R is orc_build_sync. */
+int orc_build_wide(const void *X, int64_t n, int32_t d, int dtype, int32_t S, int32_t R, int32_t M,
+                   int32_t T1, int32_t T2, uint64_t seed, int32_t W, int32_t *ids, double *dist,
+                   uint8_t *flags, int32_t *deg, int64_t *round_evals, int64_t *round_props)
+{
+    if (S < 1 || S > R || R > M || M > W || (int64_t)S > n - 1 || T1 < 1 || T2 < 1) return -1;
+    data_t D = {X, n, d, dtype};
+    list_t *G = random_graph(&D, S, seed);
+    for (int32_t t1 = 0; t1 < T1; ++t1) {
+        for (int32_t t2 = 0; t2 < T2; ++t2) {
+            int64_t ev = 0, np = 0;
+            update_neighbors_sync(&D, G, M, 1, &ev, &np);          /* lists cut to M */
+            if (round_evals) round_evals[t1 * T2 + t2] = ev;
+            if (round_props) round_props[t1 * T2 + t2] = np;
+        }
+        if (t1 != T1 - 1) add_reverse_edges(G, n, R);               /* degrees cut to R */
+    }
+    graph_to_flat(G, n, W, ids, dist, flags, deg);
+    graph_free(G, n);
+    return 0;
+}
+
 /* One block-sequential pass on a flat snapshot. */
 int orc_update_neighbors_blocks(const void *X, int64_t n, int32_t d, int dtype, int32_t R, int32_t W,
                                 int64_t nblocks, int32_t *ids, double *dist, uint8_t *flags,

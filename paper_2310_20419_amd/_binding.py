@@ -84,6 +84,8 @@ def load_library():
         L.rnnd_build.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, i32, i32, u64, vp, vp, vp]
         L.rnnd_build_ex.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, i32, i32, u64, vp, vp, vp,
                                     c.POINTER(Stats), vp]
+        L.rnnd_build_wide.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, i32, i32, i32, u64, vp, vp, vp,
+                                      c.POINTER(Stats), vp]
         L.rnnd_build_blocks.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, i32, i32, u64, i64, vp, vp, vp,
                                         c.POINTER(Stats), vp]
         L.rnnd_update_neighbors_blocks.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, vp, vp, i32, i64,
@@ -104,7 +106,7 @@ def load_library():
         for name in ("rnnd_build", "rnnd_build_ex", "rnnd_workspace_bytes", "rnnd_random_graph",
                      "rnnd_update_neighbors", "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search",
                      "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks",
-                     "rnnd_probe_gather"):
+                     "rnnd_probe_gather", "rnnd_build_wide"):
             getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -178,6 +180,21 @@ def rnnd_build_ex(X, S: int, R: int, T1: int, T2: int, seed: int, metric: int = 
     _check(load_library().rnnd_build_ex(ptr, N, d, dt, metric, S, R, T1, T2, seed, graph.data_ptr(),
                                         degree.data_ptr(), keys.data_ptr() if want_keys else None,
                                         ctypes.byref(st), _stream(stream)))
+    return graph, degree, keys, st
+
+
+def rnnd_build_wide(X, S: int, R: int, M: int, T1: int, T2: int, seed: int, metric: int = RNND_L2SQ, stream=None,
+                    want_keys: bool = True):
+    """rnnd_build_wide: returns (graph [N, M], degree, keys [N, M] int64-typed uint64 or None, Stats)."""
+    torch = _torch()
+    ptr, N, d, dt = _data_args(X)
+    graph = torch.empty((N, M), dtype=torch.int32, device=X.device)
+    degree = torch.empty((N,), dtype=torch.int32, device=X.device)
+    keys = torch.empty((N, M), dtype=torch.int64, device=X.device) if want_keys else None
+    st = Stats()
+    _check(load_library().rnnd_build_wide(ptr, N, d, dt, metric, S, R, M, T1, T2, seed, graph.data_ptr(),
+                                          degree.data_ptr(), keys.data_ptr() if want_keys else None,
+                                          ctypes.byref(st), _stream(stream)))
     return graph, degree, keys, st
 
 

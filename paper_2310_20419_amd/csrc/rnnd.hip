@@ -742,11 +742,11 @@ __global__ __launch_bounds__(BLOCK) void k_fill_bins(long long N, int R, const u
 // incoming edges (cand[v]: |list(v)| + |edges into v| > R before the union; for every other vertex
 // the union itself bounds the in-degree by R); rowflag[x] says whether the list has such an edge.
 // vcls[x] <- degree class if the list holds a "new" entry, else -1.
-__global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64 *keys, int *deg, int *fill,
+__global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int W, int R, u64 *keys, int *deg, int *fill,
                                                          const u64 *inbox, const int *binoff, const u64 *bins,
                                                          const int8_t *cand, int *cnt_in, int8_t *rowflag,
                                                          int8_t *vcls, int use_classes)
-{
+{   // rows are W slots apart (W >= R); lists are cut to R
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     // a wavefront takes two vertices, one per half: lists are short on average, and when both unions have
@@ -758,7 +758,7 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64
     const int ch = have ? fill[xh] : 0, nbh = have ? deg[xh] : 0;
     const bool small = __builtin_amdgcn_ballot_w64(nbh + ch > 32) == 0;
     if (small) {
-        u64 *row = keys + (size_t)xh * R;
+        u64 *row = keys + (size_t)xh * W;
         u64 k = KEY_PAD;
         if (have) {
             if (l32 < nbh) k = row[l32];
@@ -795,7 +795,7 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int R, u64
     for (int h = 0; h < 2; ++h) {
         const long long x = x0 + h;
         if (x >= N) break;
-        u64 *row = keys + (size_t)x * R;
+        u64 *row = keys + (size_t)x * W;
         const int c = fill[x];
         int nd = deg[x];
         if (c > 0) {
@@ -1306,8 +1306,9 @@ static void launch_compact_all(const Workspace &w, long long N, int t_next, hipS
 // second in-edge count, the per-vertex marks, the late arrival numbers and their position masks.  misc: [0] bin cursor, [1] vertices with a bin (union and out-degree cut),
 // [2] bin cursor, [3] vertices with more than R incoming edges (in-degree cut).
 static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use_classes, u64 *keys, int *deg,
-                                 int t_next, hipStream_t st, hipEvent_t e_stop = nullptr)
+                                 int t_next, hipStream_t st, hipEvent_t e_stop = nullptr, int W = 0)
 {
+    if (W == 0) W = R;      // rows are W slots apart; R is Alg. 5's bound on out- and in-degree
     const int vb = vertex_blocks(N), tb = (int)((N + 1023) / 1024);
     int *cnt_in = w.nprop;
     int8_t *cand = w.tcls, *rowflag = w.tcls + N, *mark = w.tcls + 2 * N;
@@ -1316,22 +1317,22 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, 8);
     if (t_next >= 0) hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NDEG);
     // union with reversed edges, out-lists cut to R
-    hipLaunchKernelGGL(k_reverse_scatter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, late, over,
+    hipLaunchKernelGGL(k_reverse_scatter, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, deg, w.fill, w.inbox, late, over,
                        mark);
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.fill, INBOX_CAP, INBOX_CAP, INBOX_CAP,
                        w.binoff, w.misc + 0, w.hubs, w.misc + 1, w.cnt, cnt_in, (u64 *)nullptr, deg, R, cand);
-    hipLaunchKernelGGL(k_reverse_surplus, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, late, over, mark, w.binoff,
+    hipLaunchKernelGGL(k_reverse_surplus, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, late, over, mark, w.binoff,
                        w.bins, w.misc + 1);
-    hipLaunchKernelGGL(k_reverse_merge, dim3((vb + 1) / 2), dim3(BLOCK), 0, st, N, R, keys, deg, w.fill, w.inbox, w.binoff,
+    hipLaunchKernelGGL(k_reverse_merge, dim3((vb + 1) / 2), dim3(BLOCK), 0, st, N, W, R, keys, deg, w.fill, w.inbox, w.binoff,
                        w.bins, cand, cnt_in, rowflag, w.vcls, use_classes);
     // in-lists cut to R; only vertices with more than R incoming edges need a bin
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, cnt_in, R, R, 0, w.binoff, w.misc + 2, w.hubs,
                        w.misc + 3, w.cnt, (int *)nullptr, w.thr, (const int *)nullptr, 0, (int8_t *)nullptr);
-    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, rowflag, w.binoff, w.cnt, w.bins,
+    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, deg, rowflag, w.binoff, w.cnt, w.bins,
                        0u, w.misc + 3);
     hipLaunchKernelGGL(k_incap_threshold, dim3(persistent_blocks()), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 3,
                        cnt_in, w.binoff, w.bins, w.thr);
-    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, R, keys, deg, w.thr, rowflag, w.vcls,
+    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, deg, w.thr, rowflag, w.vcls,
                        use_classes, w.misc + 3);
     if (t_next >= 0) launch_compact_all(w, N, t_next, st, e_stop);
     else if (e_stop) (void)hipEventRecord(e_stop, st);
@@ -1366,12 +1367,15 @@ extern "C" int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, 
     return RNND_OK;
 }
 
-extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
-                             int32_t R, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
-                             int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
+// Alg. 6 with synchronous rounds.  M = slots per row = the bound every UpdateNeighbors merge cuts a list to
+// (M = R: rnnd_build; M > R: rnnd_build_wide, where only AddReverseEdges cuts to R).
+static int build_sync_impl(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+                           int32_t M, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
+                           int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
 {
-    int rc = check_data_args(X, N, d, dtype, metric, R);
+    int rc = check_data_args(X, N, d, dtype, metric, M);
     if (rc) return rc;
+    if (R < 1 || R > M) return RNND_ERR_BAD_PARAM;
     if (!graph_out || !degree_out) return RNND_ERR_NULL;
     if (S < 1 || S > R || (int64_t)S > N - 1 || T1 < 1 || T2 < 1) return RNND_ERR_BAD_PARAM;
     if ((int64_t)T1 * T2 > 1000000) return RNND_ERR_BAD_PARAM;
@@ -1385,9 +1389,9 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
     hipEvent_t *ev = nullptr;
     RoundCtr *hctr = nullptr;
     int n_ev_made = 0;
-    w.bytes = ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
+    w.bytes = ws_layout(w, N, M, n_ctr, true, xs_bytes_for(N, d, variant));
     HIPCHK(hipMalloc((void **)&w.base, w.bytes));
-    ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
+    ws_layout(w, N, M, n_ctr, true, xs_bytes_for(N, d, variant));
     ev = (hipEvent_t *)calloc(n_ev + 1, sizeof(hipEvent_t));
     hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
     if (!ev || !hctr) { rc = RNND_ERR_OOM; goto done; }
@@ -1403,13 +1407,13 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
         if (variant == 2) launch_prepare_u8(w, X, N, d, st);
         if (dtype == RNND_U8)
             hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+                               vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
         else if (dtype == RNND_F16)
             hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+                               vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
         else
             hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+                               vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
         launch_compact_all(w, N, 0, st, stats ? ev[1] : nullptr);
         HIPCHK(hipGetLastError());
         for (int t1 = 0; t1 < T1; ++t1) {
@@ -1422,16 +1426,16 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
                     re.scan_stop = ev[3 + 3 * t];
                     if (t2 == T2 - 1) re.round_stop = ev[4 + 3 * t];
                 }
-                HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, w.keys, w.deg, t, st, re));
+                HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, M, w.keys, w.deg, t, st, re));
             }
             if (t1 != T1 - 1)
-                HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, t, st, stats ? ev[e_rev + t1] : nullptr));
+                HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, t, st, stats ? ev[e_rev + t1] : nullptr, M));
         }
-        hipLaunchKernelGGL(k_export, dim3((unsigned)(((size_t)N * R + 255) / 256)), dim3(256), 0, st, (long long)N, R,
+        hipLaunchKernelGGL(k_export, dim3((unsigned)(((size_t)N * M + 255) / 256)), dim3(256), 0, st, (long long)N, M,
                            w.keys, w.deg, graph_out, degree_out);
         HIPCHK(hipGetLastError());
         if (keys_out)
-            HIPCHK(hipMemcpyAsync(keys_out, w.keys, (size_t)N * R * 8, hipMemcpyDeviceToDevice, st));
+            HIPCHK(hipMemcpyAsync(keys_out, w.keys, (size_t)N * M * 8, hipMemcpyDeviceToDevice, st));
         if (stats) {
             HIPCHK(hipEventRecord(ev[e_end], st));
             HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
@@ -1468,6 +1472,21 @@ done:
     free(hctr);
     if (w.base) (void)hipFree(w.base);
     return rc;
+}
+
+extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
+                             int32_t R, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
+                             int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
+{
+    return build_sync_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, graph_out, degree_out, keys_out, stats, stream);
+}
+
+extern "C" int rnnd_build_wide(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+                               int32_t M, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
+                               int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
+{
+    if (M < 1 || M > RNND_MAX_R) return X ? RNND_ERR_BAD_PARAM : RNND_ERR_NULL;
+    return build_sync_impl(X, N, d, dtype, metric, S, R, M, T1, T2, seed, graph_out, degree_out, keys_out, stats, stream);
 }
 
 extern "C" int rnnd_build(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
@@ -1865,4 +1884,4 @@ extern "C" const char *rnnd_strerror(int status)
     }
 }
 
-extern "C" int rnnd_version(void) { return 104; }
+extern "C" int rnnd_version(void) { return 105; }

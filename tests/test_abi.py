@@ -21,7 +21,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"rnnd_build", "rnnd_build_ex", "rnnd_random_graph", "rnnd_update_neighbors",
             "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search", "rnnd_workspace_bytes",
             "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant", "rnnd_build_blocks",
-            "rnnd_update_neighbors_blocks", "rnnd_probe_gather"} <= set(names)
+            "rnnd_update_neighbors_blocks", "rnnd_probe_gather", "rnnd_build_wide"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -62,6 +62,10 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, one, one, 1, 0, None, None) == -3
     assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, None, one, 1, 4, None, None) == -1
     assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, one, one, 0, 4, None, None) == -3
+    # wide merges: R <= M <= RNND_MAX_R
+    def wide(R, M, X=one):
+        return lib.rnnd_build_wide(X, 100, 16, 0, 0, 4, R, M, 1, 1, 0, one, one, None, None, None)
+    assert wide(8, 7) == -3 and wide(8, 129) == -3 and wide(8, 0) == -3 and wide(8, 16, X=None) == -1
     # the gather probe
     import ctypes as c
     out = c.c_double(0)

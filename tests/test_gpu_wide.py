@@ -1,0 +1,73 @@
+"""rnnd_build_wide against the oracle's build_wide: UpdateNeighbors merges cut to M >= R entries, only
+AddReverseEdges cuts to R (the paper bounds degrees nowhere else).  Exact comparison, M-wide rows."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_util import assert_snapshot_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rn():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2310_20419_amd as m
+    m.load_library()
+    return m
+
+
+def cuda(a):
+    import torch
+    return torch.from_numpy(a).cuda()
+
+
+def _data(kind, n, d, seed):
+    if kind in ("gauss_u8", "unit_f32", "heavy_u8"):
+        return wl.custom(kind, n, d, seed)
+    g = np.random.default_rng(seed)
+    if kind == "dense_u8":          # three tight clusters: lists grow to the cap
+        c = g.integers(20, 236, size=(3, d))
+        return np.clip(c[g.integers(0, 3, size=n)] + g.integers(-9, 10, size=(n, d)), 0, 255).astype(np.uint8)
+    return (g.integers(-2, 3, size=(n, d)) * 0.25).astype(np.float32)
+
+
+CASES = [
+    # kind, N, d, S, R, M, T1, T2
+    ("dense_u8", 900, 64, 8, 12, 128, 3, 3),
+    ("dense_u8", 900, 64, 8, 12, 40, 3, 3),
+    ("dense_u8", 900, 128, 16, 16, 17, 2, 4),
+    ("heavy_u8", 3000, 128, 20, 24, 96, 3, 4),
+    ("gauss_u8", 2000, 33, 6, 8, 64, 3, 3),
+    ("unit_f32", 2500, 96, 10, 12, 96, 3, 3),
+    ("unit_f32", 2500, 96, 10, 12, 128, 2, 3),
+    ("lattice_f32", 800, 16, 10, 16, 100, 3, 2),
+    ("gauss_u8", 1500, 64, 5, 5, 5, 2, 3),
+]
+
+
+@pytest.mark.parametrize("kind,N,d,S,R,M,T1,T2", CASES)
+def test_build_wide_equals_oracle(rn, oracle_mod, kind, N, d, S, R, M, T1, T2):
+    X = _data(kind, N, d, 40 + N + M)
+    isf = X.dtype == np.float32
+    want = oracle_mod.build_wide(X, S, R, M, T1, T2, 13)
+    graph, degree, keys, st = rn.rnnd_build_wide(cuda(X), S, R, M, T1, T2, 13)
+    assert_snapshot_equal(want.snap, isf, keys, degree, "%s N %d R %d M %d" % (kind, N, R, M))
+    assert (graph.cpu().numpy() == want.snap.ids).all()
+    assert list(st.algo_evals[:T1 * T2]) == want.round_evals.tolist()
+    assert list(st.proposals[:T1 * T2]) == want.round_props.tolist()
+    if M == R:
+        g0, d0 = rn.rnnd_build(cuda(X), S, R, T1, T2, 13)
+        assert (g0 == graph).all() and (d0 == degree).all()
+
+
+def test_wide_rows_outgrow_R_and_reverse_edges_cut_them(rn):
+    """Between AddReverseEdges calls a list may exceed R (up to M); right after a call it may not."""
+    X = _data("dense_u8", 900, 64, 3)
+    R, M = 12, 128
+    _, deg_end, _, _ = rn.rnnd_build_wide(cuda(X), 8, R, M, 2, 3, 1)          # ends with UpdateNeighbors rounds
+    assert int(deg_end.max()) > R
+    g, deg1, keys, _ = rn.rnnd_build_wide(cuda(X), 8, R, M, 1, 3, 1)
+    rn.rnnd_add_reverse_edges(keys[:, :M].contiguous(), deg1, M)                # plain call: cap = stride = M
+    assert int(deg1.max()) <= M

@@ -438,6 +438,32 @@ def test_one_block_is_the_synchronous_round_and_n_blocks_the_in_place_order(orac
     assert (d.snap.ids != c.snap.ids).any()
 
 
+@pytest.mark.parametrize("seed,R,M", [(1, 4, 4), (2, 4, 9), (3, 3, 29), (4, 6, 7), (5, 2, 9)])
+def test_wide_merges_against_setwise_model(oracle_mod, seed, R, M):
+    """Merges that cut to M >= R while Alg. 5 cuts to R: the whole build against the dict-based models of
+    one round (cap M) and of AddReverseEdges (cap R); M = R is the synchronous build."""
+    n, S, T1, T2 = 30, min(3, R), 3, 3
+    X = small_u8(n, 2, 300 + seed, 0, 12)
+    D = sqdist_matrix(X)
+    got = oracle_mod.build_wide(X, S, R, M, T1, T2, seed)
+    model = lists_of(oracle_mod.random_graph(X, S, seed, M), n)
+    evals = []
+    for t1 in range(T1):
+        for _ in range(T2):
+            model, ev = py_sync_round(D, model, M)
+            evals.append(ev)
+        if t1 != T1 - 1:
+            model = py_add_reverse(D, model, R)
+    assert lists_of(got.snap, n) == model and got.round_evals.tolist() == evals
+    if M == R:
+        ref = oracle_mod.build_sync(X, S, R, T1, T2, seed)
+        assert (ref.snap.ids == got.snap.ids).all() and (ref.snap.deg == got.snap.deg).all()
+    if (R, M) == (2, 9):
+        # where lists do outgrow R between two AddReverseEdges calls, the wider merges change the graph
+        ref = oracle_mod.build_sync(X, S, R, T1, T2, seed)
+        assert (ref.snap.ids != got.snap.ids[:, :R]).any() or (ref.snap.deg != got.snap.deg).any()
+
+
 def test_bruteforce_knn_matches_numpy(oracle_mod):
     X = small_u8(500, 16, 41)
     Q = small_u8(20, 16, 42)
