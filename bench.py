@@ -114,6 +114,10 @@ def main():
                          "of the rounded data")
     ap.add_argument("--search-sweep", action="store_true",
                     help="search-quality leg over L in {16,32,64,128} x K in {16,...,96, no cap} (Sec. 5.2)")
+    ap.add_argument("--merge-cap", type=int, default=0,
+                    help="rows this many slots wide (R <= M <= 128): UpdateNeighbors merges cut to M, only "
+                         "AddReverseEdges cuts to R (rnnd_build_wide); 0 = fixed-width rows, the build the metric "
+                         "is quoted on")
     ap.add_argument("--blocks", type=int, default=0,
                     help="block-sequential passes with this many runs of consecutive ids per pass "
                          "(rnnd_build_blocks; 0 = the synchronous build the metric is quoted on)")
@@ -157,6 +161,8 @@ def main():
         del a, b
 
     def step():
+        if args.merge_cap:
+            return rn.rnnd_build_wide(Xd, cfg.S, cfg.R, args.merge_cap, cfg.T1, cfg.T2, wl.BUILD_SEED, want_keys=False)
         if args.blocks:
             return rn.rnnd_build_blocks(Xd, cfg.S, cfg.R, cfg.T1, cfg.T2, wl.BUILD_SEED, args.blocks, want_keys=False)
         return rn.rnnd_build_ex(Xd, cfg.S, cfg.R, cfg.T1, cfg.T2, wl.BUILD_SEED, want_keys=False)
@@ -231,7 +237,8 @@ def main():
                                % (cfg.name, cfg.N, cfg.d, cfg.dtype, cfg.S, cfg.R, cfg.T1, cfg.T2, cfg.kind),
                    "kernel_variant": args.variant,
                    "update_order": ("block-sequential, %d runs per pass" % args.blocks) if args.blocks
-                   else "synchronous rounds"},
+                   else "synchronous rounds",
+                   "row_width": args.merge_cap or cfg.R},
         "distance_evals_per_s": algo / (ms_per_step * 1e-3),
         "executed_distance_evals_per_s": execd / (ms_per_step * 1e-3),
         "algorithmic_distance_evals": algo, "executed_distance_evals": execd,
