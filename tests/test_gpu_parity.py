@@ -375,3 +375,23 @@ def test_gather_probe_reports_a_plausible_rate(rn):
         X = torch.zeros((rows, width), dtype=dtype, device="cuda")
         rate = rn.rnnd_probe_gather(X, 2_000_000)
         assert 1.0 < rate < 100_000.0, (rows, width, rate)
+
+
+def test_build_on_a_side_stream_and_repeated_calls(rn):
+    """All work goes to the stream handed in (default priority) and the call returns after it has completed;
+    the result does not depend on the stream, and repeated calls leave nothing behind that changes it."""
+    import torch
+    c = wl.CONFIGS["cfg1"]
+    X = cuda(wl.make_data(c))
+    g0, d0 = rn.rnnd_build(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        g1, d1 = rn.rnnd_build(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+        ids1, _, _ = rn.rnnd_search(X, g1, d1, X[:50].contiguous(), 32, 32, 5, 3)
+    side.synchronize()
+    ids0, _, _ = rn.rnnd_search(X, g0, d0, X[:50].contiguous(), 32, 32, 5, 3)
+    assert (g0 == g1).all() and (d0 == d1).all() and (ids0 == ids1).all()
+    for _ in range(5):
+        g2, d2 = rn.rnnd_build(X, c.S, c.R, c.T1, c.T2, wl.BUILD_SEED)
+    assert (g0 == g2).all() and (d0 == d2).all()
+    assert (ids0[:, 0].cpu() == torch.arange(50, dtype=torch.int32)).all()     # a point's nearest neighbour is itself
