@@ -8,8 +8,8 @@
  * Conventions
  *   - "device" pointers are HIP device memory owned by the caller; the library
  *     never keeps a pointer after a call returns.
- *   - X is row-major N x d, contiguous: uint8, float32, or (RNND_F16) IEEE binary16 as a
- *     storage format for float data -- every coordinate stands for the float32 value it
+ *   - X is row-major N x d, contiguous: uint8, float32, or (RNND_F16, RNND_BF16) IEEE binary16 or
+ *     bfloat16 as a storage format for float data -- every coordinate stands for the float32 value it
  *     converts to exactly, all arithmetic is that of float data, and the graph is the one
  *     rnnd_build gives for that float32 matrix; it halves the bytes the rounds gather.
  *   - vertex ids are 0-based (the paper's V = {1..n}, Sec. 2.2, shifted by one).
@@ -45,7 +45,7 @@ extern "C" {
 #define RNND_MAX_R 128          /* largest supported degree cap R */
 #define RNND_MAX_ROUNDS 256     /* per-round statistics are kept for the first 256 rounds */
 
-typedef enum { RNND_U8 = 0, RNND_F32 = 1, RNND_F16 = 2 } rnnd_dtype;
+typedef enum { RNND_U8 = 0, RNND_F32 = 1, RNND_F16 = 2, RNND_BF16 = 3 } rnnd_dtype;
 typedef enum { RNND_L2SQ = 0 } rnnd_metric;
 
 typedef enum {
@@ -195,7 +195,7 @@ int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t 
  * throughout.  Automatic uses the dense Gram-block kernels on the matrix cores where they apply
  * and the generic kernel otherwise:
  *   uint8 rows with d = 32, 64 or 128: int8 MFMA;
- *   float32 rows with d a multiple of 16, half rows with d a multiple of 32: fp32 MFMA first,
+ *   float32 rows with d a multiple of 16, 16-bit rows with d a multiple of 32: fp32 MFMA first,
  *   every pair whose outcome lies within that block's error bound decided by the exact distance,
  *   and vertices with very many such pairs redone on the f64 MFMA.
  * All give identical graphs; this exists for testing and profiling.  Process-wide, not thread-safe. */

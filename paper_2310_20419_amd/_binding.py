@@ -5,7 +5,7 @@ import ctypes
 import os
 import re
 
-RNND_U8, RNND_F32, RNND_F16 = 0, 1, 2
+RNND_U8, RNND_F32, RNND_F16, RNND_BF16 = 0, 1, 2, 3
 RNND_L2SQ = 0
 RNND_MAX_R = 128
 RNND_MAX_ROUNDS = 256
@@ -140,8 +140,10 @@ def _data_args(X):
         dt = RNND_F32
     elif X.dtype == torch.float16:
         dt = RNND_F16
+    elif X.dtype == torch.bfloat16:
+        dt = RNND_BF16
     else:
-        raise ValueError("X must be uint8, float32 or float16")
+        raise ValueError("X must be uint8, float32, float16 or bfloat16")
     return X.data_ptr(), X.shape[0], X.shape[1], dt
 
 

@@ -2,8 +2,9 @@
 // computed by a group of 8 consecutive lanes; all 8 receive the result.
 //
 //   uint8 rows : exact int32, sum of (a-b)^2 through three byte dot products per word.
-//   half rows  : IEEE binary16 storage; every coordinate stands for the float it converts to exactly,
-//                and the arithmetic is that of float rows (8 coordinates per 16-byte chunk).
+//   16-bit rows: IEEE binary16 (DT_F16) or bfloat16 (DT_BF16) storage; every coordinate stands for the
+//                float it converts to exactly, and the arithmetic is that of float rows (8 coordinates
+//                per 16-byte chunk).
 //   float rows : each lane accumulates (double)(a-b)^2 over its 16-byte chunks in chunk order,
 //                the 8 partial sums are combined in a fixed xor tree, and the double is rounded
 //                once to float.  (a-b)^2 == (b-a)^2 exactly, so delta(a,b) and delta(b,a) are the
@@ -16,9 +17,18 @@
 #define DT_U8 0
 #define DT_F32 1
 #define DT_F16 2
+#define DT_BF16 3
 
 // bytes of one coordinate
-__host__ __device__ constexpr int dt_size(int dt) { return dt == DT_U8 ? 1 : dt == DT_F16 ? 2 : 4; }
+__host__ __device__ constexpr int dt_size(int dt) { return dt == DT_U8 ? 1 : (dt == DT_F16 || dt == DT_BF16) ? 2 : 4; }
+
+// a 16-bit stored coordinate as the float it stands for (exact)
+template <int DT>
+__device__ __forceinline__ float coord16_to_float(unsigned short bits)
+{
+    if (DT == DT_BF16) return __uint_as_float((uint32_t)bits << 16);
+    return (float)__builtin_bit_cast(_Float16, bits);
+}
 
 __device__ __forceinline__ int sqdiff_word_u8(uint32_t a, uint32_t b, int acc)
 {
@@ -57,37 +67,37 @@ __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void 
         acc += __shfl_xor(acc, 2);
         acc += __shfl_xor(acc, 4);
         return (uint32_t)acc;
-    } else if (DT == DT_F16) {
-        const _Float16 *a = (const _Float16 *)pa, *b = (const _Float16 *)pb;
-        typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    } else if (DT == DT_F16 || DT == DT_BF16) {
+        const unsigned short *a = (const unsigned short *)pa, *b = (const unsigned short *)pb;
+        typedef unsigned short us8 __attribute__((ext_vector_type(8)));
         double acc = 0.0;
         if (vec_ok) {
             const int nchunk = d >> 3;
-            const h8 *pa8 = (const h8 *)a, *pb8 = (const h8 *)b;
+            const us8 *pa8 = (const us8 *)a, *pb8 = (const us8 *)b;
             int c = sub;
             for (; c + 8 * (UF - 1) < nchunk; c += 8 * UF) {
-                h8 va[UF], vb[UF];
+                us8 va[UF], vb[UF];
 #pragma unroll
                 for (int k = 0; k < UF; ++k) { va[k] = pa8[c + 8 * k]; vb[k] = pb8[c + 8 * k]; }
 #pragma unroll
                 for (int k = 0; k < UF; ++k)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const double t = (double)(float)va[k][e] - (double)(float)vb[k][e];
+                        const double t = (double)coord16_to_float<DT>(va[k][e]) - (double)coord16_to_float<DT>(vb[k][e]);
                         acc = fma(t, t, acc);
                     }
             }
             for (; c < nchunk; c += 8) {
-                const h8 va = pa8[c], vb = pb8[c];
+                const us8 va = pa8[c], vb = pb8[c];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const double t = (double)(float)va[e] - (double)(float)vb[e];
+                    const double t = (double)coord16_to_float<DT>(va[e]) - (double)coord16_to_float<DT>(vb[e]);
                     acc = fma(t, t, acc);
                 }
             }
         } else {
             for (int e = sub; e < d; e += 8) {
-                const double t = (double)(float)a[e] - (double)(float)b[e];
+                const double t = (double)coord16_to_float<DT>(a[e]) - (double)coord16_to_float<DT>(b[e]);
                 acc = fma(t, t, acc);
             }
         }

@@ -1020,7 +1020,7 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
 static int check_data_args(const void *X, long long N, int d, int dtype, int metric, int R)
 {
     if (!X) return RNND_ERR_NULL;
-    if (dtype != RNND_U8 && dtype != RNND_F32 && dtype != RNND_F16) return RNND_ERR_UNSUPPORTED;
+    if (dtype != RNND_U8 && dtype != RNND_F32 && dtype != RNND_F16 && dtype != RNND_BF16) return RNND_ERR_UNSUPPORTED;
     if (metric != RNND_L2SQ) return RNND_ERR_UNSUPPORTED;
     if (N < 2 || N > 2147483646LL || d < 1) return RNND_ERR_BAD_SHAPE;
     if (dtype == RNND_U8 && d > 33025) return RNND_ERR_BAD_SHAPE;
@@ -1044,7 +1044,7 @@ static int scan_variant_for(const void *X, int d, int dtype)
     if (g_kernel_variant == 1 || !aligned) return 1;
     if (dtype == RNND_U8 && (d == 32 || d == 64 || d == 128)) return 2;
     if (dtype == RNND_F32 && d % 16 == 0) return 3;
-    if (dtype == RNND_F16 && d % 32 == 0) return 3;      // rows of a multiple of 64 bytes
+    if ((dtype == RNND_F16 || dtype == RNND_BF16) && d % 32 == 0) return 3;      // rows of a multiple of 64 bytes
     return 1;
 }
 
@@ -1150,6 +1150,8 @@ static void launch_f32_scan(const Workspace &w, const void *X, int d, int dtype,
     // entries take the four-group kernel, which skips the tiles of the empty group)
     if (dtype == RNND_F16)
         launch_f32_scan_dt<NG, CH, (NRC == 3 ? 4 : NRC), DT_F16>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
+    else if (dtype == RNND_BF16)
+        launch_f32_scan_dt<NG, CH, (NRC == 3 ? 4 : NRC), DT_BF16>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
     else
         launch_f32_scan_dt<NG, CH, NRC, DT_F32>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
 }
@@ -1169,6 +1171,7 @@ static void launch_f32_redo(const Workspace &w, const void *X, int d, int dtype,
                             RoundCtr *c, hipStream_t st, hipEvent_t e_stop)
 {
     if (dtype == RNND_F16) launch_f32_redo_dt<DT_F16>(w, X, d, R, keys, deg, c, st, e_stop);
+    else if (dtype == RNND_BF16) launch_f32_redo_dt<DT_BF16>(w, X, d, R, keys, deg, c, st, e_stop);
     else launch_f32_redo_dt<DT_F32>(w, X, d, R, keys, deg, c, st, e_stop);
 }
 
@@ -1229,6 +1232,9 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
             if (dtype == RNND_F16)
                 hipExtLaunchKernelGGL(k_update_scan<DT_F16>, dim3(pb), dim3(BLOCK), 0, st, nullptr, stop_for(), 0, X, d,
                                       vec_ok, R, keys, deg, w.lists + (size_t)7 * N, &c->n_active[7], w.props, w.nprop, c);
+            else if (dtype == RNND_BF16)
+                hipExtLaunchKernelGGL(k_update_scan<DT_BF16>, dim3(pb), dim3(BLOCK), 0, st, nullptr, stop_for(), 0, X, d,
+                                      vec_ok, R, keys, deg, w.lists + (size_t)7 * N, &c->n_active[7], w.props, w.nprop, c);
             else
                 hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, nullptr, stop_for(), 0, X, d,
                                       vec_ok, R, keys, deg, w.lists + (size_t)7 * N, &c->n_active[7], w.props, w.nprop, c);
@@ -1238,6 +1244,9 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
                               vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);
     } else if (dtype == RNND_F16) {
         hipExtLaunchKernelGGL(k_update_scan<DT_F16>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
+                              vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);
+    } else if (dtype == RNND_BF16) {
+        hipExtLaunchKernelGGL(k_update_scan<DT_BF16>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
                               vec_ok, R, keys, deg, w.lists, &c->n_active[0], w.props, w.nprop, c);
     } else {
         hipExtLaunchKernelGGL(k_update_scan<DT_F32>, dim3(pb), dim3(BLOCK), 0, st, re.scan_start, re.scan_stop, 0, X, d,
@@ -1357,7 +1366,7 @@ static void fill_round_stats(rnnd_stats *s, const RoundCtr *h, int rounds)
 extern "C" int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, size_t *bytes)
 {
     if (!bytes) return RNND_ERR_NULL;
-    if (dtype != RNND_U8 && dtype != RNND_F32 && dtype != RNND_F16) return RNND_ERR_UNSUPPORTED;
+    if (dtype != RNND_U8 && dtype != RNND_F32 && dtype != RNND_F16 && dtype != RNND_BF16) return RNND_ERR_UNSUPPORTED;
     if (N < 2 || N > 2147483646LL || d < 1) return RNND_ERR_BAD_SHAPE;
     if (R < 1 || R > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
     Workspace w;
@@ -1410,6 +1419,9 @@ static int build_sync_impl(const void *X, int64_t N, int32_t d, int dtype, int m
                                vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
         else if (dtype == RNND_F16)
             hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
+                               vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+        else if (dtype == RNND_BF16)
+            hipLaunchKernelGGL(k_random_graph<DT_BF16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
                                vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
         else
             hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
@@ -1559,6 +1571,9 @@ extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype,
         else if (dtype == RNND_F16)
             hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
                                vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+        else if (dtype == RNND_BF16)
+            hipLaunchKernelGGL(k_random_graph<DT_BF16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
+                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
         else
             hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
                                vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
@@ -1630,6 +1645,9 @@ extern "C" int rnnd_random_graph(const void *X, int64_t N, int32_t d, int dtype,
                            S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
     else if (dtype == RNND_F16)
         hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
+                           S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
+    else if (dtype == RNND_BF16)
+        hipLaunchKernelGGL(k_random_graph<DT_BF16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
                            S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
     else
         hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
@@ -1799,6 +1817,8 @@ extern "C" int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int m
             if (L <= 64) RNND_SEARCH_LAUNCH(DT_U8, 1); else RNND_SEARCH_LAUNCH(DT_U8, 2);
         } else if (dtype == RNND_F16) {
             if (L <= 64) RNND_SEARCH_LAUNCH(DT_F16, 1); else RNND_SEARCH_LAUNCH(DT_F16, 2);
+        } else if (dtype == RNND_BF16) {
+            if (L <= 64) RNND_SEARCH_LAUNCH(DT_BF16, 1); else RNND_SEARCH_LAUNCH(DT_BF16, 2);
         } else {
             if (L <= 64) RNND_SEARCH_LAUNCH(DT_F32, 1); else RNND_SEARCH_LAUNCH(DT_F32, 2);
         }
@@ -1884,4 +1904,4 @@ extern "C" const char *rnnd_strerror(int status)
     }
 }
 
-extern "C" int rnnd_version(void) { return 105; }
+extern "C" int rnnd_version(void) { return 106; }

@@ -84,18 +84,18 @@ __device__ __forceinline__ u32 transpose16_bits_x2(u32 w, int lane)
 template <bool FAST> struct GramAcc { typedef v4d type; };
 template <> struct GramAcc<true> { typedef v4f type; };
 
-// A lane's load is 16 bytes of a row: 4 float coordinates, or 8 half coordinates (DT_F16: IEEE binary16
+// A lane's load is 16 bytes of a row: 4 float coordinates, or 8 16-bit coordinates (DT_F16: IEEE binary16, DT_BF16: bfloat16
 // storage, each coordinate standing for the float it converts to exactly).  Coordinate t of such a load:
 template <int DT>
 __device__ __forceinline__ float chunk_coord(const uint4 &raw, int t)
 {
-    if (DT == DT_F16) {
+    if (DT == DT_F16 || DT == DT_BF16) {
         const u32 w = (t >> 1) == 0 ? raw.x : (t >> 1) == 1 ? raw.y : (t >> 1) == 2 ? raw.z : raw.w;
-        return (float)__builtin_bit_cast(_Float16, (unsigned short)((t & 1) ? (w >> 16) : (w & 0xFFFFu)));
+        return coord16_to_float<DT>((unsigned short)((t & 1) ? (w >> 16) : (w & 0xFFFFu)));
     }
     return __uint_as_float(t == 0 ? raw.x : t == 1 ? raw.y : t == 2 ? raw.z : raw.w);
 }
-template <int DT> struct ChunkCoords { static constexpr int n = DT == DT_F16 ? 8 : 4; };
+template <int DT> struct ChunkCoords { static constexpr int n = (DT == DT_F16 || DT == DT_BF16) ? 8 : 4; };
 
 // One chunk (64 bytes of every row: lane (r16, q) holds bytes 16 q .. 16 q + 15 of row r16 of every group)
 // into the norms and the Gram tiles.  The matrix instruction multiplies, for each of its 4 k slots, what
@@ -141,7 +141,7 @@ __device__ __forceinline__ void gram_chunk(const uint4 (&x)[NR][CH], ACC (&acc)[
             }
             // half rows: eight coordinates per load; keep the conversions of one step next to its matrix
             // instructions instead of letting all eight steps' worth pile up in registers
-            if (DT == DT_F16) __builtin_amdgcn_sched_barrier(0);
+            if (DT == DT_F16 || DT == DT_BF16) __builtin_amdgcn_sched_barrier(0);
         }
 }
 
@@ -240,7 +240,7 @@ __device__ __forceinline__ int popc_below(u64 m0, u64 m1, int p)   // set bits o
 // NRC = 16-row groups of the list (lists of at most 16 NRC entries); NG = ceil(NRC / 2) names the
 // degree class family; CH = 64-byte chunks of every row fetched per loop iteration (rows a multiple of
 // 64 CH bytes: a longer iteration gives the prefetch more matrix work to hide behind); DT = DT_F32 or
-// DT_F16 (half-precision storage of the same kind of rows).
+// DT_F16 / DT_BF16 (16-bit storage of the same kind of rows).
 // FAST: the Gram block in single precision (gram_f32_loop).  A pair is then decided only if the outcome of
 // the prune test is beyond the error bound of that block, eps_ij = (1.25 d + 8) 2^-24 (n_i + n_j), which
 // covers the accumulation (2 x 1.01 d 2^-24 sqrt(n_i n_j) <= 1.01 d 2^-24 (n_i + n_j)) and the roundings of

@@ -47,7 +47,7 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert call(N=1) == -2 and call(d=0) == -2 and call(d=33026) == -2 and call(N=2**31 - 1) == -2
     assert call(S=0) == -3 and call(S=9) == -3 and call(R=0) == -3 and call(R=129) == -3
     assert call(T1=0) == -3 and call(T2=0) == -3 and call(N=5, S=5, R=8) == -3
-    assert call(dtype=3) == -4 and call(dtype=-1) == -4 and call(metric=1) == -4
+    assert call(dtype=4) == -4 and call(dtype=-1) == -4 and call(metric=1) == -4
     assert call(N=50_000_000, R=128, S=4) == -2          # N*R does not fit the 32-bit slot counters
     assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(3) == -3
     assert lib.rnnd_set_kernel_variant(0) == 0
@@ -58,7 +58,7 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
                                      a["T2"], 0, a.get("blocks", 4), a.get("g", one), a.get("deg", one), None, None,
                                      None)
     assert blocks(blocks=0) == -3 and blocks(blocks=101) == -3 and blocks(X=None) == -1 and blocks(g=None) == -1
-    assert blocks(T1=400, T2=400, blocks=100) == -3 and blocks(S=0) == -3 and blocks(dtype=3) == -4
+    assert blocks(T1=400, T2=400, blocks=100) == -3 and blocks(S=0) == -3 and blocks(dtype=4) == -4
     assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, one, one, 1, 0, None, None) == -3
     assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, None, one, 1, 4, None, None) == -1
     assert lib.rnnd_update_neighbors_blocks(one, 100, 16, 0, 0, 8, one, one, 0, 4, None, None) == -3
@@ -83,7 +83,7 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert search(L=0) == -3 and search(L=129) == -3 and search(K=0) == -3 and search(k=0) == -3
     assert search(k=17) == -3 and search(W=0) == -3 and search(nq=-1) == -2
     assert search(X=None) == -1 and search(g=None) == -1 and search(dg=None) == -1 and search(Q=None) == -1
-    assert search(out=None) == -1 and search(dtype=3) == -4
+    assert search(out=None) == -1 and search(dtype=4) == -4
 
 
 def test_workspace_bytes(lib):

@@ -1,6 +1,6 @@
-"""Half-precision storage (RNND_F16): every coordinate stands for the float32 value it converts to exactly,
-so the expected graph is the oracle's on the widened matrix -- ids, distances (float32 bits), flags, degrees,
-evaluation counts; search likewise."""
+"""16-bit storage (RNND_F16: IEEE half, RNND_BF16: bfloat16): every coordinate stands for the float32 value it
+converts to exactly, so the expected graph is the oracle's on the widened matrix -- ids, distances (float32
+bits), flags, degrees, evaluation counts; search likewise."""
 import numpy as np
 import pytest
 
@@ -93,3 +93,30 @@ def test_blocks_and_steps_on_half_rows(rn, oracle_mod):
     st = rn.rnnd_update_neighbors(cuda(X16), k2, d2, 40, 1)
     assert_snapshot_equal(snap, True, k2, d2, "half rows, one round")
     assert st.algo_evals[0] == evals and st.proposals[0] == props
+
+
+BF_CASES = [
+    ("unit", 3000, 96, 20, 96, 2, 4),
+    ("beta", 1000, 960, 8, 24, 2, 3),
+    ("gauss", 1500, 40, 10, 33, 2, 3),
+    ("gauss", 900, 12, 5, 9, 2, 3),
+    ("lattice", 1500, 32, 30, 96, 2, 2),
+    ("unit", 2000, 160, 40, 128, 2, 2),
+]
+
+
+@pytest.mark.parametrize("kind,N,d,S,R,T1,T2", BF_CASES)
+def test_build_on_bfloat16_rows(rn, oracle_mod, variant, kind, N, d, S, R, T1, T2):
+    import torch
+    if variant == 2 and d % 32 != 0:
+        pytest.skip("no matrix-core scan for this row length")
+    Xb = torch.from_numpy(_half(kind, N, d, 500 + N + d).astype(np.float32)).to(torch.bfloat16).cuda()
+    X = Xb.float().cpu().numpy()                    # exact widening
+    want = oracle_mod.build_sync(X, S, R, T1, T2, 22)
+    graph, degree, keys, st = rn.rnnd_build_ex(Xb, S, R, T1, T2, 22)
+    assert_snapshot_equal(want.snap, True, keys, degree, "bf16 %s N %d d %d" % (kind, N, d))
+    assert list(st.algo_evals[:T1 * T2]) == want.round_evals.tolist()
+    Qb = torch.from_numpy(_half(kind, 9, d, 8).astype(np.float32)).to(torch.bfloat16).cuda()
+    found, _, evals = rn.rnnd_search(Xb, graph, degree, Qb, 32, 16, 10, 3)
+    wfound, wevals = oracle_mod.search(X, want.snap.ids, want.snap.deg, Qb.float().cpu().numpy(), 32, 16, 10, 3)
+    assert (found.cpu().numpy() == wfound).all() and evals == wevals
