@@ -131,7 +131,8 @@ int rnnd_update_neighbors_blocks(const void *X, int64_t N, int32_t d, int dtype,
                                  uint64_t *keys, int32_t *deg, int32_t n_passes, int64_t blocks,
                                  rnnd_stats *stats, void *stream);
 
-/* Bytes of device workspace rnnd_build allocates (and frees) internally for these sizes. */
+/* Bytes of device workspace rnnd_build allocates (and frees) internally for these sizes (an upper
+ * bound; for rnnd_build_wide pass M as R). */
 int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, size_t *bytes);
 
 /* RandomGraph(S) (first step of Alg. 6): row u <- S distinct ids != u drawn from a counter-based
