@@ -40,6 +40,8 @@ struct alignas(16) F32ScanSmem {
     int pos[16 * NRC];      // list position by slot
     u32 pv[16 * NRC];       // redirected entries: slot of v ...
     u32 pw[16 * NRC];       // ... and of the w it failed against
+    float nrmf[16 * NRC];   // n by slot, rounded to float (single-precision form)
+    float distf[16 * NRC];  // delta(u, .) by slot
     uint16_t amb[F32_AMB_CAP];   // undecided pairs: row slot << 8 | column slot; bit 15 <- the exact outcome
 };
 
@@ -242,9 +244,10 @@ __device__ __forceinline__ int popc_below(u64 m0, u64 m1, int p)   // set bits o
 // 64 CH bytes: a longer iteration gives the prefetch more matrix work to hide behind); DT = DT_F32 or
 // DT_F16 / DT_BF16 (16-bit storage of the same kind of rows).
 // FAST: the Gram block in single precision (gram_f32_loop).  A pair is then decided only if the outcome of
-// the prune test is beyond the error bound of that block, eps_ij = (1.25 d + 8) 2^-24 (n_i + n_j), which
-// covers the accumulation (2 x 1.01 d 2^-24 sqrt(n_i n_j) <= 1.01 d 2^-24 (n_i + n_j)) and the roundings of
-// delta(v,w) to float on either side (delta <= 2 (n_i + n_j)); the few undecided pairs get the exact
+// the prune test is beyond the error bound of that block, eps_ij = (1.25 d + 16) 2^-24 (n_i + n_j), which
+// covers the accumulation (2 x 1.01 d 2^-24 sqrt(n_i n_j) <= 1.01 d 2^-24 (n_i + n_j)), the evaluation of
+// n_i + n_j - 2 G_ij in float from norms rounded to float (at most 4 x 2^-24 (n_i + n_j)) and the roundings
+// of delta(v,w) to float on either side (delta <= 2 (n_i + n_j)); the few undecided pairs get the exact
 // delta(v,w) from the routine every stored distance comes from, so the decisions are those of the
 // reference arithmetic.  A vertex with more than F32_AMB_CAP undecided pairs (ties in bulk: duplicates,
 // lattices) is left untouched and appended to `redo`, which the double-precision form (FAST = false)
@@ -256,7 +259,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
     int *__restrict__ nprop, RoundCtr *__restrict__ ctr, int *__restrict__ redo, u32 *__restrict__ n_redo)
 {
     typedef typename GramAcc<FAST>::type acc_t;
-    const double epsk = (1.25 * (double)d + 8.0) * 5.9604644775390625e-08;
+    const double epsk = (1.25 * (double)d + 16.0) * 5.9604644775390625e-08;
     constexpr int NT = NRC * (NRC + 1) / 2;
     constexpr int NWD = (NRC + 1) / 2;        // 32-bit words of a mask over slots
     constexpr int NSET = NRC > 4 ? 2 : 1;     // lane (r16, q) owns rows 16 q + r16 and, if NRC > 4, 64 + 16 q + r16
@@ -313,9 +316,11 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
                     const int s = isnew ? popc_below(new0, new1, p) : n_new + popc_below(old0, old1, p);
                     sm.key[s] = kreg[h];
                     sm.pos[s] = p;
+                    sm.distf[s] = __uint_as_float(key_dist(kreg[h]));
                 } else if (p < 16 * NRC) {
                     sm.key[p] = 0;      // slots past the list: vertex 0, never tested
                     sm.pos[p] = p;
+                    sm.distf[p] = 0.f;
                 }
             }
             rows += m;
@@ -368,7 +373,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
             for (int g = 0; g < NRC; ++g) {
                 nr[g] += __shfl_xor(nr[g], 16);
                 nr[g] += __shfl_xor(nr[g], 32);     // n of slot 16 g + r16, in all four quarter-waves
-                if (q == 0) sm.nrm[16 * g + r16] = nr[g];
+                if (q == 0) { sm.nrm[16 * g + r16] = nr[g]; sm.nrmf[16 * g + r16] = (float)nr[g]; }
             }
             wave_sync();
 
@@ -376,8 +381,18 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
             // group I as the tested row, bit c = column slot c of group J.  FB[t] (I != J): lane r16 = slot r16
             // of group J as the tested row, bit c = column slot c of group I.  (Same in all quarter-waves.)
             u32 FA[NT], FB[NT];
+            const float epskf = (float)epsk;
 #pragma unroll
             for (int I = 0; I < NRC; ++I) {
+                // single-precision form: the rows of group I that this lane's accumulators stand for
+                float nIf[4], dIf[4];
+                if (FAST) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        nIf[v] = sm.nrmf[16 * I + 4 * q + v];
+                        dIf[v] = sm.distf[16 * I + 4 * q + v];
+                    }
+                }
 #pragma unroll
                 for (int J = 0; J <= I; ++J) {
                     const int t = I * (I + 1) / 2 + J;
@@ -386,22 +401,35 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
                     if ((need >> t) & 1u) {     // wave-uniform
                         // lane = slot r16 of group J; accumulator v = slot 4v + q of group I (4q + v in the
                         // single-precision instruction).  Low half of a word: the test fires; high half: undecided.
-                        const float dj = __uint_as_float(key_dist(sm.key[16 * J + r16]));
                         u32 fa = 0, fb = 0;
+                        if constexpr (FAST) {
+                            // all in float: the evaluation adds at most 4 x 2^-24 (n_i + n_j) to the error of
+                            // delta(v,w), which the bound's constant covers
+                            const float dj = sm.distf[16 * J + r16];
+                            const float nJf = (float)nr[J];
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int rsel = FAST ? 4 * q + v : 4 * v + q;
-                            const int si = 16 * I + rsel;
-                            const double nsum = sm.nrm[si] + nr[J];
-                            const double dvwd = nsum - 2.0 * (double)acc[t][v];
-                            const float dvw = (float)dvwd;
-                            const float di = __uint_as_float(key_dist(sm.key[si]));
-                            fa |= (di >= dvw) ? (1u << rsel) : 0u;
-                            fb |= (dj >= dvw) ? (1u << rsel) : 0u;
-                            if (FAST) {
-                                const double tol = epsk * nsum;
-                                fa |= !(fabs((double)di - dvwd) > tol) ? (0x10000u << rsel) : 0u;      // also when not finite
-                                fb |= !(fabs((double)dj - dvwd) > tol) ? (0x10000u << rsel) : 0u;
+                            for (int v = 0; v < 4; ++v) {
+                                const int rsel = 4 * q + v;
+                                const float nsum = nIf[v] + nJf;
+                                const float dvw = fmaf(-2.f, acc[t][v], nsum);
+                                const float tol = epskf * nsum;
+                                const float ta = dIf[v] - dvw, tb = dj - dvw;
+                                fa |= (ta >= 0.f) ? (1u << rsel) : 0u;
+                                fb |= (tb >= 0.f) ? (1u << rsel) : 0u;
+                                fa |= !(fabsf(ta) > tol) ? (0x10000u << rsel) : 0u;      // also when not finite
+                                fb |= !(fabsf(tb) > tol) ? (0x10000u << rsel) : 0u;
+                            }
+                        } else {
+                            const float dj = __uint_as_float(key_dist(sm.key[16 * J + r16]));
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) {
+                                const int rsel = 4 * v + q;
+                                const int si = 16 * I + rsel;
+                                const double dvwd = sm.nrm[si] + nr[J] - 2.0 * (double)acc[t][v];
+                                const float dvw = (float)dvwd;
+                                const float di = __uint_as_float(key_dist(sm.key[si]));
+                                fa |= (di >= dvw) ? (1u << rsel) : 0u;
+                                fb |= (dj >= dvw) ? (1u << rsel) : 0u;
                             }
                         }
                         fa |= (u32)__shfl_xor((int)fa, 16);
