@@ -1146,14 +1146,16 @@ template <int NG, int CH, int NRC>
 static void launch_f32_scan(const Workspace &w, const void *X, int d, int dtype, int R, u64 *keys, int *deg,
                             long long N, RoundCtr *c, int cls, hipStream_t st, hipEvent_t e_start, hipEvent_t e_stop)
 {
-    // (half rows: the three-group shape compiles badly -- thousands of spilled registers -- so lists of 33..48
-    // entries take the four-group kernel, which skips the tiles of the empty group)
+    // (the three-group shape compiles badly -- with some versions of this code to thousands of spilled
+    // registers -- so lists of 33..48 entries take the four-group kernel, which skips the tiles of the empty
+    // group; the shape is not instantiated at all)
+    constexpr int NRK = NRC == 3 ? 4 : NRC;
     if (dtype == RNND_F16)
-        launch_f32_scan_dt<NG, CH, (NRC == 3 ? 4 : NRC), DT_F16>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
+        launch_f32_scan_dt<NG, CH, NRK, DT_F16>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
     else if (dtype == RNND_BF16)
-        launch_f32_scan_dt<NG, CH, (NRC == 3 ? 4 : NRC), DT_BF16>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
+        launch_f32_scan_dt<NG, CH, NRK, DT_BF16>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
     else
-        launch_f32_scan_dt<NG, CH, NRC, DT_F32>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
+        launch_f32_scan_dt<NG, CH, NRK, DT_F32>(w, X, d, R, keys, deg, N, c, cls, st, e_start, e_stop);
 }
 
 // The double-precision form (in its widest shape: lists of up to 96 entries) over the round's redo list.

@@ -83,8 +83,8 @@ __device__ __forceinline__ u32 transpose16_bits_x2(u32 w, int lane)
     return w;
 }
 
-template <bool FAST> struct GramAcc { typedef v4d type; };
-template <> struct GramAcc<true> { typedef v4f type; };
+template <bool FAST> struct GramAcc { typedef v4d type; typedef double norm; };
+template <> struct GramAcc<true> { typedef v4f type; typedef float norm; };
 
 // A lane's load is 16 bytes of a row: 4 float coordinates, or 8 16-bit coordinates (DT_F16: IEEE binary16, DT_BF16: bfloat16
 // storage, each coordinate standing for the float it converts to exactly).  Coordinate t of such a load:
@@ -104,8 +104,8 @@ template <int DT> struct ChunkCoords { static constexpr int n = (DT == DT_F16 ||
 // lane quarter q supplies for the row with what it supplies for the column: the same coordinate of both,
 // whichever coordinate that is.  ACC = v4f: v_mfma_f32_16x16x4_f32 on the floats; v4d: the f64 instruction.
 // TM != 0: the tiles to compute are fixed at compile time (bit I(I+1)/2 + J of TM); TM == 0: bit of `need`.
-template <int NR, int CH, u32 TM, int DT, typename ACC>
-__device__ __forceinline__ void gram_chunk(const uint4 (&x)[NR][CH], ACC (&acc)[NR * (NR + 1) / 2], double (&nr)[NR], u32 need)
+template <int NR, int CH, u32 TM, int DT, typename ACC, typename NRT>
+__device__ __forceinline__ void gram_chunk(const uint4 (&x)[NR][CH], ACC (&acc)[NR * (NR + 1) / 2], NRT (&nr)[NR], u32 need)
 {
 #pragma unroll
     for (int j = 0; j < CH; ++j)
@@ -116,8 +116,7 @@ __device__ __forceinline__ void gram_chunk(const uint4 (&x)[NR][CH], ACC (&acc)[
 #pragma unroll
                 for (int g = 0; g < NR; ++g) {
                     a[g] = chunk_coord<DT>(x[g][j], t);
-                    const double ad = (double)a[g];
-                    nr[g] = fma(ad, ad, nr[g]);
+                    nr[g] = fmaf(a[g], a[g], nr[g]);      // float: its error is part of the bound
                 }
 #pragma unroll
                 for (int I = 0; I < NR; ++I)
@@ -175,20 +174,20 @@ __device__ __forceinline__ void gram_f64_loop(const char *const (&rp)[NR], int n
 #pragma unroll
             for (int j = 0; j < CH; ++j) x[g][j] = *(const uint4 *)(rp[g] + 64 * (CH * cn + j));
         __builtin_amdgcn_sched_barrier(0);
-        gram_chunk<NR, CH, TM, DT, v4d>(xc, acc, nr, need);
+        gram_chunk<NR, CH, TM, DT, v4d, double>(xc, acc, nr, need);
     }
 }
 
 // Single-precision form: the coordinates go to v_mfma_f32_16x16x4_f32 as floats (twice the rate of the
 // double-precision instruction, half the accumulator registers).  That instruction adds its four products
 // one after the other, each product exact and each sum rounded to nearest, so after d dimensions
-// |G - G_exact| <= d 2^-24 sum_k |x_ik x_jk| (1 + 2 d 2^-24) <= 1.01 d 2^-24 sqrt(n_i n_j).  The norms stay
-// in double.  Three buffers in rotation: while the matrix cores work on one chunk, the loads of the next
+// |G - G_exact| <= d 2^-24 sum_k |x_ik x_jk| (1 + 2 d 2^-24) <= 1.01 d 2^-24 sqrt(n_i n_j).  The norms are
+// summed in float as well (each lane a quarter of the coordinates).  Three buffers in rotation: while the matrix cores work on one chunk, the loads of the next
 // two are in flight (the instruction is fast enough that one chunk of lead does not cover the latency of
 // the gathers).  Loads past the end re-read the last chunk.
 template <int NR, int CH, u32 TM, int DT>
 __device__ __forceinline__ void gram_f32_loop(const char *const (&rp)[NR], int nchunk, v4f (&acc)[NR * (NR + 1) / 2],
-                                              double (&nr)[NR], u32 need)
+                                              float (&nr)[NR], u32 need)
 {
     uint4 x0[NR][CH], x1[NR][CH], x2[NR][CH];
     const int last = nchunk - 1;
@@ -205,18 +204,18 @@ __device__ __forceinline__ void gram_f32_loop(const char *const (&rp)[NR], int n
     for (int c = 0; c < nchunk; c += 3) {
         fetch(x2, c + 2);
         __builtin_amdgcn_sched_barrier(0);
-        gram_chunk<NR, CH, TM, DT, v4f>(x0, acc, nr, need);
+        gram_chunk<NR, CH, TM, DT, v4f, float>(x0, acc, nr, need);
         __builtin_amdgcn_sched_barrier(0);
         if (c + 1 < nchunk) {
             fetch(x0, c + 3);
             __builtin_amdgcn_sched_barrier(0);
-            gram_chunk<NR, CH, TM, DT, v4f>(x1, acc, nr, need);
+            gram_chunk<NR, CH, TM, DT, v4f, float>(x1, acc, nr, need);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (c + 2 < nchunk) {
             fetch(x1, c + 4);
             __builtin_amdgcn_sched_barrier(0);
-            gram_chunk<NR, CH, TM, DT, v4f>(x2, acc, nr, need);
+            gram_chunk<NR, CH, TM, DT, v4f, float>(x2, acc, nr, need);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -244,9 +243,9 @@ __device__ __forceinline__ int popc_below(u64 m0, u64 m1, int p)   // set bits o
 // 64 CH bytes: a longer iteration gives the prefetch more matrix work to hide behind); DT = DT_F32 or
 // DT_F16 / DT_BF16 (16-bit storage of the same kind of rows).
 // FAST: the Gram block in single precision (gram_f32_loop).  A pair is then decided only if the outcome of
-// the prune test is beyond the error bound of that block, eps_ij = (1.25 d + 16) 2^-24 (n_i + n_j), which
-// covers the accumulation (2 x 1.01 d 2^-24 sqrt(n_i n_j) <= 1.01 d 2^-24 (n_i + n_j)), the evaluation of
-// n_i + n_j - 2 G_ij in float from norms rounded to float (at most 4 x 2^-24 (n_i + n_j)) and the roundings
+// the prune test is beyond the error bound of that block, eps_ij = (1.5 d + 20) 2^-24 (n_i + n_j), which
+// covers the accumulation of G (2 x 1.01 d 2^-24 sqrt(n_i n_j) <= 1.01 d 2^-24 (n_i + n_j)), the norms summed
+// in float (d / 4 + 2 roundings per norm), the evaluation of n_i + n_j - 2 G_ij in float and the roundings
 // of delta(v,w) to float on either side (delta <= 2 (n_i + n_j)); the few undecided pairs get the exact
 // delta(v,w) from the routine every stored distance comes from, so the decisions are those of the
 // reference arithmetic.  A vertex with more than F32_AMB_CAP undecided pairs (ties in bulk: duplicates,
@@ -259,7 +258,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
     int *__restrict__ nprop, RoundCtr *__restrict__ ctr, int *__restrict__ redo, u32 *__restrict__ n_redo)
 {
     typedef typename GramAcc<FAST>::type acc_t;
-    const double epsk = (1.25 * (double)d + 16.0) * 5.9604644775390625e-08;
+    const double epsk = (1.5 * (double)d + 20.0) * 5.9604644775390625e-08;
     constexpr int NT = NRC * (NRC + 1) / 2;
     constexpr int NWD = (NRC + 1) / 2;        // 32-bit words of a mask over slots
     constexpr int NSET = NRC > 4 ? 2 : 1;     // lane (r16, q) owns rows 16 q + r16 and, if NRC > 4, 64 + 16 q + r16
@@ -338,9 +337,9 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
             acc_t acc[NT];
 #pragma unroll
             for (int t = 0; t < NT; ++t) acc[t] = (acc_t)(0);
-            double nr[NRC];
+            typename GramAcc<FAST>::norm nr[NRC];
 #pragma unroll
-            for (int g = 0; g < NRC; ++g) nr[g] = 0.0;
+            for (int g = 0; g < NRC; ++g) nr[g] = 0;
             u32 need = 0;
 #pragma unroll
             for (int I = 0; I < NRC; ++I)
@@ -373,7 +372,10 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
             for (int g = 0; g < NRC; ++g) {
                 nr[g] += __shfl_xor(nr[g], 16);
                 nr[g] += __shfl_xor(nr[g], 32);     // n of slot 16 g + r16, in all four quarter-waves
-                if (q == 0) { sm.nrm[16 * g + r16] = nr[g]; sm.nrmf[16 * g + r16] = (float)nr[g]; }
+                if (q == 0) {
+                    if (FAST) sm.nrmf[16 * g + r16] = (float)nr[g];
+                    else sm.nrm[16 * g + r16] = (double)nr[g];
+                }
             }
             wave_sync();
 
