@@ -4,11 +4,11 @@
 // gathered straight into MFMA operand registers (lane l: row l%32 of a 32-row group, bytes
 // [32s + 16(l/32), +16) of K-step s) from a copy of X made once per build in which every byte is
 // the int8 x-128 (this leaves every difference, hence every delta, unchanged).  n_v = |x_v - 128|^2
-// is read off the diagonal of the Gram tile of v's block (one more pass of the same MFMAs).
+// is read off the diagonal of the Gram tile of v's block with itself.
 // For a block I of 32 list positions (rows v_i) and a block J <= I (candidates w_j) the tile
 //     T_ij = 2 <x_i, x_j> - n_j - t_i ,   t_i = n_i - delta(u, v_i)
-// is formed by v_mfma_i32_32x32x32_i8 with the accumulator started at -n_j - t_i and every K-step
-// issued twice.  The first operand is block J, the second block I, so a lane holds ROW i = l%32 of the tile
+// is formed from the Gram tile G(I, J) of v_mfma_i32_32x32x32_i8 (for J = I the one that gave the norms) by
+// one shift-add per entry.  The first operand is block J, the second block I, so a lane holds ROW i = l%32 of the tile
 // and 16 of its columns, j = 8(a/4) + 4(l/32) + a%4: by the symmetry of the Gram matrix no transpose
 // is needed.  Both operands use the same byte order, so however the hardware pairs the K bytes, the
 // two sides pair alike.  With delta(v_i, w_j) = n_i + n_j - 2<x_i, x_j> (exact in int32):
@@ -123,32 +123,7 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
     wave_sync();   // the previous vertex is done with the LDS tables
     if (lane < 32 * NG) sm.id[lane] = (int)key_id(kreg[0]);
     if (NG > 2 && lane + 64 < 32 * NG) sm.id[64 + lane] = (int)key_id(kreg[1]);
-    // n of every list entry: the diagonal of its block's Gram tile, through LDS (rows past the list
-    // are zero rows that no mask ever selects)
-    int nr[NG];
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        nr[g] = 0;
-        if (32 * g < m) {                   // wave-uniform
-            v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-            for (int s = 0; s < KS; ++s)
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[g][s], A[g][s], acc, 0, 0, 0);
-            int4 *gt = (int4 *)(sm.gt + (32 * g + l32) * GT_STRIDE + 4 * half);
-            gt[0] = make_int4(acc[0], acc[1], acc[2], acc[3]);
-            gt[2] = make_int4(acc[4], acc[5], acc[6], acc[7]);
-            gt[4] = make_int4(acc[8], acc[9], acc[10], acc[11]);
-            gt[6] = make_int4(acc[12], acc[13], acc[14], acc[15]);
-        }
-    }
-    wave_sync();
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        if (32 * g < m) nr[g] = sm.gt[(32 * g + l32) * GT_STRIDE + l32];
-        if (half == 0) sm.nrm[32 * g + l32] = nr[g];
-    }
     rows += m;
-    wave_sync();
     const u32 hm = 0x0F0F0F0Fu << (4 * half);   // the columns this half-wave holds
 
     u32 Kw[NG];                             // U' as bit masks over list positions, 32 per word (uniform)
@@ -157,13 +132,29 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
     for (int I = 0; I < NG; ++I) {
         Kw[I] = 0;
         if (32 * I < m) {                   // wave-uniform
+            // the Gram tile of the block with itself; n of its rows is the diagonal, read back through
+            // LDS (rows past the list are zero rows that no mask ever selects)
+            v16i G = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < KS; ++s) G = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[I][s], A[I][s], G, 0, 0, 0);
+            {
+                int4 *gt = (int4 *)(sm.gt + (32 * I + l32) * GT_STRIDE + 4 * half);
+                gt[0] = make_int4(G[0], G[1], G[2], G[3]);
+                gt[2] = make_int4(G[4], G[5], G[6], G[7]);
+                gt[4] = make_int4(G[8], G[9], G[10], G[11]);
+                gt[6] = make_int4(G[12], G[13], G[14], G[15]);
+            }
+            wave_sync();
+            const int nrI = sm.gt[(32 * I + l32) * GT_STRIDE + l32];
+            if (half == 0) sm.nrm[32 * I + l32] = nrI;
+            wave_sync();
             // this block's rows in lane-per-row form (lane l32 <-> list position 32 I + l32), in both halves
             const u64 kb = shfl_u64(kreg[I >> 1], 32 * (I & 1) + l32);
             const int posi = 32 * I + l32;
             const bool validi = posi < m;
             const bool newi = kb & 1ull;
             const int di = (int)key_dist(kb);
-            const int negt = di - nr[I];
+            const int negt = di - nrI;
             const u32 new_I = (u32)(newm[I >> 1] >> (32 * (I & 1)));
             u32 F[NG], E[NG];
 #pragma unroll
@@ -180,19 +171,20 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
                 if (!validi) e = 0;
                 E[J] = e & hm;
                 // lane: row l32 of block I; acc[a]: column 8(a/4) + 4 half + a%4 of block J
-                v16i acc;
+                v16i acc = G;
+                if (J < I) {
+                    acc = (v16i){0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int s = 0; s < KS; ++s)
+                        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[J][s], A[I][s], acc, 0, 0, 0);
+                }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int4 nj = ((const int4 *)sm.nrm)[8 * J + 2 * q + half];
-                    acc[4 * q + 0] = negt - nj.x;
-                    acc[4 * q + 1] = negt - nj.y;
-                    acc[4 * q + 2] = negt - nj.z;
-                    acc[4 * q + 3] = negt - nj.w;
-                }
-#pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[J][s], A[I][s], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[J][s], A[I][s], acc, 0, 0, 0);
+                    acc[4 * q + 0] = (acc[4 * q + 0] << 1) + (negt - nj.x);
+                    acc[4 * q + 1] = (acc[4 * q + 1] << 1) + (negt - nj.y);
+                    acc[4 * q + 2] = (acc[4 * q + 2] << 1) + (negt - nj.z);
+                    acc[4 * q + 3] = (acc[4 * q + 3] << 1) + (negt - nj.w);
                 }
                 int4 *gt = (int4 *)(sm.gt + (32 * J + l32) * GT_STRIDE + 4 * half);
                 gt[0] = make_int4(acc[0], acc[1], acc[2], acc[3]);
@@ -401,15 +393,16 @@ __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[K
     if (half == 0) sm.id[l32] = (int)key_id(kb);
     // n of every row: the diagonal of the Gram tile, through LDS (rows past a list are zero rows
     // that no mask ever selects)
-    {
-        v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    // lane: row l32; G[a]: <x_row, x_col> for column 8(a/4) + 4 half + a%4
+    v16i G = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[s], A[s], acc, 0, 0, 0);
+    for (int s = 0; s < KS; ++s) G = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[s], A[s], G, 0, 0, 0);
+    {
         int4 *gt = (int4 *)(sm.gt + l32 * GT_STRIDE + 4 * half);
-        gt[0] = make_int4(acc[0], acc[1], acc[2], acc[3]);
-        gt[2] = make_int4(acc[4], acc[5], acc[6], acc[7]);
-        gt[4] = make_int4(acc[8], acc[9], acc[10], acc[11]);
-        gt[6] = make_int4(acc[12], acc[13], acc[14], acc[15]);
+        gt[0] = make_int4(G[0], G[1], G[2], G[3]);
+        gt[2] = make_int4(G[4], G[5], G[6], G[7]);
+        gt[4] = make_int4(G[8], G[9], G[10], G[11]);
+        gt[6] = make_int4(G[12], G[13], G[14], G[15]);
     }
     wave_sync();
     const int ni = sm.gt[l32 * GT_STRIDE + l32];
@@ -427,20 +420,15 @@ __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[K
     E &= (1u << l32) - 1u;
     if (!valid) E = 0;
     E &= hm;
-    // lane: row l32; acc[a]: column 8(a/4) + 4 half + a%4
+    // T = 2 G - n_j - t_i from the Gram tile that gave the norms
     v16i acc;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int4 nj = ((const int4 *)sm.nrm)[2 * q + half];
-        acc[4 * q + 0] = negt - nj.x;
-        acc[4 * q + 1] = negt - nj.y;
-        acc[4 * q + 2] = negt - nj.z;
-        acc[4 * q + 3] = negt - nj.w;
-    }
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[s], A[s], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[s], A[s], acc, 0, 0, 0);
+        acc[4 * q + 0] = (G[4 * q + 0] << 1) + (negt - nj.x);
+        acc[4 * q + 1] = (G[4 * q + 1] << 1) + (negt - nj.y);
+        acc[4 * q + 2] = (G[4 * q + 2] << 1) + (negt - nj.z);
+        acc[4 * q + 3] = (G[4 * q + 3] << 1) + (negt - nj.w);
     }
     {
         int4 *gt = (int4 *)(sm.gt + l32 * GT_STRIDE + 4 * half);
