@@ -97,12 +97,22 @@ __global__ __launch_bounds__(256) void k_prepare_u8(const uint8_t *__restrict__ 
     }
 }
 
+// What a trip has in flight for the trips after it: the rows of the next vertex (or group) and the
+// list of the one after.  The memory counter of a wavefront is in order and counts stores as well, so a
+// wait for these loads that stood after the trip's stores would also wait for the stores to be
+// acknowledged; naming the registers as inputs of an empty statement just before the stores puts the
+// wait there, where the loads are a whole trip old and the stores are not yet issued.
+__device__ __forceinline__ void arrived(const v4i &x) { asm volatile("" ::"v"(x)); }
+__device__ __forceinline__ void arrived(u64 x) { asm volatile("" ::"v"(x)); }
+__device__ __forceinline__ void arrived(int x) { asm volatile("" ::"v"(x)); }
+
 // The body of Alg. 4's vertex loop for the vertex in `cur`, whose rows are in A and whose norms are in nr.
 template <int NG, int KS>
 __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG][KS], MfmaScanSmem<NG> &sm, int R, u64 *__restrict__ keys,
                                                int *__restrict__ deg, Prop *__restrict__ props,
                                                int *__restrict__ nprop, int lane, u64 &tiles, u64 &rows,
-                                               u64 &nprops_total, u32 &ev_lane)
+                                               u64 &nprops_total, u32 &ev_lane, const v4i (&An)[NG][KS],
+                                               const ScanItem &aft, int u_after)
 {
     const int l32 = lane & 31, half = lane >> 5;
     const int u = __builtin_amdgcn_readfirstlane(cur.u);      // same in every lane: keep it scalar
@@ -116,21 +126,24 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
     u64 newm[2];
     newm[0] = __builtin_amdgcn_ballot_w64(lane < m && (kreg[0] & 1ull));
     newm[1] = __builtin_amdgcn_ballot_w64(NG > 2 && lane + 64 < m && (kreg[1] & 1ull));
-    if ((newm[0] | newm[1]) == 0) {   // nothing new: every pair was tested before
-        if (lane == 0) nprop[u] = 0;
-        return;
-    }
+    const bool any_new = (newm[0] | newm[1]) != 0;   // else every pair was tested before
+    // what the scan leaves to be stored: per block one redirected edge per lane, and the kept set
+    u64 ekey[NG];
+    u32 etgt[NG];
+    int eslot[NG];
+    u32 Kw[NG];                             // U' as bit masks over list positions, 32 per word (uniform)
+#pragma unroll
+    for (int I = 0; I < NG; ++I) eslot[I] = -1, Kw[I] = 0, ekey[I] = 0, etgt[I] = 0;
+    int np_base = 0;
+    if (any_new) {
     wave_sync();   // the previous vertex is done with the LDS tables
     if (lane < 32 * NG) sm.id[lane] = (int)key_id(kreg[0]);
     if (NG > 2 && lane + 64 < 32 * NG) sm.id[64 + lane] = (int)key_id(kreg[1]);
     rows += m;
     const u32 hm = 0x0F0F0F0Fu << (4 * half);   // the columns this half-wave holds
 
-    u32 Kw[NG];                             // U' as bit masks over list positions, 32 per word (uniform)
-    int np_base = 0;
 #pragma unroll
     for (int I = 0; I < NG; ++I) {
-        Kw[I] = 0;
         if (32 * I < m) {                   // wave-uniform
             // the Gram tile of the block with itself; n of its rows is the diagonal, read back through
             // LDS (rows past the list are zero rows that no mask ever selects)
@@ -245,13 +258,25 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
                 const int tv = sm.gt[((tgt & ~31) + l32) * GT_STRIDE + (tgt & 31)];
                 const u32 dvw = (u32)(di - tv);
                 // the redirect: v enters w's list
-                emit_redirect(make_key(dvw, key_id(kb), 1u), (u32)sm.id[tgt],
-                              props + (size_t)u * R + np_base + __popcll(pm & lanes_below(lane)));
+                ekey[I] = make_key(dvw, key_id(kb), 1u);
+                etgt[I] = (u32)sm.id[tgt];
+                eslot[I] = np_base + __popcll(pm & lanes_below(lane));
             }
             np_base += __popcll(pm);
             if (I + 1 < NG) wave_sync();   // before the next block overwrites the tiles
         }
     }
+    }
+    // every store of the trip comes after this point
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) arrived(An[g][s]);
+    arrived(aft.k[0]), arrived(aft.m), arrived(u_after);
+    if (NG > 2) arrived(aft.k[1]);
+#pragma unroll
+    for (int I = 0; I < NG; ++I)
+        if (eslot[I] >= 0) emit_redirect(ekey[I], etgt[I], props + (size_t)u * R + eslot[I]);
     // kept entries, flag old, compacted back into the row
     const u64 K0 = (u64)Kw[0] | (NG > 1 ? ((u64)Kw[NG > 1 ? 1 : 0] << 32) : 0ull);
     const u64 K1 = NG > 2 ? ((u64)Kw[NG > 2 ? 2 : 0] | (NG > 3 ? ((u64)Kw[NG > 3 ? 3 : 0] << 32) : 0ull)) : 0ull;
@@ -259,7 +284,7 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
     if ((K0 >> lane) & 1ull) row[__popcll(K0 & lanes_below(lane))] = kreg[0] & ~1ull;
     if (NG > 2 && ((K1 >> lane) & 1ull)) row[nk0 + __popcll(K1 & lanes_below(lane))] = kreg[1] & ~1ull;
     if (lane == 0) {
-        deg[u] = nk0 + __popcll(K1);
+        if (any_new) deg[u] = nk0 + __popcll(K1);
         nprop[u] = np_base;
     }
     nprops_total += np_base;
@@ -276,7 +301,8 @@ __global__ __launch_bounds__(256, (NG == 1 ? 5 : NG == 2 ? 3 : 2)) void k_update
     Prop *__restrict__ props, int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
 {
     __shared__ MfmaScanSmem<NG> smem[4];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the loop control stays on the scalar unit
+    const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
     const u32 n_active = *n_list;
     MfmaScanSmem<NG> &sm = smem[wave];
@@ -289,6 +315,12 @@ __global__ __launch_bounds__(256, (NG == 1 ? 5 : NG == 2 ? 3 : 2)) void k_update
     int u_after = gw + 2 * nw < n_active ? list[gw + 2 * nw] : -1;
     v4i A0[NG][KS], A1[NG][KS];
     scan_gather<NG, KS>(X, cur, l32, half, A0);
+    // once per wavefront: the loop starts with nothing in flight
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) arrived(A0[g][s]);
+    arrived(nxt.k[0]), arrived(nxt.k[1]), arrived(nxt.m), arrived(u_after);
 
     u32 it = gw;
     while (true) {
@@ -300,7 +332,7 @@ __global__ __launch_bounds__(256, (NG == 1 ? 5 : NG == 2 ? 3 : 2)) void k_update
             u_after = j < n_active ? list[j] : -1;
         }
         scan_vertex_u8<NG, KS>(cur, A0, sm, R, keys, deg, props, nprop, lane, tiles, rows, nprops_total,
-                               ev_lane);
+                               ev_lane, A1, aft, u_after);
         cur = nxt;
         nxt = aft;
         if ((unsigned long long)it + nw >= n_active) break;
@@ -313,7 +345,7 @@ __global__ __launch_bounds__(256, (NG == 1 ? 5 : NG == 2 ? 3 : 2)) void k_update
             u_after = j < n_active ? list[j] : -1;
         }
         scan_vertex_u8<NG, KS>(cur, A1, sm, R, keys, deg, props, nprop, lane, tiles, rows, nprops_total,
-                               ev_lane);
+                               ev_lane, A0, aft, u_after);
         cur = nxt;
         nxt = aft;
         if ((unsigned long long)it + nw >= n_active) break;
@@ -371,7 +403,8 @@ template <int P, int KS>
 __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[KS], MfmaScanSmem<1> &sm, int R,
                                                  u64 *__restrict__ keys, int *__restrict__ deg,
                                                  Prop *__restrict__ props, int *__restrict__ nprop, int lane,
-                                                 u32 &tiles, u32 &rows, u32 &nprops_total, u32 &ev_lane)
+                                                 u32 &tiles, u32 &rows, u32 &nprops_total, u32 &ev_lane,
+                                                 const v4i (&An)[KS], const PackItem &aft, int u_after)
 {
     constexpr int W = 32 / P;
     const int l32 = lane & 31, half = lane >> 5, seg = l32 / W, pos = l32 % W;
@@ -384,108 +417,113 @@ __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[K
     const bool newi = valid && (kb & 1ull);
     const bool leader = u >= 0 && pos == 0 && half == 0;
     const u32 new32 = (u32)__builtin_amdgcn_ballot_w64(newi && half == 0);
-    if (new32 == 0) {   // nothing new in any of the P lists: every pair was tested before
-        if (leader) nprop[u] = 0;
-        return;
-    }
-    const u32 vmask = (u32)__builtin_amdgcn_ballot_w64(valid && half == 0);
-    wave_sync();   // the previous group is done with the LDS tables
-    if (half == 0) sm.id[l32] = (int)key_id(kb);
-    // n of every row: the diagonal of the Gram tile, through LDS (rows past a list are zero rows
-    // that no mask ever selects)
-    // lane: row l32; G[a]: <x_row, x_col> for column 8(a/4) + 4 half + a%4
-    v16i G = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int s = 0; s < KS; ++s) G = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[s], A[s], G, 0, 0, 0);
-    {
-        int4 *gt = (int4 *)(sm.gt + l32 * GT_STRIDE + 4 * half);
-        gt[0] = make_int4(G[0], G[1], G[2], G[3]);
-        gt[2] = make_int4(G[4], G[5], G[6], G[7]);
-        gt[4] = make_int4(G[8], G[9], G[10], G[11]);
-        gt[6] = make_int4(G[12], G[13], G[14], G[15]);
-    }
-    wave_sync();
-    const int ni = sm.gt[l32 * GT_STRIDE + l32];
-    if (half == 0) sm.nrm[l32] = ni;
-    rows += __popc(vmask);
-    tiles += 1;
-    wave_sync();
-
-    const int di = (int)key_dist(kb);
-    const int negt = di - ni;
+    const bool any_new = new32 != 0;   // else nothing is new in any of the P lists: every pair was tested before
     const u32 segmask = (W == 32 ? 0xFFFFFFFFu : ((1u << (W & 31)) - 1u) << (seg * W));
-    const u32 hm = 0x0F0F0F0Fu << (4 * half);   // the columns this half-wave holds
-    // the old/old skip: a pair is tested only if v or w is new; only w before v (in v's own list) count
-    u32 E = newi ? segmask : (new32 & segmask);
-    E &= (1u << l32) - 1u;
-    if (!valid) E = 0;
-    E &= hm;
-    // T = 2 G - n_j - t_i from the Gram tile that gave the norms
-    v16i acc;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int4 nj = ((const int4 *)sm.nrm)[2 * q + half];
-        acc[4 * q + 0] = (G[4 * q + 0] << 1) + (negt - nj.x);
-        acc[4 * q + 1] = (G[4 * q + 1] << 1) + (negt - nj.y);
-        acc[4 * q + 2] = (G[4 * q + 2] << 1) + (negt - nj.z);
-        acc[4 * q + 3] = (G[4 * q + 3] << 1) + (negt - nj.w);
-    }
-    {
-        int4 *gt = (int4 *)(sm.gt + l32 * GT_STRIDE + 4 * half);
-        gt[0] = make_int4(acc[0], acc[1], acc[2], acc[3]);
-        gt[2] = make_int4(acc[4], acc[5], acc[6], acc[7]);
-        gt[4] = make_int4(acc[8], acc[9], acc[10], acc[11]);
-        gt[6] = make_int4(acc[12], acc[13], acc[14], acc[15]);
-    }
-    // bit a of ok: T < 0, v passes the prune test against column a
-    u32 ok = 0;
-#pragma unroll
-    for (int a = 15; a >= 0; --a) ok = __builtin_amdgcn_alignbit(ok, (u32)acc[a], 31);
-    // bit 4q + k  ->  column 8q + 4 half + k
-    ok = (ok | (ok << 8)) & 0x00FF00FFu;
-    ok = (ok | (ok << 4)) & 0x0F0F0F0Fu;
-    ok <<= 4 * half;
-    const u32 F = E & ~ok;
-    // the loop over v on masks; what the two half-waves find for a row is joined through ballots
-    u32 Kcur = vmask;
-    for (int sweep = 0; sweep < 33; ++sweep) {
-        const u64 hit = __builtin_amdgcn_ballot_w64((F & Kcur) != 0);
-        const u32 Knew = vmask & ~((u32)hit | (u32)(hit >> 32));
-        if (Knew == Kcur) break;
-        Kcur = Knew;
-    }
-    const bool kept = (Kcur >> l32) & 1u;
-    const bool pruned = valid && !kept && half == 0;
-    // first failing w over both halves
-    int tgt = 0x7FFFFFFF;
-    {
-        const u32 fk = F & Kcur;
-        if (fk) tgt = __builtin_ctz(fk);
-        const int other = __shfl_xor(tgt, 32);
-        tgt = other < tgt ? other : tgt;
-    }
-    // the evaluations Alg. 4 makes for this row: tested candidates up to and including w
-    {
-        const u32 upto = tgt >= 31 ? 0xFFFFFFFFu : ((2u << tgt) - 1u);
-        ev_lane += (u32)__popc(E & Kcur & upto);
-    }
-    wave_sync();   // the tile is in LDS
-    const u32 pm = (u32)__builtin_amdgcn_ballot_w64(pruned);
     const u32 below = (1u << l32) - 1u;
-    if (pruned) {
-        const int tv = sm.gt[l32 * GT_STRIDE + tgt];
-        const u32 dvw = (u32)(di - tv);
-        // the redirect: v enters w's list
-        emit_redirect(make_key(dvw, key_id(kb), 1u), (u32)sm.id[tgt],
-                      props + (size_t)u * R + __popc(pm & segmask & below));
+    // what the scan leaves to be stored
+    bool pruned = false, kept = false;
+    u32 Kcur = 0, pm = 0, dvw = 0, tgt_id = 0;
+    if (any_new) {
+        const u32 vmask = (u32)__builtin_amdgcn_ballot_w64(valid && half == 0);
+        wave_sync();   // the previous group is done with the LDS tables
+        if (half == 0) sm.id[l32] = (int)key_id(kb);
+        // n of every row: the diagonal of the Gram tile, through LDS (rows past a list are zero rows
+        // that no mask ever selects)
+        // lane: row l32; G[a]: <x_row, x_col> for column 8(a/4) + 4 half + a%4
+        v16i G = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) G = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[s], A[s], G, 0, 0, 0);
+        {
+            int4 *gt = (int4 *)(sm.gt + l32 * GT_STRIDE + 4 * half);
+            gt[0] = make_int4(G[0], G[1], G[2], G[3]);
+            gt[2] = make_int4(G[4], G[5], G[6], G[7]);
+            gt[4] = make_int4(G[8], G[9], G[10], G[11]);
+            gt[6] = make_int4(G[12], G[13], G[14], G[15]);
+        }
+        wave_sync();
+        const int ni = sm.gt[l32 * GT_STRIDE + l32];
+        if (half == 0) sm.nrm[l32] = ni;
+        rows += __popc(vmask);
+        tiles += 1;
+        wave_sync();
+
+        const int di = (int)key_dist(kb);
+        const int negt = di - ni;
+        const u32 hm = 0x0F0F0F0Fu << (4 * half);   // the columns this half-wave holds
+        // the old/old skip: a pair is tested only if v or w is new; only w before v (in v's own list) count
+        u32 E = newi ? segmask : (new32 & segmask);
+        E &= below;
+        if (!valid) E = 0;
+        E &= hm;
+        // T = 2 G - n_j - t_i from the Gram tile that gave the norms
+        v16i acc;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int4 nj = ((const int4 *)sm.nrm)[2 * q + half];
+            acc[4 * q + 0] = (G[4 * q + 0] << 1) + (negt - nj.x);
+            acc[4 * q + 1] = (G[4 * q + 1] << 1) + (negt - nj.y);
+            acc[4 * q + 2] = (G[4 * q + 2] << 1) + (negt - nj.z);
+            acc[4 * q + 3] = (G[4 * q + 3] << 1) + (negt - nj.w);
+        }
+        {
+            int4 *gt = (int4 *)(sm.gt + l32 * GT_STRIDE + 4 * half);
+            gt[0] = make_int4(acc[0], acc[1], acc[2], acc[3]);
+            gt[2] = make_int4(acc[4], acc[5], acc[6], acc[7]);
+            gt[4] = make_int4(acc[8], acc[9], acc[10], acc[11]);
+            gt[6] = make_int4(acc[12], acc[13], acc[14], acc[15]);
+        }
+        // bit a of ok: T < 0, v passes the prune test against column a
+        u32 ok = 0;
+#pragma unroll
+        for (int a = 15; a >= 0; --a) ok = __builtin_amdgcn_alignbit(ok, (u32)acc[a], 31);
+        // bit 4q + k  ->  column 8q + 4 half + k
+        ok = (ok | (ok << 8)) & 0x00FF00FFu;
+        ok = (ok | (ok << 4)) & 0x0F0F0F0Fu;
+        ok <<= 4 * half;
+        const u32 F = E & ~ok;
+        // the loop over v on masks; what the two half-waves find for a row is joined through ballots
+        Kcur = vmask;
+        for (int sweep = 0; sweep < 33; ++sweep) {
+            const u64 hit = __builtin_amdgcn_ballot_w64((F & Kcur) != 0);
+            const u32 Knew = vmask & ~((u32)hit | (u32)(hit >> 32));
+            if (Knew == Kcur) break;
+            Kcur = Knew;
+        }
+        kept = (Kcur >> l32) & 1u;
+        pruned = valid && !kept && half == 0;
+        // first failing w over both halves
+        int tgt = 0x7FFFFFFF;
+        {
+            const u32 fk = F & Kcur;
+            if (fk) tgt = __builtin_ctz(fk);
+            const int other = __shfl_xor(tgt, 32);
+            tgt = other < tgt ? other : tgt;
+        }
+        // the evaluations Alg. 4 makes for this row: tested candidates up to and including w
+        {
+            const u32 upto = tgt >= 31 ? 0xFFFFFFFFu : ((2u << tgt) - 1u);
+            ev_lane += (u32)__popc(E & Kcur & upto);
+        }
+        wave_sync();   // the tile is in LDS
+        pm = (u32)__builtin_amdgcn_ballot_w64(pruned);
+        if (pruned) {
+            dvw = (u32)(di - sm.gt[l32 * GT_STRIDE + tgt]);
+            tgt_id = (u32)sm.id[tgt];
+        }
+        nprops_total += __popc(pm);
     }
+    // every store of the trip comes after this point
+#pragma unroll
+    for (int s = 0; s < KS; ++s) arrived(An[s]);
+    arrived(aft.k), arrived(aft.m), arrived(u_after);
+    // the redirect: v enters w's list
+    if (pruned) emit_redirect(make_key(dvw, key_id(kb), 1u), tgt_id, props + (size_t)u * R + __popc(pm & segmask & below));
     // kept entries, flag old, compacted back into the row
     if (kept && half == 0) keys[(size_t)u * R + __popc(Kcur & segmask & below)] = kb & ~1ull;
     if (leader) {
-        deg[u] = __popc(Kcur & segmask);
+        if (any_new) deg[u] = __popc(Kcur & segmask);
         nprop[u] = __popc(pm & segmask);
     }
-    nprops_total += __popc(pm);
 }
 
 // Same two-deep software pipeline as k_update_scan_mfma_u8; trip g of a wavefront takes list entries
@@ -498,7 +536,8 @@ __device__ __forceinline__ void scan_packed_body(const int8_t *__restrict__ X, i
                                                  MfmaScanSmem<1> &sm)
 {
     constexpr int W = 32 / P;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the loop control stays on the scalar unit
+    const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const int seg = l32 / W, pos = l32 % W;
     const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
     const u32 n_groups = (n_active + (u32)P - 1u) / (u32)P;
@@ -515,6 +554,10 @@ __device__ __forceinline__ void scan_packed_body(const int8_t *__restrict__ X, i
     int u_after = vertex_of((unsigned long long)gw + 2ull * nw);
     v4i A0[KS], A1[KS];
     pack_gather<P, KS>(X, cur, pos, half, A0);
+    // once per wavefront: the loop starts with nothing in flight
+#pragma unroll
+    for (int s = 0; s < KS; ++s) arrived(A0[s]);
+    arrived(nxt.k), arrived(nxt.m), arrived(u_after);
 
     u32 it = gw;
     while (true) {
@@ -522,7 +565,8 @@ __device__ __forceinline__ void scan_packed_body(const int8_t *__restrict__ X, i
         pack_gather<P, KS>(X, nxt, pos, half, A1);
         PackItem aft = pack_item_load<P>(u_after, keys, deg, R, pos);
         u_after = vertex_of((unsigned long long)it + 3ull * nw);
-        pack_vertices_u8<P, KS>(cur, A0, sm, R, keys, deg, props, nprop, lane, tiles, rows, nprops_total, ev_lane);
+        pack_vertices_u8<P, KS>(cur, A0, sm, R, keys, deg, props, nprop, lane, tiles, rows, nprops_total, ev_lane,
+                                A1, aft, u_after);
         cur = nxt;
         nxt = aft;
         if ((unsigned long long)it + nw >= n_groups) break;
@@ -531,7 +575,8 @@ __device__ __forceinline__ void scan_packed_body(const int8_t *__restrict__ X, i
         pack_gather<P, KS>(X, nxt, pos, half, A0);
         aft = pack_item_load<P>(u_after, keys, deg, R, pos);
         u_after = vertex_of((unsigned long long)it + 3ull * nw);
-        pack_vertices_u8<P, KS>(cur, A1, sm, R, keys, deg, props, nprop, lane, tiles, rows, nprops_total, ev_lane);
+        pack_vertices_u8<P, KS>(cur, A1, sm, R, keys, deg, props, nprop, lane, tiles, rows, nprops_total, ev_lane,
+                                A0, aft, u_after);
         cur = nxt;
         nxt = aft;
         if ((unsigned long long)it + nw >= n_groups) break;
