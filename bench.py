@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # a plain 1 GiB copy in the same run); see profiles/update_scan_cfg3_hbm_traffic.txt and
 # profiles/update_scan_cfg5_hbm_traffic.txt.  Keyed by (workload, kernel variant); None where it has
 # not been measured.
-TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.022e9, ("cfg5", 3): 8.233e10}
+TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.022e9, ("cfg5", 3): 8.337e10}
 
 
 def cpu_baseline(cfg, X, sample_n):
