@@ -301,20 +301,18 @@ def test_cfg4_full_size_parity(rn, oracle_mod):
     assert list(st.algo_evals[:60]) == want.round_evals.tolist()
 
 
-@pytest.mark.slow
-@live
-def test_cfg5_full_size_sampled_parity(rn, oracle_mod):
-    """Workload cfg5 (N = 1,000,000, d = 960 float32) in the launch configuration bench.py
-    times.  A full oracle run would take hours, so outputs are sampled: after the GPU has run RandomGraph
+def _full_size_sampled_parity(rn, oracle_mod, name):
+    """A float workload at full size in the launch configuration bench.py times.  A full oracle run takes
+    minutes (cfg4) to hours (cfg5), so outputs are sampled: after the GPU has run RandomGraph
     and k rounds, one more round is run on the GPU, and for 2,000 sampled vertices the oracle computes
     that round one vertex at a time (a snapshot in which only the sampled lists are non-empty).  The
     entries the GPU kept for a sampled vertex (flag old) must equal the oracle's kept list, key for key
     (up to the cut at R when the full graph redirected more edges to it than the sample can know);
     RandomGraph rows of the sample are compared the same way; structure (sorted, distinct, no self loop,
     degree <= R, distances = float64 numpy) is checked on the sample of the final graph."""
-    c = wl.CONFIGS["cfg5"]
+    c = wl.CONFIGS[name]
     X = wl.make_data(c)
-    print("cfg5 data ready", flush=True)
+    print("%s data ready" % name, flush=True)
     Xd = cuda(X)
     R = c.R
     g = np.random.default_rng(1)
@@ -364,6 +362,21 @@ def test_cfg5_full_size_sampled_parity(rn, oracle_mod):
         assert (bits[u, :m].view(np.float32) == ref).all()
         key = list(zip(bits[u, :m].tolist(), row.tolist()))
         assert key == sorted(key)
+
+
+@pytest.mark.slow
+@live
+def test_cfg5_full_size_sampled_parity(rn, oracle_mod):
+    """Workload cfg5 (N = 1,000,000, d = 960 float32)."""
+    _full_size_sampled_parity(rn, oracle_mod, "cfg5")
+
+
+@pytest.mark.slow
+@live
+def test_cfg4_full_size_sampled_parity(rn, oracle_mod):
+    """Workload cfg4 (N = 1,000,000, d = 96 float32, unit vectors); the full oracle run is
+    test_cfg4_full_size_parity."""
+    _full_size_sampled_parity(rn, oracle_mod, "cfg4")
 
 
 def test_gather_probe_reports_a_plausible_rate(rn):
