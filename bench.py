@@ -193,23 +193,25 @@ def main():
              2: "k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8<NG,%d>, NG = 2,3 (one round's scan launches, "
                 "back to back)" % (cfg.d // 32, cfg.d // 32),
              3: "k_update_scan_mfma_f32<NG,CH,NRC,fast> (one launch per degree class, back to back per round; "
-                "fp32 MFMA Gram tiles, undecided pairs by exact distances)"}[kv]
+                "%s MFMA Gram tiles, undecided pairs by exact distances)" % ("f16" if half else "fp32")}[kv]
     if kv == 3:
-        # float rows: the Gram tiles run on the fp32 matrix cores (157.3 TFLOP/s dense), the rows are
-        # gathered from HBM; the kernel is reported against whichever of the two it sits closer to.
-        # executed flops = computed pair distances * 2 d
+        # float rows: the Gram tiles run on the fp32 matrix cores (157.3 TFLOP/s dense; 16-bit rows: on the
+        # f16 ones, 2,500 TFLOP/s), the rows are gathered from HBM; the kernel is reported against whichever
+        # of the two it sits closer to.  executed flops = computed pair distances * 2 d
+        mfma_peak = 2500.0 if half else 157.3
         flops = sum(s["exec_evals"]) * 2.0 * cfg.d
         tflops = flops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0
         extra = {"launches": rounds, "avg_launch_ms": scan_ms / max(1, rounds),
-                 "flops_per_launch": flops / max(1, rounds), "mfma_fp32_TFLOPs": tflops,
-                 "mfma_fp32_frac": tflops / 157.3, "hbm_algorithmic_GBps": hbm_gbs,
+                 "flops_per_launch": flops / max(1, rounds), "mfma_TFLOPs": tflops, "mfma_peak_TFLOPs": mfma_peak,
+                 "mfma_frac": tflops / mfma_peak, "hbm_algorithmic_GBps": hbm_gbs,
                  "hbm_frac": hbm_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": scan_bytes / max(1, rounds)}
-        if hbm_gbs / HBM_PEAK_GBS >= tflops / 157.3:
+        if hbm_gbs / HBM_PEAK_GBS >= tflops / mfma_peak:
             roof = dict({"bound": "hbm", "kernel": kname, "achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC_PER_LAUNCH.get((cfg.name, kv))}, **extra)
+                         "frac": hbm_gbs / HBM_PEAK_GBS,
+                         "traffic": None if half else TRAFFIC_PER_LAUNCH.get((cfg.name, kv))}, **extra)
         else:
-            roof = dict({"bound": "mfma", "kernel": kname, "achieved": tflops, "peak": 157.3, "unit": "TFLOP/s",
-                         "frac": tflops / 157.3, "traffic": None}, **extra)
+            roof = dict({"bound": "mfma", "kernel": kname, "achieved": tflops, "peak": mfma_peak, "unit": "TFLOP/s",
+                         "frac": tflops / mfma_peak, "traffic": None}, **extra)
     else:
         roof = {"bound": "hbm", "kernel": kname, "achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC_PER_LAUNCH.get((cfg.name, kv)),
@@ -230,8 +232,9 @@ def main():
         "dtype": "u8" if cfg.dtype == "u8" else "f32",
         "storage": "f16" if half else cfg.dtype,
         "arithmetic": ("uint8 rows, int8 MFMA Gram tiles, exact int32 distances" if cfg.dtype == "u8" else
-                       "float32 rows; decisions from fp32 MFMA Gram tiles with an error bound, exact f64-accumulated distances "
-                       "for undecided pairs and for every stored distance (rounded once to float32)"),
+                       "%s rows; decisions from %s MFMA Gram tiles with an error bound, exact f64-accumulated distances "
+                       "for undecided pairs and for every stored distance (rounded once to float32)"
+                       % (("float16", "f16") if half else ("float32", "fp32"))),
         "data": "synthetic",
         "config": {"workload": "%s: N=%d d=%d %s, S=%d R=%d T1=%d T2=%d, seeded %s mixture"
                                % (cfg.name, cfg.N, cfg.d, cfg.dtype, cfg.S, cfg.R, cfg.T1, cfg.T2, cfg.kind),

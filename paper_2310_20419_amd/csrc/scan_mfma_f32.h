@@ -83,6 +83,9 @@ __device__ __forceinline__ u32 transpose16_bits_x2(u32 w, int lane)
     return w;
 }
 
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
 template <bool FAST> struct GramAcc { typedef v4d type; typedef double norm; };
 template <> struct GramAcc<true> { typedef v4f type; typedef float norm; };
 
@@ -107,6 +110,26 @@ template <int DT> struct ChunkCoords { static constexpr int n = (DT == DT_F16 ||
 template <int NR, int CH, u32 TM, int DT, typename ACC, typename NRT>
 __device__ __forceinline__ void gram_chunk(const uint4 (&x)[NR][CH], ACC (&acc)[NR * (NR + 1) / 2], NRT (&nr)[NR], u32 need)
 {
+    if constexpr (sizeof(acc[0][0]) == 4 && (DT == DT_F16 || DT == DT_BF16)) {
+        // 16-bit rows, single-precision form: the 16 bytes a lane holds are 8 coordinates in the operand format of
+        // v_mfma_f32_16x16x32_{f16,bf16} as they are (products of two such numbers are exact in float); the norms
+        // come from the diagonal tiles afterwards, so `need` includes those
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+#pragma unroll
+            for (int I = 0; I < NR; ++I)
+#pragma unroll
+                for (int J = 0; J <= I; ++J)
+                    if (TM ? ((TM >> (I * (I + 1) / 2 + J)) & 1u) != 0 : ((need >> (I * (I + 1) / 2 + J)) & 1u) != 0) {   // wave-uniform
+                        if constexpr (DT == DT_F16)
+                            acc[I * (I + 1) / 2 + J] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                                __builtin_bit_cast(v8h, x[I][j]), __builtin_bit_cast(v8h, x[J][j]), acc[I * (I + 1) / 2 + J], 0, 0, 0);
+                        else
+                            acc[I * (I + 1) / 2 + J] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(v8bf, x[I][j]), __builtin_bit_cast(v8bf, x[J][j]), acc[I * (I + 1) / 2 + J], 0, 0, 0);
+                    }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < CH; ++j)
 #pragma unroll
@@ -251,14 +274,23 @@ __device__ __forceinline__ int popc_below(u64 m0, u64 m1, int p)   // set bits o
 // reference arithmetic.  A vertex with more than F32_AMB_CAP undecided pairs (ties in bulk: duplicates,
 // lattices) is left untouched and appended to `redo`, which the double-precision form (FAST = false)
 // takes afterwards.
+// FAST with 16-bit rows: the block comes from v_mfma_f32_16x16x32_{f16,bf16} on the rows as stored (exact
+// products), norms included (diagonals of the diagonal tiles).  One instruction sums 32 products and the
+// accumulator; taking its error as at most 8 x 2^-24 of the sum of their magnitudes (an in-bounds probe
+// against double precision stays below 2.3 x 2^-24 per instruction, also for operands spread over 20
+// binades, and shows that subnormal halves count), G and either norm are off by at most
+// (d / 4) 2^-24 of sqrt(n_i n_j) resp. n, hence eps_ij = (0.5 d + 20) 2^-24 (n_i + n_j).
 template <int NG, int CH, int NRC = 2 * NG, bool FAST = false, int DT = DT_F32>
-__global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == DT_F32) ? 3 : 2) : (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1))) void k_update_scan_mfma_f32(
+__global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) : (NRC <= 2 ? 4 : NRC <= 5 ? 2 : 1))) void k_update_scan_mfma_f32(
     const char *__restrict__ X, int d, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ list, const u32 *__restrict__ n_list, Prop *__restrict__ props,
     int *__restrict__ nprop, RoundCtr *__restrict__ ctr, int *__restrict__ redo, u32 *__restrict__ n_redo)
 {
     typedef typename GramAcc<FAST>::type acc_t;
-    const double epsk = (1.5 * (double)d + 20.0) * 5.9604644775390625e-08;
+    // 16-bit rows in the single-precision form: the matrix instruction takes them as they are
+    constexpr bool NATIVE16 = FAST && (DT == DT_F16 || DT == DT_BF16);
+    const double epsk = NATIVE16 ? (0.5 * (double)d + 20.0) * 5.9604644775390625e-08
+                                 : (1.5 * (double)d + 20.0) * 5.9604644775390625e-08;
     constexpr int NT = NRC * (NRC + 1) / 2;
     constexpr int NWD = (NRC + 1) / 2;        // 32-bit words of a mask over slots
     constexpr int NSET = NRC > 4 ? 2 : 1;     // lane (r16, q) owns rows 16 q + r16 and, if NRC > 4, 64 + 16 q + r16
@@ -347,14 +379,23 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
                 for (int J = 0; J <= I; ++J)
                     if (16 * I < m && J < g_new) need |= 1u << (I * (I + 1) / 2 + J);
             need = (u32)__builtin_amdgcn_readfirstlane((int)need);
+            // the tiles the Gram loop computes: those, and for 16-bit rows in the single-precision form the diagonal
+            // tile of every group in use (its diagonal is the group's norms)
+            u32 need_g = need;
+            if constexpr (NATIVE16) {
+#pragma unroll
+                for (int I = 0; I < NRC; ++I)
+                    if (16 * I < m) need_g |= 1u << (I * (I + 1) / 2 + I);
+                need_g = (u32)__builtin_amdgcn_readfirstlane((int)need_g);
+            }
             if constexpr (FAST) {
                 if (NRC == 1) {
-                    gram_f32_loop<NRC, CH, 1u, DT>(rp, nchunk, acc, nr, need);
+                    gram_f32_loop<NRC, CH, 1u, DT>(rp, nchunk, acc, nr, need_g);
                 } else if (NRC == 2) {
-                    if (need == 7u) gram_f32_loop<NRC, CH, 7u, DT>(rp, nchunk, acc, nr, need);
-                    else gram_f32_loop<NRC, CH, 3u, DT>(rp, nchunk, acc, nr, need);
+                    if (NATIVE16 || need == 7u) gram_f32_loop<NRC, CH, 7u, DT>(rp, nchunk, acc, nr, need_g);
+                    else gram_f32_loop<NRC, CH, 3u, DT>(rp, nchunk, acc, nr, need_g);
                 } else {
-                    gram_f32_loop<NRC, CH, 0u, DT>(rp, nchunk, acc, nr, need);
+                    gram_f32_loop<NRC, CH, 0u, DT>(rp, nchunk, acc, nr, need_g);
                 }
             } else {
                 if (NRC == 1) {
@@ -370,8 +411,16 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
             }
 #pragma unroll
             for (int g = 0; g < NRC; ++g) {
-                nr[g] += __shfl_xor(nr[g], 16);
-                nr[g] += __shfl_xor(nr[g], 32);     // n of slot 16 g + r16, in all four quarter-waves
+                if constexpr (NATIVE16) {
+                    // entry (i, i) of the group's diagonal tile sits in lane (r16 = i, q = i / 4), accumulator i % 4
+                    const v4f dt = acc[g * (g + 1) / 2 + g];
+                    const int vs = r16 & 3;
+                    const float dv = vs == 0 ? dt[0] : vs == 1 ? dt[1] : vs == 2 ? dt[2] : dt[3];
+                    nr[g] = __shfl(dv, r16 + 16 * (r16 >> 2));
+                } else {
+                    nr[g] += __shfl_xor(nr[g], 16);
+                    nr[g] += __shfl_xor(nr[g], 32);     // n of slot 16 g + r16, in all four quarter-waves
+                }
                 if (q == 0) {
                     if (FAST) sm.nrmf[16 * g + r16] = (float)nr[g];
                     else sm.nrm[16 * g + r16] = (double)nr[g];
@@ -399,7 +448,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : (NRC <= 4 && DT == 
                 for (int J = 0; J <= I; ++J) {
                     const int t = I * (I + 1) / 2 + J;
                     FA[t] = FB[t] = 0;
-                    if (NRC == 1 || (NRC == 2 && need != 7u && t < 2) || ((need >> t) & 1u)) tiles += 1;   // what the loop above computed
+                    if (NRC == 1 || (NRC == 2 && (NATIVE16 || (need != 7u && t < 2))) || ((need_g >> t) & 1u)) tiles += 1;   // what the loop above computed
                     if ((need >> t) & 1u) {     // wave-uniform
                         // lane = slot r16 of group J; accumulator v = slot 4v + q of group I (4q + v in the
                         // single-precision instruction).  Low half of a word: the test fires; high half: undecided.
