@@ -1906,4 +1906,4 @@ extern "C" const char *rnnd_strerror(int status)
     }
 }
 
-extern "C" int rnnd_version(void) { return 106; }
+extern "C" int rnnd_version(void) { return 107; }
