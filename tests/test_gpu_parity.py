@@ -301,7 +301,7 @@ def test_cfg4_full_size_parity(rn, oracle_mod):
     assert list(st.algo_evals[:60]) == want.round_evals.tolist()
 
 
-def _full_size_sampled_parity(rn, oracle_mod, name):
+def _full_size_sampled_parity(rn, oracle_mod, name, half=False):
     """A float workload at full size in the launch configuration bench.py times.  A full oracle run takes
     minutes (cfg4) to hours (cfg5), so outputs are sampled: after the GPU has run RandomGraph
     and k rounds, one more round is run on the GPU, and for 2,000 sampled vertices the oracle computes
@@ -313,7 +313,12 @@ def _full_size_sampled_parity(rn, oracle_mod, name):
     c = wl.CONFIGS[name]
     X = wl.make_data(c)
     print("%s data ready" % name, flush=True)
-    Xd = cuda(X)
+    if half:        # half-precision storage: the expected graph is the oracle's on the floats the halves stand for
+        X16 = X.astype(np.float16)
+        X = X16.astype(np.float32)
+        Xd = cuda(X16)
+    else:
+        Xd = cuda(X)
     R = c.R
     g = np.random.default_rng(1)
     sample = np.sort(g.choice(c.N, 2000, replace=False))
@@ -377,6 +382,13 @@ def test_cfg4_full_size_sampled_parity(rn, oracle_mod):
     """Workload cfg4 (N = 1,000,000, d = 96 float32, unit vectors); the full oracle run is
     test_cfg4_full_size_parity."""
     _full_size_sampled_parity(rn, oracle_mod, "cfg4")
+
+
+@pytest.mark.slow
+@live
+def test_cfg4_full_size_sampled_parity_half_storage(rn, oracle_mod):
+    """The same with the rows handed over in half precision (the f16 matrix-instruction path of the scan)."""
+    _full_size_sampled_parity(rn, oracle_mod, "cfg4", half=True)
 
 
 def test_gather_probe_reports_a_plausible_rate(rn):
