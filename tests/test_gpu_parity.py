@@ -391,6 +391,13 @@ def test_cfg4_full_size_sampled_parity_half_storage(rn, oracle_mod):
     _full_size_sampled_parity(rn, oracle_mod, "cfg4", half=True)
 
 
+@pytest.mark.slow
+@live
+def test_cfg5_full_size_sampled_parity_half_storage(rn, oracle_mod):
+    """Workload cfg5 (rows of 960 coordinates) in half precision."""
+    _full_size_sampled_parity(rn, oracle_mod, "cfg5", half=True)
+
+
 def test_gather_probe_reports_a_plausible_rate(rn):
     """The measurement aid behind the 'gather ceiling' of the benchmark line: it must run on rows of any
     multiple of 16 bytes and report something between a trickle and the HBM peak times the cache effect."""
