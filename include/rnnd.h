@@ -196,9 +196,10 @@ int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t 
  * throughout.  Automatic uses the dense Gram-block kernels on the matrix cores where they apply
  * and the generic kernel otherwise:
  *   uint8 rows with d = 32, 64 or 128: int8 MFMA;
- *   float32 rows with d a multiple of 16, 16-bit rows with d a multiple of 32: fp32 MFMA first,
- *   every pair whose outcome lies within that block's error bound decided by the exact distance,
- *   and vertices with very many such pairs redone on the f64 MFMA.
+ *   float32 rows with d a multiple of 16, 16-bit rows with d a multiple of 32: a single-precision
+ *   Gram block first (fp32 MFMA on float32 rows; f16 / bf16 MFMA on 16-bit rows as stored), every
+ *   pair whose outcome lies within that block's error bound decided by the exact distance, and
+ *   vertices with very many such pairs redone on the f64 MFMA.
  * All give identical graphs; this exists for testing and profiling.  Process-wide, not thread-safe. */
 int rnnd_set_kernel_variant(int variant);
 
