@@ -913,6 +913,38 @@ __global__ void k_export(long long N, int R, const u64 *keys, const int *deg, in
     if (e == 0) degree_out[u] = m;
 }
 
+// The same, four slots per thread (R a multiple of 4, graph_out 16-byte aligned).
+__global__ __launch_bounds__(256) void k_export4(long long N, int R4, const u64 *keys, const int *deg, int4 *graph_out,
+                                                 int *degree_out)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;      // group of four slots
+    if (i >= N * R4) return;
+    const long long u = i / R4;
+    const int e = 4 * (int)(i - u * R4);
+    const int m = deg[u];
+    int4 o = make_int4(-1, -1, -1, -1);
+    if (e < m) {
+        const ulonglong2 a = ((const ulonglong2 *)keys)[2 * i], b = ((const ulonglong2 *)keys)[2 * i + 1];
+        o.x = (int)key_id(a.x);
+        if (e + 1 < m) o.y = (int)key_id(a.y);
+        if (e + 2 < m) o.z = (int)key_id(b.x);
+        if (e + 3 < m) o.w = (int)key_id(b.y);
+    }
+    graph_out[i] = o;
+    if (e == 0) degree_out[u] = m;
+}
+
+static void launch_export(long long N, int R, const u64 *keys, const int *deg, int *graph_out, int *degree_out,
+                          hipStream_t st)
+{
+    if (R % 4 == 0 && ((uintptr_t)graph_out & 15) == 0 && ((uintptr_t)keys & 15) == 0)
+        hipLaunchKernelGGL(k_export4, dim3((unsigned)(((size_t)N * (R / 4) + 255) / 256)), dim3(256), 0, st, N, R / 4, keys,
+                           deg, (int4 *)graph_out, degree_out);
+    else
+        hipLaunchKernelGGL(k_export, dim3((unsigned)(((size_t)N * R + 255) / 256)), dim3(256), 0, st, N, R, keys, deg,
+                           graph_out, degree_out);
+}
+
 // Measurement aid: random row gathers and nothing else.  Every wavefront draws row numbers from the
 // counter generator and reads whole rows, LPR lanes per row with 16 bytes per lane and piece, four
 // rows' worth of loads per lane in flight; the values are folded into one word per thread so that
@@ -1445,8 +1477,7 @@ static int build_sync_impl(const void *X, int64_t N, int32_t d, int dtype, int m
             if (t1 != T1 - 1)
                 HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, t, st, stats ? ev[e_rev + t1] : nullptr, M));
         }
-        hipLaunchKernelGGL(k_export, dim3((unsigned)(((size_t)N * M + 255) / 256)), dim3(256), 0, st, (long long)N, M,
-                           w.keys, w.deg, graph_out, degree_out);
+        launch_export(N, M, w.keys, w.deg, graph_out, degree_out, st);
         HIPCHK(hipGetLastError());
         if (keys_out)
             HIPCHK(hipMemcpyAsync(keys_out, w.keys, (size_t)N * M * 8, hipMemcpyDeviceToDevice, st));
@@ -1591,8 +1622,7 @@ extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype,
             if (t1 != T1 - 1)
                 HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, -1, st, stats ? ev[e_rev + t1] : nullptr));
         }
-        hipLaunchKernelGGL(k_export, dim3((unsigned)(((size_t)N * R + 255) / 256)), dim3(256), 0, st, (long long)N, R,
-                           w.keys, w.deg, graph_out, degree_out);
+        launch_export(N, R, w.keys, w.deg, graph_out, degree_out, st);
         HIPCHK(hipGetLastError());
         if (keys_out)
             HIPCHK(hipMemcpyAsync(keys_out, w.keys, (size_t)N * R * 8, hipMemcpyDeviceToDevice, st));
@@ -1772,8 +1802,7 @@ extern "C" int rnnd_export_graph(int64_t N, int32_t R, const uint64_t *keys, con
     if (N < 1 || N > 2147483646LL) return RNND_ERR_BAD_SHAPE;
     if (R < 1 || R > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(k_export, dim3((unsigned)(((size_t)N * R + 255) / 256)), dim3(256), 0, st, (long long)N, R,
-                       (const u64 *)keys, deg, graph_out, degree_out);
+    launch_export(N, R, (const u64 *)keys, deg, graph_out, degree_out, st);
     HIPCHK(hipGetLastError());
     HIPCHK(hipStreamSynchronize(st));
 done:
