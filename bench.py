@@ -109,9 +109,9 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="UpdateNeighbors kernel: 0 auto, 1 generic, 2 auto with the float scan in double precision")
     ap.add_argument("--cpu-sample", type=int, default=0)
     ap.add_argument("--n", type=int, default=0, help="override the workload's N (same generator; scale checks)")
-    ap.add_argument("--storage", choices=["native", "f16"], default="native",
-                    help="f16: float workloads are stored as IEEE half precision (RNND_F16); the graph is the one "
-                         "of the rounded data")
+    ap.add_argument("--storage", choices=["native", "f16", "bf16"], default="native",
+                    help="f16 / bf16: float workloads are stored as IEEE half precision (RNND_F16) or bfloat16 "
+                         "(RNND_BF16); the graph is the one of the rounded data")
     ap.add_argument("--search-sweep", action="store_true",
                     help="search-quality leg over L in {16,32,64,128} x K in {16,...,96, no cap} (Sec. 5.2)")
     ap.add_argument("--merge-cap", type=int, default=0,
@@ -144,10 +144,17 @@ def main():
     t0 = time.perf_counter()
     X = wl.make_data(cfg)
     gen_s = time.perf_counter() - t0
-    half = args.storage == "f16" and cfg.dtype != "u8"
-    if half:
+    half = args.storage in ("f16", "bf16") and cfg.dtype != "u8"
+    st16 = args.storage if half else None
+    if st16 == "f16":
         X = X.astype(np.float16)
-    Xd = torch.from_numpy(X).cuda()
+        Xd = torch.from_numpy(X).cuda()
+    elif st16 == "bf16":
+        Xb = torch.from_numpy(X).to(torch.bfloat16)      # round to nearest even
+        X = Xb.float().numpy()                             # the floats the stored numbers stand for (host side)
+        Xd = Xb.cuda()
+    else:
+        Xd = torch.from_numpy(X).cuda()
     esz = 1 if cfg.dtype == "u8" else 2 if half else 4
     torch.cuda.synchronize()
 
@@ -193,7 +200,7 @@ def main():
              2: "k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8<NG,%d>, NG = 2,3 (one round's scan launches, "
                 "back to back)" % (cfg.d // 32, cfg.d // 32),
              3: "k_update_scan_mfma_f32<NG,CH,NRC,fast> (one launch per degree class, back to back per round; "
-                "%s MFMA Gram tiles, undecided pairs by exact distances)" % ("f16" if half else "fp32")}[kv]
+                "%s MFMA Gram tiles, undecided pairs by exact distances)" % (st16 if half else "fp32")}[kv]
     if kv == 3:
         # float rows: the Gram tiles run on the fp32 matrix cores (157.3 TFLOP/s dense; 16-bit rows: on the
         # f16 ones, 2,500 TFLOP/s), the rows are gathered from HBM; the kernel is reported against whichever
@@ -230,11 +237,11 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8" if cfg.dtype == "u8" else "f32",
-        "storage": "f16" if half else cfg.dtype,
+        "storage": st16 if half else cfg.dtype,
         "arithmetic": ("uint8 rows, int8 MFMA Gram tiles, exact int32 distances" if cfg.dtype == "u8" else
                        "%s rows; decisions from %s MFMA Gram tiles with an error bound, exact f64-accumulated distances "
                        "for undecided pairs and for every stored distance (rounded once to float32)"
-                       % (("float16", "f16") if half else ("float32", "fp32"))),
+                       % (({"f16": "float16", "bf16": "bfloat16"}[st16], st16) if half else ("float32", "fp32"))),
         "data": "synthetic",
         "config": {"workload": "%s: N=%d d=%d %s, S=%d R=%d T1=%d T2=%d, seeded %s mixture"
                                % (cfg.name, cfg.N, cfg.d, cfg.dtype, cfg.S, cfg.R, cfg.T1, cfg.T2, cfg.kind),
