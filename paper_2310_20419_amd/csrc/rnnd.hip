@@ -664,18 +664,23 @@ __global__ __launch_bounds__(256) void k_store_classes(const u32 *n_touched, con
 // key(delta, u, new).  A later arrival is remembered with its edge (late[] holds its number, over[u]
 // one bit per list position of u, mark[u] says that u has any) and k_reverse_surplus places it in
 // v's bin once bins exist.
+// 16 lanes per vertex (lists are mostly short: a wavefront per vertex would leave most lanes idle and the
+// kernel is bound by its three dependent trips to memory: degree, list entry, arrival number).
 __global__ __launch_bounds__(BLOCK) void k_reverse_scatter(long long N, int R, const u64 *keys, const int *deg,
                                                            int *fill, u64 *inbox, u32 *late, u64 *over,
                                                            int8_t *mark)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
-    if (u >= N) return;
-    const int m = deg[u];
+    const int lane = threadIdx.x & 63, sub = lane & 15, gsh = lane & ~15;
+    const long long u = ((long long)blockIdx.x * BLOCK + threadIdx.x) >> 4;
+    const bool valid = u < N;
+    const int m = valid ? deg[u] : 0;
+    // the same number of trips for the four vertices of a wavefront (the ballot below is the wavefront's)
+    int mmax = m;
+    mmax = max(mmax, __shfl_xor(mmax, 16));
+    mmax = max(mmax, __shfl_xor(mmax, 32));
     u64 ov[2] = {0ull, 0ull};
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        const int e = 64 * r + lane;
+    for (int e0 = 0; e0 < mmax; e0 += 16) {
+        const int e = e0 + sub;
         bool is_late = false;
         if (e < m) {
             const u64 k = keys[(size_t)u * R + e];
@@ -688,9 +693,10 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_scatter(long long N, int R, c
                 is_late = true;
             }
         }
-        ov[r] = __builtin_amdgcn_ballot_w64(is_late);
+        const u64 bits = (__builtin_amdgcn_ballot_w64(is_late) >> gsh) & 0xFFFFull;     // my vertex's 16 positions
+        ov[e0 >> 6] |= bits << (e0 & 63);
     }
-    if (lane == 0) {
+    if (valid && sub == 0) {
         const bool any = (ov[0] | ov[1]) != 0;
         mark[u] = (int8_t)any;
         if (any) { over[2 * u] = ov[0]; over[2 * u + 1] = ov[1]; }
@@ -1360,8 +1366,8 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, 8);
     if (t_next >= 0) hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NDEG);
     // union with reversed edges, out-lists cut to R
-    hipLaunchKernelGGL(k_reverse_scatter, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, deg, w.fill, w.inbox, late, over,
-                       mark);
+    hipLaunchKernelGGL(k_reverse_scatter, dim3((unsigned)((N * 16 + BLOCK - 1) / BLOCK)), dim3(BLOCK), 0, st, N, W, keys, deg,
+                       w.fill, w.inbox, late, over, mark);
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.fill, INBOX_CAP, INBOX_CAP, INBOX_CAP,
                        w.binoff, w.misc + 0, w.hubs, w.misc + 1, w.cnt, cnt_in, (u64 *)nullptr, deg, R, cand);
     hipLaunchKernelGGL(k_reverse_surplus, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, late, over, mark, w.binoff,
