@@ -69,7 +69,7 @@ def exact_top10(Xd, Qd):
 
 def search_quality(cfg, rn, Xd, graph, degree, nq, L=64, K=32, sweep=False):
     """Search on the graph just built, by the library's own GPU search (Alg. 1 with the cap K): queries per
-    second, recall@10 and R@1 against the exact neighbours.  sweep: also the grid of L and K of Sec. 5.2."""
+    second, recall@10 and R@1 against the exact neighbours.  sweep: also the grid of L and K of Sec. 5.4 (Eq. 4 is in Sec. 4.4)."""
     import time
     import numpy as np
     import torch
@@ -113,7 +113,7 @@ def main():
                     help="f16 / bf16: float workloads are stored as IEEE half precision (RNND_F16) or bfloat16 "
                          "(RNND_BF16); the graph is the one of the rounded data")
     ap.add_argument("--search-sweep", action="store_true",
-                    help="search-quality leg over L in {16,32,64,128} x K in {16,...,96, no cap} (Sec. 5.2)")
+                    help="search-quality leg over L in {16,32,64,128} x K in {16,...,96, no cap} (Sec. 5.4)")
     ap.add_argument("--merge-cap", type=int, default=0,
                     help="rows this many slots wide (R <= M <= 128): UpdateNeighbors merges cut to M, only "
                          "AddReverseEdges cuts to R (rnnd_build_wide); 0 = fixed-width rows, the build the metric "

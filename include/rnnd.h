@@ -7,7 +7,8 @@
  *
  * Conventions
  *   - "device" pointers are HIP device memory owned by the caller; the library
- *     never keeps a pointer after a call returns.
+ *     never keeps a caller's pointer after a call returns.  Its own workspace is one
+ *     block per device that it keeps between calls (see rnnd_workspace_bytes).
  *   - X is row-major N x d, contiguous: uint8, float32, or (RNND_F16, RNND_BF16) IEEE binary16 or
  *     bfloat16 as a storage format for float data -- every coordinate stands for the float32 value it
  *     converts to exactly, all arithmetic is that of float data, and the graph is the one
@@ -51,10 +52,11 @@ typedef enum { RNND_L2SQ = 0 } rnnd_metric;
 typedef enum {
     RNND_OK = 0,
     RNND_ERR_NULL = -1,         /* a required pointer is NULL */
-    RNND_ERR_BAD_SHAPE = -2,    /* N < 2, N > 2^31-2, N*R >= 2^32-256, d < 1, or uint8 d > 33025 (int32 overflow) */
-    RNND_ERR_BAD_PARAM = -3,    /* S < 1, S > R, S > N-1, R < 1, R > RNND_MAX_R, T1 < 1, T2 < 1 */
+    RNND_ERR_BAD_SHAPE = -2,    /* N < 2, N > 2^31-2, N * (slots per row) > 2^31-256, d < 1, or uint8 d > 33025 (int32 overflow) */
+    RNND_ERR_BAD_PARAM = -3,    /* S < 1, S > R, S > N-1, R < 1, R > RNND_MAX_R, T1 < 1, T2 < 1, T1*T2 (x runs per pass) > 131072 */
     RNND_ERR_UNSUPPORTED = -4,  /* unknown dtype or metric */
-    RNND_ERR_OOM = -5,          /* workspace allocation failed */
+    RNND_ERR_OOM = -5,          /* workspace allocation failed (also: a workspace of more than 1 TiB, which no
+                                   device holds, is refused before any device is touched) */
     RNND_ERR_HIP = -6           /* a HIP call or kernel failed (no GPU, launch error, ...) */
 } rnnd_status;
 
@@ -100,7 +102,7 @@ int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int metric, in
 
 /* Alg. 6 with synchronous rounds whose merges cut a list to M >= R entries instead of R: in the
  * paper UpdateNeighbors never drops an edge for lack of room and only AddReverseEdges bounds the
- * degrees by R (Sec. 5.1 reports out-degrees above R in the finished graphs), whereas rnnd_build
+ * degrees by R (Sec. 5.3 reports out-degrees above R in the finished graphs), whereas rnnd_build
  * keeps rows of fixed width R throughout.  Here rows are M slots wide, 1 <= R <= M <= RNND_MAX_R:
  * between two AddReverseEdges calls, and in the result, a list may hold up to M entries.
  *   graph_out  device int32 [N * M], keys_out device uint64 [N * M] or NULL
@@ -118,7 +120,7 @@ int rnnd_build_wide(const void *X, int64_t N, int32_t d, int dtype, int metric, 
  * entries as in rnnd_build) before the next run starts.  blocks = 1 gives the graph of rnnd_build;
  * blocks = N visits the vertices in Alg. 4's own order.  Every value of blocks defines one graph
  * per seed, bit for bit.
- *   blocks     1 <= blocks <= N, and T1 * T2 * (runs per pass) <= 131072
+ *   blocks     1 <= blocks <= N, and T1 * T2 * (runs per pass) <= 131072 (one small counter block each)
  *   keys_out   device uint64 [N*R] or NULL; stats: host or NULL (per-pass sums; scan_ms is not measured)
  * Other arguments, ownership and errors as for rnnd_build_ex. */
 int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
@@ -131,9 +133,20 @@ int rnnd_update_neighbors_blocks(const void *X, int64_t N, int32_t d, int dtype,
                                  uint64_t *keys, int32_t *deg, int32_t n_passes, int64_t blocks,
                                  rnnd_stats *stats, void *stream);
 
-/* Bytes of device workspace rnnd_build allocates (and frees) internally for these sizes (an upper
- * bound; for rnnd_build_wide pass M as R). */
-int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, size_t *bytes);
+/* Bytes of device workspace a build of `rounds` = T1 * T2 UpdateNeighbors rounds (times the runs per pass for
+ * rnnd_build_blocks; at most 131072) needs for these sizes (an upper bound; for rnnd_build_wide pass M as R).
+ * The library allocates it at the first call that needs it and keeps it, per device, for later calls (a
+ * larger request replaces it); rnnd_release_workspace hands it back. */
+int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, int64_t rounds, size_t *bytes);
+
+/* Frees the workspace block the library keeps on the current device between calls (no-op if there is none
+ * or a call is using it). */
+int rnnd_release_workspace(void);
+
+/* Testing aid: with on != 0 every workspace (kept block or fresh allocation) is filled with
+ * 0xA5 bytes before a call clears what it needs cleared, so that a kernel that relies on memory the library
+ * never initialised shows up as a wrong result instead of passing on zeroed pages.  Process-wide. */
+int rnnd_set_workspace_poison(int on);
 
 /* RandomGraph(S) (first step of Alg. 6): row u <- S distinct ids != u drawn from a counter-based
  * generator (draw j of vertex u = mix64(mix64(seed + G*(u+1)) + G*(j+1)), mix64 = splitmix64's
@@ -153,11 +166,16 @@ int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dtype, int me
  * every in-list is cut to its R shortest by (delta, source id). */
 int rnnd_add_reverse_edges(int64_t N, int32_t R, uint64_t *keys, int32_t *deg, void *stream);
 
+/* The same on a snapshot whose rows are M >= R slots wide and may hold up to M entries on entry (the state
+ * rnnd_build_wide is in between two calls): afterwards every out-list and every in-list holds at most R.
+ * keys: device uint64 [N * M].  M = R is rnnd_add_reverse_edges. */
+int rnnd_add_reverse_edges_wide(int64_t N, int32_t R, int32_t M, uint64_t *keys, int32_t *deg, void *stream);
+
 /* Snapshot -> output format of rnnd_build (ids, -1 padded; degrees). */
 int rnnd_export_graph(int64_t N, int32_t R, const uint64_t *keys, const int32_t *deg,
                       int32_t *graph_out, int32_t *degree_out, void *stream);
 
-/* Search (Alg. 1) on a built graph, with the out-degree cap K of Eq. 4 (Sec. 5.2): for each of nq
+/* Search (Alg. 1) on a built graph, with the out-degree cap K of Eq. 4 (Sec. 4.4; studied in Sec. 5.4): for each of nq
  * queries, the candidate list C of at most L points starts from min(L, N) distinct seeded random
  * vertices (InitializeCandidates is not specified by the paper; the generator is the one RandomGraph
  * uses, keyed by seed + 0x9E3779B97F4A7C15 * query index), the nearest unvisited member of C is

@@ -531,7 +531,7 @@ int orc_build_sync(const void *X, int64_t n, int32_t d, int dtype, int32_t S, in
 
 /* Alg. 6 with synchronous rounds whose merges cut a list to M >= R entries; only AddReverseEdges
  * bounds the degrees by R, as in the paper, where UpdateNeighbors itself never drops an edge for
- * lack of room (Sec. 5.1 reports out-degrees above R at the end).  M = R is orc_build_sync. */
+ * lack of room (Sec. 5.3 reports out-degrees above R at the end).  M = R is orc_build_sync. */
 int orc_build_wide(const void *X, int64_t n, int32_t d, int dtype, int32_t S, int32_t R, int32_t M,
                    int32_t T1, int32_t T2, uint64_t seed, int32_t W, int32_t *ids, double *dist,
                    uint8_t *flags, int32_t *deg, int64_t *round_evals, int64_t *round_props)

@@ -90,11 +90,14 @@ def load_library():
                                         c.POINTER(Stats), vp]
         L.rnnd_update_neighbors_blocks.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, vp, vp, i32, i64,
                                                    c.POINTER(Stats), vp]
-        L.rnnd_workspace_bytes.argtypes = [i64, i32, c.c_int, i32, c.POINTER(c.c_size_t)]
+        L.rnnd_workspace_bytes.argtypes = [i64, i32, c.c_int, i32, i64, c.POINTER(c.c_size_t)]
+        L.rnnd_release_workspace.argtypes = []
+        L.rnnd_set_workspace_poison.argtypes = [c.c_int]
         L.rnnd_random_graph.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, u64, vp, vp, vp]
         L.rnnd_update_neighbors.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, vp, vp, i32,
                                             c.POINTER(Stats), vp]
         L.rnnd_add_reverse_edges.argtypes = [i64, i32, vp, vp, vp]
+        L.rnnd_add_reverse_edges_wide.argtypes = [i64, i32, i32, vp, vp, vp]
         L.rnnd_export_graph.argtypes = [i64, i32, vp, vp, vp, vp, vp]
         L.rnnd_search.argtypes = [vp, i64, i32, c.c_int, c.c_int, vp, vp, i32, vp, i64, i32, i32, i32, c.c_uint64,
                                   vp, vp, c.POINTER(c.c_int64), vp]
@@ -106,7 +109,8 @@ def load_library():
         for name in ("rnnd_build", "rnnd_build_ex", "rnnd_workspace_bytes", "rnnd_random_graph",
                      "rnnd_update_neighbors", "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search",
                      "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks",
-                     "rnnd_probe_gather", "rnnd_build_wide"):
+                     "rnnd_probe_gather", "rnnd_build_wide", "rnnd_release_workspace",
+                     "rnnd_set_workspace_poison", "rnnd_add_reverse_edges_wide"):
             getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -153,10 +157,18 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def rnnd_workspace_bytes(N: int, d: int, dtype: int, R: int) -> int:
+def rnnd_workspace_bytes(N: int, d: int, dtype: int, R: int, rounds: int) -> int:
     b = ctypes.c_size_t(0)
-    _check(load_library().rnnd_workspace_bytes(N, d, dtype, R, ctypes.byref(b)))
+    _check(load_library().rnnd_workspace_bytes(N, d, dtype, R, rounds, ctypes.byref(b)))
     return b.value
+
+
+def rnnd_release_workspace():
+    _check(load_library().rnnd_release_workspace())
+
+
+def rnnd_set_workspace_poison(on: bool):
+    _check(load_library().rnnd_set_workspace_poison(1 if on else 0))
 
 
 def rnnd_build(X, S: int, R: int, T1: int, T2: int, seed: int, metric: int = RNND_L2SQ, stream=None):
@@ -262,6 +274,14 @@ def rnnd_add_reverse_edges(keys, deg, R: int, stream=None):
     assert keys.is_cuda and keys.is_contiguous() and keys.shape == (N, R) and keys.element_size() == 8
     assert deg.is_cuda and deg.is_contiguous() and deg.shape == (N,) and deg.element_size() == 4
     _check(load_library().rnnd_add_reverse_edges(N, R, keys.data_ptr(), deg.data_ptr(), _stream(stream)))
+
+
+def rnnd_add_reverse_edges_wide(keys, deg, R: int, stream=None):
+    """Rows are keys.shape[1] >= R slots wide."""
+    N, M = keys.shape
+    assert keys.is_cuda and keys.is_contiguous() and keys.element_size() == 8
+    assert deg.is_cuda and deg.is_contiguous() and deg.shape == (N,) and deg.element_size() == 4
+    _check(load_library().rnnd_add_reverse_edges_wide(N, R, M, keys.data_ptr(), deg.data_ptr(), _stream(stream)))
 
 
 def rnnd_export_graph(keys, deg, R: int, stream=None):

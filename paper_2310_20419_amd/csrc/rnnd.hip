@@ -19,6 +19,7 @@
 #include <stdint.h>
 #include <stdio.h>
 #include <string.h>
+#include <mutex>
 
 #include "../../include/rnnd.h"
 #include "wave_prims.h"
@@ -26,6 +27,8 @@
 #define WAVES_PER_BLOCK 4
 #define BLOCK (64 * WAVES_PER_BLOCK)
 #define GOLDEN64 0x9E3779B97F4A7C15ull
+#define RNND_MAX_SLOTS 0x7FFFFF00ull   // N * (slots per row): bin offsets are ints, -1 = no bin
+#define RNND_MAX_RUN_SLOTS 131072      // rounds (x runs per pass): one small counter block each
 #define NDEG 8   // degree classes of the active lists (see degree_class)
 #define NMRG 4   // merge classes of the touched lists: kept + received at most 16, 32, 64, more
 #ifndef INBOX_CAP
@@ -804,6 +807,7 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int W, int
         u64 *row = keys + (size_t)x * W;
         const int c = fill[x];
         int nd = deg[x];
+        if (c == 0 && nd > R) nd = R;   // Alg. 5 cuts every out-list to its R shortest; the row is sorted and distinct
         if (c > 0) {
             bool any_new;
             const int ca = c < INBOX_CAP ? c : INBOX_CAP;
@@ -886,10 +890,9 @@ __global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 
     }
 }
 
-__global__ void k_zero_u32(u32 *p, int n)
+__global__ void k_zero_u32(u32 *p, size_t n)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
 // vcls[u] for a snapshot handed in by the caller
@@ -988,6 +991,7 @@ __global__ __launch_bounds__(256) void k_probe_gather(const uint4 *X, u32 n_rows
         if (e_ != hipSuccess) {                                                    \
             snprintf(g_last_hip_error, sizeof g_last_hip_error, "%s: %s", #x, hipGetErrorString(e_)); \
             rc = (e_ == hipErrorOutOfMemory) ? RNND_ERR_OOM : RNND_ERR_HIP;        \
+            (void)hipGetLastError();   /* reported here: must not surface again in a later call */ \
             goto done;                                                             \
         }                                                                          \
     } while (0)
@@ -1013,6 +1017,10 @@ struct Workspace {
     RoundCtr *ctr = nullptr;   // [n_ctr]
     u32 *misc = nullptr;       // [8]: small cursors for AddReverseEdges
     int n_ctr = 0;
+    // cnt[], fill[] and ctr[] must read zero when a call starts; they lie next to each other so that one
+    // fill kernel clears them (ws_clear)
+    u32 *zero_begin = nullptr;
+    size_t zero_words = 0;
 };
 
 static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_graph, size_t xs_bytes)
@@ -1025,13 +1033,14 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
     size_t o_props = take((size_t)N * R * sizeof(Prop));
     size_t o_bins = take((size_t)N * R * 8);
     size_t o_thr = take((size_t)N * 8);
-    size_t o_cnt = take((size_t)N * 4), o_binoff = take((size_t)N * 4), o_fill = take((size_t)N * 4);
+    size_t o_binoff = take((size_t)N * 4);
     size_t o_touched = take((size_t)N * 4 * NMRG), o_hubs = take((size_t)N * 4), o_nprop = take((size_t)N * 4);
     size_t o_xs = take(xs_bytes);
     size_t o_lists = take((size_t)N * 4 * NDEG);
     size_t o_vcls = take((size_t)N), o_tcls = take((size_t)N * NMRG);
-    size_t o_ctr = take((size_t)n_ctr * sizeof(RoundCtr));
     size_t o_misc = take(8 * 4);
+    size_t o_cnt = take((size_t)N * 4), o_fill = take((size_t)N * 4);      // the zeroed span: cnt, fill, ctr
+    size_t o_ctr = take((size_t)n_ctr * sizeof(RoundCtr));
     if (w.base) {
         if (own_graph) { w.keys = (u64 *)(w.base + o_keys); w.deg = (int *)(w.base + o_deg); }
         w.inbox = (u64 *)(w.base + o_inbox);
@@ -1051,8 +1060,19 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
         w.ctr = (RoundCtr *)(w.base + o_ctr);
         w.misc = (u32 *)(w.base + o_misc);
         w.n_ctr = n_ctr;
+        w.zero_begin = (u32 *)(w.base + o_cnt);
+        w.zero_words = (off - o_cnt) / 4;
     }
     return off;
+}
+
+// Every entry point clears the counters of its workspace with this before its first kernel: a fill kernel,
+// not a memset node, so that the same sequence stays valid inside a captured graph.
+static void ws_clear(const Workspace &w, hipStream_t st)
+{
+    const size_t n = w.zero_words;
+    const unsigned blocks = (unsigned)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048);
+    hipLaunchKernelGGL(k_zero_u32, dim3(blocks ? blocks : 1), dim3(256), 0, st, w.zero_begin, n);
 }
 
 static int check_data_args(const void *X, long long N, int d, int dtype, int metric, int R)
@@ -1063,8 +1083,8 @@ static int check_data_args(const void *X, long long N, int d, int dtype, int met
     if (N < 2 || N > 2147483646LL || d < 1) return RNND_ERR_BAD_SHAPE;
     if (dtype == RNND_U8 && d > 33025) return RNND_ERR_BAD_SHAPE;
     if (R < 1 || R > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
-    // list slots are counted in 32-bit device counters (bin space handed out per round)
-    if ((unsigned long long)N * (unsigned long long)R > 0xFFFFFF00ull) return RNND_ERR_BAD_SHAPE;
+    // list slots are counted in 32-bit device counters, and a bin offset is an int with -1 for "no bin"
+    if ((unsigned long long)N * (unsigned long long)R > RNND_MAX_SLOTS) return RNND_ERR_BAD_SHAPE;
     return RNND_OK;
 }
 
@@ -1363,8 +1383,8 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     int8_t *cand = w.tcls, *rowflag = w.tcls + N, *mark = w.tcls + 2 * N;
     u32 *late = (u32 *)w.props;          // one word per list slot (props is 16 bytes per slot)
     u64 *over = (u64 *)w.touched;        // two words per vertex (touched is 16 bytes per vertex)
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, 8);
-    if (t_next >= 0) hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, NDEG);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, (size_t)8);
+    if (t_next >= 0) hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, (size_t)NDEG);
     // union with reversed edges, out-lists cut to R
     hipLaunchKernelGGL(k_reverse_scatter, dim3((unsigned)((N * 16 + BLOCK - 1) / BLOCK)), dim3(BLOCK), 0, st, N, W, keys, deg,
                        w.fill, w.inbox, late, over, mark);
@@ -1403,149 +1423,136 @@ static void fill_round_stats(rnnd_stats *s, const RoundCtr *h, int rounds)
     }
 }
 
-extern "C" int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, size_t *bytes)
+// --------------------------------------------------------------- where a call's workspace comes from
+// 1. the block the library keeps per device between calls (allocated by the first call that needs it, grown
+//    when a later call needs more, handed back by rnnd_release_workspace): repeated builds pay no allocation;
+// 2. a fresh allocation, freed when the call ends, if another thread's call holds that block;
+#define RNND_MAX_DEVICES 64
+
+struct DeviceSlot {
+    char *cached = nullptr;        // the kept block
+    size_t cached_bytes = 0;
+    bool busy = false;             // a call is using it
+};
+static std::mutex g_ws_mu;
+static DeviceSlot g_dev[RNND_MAX_DEVICES];
+static int g_poison = 0;           // testing aid: every workspace is filled with 0xA5 bytes before it is cleared
+
+enum WsSource { WS_NONE = 0, WS_CACHED, WS_FRESH };
+struct WsLease {
+    char *base = nullptr;
+    int dev = -1;
+    WsSource src = WS_NONE;
+};
+
+__global__ void k_fill_u32(u32 *p, size_t n, u32 v)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// No device holds a workspace of this size; asking for one is an allocation failure that needs no device to detect.
+#define RNND_WS_HARD_LIMIT ((size_t)1 << 40)
+
+static int ws_acquire(size_t bytes, hipStream_t st, WsLease *out)
+{
+    int rc = RNND_OK, dev = 0;
+    if (bytes > RNND_WS_HARD_LIMIT) return RNND_ERR_OOM;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= RNND_MAX_DEVICES) {
+        snprintf(g_last_hip_error, sizeof g_last_hip_error, "device index %d is beyond the %d this library tracks", dev,
+                 RNND_MAX_DEVICES);
+        return RNND_ERR_HIP;
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_ws_mu);
+        DeviceSlot &d = g_dev[dev];
+        if (!d.busy) {
+            if (d.cached && d.cached_bytes < bytes) {
+                (void)hipFree(d.cached);
+                d.cached = nullptr;
+                d.cached_bytes = 0;
+            }
+            if (!d.cached) {
+                HIPCHK(hipMalloc((void **)&d.cached, bytes));
+                d.cached_bytes = bytes;
+            }
+            d.busy = true;
+            out->base = d.cached;
+            out->src = WS_CACHED;
+        } else {
+            HIPCHK(hipMalloc((void **)&out->base, bytes));
+            out->src = WS_FRESH;
+        }
+        out->dev = dev;
+    }
+    if (g_poison) hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, st, (u32 *)out->base, bytes / 4, 0xA5A5A5A5u);
+done:
+    return rc;
+}
+
+static void ws_release(WsLease *l)
+{
+    if (l->src == WS_FRESH) {
+        (void)hipFree(l->base);
+    } else if (l->src == WS_CACHED) {
+        std::lock_guard<std::mutex> lock(g_ws_mu);
+        g_dev[l->dev].busy = false;
+    }
+    l->src = WS_NONE;
+    l->base = nullptr;
+}
+
+extern "C" int rnnd_release_workspace(void)
+{
+    int rc = RNND_OK, dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev >= 0 && dev < RNND_MAX_DEVICES) {
+        std::lock_guard<std::mutex> lock(g_ws_mu);
+        DeviceSlot &d = g_dev[dev];
+        if (d.cached && !d.busy) {
+            HIPCHK(hipFree(d.cached));
+            d.cached = nullptr;
+            d.cached_bytes = 0;
+        }
+    }
+done:
+    return rc;
+}
+
+extern "C" int rnnd_set_workspace_poison(int on)
+{
+    g_poison = on ? 1 : 0;
+    return RNND_OK;
+}
+
+extern "C" int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, int64_t rounds, size_t *bytes)
 {
     if (!bytes) return RNND_ERR_NULL;
     if (dtype != RNND_U8 && dtype != RNND_F32 && dtype != RNND_F16 && dtype != RNND_BF16) return RNND_ERR_UNSUPPORTED;
     if (N < 2 || N > 2147483646LL || d < 1) return RNND_ERR_BAD_SHAPE;
-    if (R < 1 || R > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
+    if (R < 1 || R > RNND_MAX_R || rounds < 1 || rounds > RNND_MAX_RUN_SLOTS) return RNND_ERR_BAD_PARAM;
     Workspace w;
     // upper bound: the int8 copy exists only for uint8 rows of 32, 64 or 128 bytes
-    *bytes = ws_layout(w, N, R, RNND_MAX_ROUNDS + 2, true,
+    *bytes = ws_layout(w, N, R, (int)rounds + 2, true,
                        (dtype == RNND_U8 && (d == 32 || d == 64 || d == 128)) ? (size_t)N * d : 0);
     return RNND_OK;
 }
 
-// Alg. 6 with synchronous rounds.  M = slots per row = the bound every UpdateNeighbors merge cuts a list to
-// (M = R: rnnd_build; M > R: rnnd_build_wide, where only AddReverseEdges cuts to R).
-static int build_sync_impl(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
-                           int32_t M, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
-                           int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
+template <int DT>
+static void launch_random_graph_dt(const void *X, long long N, int d, int vec_ok, int S, int R, u64 seed, u64 *keys,
+                                   int *deg, int8_t *vcls, int use_classes, hipStream_t st)
 {
-    int rc = check_data_args(X, N, d, dtype, metric, M);
-    if (rc) return rc;
-    if (R < 1 || R > M) return RNND_ERR_BAD_PARAM;
-    if (!graph_out || !degree_out) return RNND_ERR_NULL;
-    if (S < 1 || S > R || (int64_t)S > N - 1 || T1 < 1 || T2 < 1) return RNND_ERR_BAD_PARAM;
-    if ((int64_t)T1 * T2 > 1000000) return RNND_ERR_BAD_PARAM;
-    hipStream_t st = (hipStream_t)stream;
-    const int rounds = T1 * T2, n_ctr = rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
-    // events (only when statistics are wanted): start, end of init, (scan start, scan stop, round
-    // stop) per round, end of each reverse call, end
-    const int n_ev = stats ? 3 * rounds + T1 + 3 : 0;
-    Workspace w;
-    hipEvent_t *ev = nullptr;
-    RoundCtr *hctr = nullptr;
-    int n_ev_made = 0;
-    w.bytes = ws_layout(w, N, M, n_ctr, true, xs_bytes_for(N, d, variant));
-    HIPCHK(hipMalloc((void **)&w.base, w.bytes));
-    ws_layout(w, N, M, n_ctr, true, xs_bytes_for(N, d, variant));
-    ev = (hipEvent_t *)calloc(n_ev + 1, sizeof(hipEvent_t));
-    hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
-    if (!ev || !hctr) { rc = RNND_ERR_OOM; goto done; }
-    for (; n_ev_made < n_ev; ++n_ev_made) HIPCHK(hipEventCreate(&ev[n_ev_made]));
-    {
-        // event indices: 0 start, 1 end of init, 2 + 3t .. 4 + 3t round t, then the reverse calls, then the end
-        const int e_rev = 2 + 3 * rounds, e_end = e_rev + T1;
-        int t = 0;
-        if (stats) HIPCHK(hipEventRecord(ev[0], st));
-        HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
-        HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
-        HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
-        if (variant == 2) launch_prepare_u8(w, X, N, d, st);
-        if (dtype == RNND_U8)
-            hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
-        else if (dtype == RNND_F16)
-            hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
-        else if (dtype == RNND_BF16)
-            hipLaunchKernelGGL(k_random_graph<DT_BF16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
-        else
-            hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
-        launch_compact_all(w, N, 0, st, stats ? ev[1] : nullptr);
-        HIPCHK(hipGetLastError());
-        for (int t1 = 0; t1 < T1; ++t1) {
-            for (int t2 = 0; t2 < T2; ++t2, ++t) {
-                RoundEvents re;
-                // a round ends where the next one starts; only the last round before a reverse call or
-                // the export needs an event of its own for that (every event costs a few microseconds)
-                if (stats) {
-                    re.scan_start = ev[2 + 3 * t];
-                    re.scan_stop = ev[3 + 3 * t];
-                    if (t2 == T2 - 1) re.round_stop = ev[4 + 3 * t];
-                }
-                HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, M, w.keys, w.deg, t, st, re));
-            }
-            if (t1 != T1 - 1)
-                HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, t, st, stats ? ev[e_rev + t1] : nullptr, M));
-        }
-        launch_export(N, M, w.keys, w.deg, graph_out, degree_out, st);
-        HIPCHK(hipGetLastError());
-        if (keys_out)
-            HIPCHK(hipMemcpyAsync(keys_out, w.keys, (size_t)N * M * 8, hipMemcpyDeviceToDevice, st));
-        if (stats) {
-            HIPCHK(hipEventRecord(ev[e_end], st));
-            HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
-        }
-        HIPCHK(hipStreamSynchronize(st));
-        if (stats) {
-            memset(stats, 0, sizeof *stats);
-            fill_round_stats(stats, hctr, rounds);
-            stats->reverse_calls = T1 - 1;
-            stats->init_evals = (int64_t)N * S;
-            stats->kernel_variant = variant;
-            float ms = 0;
-            (void)hipEventElapsedTime(&ms, ev[0], ev[1]); stats->init_ms = ms;
-            int tt = 0;
-            for (int t1 = 0; t1 < T1; ++t1) {
-                for (int t2 = 0; t2 < T2; ++t2, ++tt) {
-                    if (tt >= RNND_MAX_ROUNDS) continue;
-                    (void)hipEventElapsedTime(&ms, ev[2 + 3 * tt], ev[3 + 3 * tt]); stats->scan_ms[tt] = ms;
-                    (void)hipEventElapsedTime(&ms, ev[2 + 3 * tt], t2 == T2 - 1 ? ev[4 + 3 * tt] : ev[2 + 3 * (tt + 1)]);
-                    stats->round_ms[tt] = ms;
-                }
-                if (t1 != T1 - 1 && t1 < RNND_MAX_ROUNDS) {
-                    // from the end of the last round before the call to the end of the call
-                    (void)hipEventElapsedTime(&ms, ev[4 + 3 * (tt - 1)], ev[e_rev + t1]);
-                    stats->reverse_ms[t1] = ms;
-                }
-            }
-            (void)hipEventElapsedTime(&ms, ev[0], ev[e_end]); stats->total_ms = ms;
-        }
-    }
-done:
-    for (int i = 0; i < n_ev_made; ++i) (void)hipEventDestroy(ev[i]);
-    free(ev);
-    free(hctr);
-    if (w.base) (void)hipFree(w.base);
-    return rc;
+    hipLaunchKernelGGL(k_random_graph<DT>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, N, d, vec_ok, S, R, seed, keys,
+                       deg, vcls, use_classes);
 }
 
-extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
-                             int32_t R, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
-                             int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
+static void launch_random_graph(const void *X, long long N, int d, int dtype, int vec_ok, int S, int R, u64 seed,
+                                u64 *keys, int *deg, int8_t *vcls, int use_classes, hipStream_t st)
 {
-    return build_sync_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, graph_out, degree_out, keys_out, stats, stream);
-}
-
-extern "C" int rnnd_build_wide(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
-                               int32_t M, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
-                               int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
-{
-    if (M < 1 || M > RNND_MAX_R) return X ? RNND_ERR_BAD_PARAM : RNND_ERR_NULL;
-    return build_sync_impl(X, N, d, dtype, metric, S, R, M, T1, T2, seed, graph_out, degree_out, keys_out, stats, stream);
-}
-
-extern "C" int rnnd_build(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
-                          int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out, int32_t *degree_out,
-                          void *stream)
-{
-    return rnnd_build_ex(X, N, d, dtype, metric, S, R, T1, T2, seed, graph_out, degree_out, nullptr, nullptr,
-                         stream);
+    if (dtype == RNND_U8) launch_random_graph_dt<DT_U8>(X, N, d, vec_ok, S, R, seed, keys, deg, vcls, use_classes, st);
+    else if (dtype == RNND_F16) launch_random_graph_dt<DT_F16>(X, N, d, vec_ok, S, R, seed, keys, deg, vcls, use_classes, st);
+    else if (dtype == RNND_BF16) launch_random_graph_dt<DT_BF16>(X, N, d, vec_ok, S, R, seed, keys, deg, vcls, use_classes, st);
+    else launch_random_graph_dt<DT_F32>(X, N, d, vec_ok, S, R, seed, keys, deg, vcls, use_classes, st);
 }
 
 // per-pass statistics of a block-sequential run: slot sums of the runs of each pass
@@ -1566,72 +1573,80 @@ static void fill_pass_stats(rnnd_stats *s, const RoundCtr *h, int passes, int pe
     }
 }
 
-#define RNND_MAX_RUN_SLOTS 131072   // passes x runs per pass: one small counter block each
-
-extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
-                                 int32_t R, int32_t T1, int32_t T2, uint64_t seed, int64_t blocks,
-                                 int32_t *graph_out, int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats,
-                                 void *stream)
+// Alg. 6, every variant of the driver.
+//   M       slots per row = the bound every UpdateNeighbors merge cuts a list to (M = R: rnnd_build;
+//           M > R: rnnd_build_wide, where only AddReverseEdges cuts to R)
+//   blocks  0: synchronous rounds; >= 1: block-sequential passes of that many runs (rnnd_build_blocks)
+static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R, int32_t M,
+                      int32_t T1, int32_t T2, uint64_t seed, int64_t blocks, int32_t *graph_out,
+                      int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
 {
-    int rc = check_data_args(X, N, d, dtype, metric, R);
+    int rc = check_data_args(X, N, d, dtype, metric, M);
     if (rc) return rc;
+    if (R < 1 || R > M) return RNND_ERR_BAD_PARAM;
     if (!graph_out || !degree_out) return RNND_ERR_NULL;
     if (S < 1 || S > R || (int64_t)S > N - 1 || T1 < 1 || T2 < 1) return RNND_ERR_BAD_PARAM;
-    if ((int64_t)T1 * T2 > 1000000 || blocks < 1 || blocks > N) return RNND_ERR_BAD_PARAM;
-    const long long per_pass = runs_per_pass(N, blocks);
+    if ((int64_t)T1 * T2 > RNND_MAX_RUN_SLOTS || blocks < 0 || blocks > N) return RNND_ERR_BAD_PARAM;
+    const long long per_pass = blocks ? runs_per_pass(N, blocks) : 1;
     if ((long long)T1 * T2 * per_pass > RNND_MAX_RUN_SLOTS) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
-    const int passes = T1 * T2, n_ctr = (int)(passes * per_pass) + 2, vec_ok = vec_ok_for(X, d, dtype);
+    const int rounds = T1 * T2, n_ctr = (int)(rounds * per_pass) + 2, vec_ok = vec_ok_for(X, d, dtype);
     const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
-    // events (only when statistics are wanted): 0 start, 1 end of init, 2 + p end of pass p, then the end of
-    // each AddReverseEdges call, then the end
-    const int e_rev = 2 + passes, e_end = e_rev + T1, n_ev = stats ? e_end + 1 : 0;
+    // events (only when statistics are wanted): 0 start, 1 end of init, 2 + 3t .. 4 + 3t = scan start, scan stop,
+    // end of round t (block-sequential passes record only the last), then the end of each reverse call, then the end
+    const int e_rev = 2 + 3 * rounds, e_end = e_rev + T1, n_ev = stats ? e_end + 1 : 0;
     Workspace w;
+    WsLease lease;
     hipEvent_t *ev = nullptr;
     RoundCtr *hctr = nullptr;
     int n_ev_made = 0;
-    w.bytes = ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
-    HIPCHK(hipMalloc((void **)&w.base, w.bytes));
-    ws_layout(w, N, R, n_ctr, true, xs_bytes_for(N, d, variant));
-    ev = (hipEvent_t *)calloc(n_ev + 1, sizeof(hipEvent_t));
-    hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
-    if (!ev || !hctr) { rc = RNND_ERR_OOM; goto done; }
-    for (; n_ev_made < n_ev; ++n_ev_made) HIPCHK(hipEventCreate(&ev[n_ev_made]));
+    w.bytes = ws_layout(w, N, M, n_ctr, true, xs_bytes_for(N, d, variant));
+    rc = ws_acquire(w.bytes, st, &lease);
+    if (rc) return rc;
+    w.base = lease.base;
+    ws_layout(w, N, M, n_ctr, true, xs_bytes_for(N, d, variant));
+    if (stats) {
+        ev = (hipEvent_t *)calloc(n_ev + 1, sizeof(hipEvent_t));
+        hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
+        if (!ev || !hctr) { rc = RNND_ERR_OOM; goto done; }
+        for (; n_ev_made < n_ev; ++n_ev_made) HIPCHK(hipEventCreate(&ev[n_ev_made]));
+    }
     {
-        int p = 0;
+        int t = 0;
         if (stats) HIPCHK(hipEventRecord(ev[0], st));
-        HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
-        HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
-        HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
+        ws_clear(w, st);
         if (variant == 2) launch_prepare_u8(w, X, N, d, st);
-        if (dtype == RNND_U8)
-            hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
-        else if (dtype == RNND_F16)
-            hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
-        else if (dtype == RNND_BF16)
-            hipLaunchKernelGGL(k_random_graph<DT_BF16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
-        else
-            hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d,
-                               vec_ok, S, R, (u64)seed, w.keys, w.deg, w.vcls, use_classes);
+        launch_random_graph(X, N, d, dtype, vec_ok, S, M, (u64)seed, w.keys, w.deg, w.vcls, use_classes, st);
+        if (!blocks) launch_compact_all(w, N, 0, st, stats ? ev[1] : nullptr);
+        else if (stats) HIPCHK(hipEventRecord(ev[1], st));
         HIPCHK(hipGetLastError());
-        if (stats) HIPCHK(hipEventRecord(ev[1], st));
         for (int t1 = 0; t1 < T1; ++t1) {
-            for (int t2 = 0; t2 < T2; ++t2, ++p) {
-                int used = 0;
-                HIPCHK(launch_update_pass_blocks(w, X, N, d, dtype, vec_ok, variant, R, w.keys, w.deg,
-                                                 (int)(p * per_pass), blocks, st, &used));
-                if (stats) HIPCHK(hipEventRecord(ev[2 + p], st));
+            for (int t2 = 0; t2 < T2; ++t2, ++t) {
+                if (blocks) {
+                    int used = 0;
+                    HIPCHK(launch_update_pass_blocks(w, X, N, d, dtype, vec_ok, variant, M, w.keys, w.deg,
+                                                     (int)(t * per_pass), blocks, st, &used));
+                    if (stats) HIPCHK(hipEventRecord(ev[4 + 3 * t], st));
+                    continue;
+                }
+                RoundEvents re;
+                // a round ends where the next one starts; only the last round before a reverse call or
+                // the export needs an event of its own for that (every event costs a few microseconds)
+                if (stats) {
+                    re.scan_start = ev[2 + 3 * t];
+                    re.scan_stop = ev[3 + 3 * t];
+                    if (t2 == T2 - 1) re.round_stop = ev[4 + 3 * t];
+                }
+                HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, M, w.keys, w.deg, t, st, re));
             }
             if (t1 != T1 - 1)
-                HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, -1, st, stats ? ev[e_rev + t1] : nullptr));
+                HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, blocks ? -1 : t, st,
+                                      stats ? ev[e_rev + t1] : nullptr, M));
         }
-        launch_export(N, R, w.keys, w.deg, graph_out, degree_out, st);
+        launch_export(N, M, w.keys, w.deg, graph_out, degree_out, st);
         HIPCHK(hipGetLastError());
         if (keys_out)
-            HIPCHK(hipMemcpyAsync(keys_out, w.keys, (size_t)N * R * 8, hipMemcpyDeviceToDevice, st));
+            HIPCHK(hipMemcpyAsync(keys_out, w.keys, (size_t)N * M * 8, hipMemcpyDeviceToDevice, st));
         if (stats) {
             HIPCHK(hipEventRecord(ev[e_end], st));
             HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
@@ -1639,22 +1654,30 @@ extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype,
         HIPCHK(hipStreamSynchronize(st));
         if (stats) {
             memset(stats, 0, sizeof *stats);
-            fill_pass_stats(stats, hctr, passes, (int)per_pass);
+            if (blocks) fill_pass_stats(stats, hctr, rounds, (int)per_pass);
+            else fill_round_stats(stats, hctr, rounds);
             stats->reverse_calls = T1 - 1;
             stats->init_evals = (int64_t)N * S;
             stats->kernel_variant = variant;
             float ms = 0;
             (void)hipEventElapsedTime(&ms, ev[0], ev[1]); stats->init_ms = ms;
-            int pp = 0;
+            int tt = 0;
             for (int t1 = 0; t1 < T1; ++t1) {
-                for (int t2 = 0; t2 < T2; ++t2, ++pp) {
-                    if (pp >= RNND_MAX_ROUNDS) continue;
-                    // a pass starts where the one before it, the init or the reverse call ended
-                    hipEvent_t from = t2 > 0 ? ev[2 + pp - 1] : (t1 == 0 ? ev[1] : ev[e_rev + t1 - 1]);
-                    (void)hipEventElapsedTime(&ms, from, ev[2 + pp]); stats->round_ms[pp] = ms;
+                for (int t2 = 0; t2 < T2; ++t2, ++tt) {
+                    if (tt >= RNND_MAX_ROUNDS) continue;
+                    if (blocks) {
+                        // a pass starts where the one before it, the init or the reverse call ended
+                        hipEvent_t from = t2 > 0 ? ev[4 + 3 * (tt - 1)] : (t1 == 0 ? ev[1] : ev[e_rev + t1 - 1]);
+                        (void)hipEventElapsedTime(&ms, from, ev[4 + 3 * tt]); stats->round_ms[tt] = ms;
+                        continue;
+                    }
+                    (void)hipEventElapsedTime(&ms, ev[2 + 3 * tt], ev[3 + 3 * tt]); stats->scan_ms[tt] = ms;
+                    (void)hipEventElapsedTime(&ms, ev[2 + 3 * tt], t2 == T2 - 1 ? ev[4 + 3 * tt] : ev[2 + 3 * (tt + 1)]);
+                    stats->round_ms[tt] = ms;
                 }
                 if (t1 != T1 - 1 && t1 < RNND_MAX_ROUNDS) {
-                    (void)hipEventElapsedTime(&ms, ev[2 + pp - 1], ev[e_rev + t1]);
+                    // from the end of the last round before the call to the end of the call
+                    (void)hipEventElapsedTime(&ms, ev[4 + 3 * (tt - 1)], ev[e_rev + t1]);
                     stats->reverse_ms[t1] = ms;
                 }
             }
@@ -1662,11 +1685,43 @@ extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype,
         }
     }
 done:
+    if (rc == RNND_ERR_HIP || rc == RNND_ERR_OOM) (void)hipStreamSynchronize(st);   // nothing may still use the workspace
     for (int i = 0; i < n_ev_made; ++i) (void)hipEventDestroy(ev[i]);
     free(ev);
     free(hctr);
-    if (w.base) (void)hipFree(w.base);
+    ws_release(&lease);
     return rc;
+}
+
+extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
+                             int32_t R, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
+                             int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
+{
+    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, 0, graph_out, degree_out, keys_out, stats, stream);
+}
+
+extern "C" int rnnd_build_wide(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+                               int32_t M, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
+                               int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
+{
+    if (M < 1 || M > RNND_MAX_R) return X ? RNND_ERR_BAD_PARAM : RNND_ERR_NULL;
+    return build_impl(X, N, d, dtype, metric, S, R, M, T1, T2, seed, 0, graph_out, degree_out, keys_out, stats, stream);
+}
+
+extern "C" int rnnd_build(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+                          int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out, int32_t *degree_out,
+                          void *stream)
+{
+    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, 0, graph_out, degree_out, nullptr, nullptr, stream);
+}
+
+extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
+                                 int32_t R, int32_t T1, int32_t T2, uint64_t seed, int64_t blocks,
+                                 int32_t *graph_out, int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats,
+                                 void *stream)
+{
+    if (blocks < 1) return X ? RNND_ERR_BAD_PARAM : RNND_ERR_NULL;
+    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, blocks, graph_out, degree_out, keys_out, stats, stream);
 }
 
 extern "C" int rnnd_random_graph(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
@@ -1677,22 +1732,66 @@ extern "C" int rnnd_random_graph(const void *X, int64_t N, int32_t d, int dtype,
     if (!keys || !deg) return RNND_ERR_NULL;
     if (S < 1 || S > R || (int64_t)S > N - 1) return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
-    const int vec_ok = vec_ok_for(X, d, dtype);
-    if (dtype == RNND_U8)
-        hipLaunchKernelGGL(k_random_graph<DT_U8>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
-                           S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
-    else if (dtype == RNND_F16)
-        hipLaunchKernelGGL(k_random_graph<DT_F16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
-                           S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
-    else if (dtype == RNND_BF16)
-        hipLaunchKernelGGL(k_random_graph<DT_BF16>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
-                           S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
-    else
-        hipLaunchKernelGGL(k_random_graph<DT_F32>, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, X, (long long)N, d, vec_ok,
-                           S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0);
+    launch_random_graph(X, N, d, dtype, vec_ok_for(X, d, dtype), S, R, (u64)seed, (u64 *)keys, deg, (int8_t *)nullptr, 0, st);
     HIPCHK(hipGetLastError());
     HIPCHK(hipStreamSynchronize(st));
 done:
+    return rc;
+}
+
+// UpdateNeighbors applied in place to a caller's snapshot: n_rounds synchronous rounds (blocks = 0) or
+// block-sequential passes of `blocks` runs.
+static int update_impl(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t R, uint64_t *keys,
+                       int32_t *deg, int32_t n_rounds, int64_t blocks, rnnd_stats *stats, void *stream)
+{
+    int rc = check_data_args(X, N, d, dtype, metric, R);
+    if (rc) return rc;
+    if (!keys || !deg) return RNND_ERR_NULL;
+    if (n_rounds < 1 || n_rounds > RNND_MAX_RUN_SLOTS || blocks < 0 || blocks > N) return RNND_ERR_BAD_PARAM;
+    const long long per_pass = blocks ? runs_per_pass(N, blocks) : 1;
+    if ((long long)n_rounds * per_pass > RNND_MAX_RUN_SLOTS) return RNND_ERR_BAD_PARAM;
+    hipStream_t st = (hipStream_t)stream;
+    const int n_ctr = (int)(n_rounds * per_pass) + 2, vec_ok = vec_ok_for(X, d, dtype);
+    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
+    Workspace w;
+    WsLease lease;
+    RoundCtr *hctr = nullptr;
+    w.bytes = ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
+    rc = ws_acquire(w.bytes, st, &lease);
+    if (rc) return rc;
+    w.base = lease.base;
+    ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
+    if (stats) {
+        hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
+        if (!hctr) { rc = RNND_ERR_OOM; goto done; }
+    }
+    ws_clear(w, st);
+    if (variant == 2) launch_prepare_u8(w, X, N, d, st);
+    hipLaunchKernelGGL(k_classify, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, (long long)N, R, (const u64 *)keys,
+                       deg, w.vcls, use_classes);
+    if (!blocks) launch_compact_all(w, N, 0, st);
+    HIPCHK(hipGetLastError());
+    for (int t = 0; t < n_rounds; ++t) {
+        if (blocks) {
+            int used = 0;
+            HIPCHK(launch_update_pass_blocks(w, X, N, d, dtype, vec_ok, variant, R, (u64 *)keys, deg,
+                                             (int)(t * per_pass), blocks, st, &used));
+        } else {
+            HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, (u64 *)keys, deg, t, st));
+        }
+    }
+    if (stats) HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
+    HIPCHK(hipStreamSynchronize(st));
+    if (stats) {
+        memset(stats, 0, sizeof *stats);
+        if (blocks) fill_pass_stats(stats, hctr, n_rounds, (int)per_pass);
+        else fill_round_stats(stats, hctr, n_rounds);
+        stats->kernel_variant = variant;
+    }
+done:
+    if (rc == RNND_ERR_HIP || rc == RNND_ERR_OOM) (void)hipStreamSynchronize(st);
+    free(hctr);
+    ws_release(&lease);
     return rc;
 }
 
@@ -1700,104 +1799,45 @@ extern "C" int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dt
                                      uint64_t *keys, int32_t *deg, int32_t n_rounds, rnnd_stats *stats,
                                      void *stream)
 {
-    int rc = check_data_args(X, N, d, dtype, metric, R);
-    if (rc) return rc;
-    if (!keys || !deg) return RNND_ERR_NULL;
-    if (n_rounds < 1 || n_rounds > 1000000) return RNND_ERR_BAD_PARAM;
-    hipStream_t st = (hipStream_t)stream;
-    const int n_ctr = n_rounds + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
-    Workspace w;
-    RoundCtr *hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
-    if (!hctr) return RNND_ERR_OOM;
-    w.bytes = ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
-    HIPCHK(hipMalloc((void **)&w.base, w.bytes));
-    ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
-    HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
-    HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
-    HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
-    if (variant == 2) launch_prepare_u8(w, X, N, d, st);
-    hipLaunchKernelGGL(k_classify, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, (long long)N, R, (const u64 *)keys,
-                       deg, w.vcls, use_classes);
-    launch_compact_all(w, N, 0, st);
-    HIPCHK(hipGetLastError());
-    for (int t = 0; t < n_rounds; ++t)
-        HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, (u64 *)keys, deg, t, st));
-    HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
-    HIPCHK(hipStreamSynchronize(st));
-    if (stats) {
-        memset(stats, 0, sizeof *stats);
-        fill_round_stats(stats, hctr, n_rounds);
-        stats->kernel_variant = variant;
-    }
-done:
-    free(hctr);
-    if (w.base) (void)hipFree(w.base);
-    return rc;
+    return update_impl(X, N, d, dtype, metric, R, keys, deg, n_rounds, 0, stats, stream);
 }
 
 extern "C" int rnnd_update_neighbors_blocks(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t R,
-                                           uint64_t *keys, int32_t *deg, int32_t n_passes, int64_t blocks,
-                                           rnnd_stats *stats, void *stream)
+                                            uint64_t *keys, int32_t *deg, int32_t n_passes, int64_t blocks,
+                                            rnnd_stats *stats, void *stream)
 {
-    int rc = check_data_args(X, N, d, dtype, metric, R);
-    if (rc) return rc;
+    if (blocks < 1) return X ? RNND_ERR_BAD_PARAM : RNND_ERR_NULL;
+    return update_impl(X, N, d, dtype, metric, R, keys, deg, n_passes, blocks, stats, stream);
+}
+
+extern "C" int rnnd_add_reverse_edges_wide(int64_t N, int32_t R, int32_t M, uint64_t *keys, int32_t *deg,
+                                           void *stream)
+{
+    int rc = RNND_OK;
     if (!keys || !deg) return RNND_ERR_NULL;
-    if (n_passes < 1 || n_passes > 1000000 || blocks < 1 || blocks > N) return RNND_ERR_BAD_PARAM;
-    const long long per_pass = runs_per_pass(N, blocks);
-    if ((long long)n_passes * per_pass > RNND_MAX_RUN_SLOTS) return RNND_ERR_BAD_PARAM;
+    if (N < 2 || N > 2147483646LL) return RNND_ERR_BAD_SHAPE;
+    if (R < 1 || M < R || M > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
+    if ((unsigned long long)N * (unsigned long long)M > RNND_MAX_SLOTS) return RNND_ERR_BAD_SHAPE;
     hipStream_t st = (hipStream_t)stream;
-    const int n_ctr = (int)(n_passes * per_pass) + 2, vec_ok = vec_ok_for(X, d, dtype);
-    const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
     Workspace w;
-    RoundCtr *hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
-    if (!hctr) return RNND_ERR_OOM;
-    w.bytes = ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
-    HIPCHK(hipMalloc((void **)&w.base, w.bytes));
-    ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
-    HIPCHK(hipMemsetAsync(w.ctr, 0, (size_t)n_ctr * sizeof(RoundCtr), st));
-    HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
-    HIPCHK(hipMemsetAsync(w.fill, 0, (size_t)N * 4, st));
-    if (variant == 2) launch_prepare_u8(w, X, N, d, st);
-    hipLaunchKernelGGL(k_classify, dim3(vertex_blocks(N)), dim3(BLOCK), 0, st, (long long)N, R, (const u64 *)keys,
-                       deg, w.vcls, use_classes);
-    HIPCHK(hipGetLastError());
-    for (int p = 0; p < n_passes; ++p) {
-        int used = 0;
-        HIPCHK(launch_update_pass_blocks(w, X, N, d, dtype, vec_ok, variant, R, (u64 *)keys, deg, (int)(p * per_pass),
-                                         blocks, st, &used));
-    }
-    HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
+    WsLease lease;
+    w.bytes = ws_layout(w, N, M, 2, false, 0);
+    rc = ws_acquire(w.bytes, st, &lease);
+    if (rc) return rc;
+    w.base = lease.base;
+    ws_layout(w, N, M, 2, false, 0);
+    ws_clear(w, st);      // launch_reverse expects fill[] == 0, cnt[] == 0 and zeroed counters
+    HIPCHK(launch_reverse(w, N, R, 0, (u64 *)keys, deg, 0, st, nullptr, M));
     HIPCHK(hipStreamSynchronize(st));
-    if (stats) {
-        memset(stats, 0, sizeof *stats);
-        fill_pass_stats(stats, hctr, n_passes, (int)per_pass);
-        stats->kernel_variant = variant;
-    }
 done:
-    free(hctr);
-    if (w.base) (void)hipFree(w.base);
+    if (rc == RNND_ERR_HIP || rc == RNND_ERR_OOM) (void)hipStreamSynchronize(st);
+    ws_release(&lease);
     return rc;
 }
 
 extern "C" int rnnd_add_reverse_edges(int64_t N, int32_t R, uint64_t *keys, int32_t *deg, void *stream)
 {
-    int rc = RNND_OK;
-    if (!keys || !deg) return RNND_ERR_NULL;
-    if (N < 2 || N > 2147483646LL) return RNND_ERR_BAD_SHAPE;
-    if (R < 1 || R > RNND_MAX_R) return RNND_ERR_BAD_PARAM;
-    hipStream_t st = (hipStream_t)stream;
-    Workspace w;
-    w.bytes = ws_layout(w, N, R, 2, false, 0);
-    HIPCHK(hipMalloc((void **)&w.base, w.bytes));
-    ws_layout(w, N, R, 2, false, 0);
-    HIPCHK(hipMemsetAsync(w.ctr, 0, 2 * sizeof(RoundCtr), st));
-    HIPCHK(hipMemsetAsync(w.cnt, 0, (size_t)N * 4, st));
-    HIPCHK(launch_reverse(w, N, R, 0, (u64 *)keys, deg, 0, st));
-    HIPCHK(hipStreamSynchronize(st));
-done:
-    if (w.base) (void)hipFree(w.base);
-    return rc;
+    return rnnd_add_reverse_edges_wide(N, R, R, keys, deg, stream);
 }
 
 extern "C" int rnnd_export_graph(int64_t N, int32_t R, const uint64_t *keys, const int32_t *deg,
@@ -1941,4 +1981,4 @@ extern "C" const char *rnnd_strerror(int status)
     }
 }
 
-extern "C" int rnnd_version(void) { return 107; }
+extern "C" int rnnd_version(void) { return 200; }

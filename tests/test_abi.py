@@ -21,7 +21,8 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"rnnd_build", "rnnd_build_ex", "rnnd_random_graph", "rnnd_update_neighbors",
             "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search", "rnnd_workspace_bytes",
             "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant", "rnnd_build_blocks",
-            "rnnd_update_neighbors_blocks", "rnnd_probe_gather", "rnnd_build_wide"} <= set(names)
+            "rnnd_update_neighbors_blocks", "rnnd_probe_gather", "rnnd_build_wide", "rnnd_release_workspace",
+            "rnnd_set_workspace_poison"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -49,6 +50,10 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert call(T1=0) == -3 and call(T2=0) == -3 and call(N=5, S=5, R=8) == -3
     assert call(dtype=4) == -4 and call(dtype=-1) == -4 and call(metric=1) == -4
     assert call(N=50_000_000, R=128, S=4) == -2          # N*R does not fit the 32-bit slot counters
+    assert call(N=25_000_000, R=96, S=4) == -2           # ... nor the signed bin offsets (N*R > 2^31 - 256)
+    assert call(T1=400, T2=400) == -3                    # more rounds than counter blocks
+    assert lib.rnnd_add_reverse_edges(25_000_000, 96, one, one, None) == -2
+    assert lib.rnnd_add_reverse_edges(100, 8, None, one, None) == -1
     assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(3) == -3
     assert lib.rnnd_set_kernel_variant(0) == 0
     # block-sequential entry points: same checks, plus the number of runs
@@ -86,17 +91,34 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert search(out=None) == -1 and search(dtype=4) == -4
 
 
+def test_an_impossible_workspace_is_an_allocation_failure_without_a_gpu(lib):
+    """N * R is inside the slot bound, but the workspace (about 1.4 TB) is beyond any device: RNND_ERR_OOM,
+    decided before the first HIP call, so it is the same on a box without a GPU."""
+    one = ctypes.c_void_p(1)
+    n = 2**31 - 512
+    assert rn.rnnd_workspace_bytes(n, 16, rn.RNND_U8, 1, 1) > 2**40
+    assert lib.rnnd_build(one, n, 16, 0, 0, 1, 1, 1, 1, 0, one, one, None) == -5
+    assert lib.rnnd_update_neighbors(one, n, 16, 0, 0, 1, one, one, 1, None, None) == -5
+    assert lib.rnnd_add_reverse_edges(n, 1, one, one, None) == -5
+    assert "memory" in rn.rnnd_strerror(-5)
+
+
 def test_workspace_bytes(lib):
-    b = rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 96)
+    b = rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 96, 60)
+    # the size grows with the number of rounds (one counter block each), and the query covers every
+    # number of rounds a build accepts
+    assert rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 96, 131072) > b + 131000 * 2000
+    with pytest.raises(rn.RnndError):
+        rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 96, 131073)
     # graph (8 B) + redirected-edge slots (16 B) + bins (8 B) per list slot, a 64-key inbox per vertex, and
     # (uint8 rows of 32/64/128 bytes) the int8 copy of X dominate; small per-vertex arrays on top
     per_vertex = 96 * 32 + 512 + 128
     assert 1_000_000 * per_vertex <= b < 1_000_000 * (per_vertex + 128)
     # float rows have no int8 copy
-    bf = rn.rnnd_workspace_bytes(1_000_000, 96, rn.RNND_F32, 96)
+    bf = rn.rnnd_workspace_bytes(1_000_000, 96, rn.RNND_F32, 96, 60)
     assert 1_000_000 * (96 * 32 + 512) <= bf < 1_000_000 * (96 * 32 + 512 + 128)
     with pytest.raises(rn.RnndError):
-        rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 500)
+        rn.rnnd_workspace_bytes(1_000_000, 128, rn.RNND_U8, 500, 60)
 
 
 def test_key_packing_roundtrip():

@@ -71,3 +71,29 @@ def test_wide_rows_outgrow_R_and_reverse_edges_cut_them(rn):
     g, deg1, keys, _ = rn.rnnd_build_wide(cuda(X), 8, R, M, 1, 3, 1)
     rn.rnnd_add_reverse_edges(keys[:, :M].contiguous(), deg1, M)                # plain call: cap = stride = M
     assert int(deg1.max()) <= M
+
+
+def test_reverse_edges_cut_a_long_list_that_receives_nothing(rn, oracle_mod):
+    """Alg. 5's first loop cuts EVERY out-list to its R shortest, also the list of a vertex no edge points to.
+    Rows are M = 64 wide, R = 12; vertices 0 .. 5 hold 40 entries each and appear in nobody's list (their unions
+    exceed 32 keys, so they take the one-vertex-at-a-time path of the union kernel), everyone else holds a short
+    list among the ids >= 6.  Step-wise call on the snapshot, against the oracle's AddReverseEdges on M-wide rows."""
+    from gpu_util import snapshot_to_device
+    g = np.random.default_rng(5)
+    n, d, R, M, lonely = 400, 32, 12, 64, 6
+    X = np.clip(128 + g.normal(0, 30, size=(n, d)), 0, 255).astype(np.uint8)
+    Xl = X.astype(np.int64)
+    snap = oracle_mod.Snapshot.empty(n, M)
+    for u in range(n):
+        m = 40 if u < lonely else int(g.integers(0, 9))
+        ids = g.choice(np.arange(lonely, n)[np.arange(lonely, n) != u], size=m, replace=False)
+        dist = ((Xl[ids] - Xl[u]) ** 2).sum(1)
+        order = np.lexsort((ids, dist))
+        snap.ids[u, :m], snap.dist[u, :m] = ids[order], dist[order]
+        snap.flags[u, :m] = g.integers(0, 2, size=m)
+        snap.deg[u] = m
+    want = oracle_mod.add_reverse_edges(snap, R)
+    assert (want.deg[:lonely] == R).all() and want.deg.max() <= R       # the oracle cuts them (Alg. 5, first loop)
+    keys, deg = snapshot_to_device(snap, False, M)
+    rn.rnnd_add_reverse_edges_wide(keys, deg, R)
+    assert_snapshot_equal(want, False, keys, deg, "lonely long lists")
