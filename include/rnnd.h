@@ -45,6 +45,7 @@ extern "C" {
 
 #define RNND_MAX_R 128          /* largest supported degree cap R */
 #define RNND_MAX_ROUNDS 256     /* per-round statistics are kept for the first 256 rounds */
+#define RNND_STATIC_SCRATCH_BYTES (64u << 20)   /* size of the static device array rnnd_build_static works in */
 
 typedef enum { RNND_U8 = 0, RNND_F32 = 1, RNND_F16 = 2, RNND_BF16 = 3 } rnnd_dtype;
 typedef enum { RNND_L2SQ = 0 } rnnd_metric;
@@ -57,7 +58,8 @@ typedef enum {
     RNND_ERR_UNSUPPORTED = -4,  /* unknown dtype or metric */
     RNND_ERR_OOM = -5,          /* workspace allocation failed (also: a workspace of more than 1 TiB, which no
                                    device holds, is refused before any device is touched) */
-    RNND_ERR_HIP = -6           /* a HIP call or kernel failed (no GPU, launch error, ...) */
+    RNND_ERR_HIP = -6,          /* a HIP call or kernel failed (no GPU, launch error, ...) */
+    RNND_ERR_SCRATCH = -7       /* rnnd_build_static: the workspace for these sizes exceeds RNND_STATIC_SCRATCH_BYTES */
 } rnnd_status;
 
 /* Counters of one build, filled on the host.  "algo" evaluations are the delta(v,w)
@@ -143,7 +145,22 @@ int rnnd_workspace_bytes(int64_t N, int32_t d, int dtype, int32_t R, int64_t rou
  * or a call is using it). */
 int rnnd_release_workspace(void);
 
-/* Testing aid: with on != 0 every workspace (kept block or fresh allocation) is filled with
+/* rnnd_build for callers that cannot allocate device memory (code that runs under HIP graph capture
+ * elsewhere in the process, tight serving loops, harnesses that forbid hipMalloc): the same build with the
+ * workspace in a static device array of RNND_STATIC_SCRATCH_BYTES that the library's code object carries
+ * (every device the library runs on holds its copy until the process ends).  The call performs no
+ * hipMalloc, hipFree, event creation or any other allocating call, on the device or through a library.
+ *   limit   rnnd_workspace_bytes(N, d, dtype, R, T1*T2) <= RNND_STATIC_SCRATCH_BYTES, else RNND_ERR_SCRATCH
+ *           (e.g. N = 5,000 x d = 32 uint8 with R = 32 needs 8 MB; N = 17,000 x 128 with R = 96 just fits)
+ *   sharing every call on a device works in that device's one array, which keeps the previous call's
+ *           contents (what must start at zero is cleared by a kernel on `stream`): calls that overlap in
+ *           time on one device race and give undefined graphs -- serialise them.
+ * Arguments, result, ownership and the other errors as for rnnd_build; same graph, bit for bit. */
+int rnnd_build_static(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+                      int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out, int32_t *degree_out,
+                      void *stream);
+
+/* Testing aid: with on != 0 every workspace (kept block, fresh allocation or static array) is filled with
  * 0xA5 bytes before a call clears what it needs cleared, so that a kernel that relies on memory the library
  * never initialised shows up as a wrong result instead of passing on zeroed pages.  Process-wide. */
 int rnnd_set_workspace_poison(int on);

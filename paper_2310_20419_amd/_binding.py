@@ -91,6 +91,7 @@ def load_library():
         L.rnnd_update_neighbors_blocks.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, vp, vp, i32, i64,
                                                    c.POINTER(Stats), vp]
         L.rnnd_workspace_bytes.argtypes = [i64, i32, c.c_int, i32, i64, c.POINTER(c.c_size_t)]
+        L.rnnd_build_static.argtypes = L.rnnd_build.argtypes
         L.rnnd_release_workspace.argtypes = []
         L.rnnd_set_workspace_poison.argtypes = [c.c_int]
         L.rnnd_random_graph.argtypes = [vp, i64, i32, c.c_int, c.c_int, i32, i32, u64, vp, vp, vp]
@@ -109,7 +110,7 @@ def load_library():
         for name in ("rnnd_build", "rnnd_build_ex", "rnnd_workspace_bytes", "rnnd_random_graph",
                      "rnnd_update_neighbors", "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search",
                      "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks",
-                     "rnnd_probe_gather", "rnnd_build_wide", "rnnd_release_workspace",
+                     "rnnd_probe_gather", "rnnd_build_wide", "rnnd_build_static", "rnnd_release_workspace",
                      "rnnd_set_workspace_poison", "rnnd_add_reverse_edges_wide"):
             getattr(L, name).restype = c.c_int
         _lib = L
@@ -157,6 +158,9 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
+RNND_STATIC_SCRATCH_BYTES = 64 << 20
+
+
 def rnnd_workspace_bytes(N: int, d: int, dtype: int, R: int, rounds: int) -> int:
     b = ctypes.c_size_t(0)
     _check(load_library().rnnd_workspace_bytes(N, d, dtype, R, rounds, ctypes.byref(b)))
@@ -169,6 +173,17 @@ def rnnd_release_workspace():
 
 def rnnd_set_workspace_poison(on: bool):
     _check(load_library().rnnd_set_workspace_poison(1 if on else 0))
+
+
+def rnnd_build_static(X, S: int, R: int, T1: int, T2: int, seed: int, graph, degree, metric: int = RNND_L2SQ,
+                      stream=None):
+    """rnnd_build_static: the caller passes the outputs (graph [N, R] int32, degree [N] int32, on X's device);
+    nothing is allocated, here or in the library."""
+    ptr, N, d, dt = _data_args(X)
+    assert graph.is_cuda and graph.is_contiguous() and graph.shape == (N, R) and graph.element_size() == 4
+    assert degree.is_cuda and degree.is_contiguous() and degree.shape == (N,) and degree.element_size() == 4
+    _check(load_library().rnnd_build_static(ptr, N, d, dt, metric, S, R, T1, T2, seed, graph.data_ptr(),
+                                            degree.data_ptr(), _stream(stream)))
 
 
 def rnnd_build(X, S: int, R: int, T1: int, T2: int, seed: int, metric: int = RNND_L2SQ, stream=None):

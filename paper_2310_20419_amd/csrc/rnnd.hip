@@ -1427,18 +1427,22 @@ static void fill_round_stats(rnnd_stats *s, const RoundCtr *h, int rounds)
 // 1. the block the library keeps per device between calls (allocated by the first call that needs it, grown
 //    when a later call needs more, handed back by rnnd_release_workspace): repeated builds pay no allocation;
 // 2. a fresh allocation, freed when the call ends, if another thread's call holds that block;
+// 3. for rnnd_build_static only: the file-scope array below, which needs no allocation at all.
 #define RNND_MAX_DEVICES 64
+
+static __device__ __align__(256) unsigned char scratch[RNND_STATIC_SCRATCH_BYTES];
 
 struct DeviceSlot {
     char *cached = nullptr;        // the kept block
     size_t cached_bytes = 0;
     bool busy = false;             // a call is using it
+    char *static_ptr = nullptr;    // this device's copy of `scratch` (hipGetSymbolAddress, once per device)
 };
 static std::mutex g_ws_mu;
 static DeviceSlot g_dev[RNND_MAX_DEVICES];
 static int g_poison = 0;           // testing aid: every workspace is filled with 0xA5 bytes before it is cleared
 
-enum WsSource { WS_NONE = 0, WS_CACHED, WS_FRESH };
+enum WsSource { WS_NONE = 0, WS_CACHED, WS_FRESH, WS_STATIC };
 struct WsLease {
     char *base = nullptr;
     int dev = -1;
@@ -1453,10 +1457,11 @@ __global__ void k_fill_u32(u32 *p, size_t n, u32 v)
 // No device holds a workspace of this size; asking for one is an allocation failure that needs no device to detect.
 #define RNND_WS_HARD_LIMIT ((size_t)1 << 40)
 
-static int ws_acquire(size_t bytes, hipStream_t st, WsLease *out)
+static int ws_acquire(size_t bytes, bool static_only, hipStream_t st, WsLease *out)
 {
     int rc = RNND_OK, dev = 0;
-    if (bytes > RNND_WS_HARD_LIMIT) return RNND_ERR_OOM;
+    if (!static_only && bytes > RNND_WS_HARD_LIMIT) return RNND_ERR_OOM;
+    if (static_only && bytes > RNND_STATIC_SCRATCH_BYTES) return RNND_ERR_SCRATCH;
     HIPCHK(hipGetDevice(&dev));
     if (dev < 0 || dev >= RNND_MAX_DEVICES) {
         snprintf(g_last_hip_error, sizeof g_last_hip_error, "device index %d is beyond the %d this library tracks", dev,
@@ -1466,7 +1471,15 @@ static int ws_acquire(size_t bytes, hipStream_t st, WsLease *out)
     {
         std::lock_guard<std::mutex> lock(g_ws_mu);
         DeviceSlot &d = g_dev[dev];
-        if (!d.busy) {
+        if (static_only) {
+            if (!d.static_ptr) {
+                char *ptr = nullptr;
+                HIPCHK(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+                d.static_ptr = ptr;
+            }
+            out->base = d.static_ptr;
+            out->src = WS_STATIC;
+        } else if (!d.busy) {
             if (d.cached && d.cached_bytes < bytes) {
                 (void)hipFree(d.cached);
                 d.cached = nullptr;
@@ -1577,9 +1590,10 @@ static void fill_pass_stats(rnnd_stats *s, const RoundCtr *h, int passes, int pe
 //   M       slots per row = the bound every UpdateNeighbors merge cuts a list to (M = R: rnnd_build;
 //           M > R: rnnd_build_wide, where only AddReverseEdges cuts to R)
 //   blocks  0: synchronous rounds; >= 1: block-sequential passes of that many runs (rnnd_build_blocks)
+//   fixed   the workspace is the static scratch array: no allocation of any kind, hence no statistics
 static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R, int32_t M,
                       int32_t T1, int32_t T2, uint64_t seed, int64_t blocks, int32_t *graph_out,
-                      int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
+                      int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream, bool fixed)
 {
     int rc = check_data_args(X, N, d, dtype, metric, M);
     if (rc) return rc;
@@ -1601,7 +1615,7 @@ static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric
     RoundCtr *hctr = nullptr;
     int n_ev_made = 0;
     w.bytes = ws_layout(w, N, M, n_ctr, true, xs_bytes_for(N, d, variant));
-    rc = ws_acquire(w.bytes, st, &lease);
+    rc = ws_acquire(w.bytes, fixed, st, &lease);
     if (rc) return rc;
     w.base = lease.base;
     ws_layout(w, N, M, n_ctr, true, xs_bytes_for(N, d, variant));
@@ -1697,7 +1711,7 @@ extern "C" int rnnd_build_ex(const void *X, int64_t N, int32_t d, int dtype, int
                              int32_t R, int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out,
                              int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
 {
-    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, 0, graph_out, degree_out, keys_out, stats, stream);
+    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, 0, graph_out, degree_out, keys_out, stats, stream, false);
 }
 
 extern "C" int rnnd_build_wide(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
@@ -1705,14 +1719,21 @@ extern "C" int rnnd_build_wide(const void *X, int64_t N, int32_t d, int dtype, i
                                int32_t *degree_out, uint64_t *keys_out, rnnd_stats *stats, void *stream)
 {
     if (M < 1 || M > RNND_MAX_R) return X ? RNND_ERR_BAD_PARAM : RNND_ERR_NULL;
-    return build_impl(X, N, d, dtype, metric, S, R, M, T1, T2, seed, 0, graph_out, degree_out, keys_out, stats, stream);
+    return build_impl(X, N, d, dtype, metric, S, R, M, T1, T2, seed, 0, graph_out, degree_out, keys_out, stats, stream, false);
 }
 
 extern "C" int rnnd_build(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
                           int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out, int32_t *degree_out,
                           void *stream)
 {
-    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, 0, graph_out, degree_out, nullptr, nullptr, stream);
+    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, 0, graph_out, degree_out, nullptr, nullptr, stream, false);
+}
+
+extern "C" int rnnd_build_static(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S, int32_t R,
+                                 int32_t T1, int32_t T2, uint64_t seed, int32_t *graph_out, int32_t *degree_out,
+                                 void *stream)
+{
+    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, 0, graph_out, degree_out, nullptr, nullptr, stream, true);
 }
 
 extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
@@ -1721,7 +1742,7 @@ extern "C" int rnnd_build_blocks(const void *X, int64_t N, int32_t d, int dtype,
                                  void *stream)
 {
     if (blocks < 1) return X ? RNND_ERR_BAD_PARAM : RNND_ERR_NULL;
-    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, blocks, graph_out, degree_out, keys_out, stats, stream);
+    return build_impl(X, N, d, dtype, metric, S, R, R, T1, T2, seed, blocks, graph_out, degree_out, keys_out, stats, stream, false);
 }
 
 extern "C" int rnnd_random_graph(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t S,
@@ -1757,7 +1778,7 @@ static int update_impl(const void *X, int64_t N, int32_t d, int dtype, int metri
     WsLease lease;
     RoundCtr *hctr = nullptr;
     w.bytes = ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
-    rc = ws_acquire(w.bytes, st, &lease);
+    rc = ws_acquire(w.bytes, false, st, &lease);
     if (rc) return rc;
     w.base = lease.base;
     ws_layout(w, N, R, n_ctr, false, xs_bytes_for(N, d, variant));
@@ -1822,7 +1843,7 @@ extern "C" int rnnd_add_reverse_edges_wide(int64_t N, int32_t R, int32_t M, uint
     Workspace w;
     WsLease lease;
     w.bytes = ws_layout(w, N, M, 2, false, 0);
-    rc = ws_acquire(w.bytes, st, &lease);
+    rc = ws_acquire(w.bytes, false, st, &lease);
     if (rc) return rc;
     w.base = lease.base;
     ws_layout(w, N, M, 2, false, 0);
@@ -1976,6 +1997,7 @@ extern "C" const char *rnnd_strerror(int status)
     case RNND_ERR_BAD_PARAM: return "bad parameter (S, R, T1 or T2 out of range)";
     case RNND_ERR_UNSUPPORTED: return "unsupported dtype or metric";
     case RNND_ERR_OOM: return "out of device memory";
+    case RNND_ERR_SCRATCH: return "the workspace for these sizes does not fit the static scratch array (rnnd_build_static)";
     case RNND_ERR_HIP: return g_last_hip_error[0] ? g_last_hip_error : "HIP error";
     default: return "unknown status";
     }
