@@ -52,6 +52,16 @@ def test_mix64_matches_published_splitmix64_vector(oracle_mod):
         assert oracle_mod.mix64(x) == want
 
 
+def test_draw_is_two_nested_mix64_calls(oracle_mod):
+    """draw j of vertex u = mix64(mix64(seed + G (u + 1)) + G (j + 1)), recomputed here from mix64 alone (which
+    the published vector above pins): a swapped u and j, a missing + 1 or a single mix would all differ."""
+    G = 0x9E3779B97F4A7C15
+    for seed, u, j in [(0, 0, 0), (2310, 5, 0), (2310, 0, 5), (99, 123456, 77), (M64, 2**31 - 2, 1023)]:
+        inner = oracle_mod.mix64((seed + G * (u + 1)) & M64)
+        assert oracle_mod.draw(seed, u, j) == oracle_mod.mix64((inner + G * (j + 1)) & M64)
+    assert oracle_mod.draw(1, 2, 3) != oracle_mod.draw(1, 3, 2)
+
+
 def test_random_ids_are_distinct_in_range_and_seeded(oracle_mod):
     n, S = 1000, 20
     seen_rows = []
@@ -529,9 +539,11 @@ def test_search_matches_a_setwise_model_on_small_inputs(oracle_mod, L, K, k):
     assert evals == total
 
 
-def test_search_quality_sync_vs_paper_order_vs_no_reverse_edges(oracle_mod):
-    c = wl.CONFIGS["cfg1"]
-    X, Q = wl.make_data(c), wl.make_queries(c)
+@pytest.mark.parametrize("name,n,nq", [("cfg1", 5000, 100), ("cfg2", 20000, 200)])
+def test_search_quality_sync_vs_paper_order_vs_no_reverse_edges(oracle_mod, name, n, nq):
+    """cfg1 as it is, and cfg2's generator and parameters (S=20 R=96 T1=4 T2=15) on its first 20,000 rows."""
+    c = wl.CONFIGS[name]
+    X, Q = wl.make_data(c, n), wl.make_queries(c, nq)
     gt = oracle_mod.bruteforce_knn(X, Q, 10)
 
     def recall(ids, deg, L=64):
@@ -544,6 +556,7 @@ def test_search_quality_sync_vs_paper_order_vs_no_reverse_edges(oracle_mod):
     t1only = oracle_mod.build_sync(X, c.S, c.R, 1, c.T1 * c.T2, wl.BUILD_SEED).snap
     r_sync, r_paper = recall(sync.ids, sync.deg), recall(pids, pdeg)
     r_init, r_t1 = recall(init.ids, init.deg), recall(t1only.ids, t1only.deg)
+    print("%s: recall@10 sync %.4f, paper order %.4f, T1 = 1 %.4f, random init %.4f" % (name, r_sync, r_paper, r_t1, r_init))
     assert r_sync > 0.97 and r_paper > 0.97
     assert abs(r_sync - r_paper) < 0.03                          # same method, different update order
     assert r_init < 0.5 < r_sync
