@@ -238,6 +238,14 @@ int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t 
  * All give identical graphs; this exists for testing and profiling.  Process-wide, not thread-safe. */
 int rnnd_set_kernel_variant(int variant);
 
+/* Selects how AddReverseEdges transposes the edge set (every edge (u, v) must reach v's list): 0 = by size
+ * (default: N >= 262,144 and N <= 2^25 binned, else atomics), 1 = one arrival-number atomic per edge,
+ * 2 = binned by target range (blocks count their edges per range of 2,048 targets, a prefix over the counts
+ * places them in one array ordered by range, one workgroup per range then numbers the arrivals in LDS; needs
+ * N <= 2^25, else falls back to 1).  Both give identical graphs; this exists for testing and profiling.
+ * Process-wide, not thread-safe. */
+int rnnd_set_transpose_path(int path);
+
 const char *rnnd_strerror(int status);
 int rnnd_version(void);
 

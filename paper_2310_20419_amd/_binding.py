@@ -104,6 +104,7 @@ def load_library():
                                   vp, vp, c.POINTER(c.c_int64), vp]
         L.rnnd_probe_gather.argtypes = [vp, i64, i64, i64, u64, c.POINTER(c.c_double), vp]
         L.rnnd_set_kernel_variant.argtypes = [c.c_int]
+        L.rnnd_set_transpose_path.argtypes = [c.c_int]
         L.rnnd_strerror.argtypes = [c.c_int]
         L.rnnd_strerror.restype = c.c_char_p
         L.rnnd_version.restype = c.c_int
@@ -111,7 +112,7 @@ def load_library():
                      "rnnd_update_neighbors", "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search",
                      "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks",
                      "rnnd_probe_gather", "rnnd_build_wide", "rnnd_build_static", "rnnd_release_workspace",
-                     "rnnd_set_workspace_poison", "rnnd_add_reverse_edges_wide"):
+                     "rnnd_set_workspace_poison", "rnnd_add_reverse_edges_wide", "rnnd_set_transpose_path"):
             getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -325,6 +326,10 @@ def rnnd_search(X, graph, degree, Q, L: int, K: int, k: int, seed: int, want_dis
                                       Q.data_ptr(), nq, L, K, k, seed, ids.data_ptr(),
                                       dist.data_ptr() if want_dist else None, ctypes.byref(ev), _stream(stream)))
     return ids, dist, ev.value
+
+
+def rnnd_set_transpose_path(path: int):
+    _check(load_library().rnnd_set_transpose_path(path))
 
 
 def rnnd_set_kernel_variant(variant: int):

@@ -727,6 +727,269 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_surplus(long long N, int R, c
     }
 }
 
+// ---- the same transposition without one device-scope atomic per edge (large N) -------------------------
+// Targets are cut into ranges of RANGE_TARGETS consecutive ids.  Every block of BIN_CHUNK source vertices
+// counts its edges per range in LDS (k_bin_count); a column-wise prefix over the blocks turns the counts into
+// the place of every (block, range) run in one edge array ordered by range (k_bin_offsets, k_bin_bases: no
+// atomics, the layout is a pure function of the graph); the blocks copy their edges there, taking ranks from
+// LDS counters (k_bin_partition); then one workgroup per range, which alone owns its targets, counts the edges
+// of each target in LDS, hands out the surplus bins, and moves every edge into its target's inbox or bin with
+// arrival numbers from the LDS counters (k_bin_place).  What k_reverse_scatter, the first k_assign_bins and
+// k_reverse_surplus leave behind -- fill[], inbox, binoff[], bins, cand[], zeroed cnt[] and cnt_in[] -- is
+// left in the same form (slot order inside an inbox is arbitrary in both; every consumer sorts).
+#define RANGE_BITS 11
+#define RANGE_TARGETS (1 << RANGE_BITS)
+#define RANGE_MAX 16384       // ranges a block can histogram in LDS (64 KB): N <= RANGE_MAX * RANGE_TARGETS
+#define BIN_CHUNK 2048        // source vertices per block of the count and partition kernels
+#define BIN_THREADS 1024
+
+// Walks the edges of the block's BIN_CHUNK source vertices: thread t of a pass takes list position t % 16 of
+// vertex t / 16 (lists are short on average; longer ones take further trips), four vertices per thread in
+// flight.  f(u, key) is called once per edge.
+template <typename F>
+__device__ __forceinline__ void for_each_edge_of_chunk(long long N, int W, const u64 *__restrict__ keys,
+                                                       const int *__restrict__ deg, F f)
+{
+    const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;      // 64 groups of 16 lanes
+    const long long u0 = (long long)blockIdx.x * BIN_CHUNK;
+    constexpr int GROUPS = BIN_THREADS / 16, UNROLL = 4;
+    for (int i = grp; i < BIN_CHUNK; i += GROUPS * UNROLL) {
+        long long u[UNROLL];
+        int m[UNROLL];
+        u64 k[UNROLL];
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) {
+            u[j] = u0 + i + j * GROUPS;
+            m[j] = (i + j * GROUPS < BIN_CHUNK && u[j] < N) ? deg[u[j]] : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) k[j] = sub < m[j] ? keys[(size_t)u[j] * W + sub] : 0ull;
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) {
+            if (sub < m[j]) f(u[j], k[j]);
+            for (int e = sub + 16; e < m[j]; e += 16) f(u[j], keys[(size_t)u[j] * W + e]);
+        }
+    }
+}
+
+__global__ __launch_bounds__(BIN_THREADS) void k_bin_count(long long N, int W, const u64 *__restrict__ keys,
+                                                           const int *__restrict__ deg, u32 nranges, u32 *__restrict__ blockhist)
+{
+    __shared__ u32 hist[RANGE_MAX];
+    for (u32 r = threadIdx.x; r < nranges; r += BIN_THREADS) hist[r] = 0;
+    __syncthreads();
+    for_each_edge_of_chunk(N, W, keys, deg, [&](long long, u64 k) { atomicAdd(&hist[key_id(k) >> RANGE_BITS], 1u); });
+    __syncthreads();
+    u32 *out = blockhist + (size_t)blockIdx.x * nranges;
+    for (u32 r = threadIdx.x; r < nranges; r += BIN_THREADS) out[r] = hist[r];
+}
+
+// blockhist[b][r] <- edges of range r in the blocks before b; range_tot[r] <- edges of range r in all.
+// A workgroup takes 64 ranges; its 16 wavefronts each take a slice of consecutive blocks (a wavefront reads
+// 64 consecutive counters of one block at a time), sum it, and after a prefix over the slices walk it again.
+__global__ __launch_bounds__(1024) void k_bin_offsets(u32 nblocks, u32 nranges, u32 *__restrict__ blockhist,
+                                                      u32 *__restrict__ range_tot)
+{
+    __shared__ u32 s_sum[16][64];
+    const u32 col = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const u32 r = blockIdx.x * 64 + col;
+    const bool have = r < nranges;
+    const u32 per = (nblocks + 15) / 16;
+    const u32 b0 = slice * per < nblocks ? slice * per : nblocks, b1 = b0 + per < nblocks ? b0 + per : nblocks;
+    u32 sum = 0;
+    if (have) {
+        u32 b = b0;
+        for (; b + 4 <= b1; b += 4) {
+            const u32 c0 = blockhist[(size_t)b * nranges + r], c1 = blockhist[(size_t)(b + 1) * nranges + r];
+            const u32 c2 = blockhist[(size_t)(b + 2) * nranges + r], c3 = blockhist[(size_t)(b + 3) * nranges + r];
+            sum += c0 + c1 + c2 + c3;
+        }
+        for (; b < b1; ++b) sum += blockhist[(size_t)b * nranges + r];
+    }
+    s_sum[slice][col] = sum;
+    __syncthreads();
+    u32 run = 0, all = 0;
+    for (u32 sl = 0; sl < 16; ++sl) {
+        const u32 v = s_sum[sl][col];
+        run += sl < slice ? v : 0u;
+        all += v;
+    }
+    if (have) {
+        if (slice == 0) range_tot[r] = all;
+        u32 b = b0;
+        for (; b + 4 <= b1; b += 4) {
+            const u32 c0 = blockhist[(size_t)b * nranges + r], c1 = blockhist[(size_t)(b + 1) * nranges + r];
+            const u32 c2 = blockhist[(size_t)(b + 2) * nranges + r], c3 = blockhist[(size_t)(b + 3) * nranges + r];
+            blockhist[(size_t)b * nranges + r] = run;
+            blockhist[(size_t)(b + 1) * nranges + r] = run + c0;
+            blockhist[(size_t)(b + 2) * nranges + r] = run + c0 + c1;
+            blockhist[(size_t)(b + 3) * nranges + r] = run + c0 + c1 + c2;
+            run += c0 + c1 + c2 + c3;
+        }
+        for (; b < b1; ++b) {
+            const u32 c = blockhist[(size_t)b * nranges + r];
+            blockhist[(size_t)b * nranges + r] = run;
+            run += c;
+        }
+    }
+}
+
+// range_base[r] <- edges of the ranges before r (one block; nranges <= RANGE_MAX); range_base[nranges] <- all.
+__global__ __launch_bounds__(1024) void k_bin_bases(u32 nranges, const u32 *__restrict__ range_tot, u32 *__restrict__ range_base)
+{
+    __shared__ u32 s_w[16];
+    constexpr int PER = RANGE_MAX / 1024;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    u32 v[PER], mine = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const u32 r = threadIdx.x * PER + k;
+        v[k] = r < nranges ? range_tot[r] : 0u;
+        mine += v[k];
+    }
+    u32 incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const u32 t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    u32 before = 0;
+    for (int w = 0; w < wave; ++w) before += s_w[w];
+    u32 run = before + incl - mine;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const u32 r = threadIdx.x * PER + k;
+        if (r < nranges) range_base[r] = run;
+        run += v[k];
+    }
+    if (threadIdx.x == 1023) range_base[nranges] = run;
+}
+
+// Edge (u, v) -> part[place of (my block, range of v) + rank inside it] = { key(delta, u, new), v }.
+__global__ __launch_bounds__(BIN_THREADS) void k_bin_partition(long long N, int W, const u64 *__restrict__ keys,
+                                                               const int *__restrict__ deg, u32 nranges,
+                                                               const u32 *__restrict__ blockhist,
+                                                               const u32 *__restrict__ range_base, Prop *__restrict__ part)
+{
+    __shared__ u32 cursor[RANGE_MAX];
+    const u32 *mine = blockhist + (size_t)blockIdx.x * nranges;
+    for (u32 r = threadIdx.x; r < nranges; r += BIN_THREADS) cursor[r] = range_base[r] + mine[r];
+    __syncthreads();
+    for_each_edge_of_chunk(N, W, keys, deg, [&](long long u, u64 k) {
+        const u32 v = key_id(k);
+        const u32 at = atomicAdd(&cursor[v >> RANGE_BITS], 1u);
+        Prop pr;
+        pr.key = make_key(key_dist(k), (u32)u, 1u);
+        pr.tgt = v;
+        pr.arrival = 0;
+        part[at] = pr;
+    });
+}
+
+// One workgroup per range of targets.  One sweep over the range's edges numbers the arrivals per target in LDS
+// and writes the first INBOX_CAP of each target straight into its inbox; later arrivals (hubs: rare) wait in an
+// LDS stash until the sweep has counted every target and the surplus bins are handed out.  A range whose
+// stash overflows is swept again with the bins known, rewriting every place.
+#define PLACE_THREADS 512
+#define PLACE_STASH 2048
+__global__ __launch_bounds__(PLACE_THREADS) void k_bin_place(long long N, int R, const Prop *__restrict__ part,
+                                                             const u32 *__restrict__ range_base, const int *__restrict__ deg,
+                                                             int *__restrict__ fill, u64 *__restrict__ inbox,
+                                                             int *__restrict__ binoff, u64 *__restrict__ bins,
+                                                             u32 *__restrict__ bin_cursor, int *__restrict__ zero_a,
+                                                             int *__restrict__ zero_b, int8_t *__restrict__ cand)
+{
+    __shared__ u32 arr[RANGE_TARGETS], bin_at[RANGE_TARGETS];
+    __shared__ u64 st_key[PLACE_STASH];
+    __shared__ u32 st_tgt[PLACE_STASH], st_arr[PLACE_STASH];
+    __shared__ u32 s_w[PLACE_THREADS / 64], s_base, s_stash;
+    constexpr int PER = RANGE_TARGETS / PLACE_THREADS, NW = PLACE_THREADS / 64, UNROLL = 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const u32 first = blockIdx.x << RANGE_BITS;          // first target of my range
+    const u32 e0 = range_base[blockIdx.x], e1 = range_base[blockIdx.x + 1];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) arr[threadIdx.x * PER + k] = 0;
+    if (threadIdx.x == 0) s_stash = 0;
+    __syncthreads();
+    // pass == 0: arrivals below INBOX_CAP to the inbox, later ones to the stash.  pass == 1 (only after a stash
+    // overflow): every edge again, surplus straight to the bins.
+    auto sweep = [&](const int pass) {
+        for (u32 e = e0 + threadIdx.x; e < e1; e += PLACE_THREADS * UNROLL) {
+            Prop pr[UNROLL];
+#pragma unroll
+            for (int j = 0; j < UNROLL; ++j) {
+                pr[j].tgt = 0xFFFFFFFFu;
+                if (e + j * PLACE_THREADS < e1) pr[j] = part[e + j * PLACE_THREADS];
+            }
+#pragma unroll
+            for (int j = 0; j < UNROLL; ++j) {
+                if (pr[j].tgt == 0xFFFFFFFFu) continue;
+                const u32 t = pr[j].tgt - first;
+                const u32 a = atomicAdd(&arr[t], 1u);
+                if (a < (u32)INBOX_CAP) {
+                    inbox[(size_t)pr[j].tgt * INBOX_CAP + a] = pr[j].key;
+                } else if (pass == 1) {
+                    bins[(size_t)bin_at[t] + (a - INBOX_CAP)] = pr[j].key;
+                } else {
+                    const u32 at = atomicAdd(&s_stash, 1u);
+                    if (at < (u32)PLACE_STASH) { st_key[at] = pr[j].key; st_tgt[at] = t; st_arr[at] = a; }
+                }
+            }
+        }
+    };
+    sweep(0);
+    __syncthreads();
+    // per target: the count, the candidate mark of the in-degree cut, cleared counters, a bin for the surplus
+    u32 c[PER], surplus[PER], mine = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        c[k] = arr[threadIdx.x * PER + k];
+        surplus[k] = c[k] > (u32)INBOX_CAP ? c[k] - (u32)INBOX_CAP : 0u;
+        mine += surplus[k];
+    }
+    u32 incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const u32 t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 tot = 0;
+        for (int w = 0; w < NW; ++w) { const u32 a = s_w[w]; s_w[w] = tot; tot += a; }
+        s_base = tot ? atomicAdd(bin_cursor, tot) : 0u;
+    }
+    __syncthreads();
+    u32 run = s_base + s_w[wave] + incl - mine;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const long long v = (long long)first + threadIdx.x * PER + k;
+        if (v < N) {
+            fill[v] = (int)c[k];
+            zero_a[v] = 0;
+            zero_b[v] = 0;
+            cand[v] = (int8_t)(deg[v] + (int)c[k] > R);
+            binoff[v] = surplus[k] ? (int)run : -1;
+        }
+        bin_at[threadIdx.x * PER + k] = run;     // where the target's bin starts (if it has one)
+        run += surplus[k];
+    }
+    __syncthreads();
+    const u32 stashed = s_stash;
+    if (stashed <= (u32)PLACE_STASH) {
+        for (u32 i = threadIdx.x; i < stashed; i += PLACE_THREADS)
+            bins[(size_t)bin_at[st_tgt[i]] + (st_arr[i] - INBOX_CAP)] = st_key[i];
+    } else {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) arr[threadIdx.x * PER + k] = 0;
+        __syncthreads();
+        sweep(1);
+    }
+}
+
 // For every edge (u, v) of a flagged list whose v owns a bin: bins[v] <- key(delta, u, flag).  Nothing to
 // do when no bin was handed out (*n_binned == 0).
 __global__ __launch_bounds__(BLOCK) void k_fill_bins(long long N, int R, const u64 *keys, const int *deg,
@@ -998,6 +1261,8 @@ __global__ __launch_bounds__(256) void k_probe_gather(const uint4 *X, u32 n_rows
 
 static char g_last_hip_error[512];
 static int g_kernel_variant = 0;
+static int g_transpose_path = 0;   // AddReverseEdges' transposition: 0 by size, 1 atomics, 2 binned
+#define BIN_MIN_N 262144            // below this the binned transposition's extra launches cost more than its atomics save
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -1016,12 +1281,17 @@ struct Workspace {
     int8_t *vcls = nullptr, *tcls = nullptr;   // [N], [NMRG*N]
     RoundCtr *ctr = nullptr;   // [n_ctr]
     u32 *misc = nullptr;       // [8]: small cursors for AddReverseEdges
+    u32 *blockhist = nullptr;  // binned transposition: [blocks of BIN_CHUNK vertices][ranges], null when N is out of its range
+    u32 *range_tot = nullptr, *range_base = nullptr;   // [RANGE_MAX + 1] each
     int n_ctr = 0;
     // cnt[], fill[] and ctr[] must read zero when a call starts; they lie next to each other so that one
     // fill kernel clears them (ws_clear)
     u32 *zero_begin = nullptr;
     size_t zero_words = 0;
 };
+
+static size_t bin_blocks(long long N) { return (size_t)((N + BIN_CHUNK - 1) / BIN_CHUNK); }
+static size_t bin_ranges(long long N) { return (size_t)((N + RANGE_TARGETS - 1) >> RANGE_BITS); }
 
 static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_graph, size_t xs_bytes)
 {
@@ -1039,6 +1309,9 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
     size_t o_lists = take((size_t)N * 4 * NDEG);
     size_t o_vcls = take((size_t)N), o_tcls = take((size_t)N * NMRG);
     size_t o_misc = take(8 * 4);
+    const bool binnable = N >= 2 && (unsigned long long)N <= (unsigned long long)RANGE_MAX * RANGE_TARGETS;
+    size_t o_range = take(binnable ? (size_t)2 * (RANGE_MAX + 1) * 4 : 0);
+    size_t o_blockhist = take(binnable ? bin_blocks(N) * bin_ranges(N) * 4 : 0);
     size_t o_cnt = take((size_t)N * 4), o_fill = take((size_t)N * 4);      // the zeroed span: cnt, fill, ctr
     size_t o_ctr = take((size_t)n_ctr * sizeof(RoundCtr));
     if (w.base) {
@@ -1059,6 +1332,9 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
         w.tcls = (int8_t *)(w.base + o_tcls);
         w.ctr = (RoundCtr *)(w.base + o_ctr);
         w.misc = (u32 *)(w.base + o_misc);
+        w.blockhist = binnable ? (u32 *)(w.base + o_blockhist) : nullptr;
+        w.range_tot = (u32 *)(w.base + o_range);
+        w.range_base = w.range_tot + (RANGE_MAX + 1);
         w.n_ctr = n_ctr;
         w.zero_begin = (u32 *)(w.base + o_cnt);
         w.zero_words = (off - o_cnt) / 4;
@@ -1386,12 +1662,25 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, (size_t)8);
     if (t_next >= 0) hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, (size_t)NDEG);
     // union with reversed edges, out-lists cut to R
-    hipLaunchKernelGGL(k_reverse_scatter, dim3((unsigned)((N * 16 + BLOCK - 1) / BLOCK)), dim3(BLOCK), 0, st, N, W, keys, deg,
-                       w.fill, w.inbox, late, over, mark);
-    hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.fill, INBOX_CAP, INBOX_CAP, INBOX_CAP,
-                       w.binoff, w.misc + 0, w.hubs, w.misc + 1, w.cnt, cnt_in, (u64 *)nullptr, deg, R, cand);
-    hipLaunchKernelGGL(k_reverse_surplus, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, late, over, mark, w.binoff,
-                       w.bins, w.misc + 1);
+    // the transposition: one arrival-number atomic per edge, or (large N, see k_bin_count) binned by target range
+    const bool binned = w.blockhist && g_transpose_path != 1 && (g_transpose_path == 2 || N >= BIN_MIN_N);
+    if (binned) {
+        const unsigned nb = (unsigned)bin_blocks(N), nr = (unsigned)bin_ranges(N);
+        hipLaunchKernelGGL(k_bin_count, dim3(nb), dim3(BIN_THREADS), 0, st, N, W, (const u64 *)keys, (const int *)deg, nr, w.blockhist);
+        hipLaunchKernelGGL(k_bin_offsets, dim3((nr + 63) / 64), dim3(1024), 0, st, nb, nr, w.blockhist, w.range_tot);
+        hipLaunchKernelGGL(k_bin_bases, dim3(1), dim3(1024), 0, st, nr, (const u32 *)w.range_tot, w.range_base);
+        hipLaunchKernelGGL(k_bin_partition, dim3(nb), dim3(BIN_THREADS), 0, st, N, W, (const u64 *)keys, (const int *)deg, nr,
+                           (const u32 *)w.blockhist, (const u32 *)w.range_base, w.props);
+        hipLaunchKernelGGL(k_bin_place, dim3(nr), dim3(PLACE_THREADS), 0, st, N, R, (const Prop *)w.props, (const u32 *)w.range_base,
+                           (const int *)deg, w.fill, w.inbox, w.binoff, w.bins, w.misc + 0, w.cnt, cnt_in, cand);
+    } else {
+        hipLaunchKernelGGL(k_reverse_scatter, dim3((unsigned)((N * 16 + BLOCK - 1) / BLOCK)), dim3(BLOCK), 0, st, N, W, keys, deg,
+                           w.fill, w.inbox, late, over, mark);
+        hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, w.fill, INBOX_CAP, INBOX_CAP, INBOX_CAP,
+                           w.binoff, w.misc + 0, w.hubs, w.misc + 1, w.cnt, cnt_in, (u64 *)nullptr, deg, R, cand);
+        hipLaunchKernelGGL(k_reverse_surplus, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, late, over, mark, w.binoff,
+                           w.bins, w.misc + 1);
+    }
     hipLaunchKernelGGL(k_reverse_merge, dim3((vb + 1) / 2), dim3(BLOCK), 0, st, N, W, R, keys, deg, w.fill, w.inbox, w.binoff,
                        w.bins, cand, cnt_in, rowflag, w.vcls, use_classes);
     // in-lists cut to R; only vertices with more than R incoming edges need a bin
@@ -1985,6 +2274,13 @@ extern "C" int rnnd_set_kernel_variant(int variant)
 {
     if (variant < 0 || variant > 2) return RNND_ERR_BAD_PARAM;
     g_kernel_variant = variant;
+    return RNND_OK;
+}
+
+extern "C" int rnnd_set_transpose_path(int path)
+{
+    if (path < 0 || path > 2) return RNND_ERR_BAD_PARAM;
+    g_transpose_path = path;
     return RNND_OK;
 }
 
