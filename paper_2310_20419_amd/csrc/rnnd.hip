@@ -990,30 +990,52 @@ __global__ __launch_bounds__(PLACE_THREADS) void k_bin_place(long long N, int R,
     }
 }
 
-// For every edge (u, v) of a flagged list whose v owns a bin: bins[v] <- key(delta, u, flag).  Nothing to
-// do when no bin was handed out (*n_binned == 0).
-__global__ __launch_bounds__(BLOCK) void k_fill_bins(long long N, int R, const u64 *keys, const int *deg,
-                                                     const int8_t *rowflag, const int *binoff, int *fill,
+// For every edge (u, v) of a flagged list whose v owns a bin: bins[v] <- key(delta, u, flag).  The flagged
+// vertices come as a list (one wavefront per vertex).  Nothing to do when no bin was handed out (*n_binned == 0).
+__global__ __launch_bounds__(BLOCK) void k_fill_bins(int R, const u64 *keys, const int *deg, const int *flagged,
+                                                     const u32 *n_flagged, const int *binoff, int *fill,
                                                      u64 *bins, u32 flag, const u32 *n_binned)
 {
     if (*n_binned == 0u) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
-    if (u >= N || !rowflag[u]) return;
-    const int m = deg[u];
-    for (int e = lane; e < m; e += 64) {
-        const u64 k = keys[(size_t)u * R + e];
-        const u32 v = key_id(k);
-        const int off = binoff[v];
-        if (off >= 0) bins[(size_t)off + atomicAdd(&fill[v], 1)] = make_key(key_dist(k), (u32)u, flag);
+    const u32 n = *n_flagged, nw = gridDim.x * WAVES_PER_BLOCK;
+    for (u32 it = blockIdx.x * WAVES_PER_BLOCK + wave; it < n; it += nw) {
+        const int u = flagged[it];
+        const int m = deg[u];
+        for (int e = lane; e < m; e += 64) {
+            const u64 k = keys[(size_t)u * R + e];
+            const u32 v = key_id(k);
+            const int off = binoff[v];
+            if (off >= 0) bins[(size_t)off + atomicAdd(&fill[v], 1)] = make_key(key_dist(k), (u32)u, flag);
+        }
     }
 }
 
 // Alg. 5, union and out-degree cut: list(x) <- first R distinct of list(x) + reversed edges into x (flag new).
 // Then the edges of the new list are counted at those targets that can end up with more than R
 // incoming edges (cand[v]: |list(v)| + |edges into v| > R before the union; for every other vertex
-// the union itself bounds the in-degree by R); rowflag[x] says whether the list has such an edge.
+// the union itself bounds the in-degree by R); rowflag[x] = 0 if the list has such an edge, else -1.
 // vcls[x] <- degree class if the list holds a "new" entry, else -1.
+struct RevItem {       // what a half-wave holds of its vertex before it is that vertex's turn
+    int c, nb;         // reversed edges received, entries held
+    u64 kr, ki;        // list slot l32, inbox slot 31 - l32 (either may be garbage: masked by nb, c)
+};
+
+__device__ __forceinline__ RevItem rev_item_load(long long x, long long N, int W, const u64 *keys, const int *deg,
+                                                 const int *fill, const u64 *inbox, int l32)
+{
+    RevItem it;
+    it.c = it.nb = 0;
+    it.kr = it.ki = KEY_PAD;
+    if (x < N) {
+        it.c = fill[x];
+        it.nb = deg[x];
+        if (l32 < W) it.kr = keys[(size_t)x * W + l32];
+        it.ki = inbox[(size_t)x * INBOX_CAP + (31 - l32)];
+    }
+    return it;
+}
+
 __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int W, int R, u64 *keys, int *deg, int *fill,
                                                          const u64 *inbox, const int *binoff, const u64 *bins,
                                                          const int8_t *cand, int *cnt_in, int8_t *rowflag,
@@ -1021,81 +1043,88 @@ __global__ __launch_bounds__(BLOCK) void k_reverse_merge(long long N, int W, int
 {   // rows are W slots apart (W >= R); lists are cut to R
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
-    // a wavefront takes two vertices, one per half: lists are short on average, and when both unions have
-    // at most 32 keys they are formed side by side (32-lane sorts); otherwise one after the other
-    const long long x0 = ((long long)blockIdx.x * WAVES_PER_BLOCK + wave) * 2;
-    if (x0 >= N) return;
-    const long long xh = x0 + half;
-    const bool have = xh < N;
-    const int ch = have ? fill[xh] : 0, nbh = have ? deg[xh] : 0;
-    const bool small = __builtin_amdgcn_ballot_w64(nbh + ch > 32) == 0;
-    if (small) {
-        u64 *row = keys + (size_t)xh * W;
-        u64 k = KEY_PAD;
-        if (have) {
-            if (l32 < nbh) k = row[l32];
-            else if (31 - l32 < ch) k = inbox[(size_t)xh * INBOX_CAP + (31 - l32)];
-        }
-        k = group_sort<32>(k, lane);
-        u64 prev = shfl_up1_u64(k);
-        if (l32 == 0) prev = KEY_PAD;
-        const bool keep = (k != KEY_PAD) && ((k >> 1) != (prev >> 1));
-        const u32 m = (u32)(__builtin_amdgcn_ballot_w64(keep) >> (32 * half));
-        const int pos = __popc(m & ((1u << l32) - 1u));
-        const bool w = keep && pos < R;
-        if (w) row[pos] = k;
-        bool cd = false;
-        if (w) {
-            const u32 v = key_id(k);
-            if (cand[v]) {
-                atomicAdd(&cnt_in[v], 1);
-                cd = true;
+    // a wavefront takes two vertices at a time, one per half: lists are short on average, and when both unions
+    // have at most 32 keys they are formed side by side (32-lane sorts); otherwise one after the other.  The
+    // grid is persistent: what the next pair needs in the short case is loaded before the current pair is sorted.
+    const long long npairs = (N + 1) / 2;
+    const long long gw = (long long)blockIdx.x * WAVES_PER_BLOCK + wave, nw = (long long)gridDim.x * WAVES_PER_BLOCK;
+    if (gw >= npairs) return;
+    RevItem cur = rev_item_load(2 * gw + half, N, W, keys, deg, fill, inbox, l32);
+    for (long long pair = gw; pair < npairs; pair += nw) {
+        const RevItem nxt = rev_item_load(2 * (pair + nw) + half, pair + nw < npairs ? N : 0, W, keys, deg, fill, inbox, l32);
+        const long long x0 = 2 * pair, xh = x0 + half;
+        const bool have = xh < N;
+        const int ch = cur.c, nbh = cur.nb;
+        const bool small = __builtin_amdgcn_ballot_w64(nbh + ch > 32) == 0;
+        if (small) {
+            u64 *row = keys + (size_t)xh * W;
+            u64 k = KEY_PAD;
+            if (have) {
+                if (l32 < nbh) k = cur.kr;
+                else if (31 - l32 < ch) k = cur.ki;
+            }
+            k = group_sort<32>(k, lane);
+            u64 prev = shfl_up1_u64(k);
+            if (l32 == 0) prev = KEY_PAD;
+            const bool keep = (k != KEY_PAD) && ((k >> 1) != (prev >> 1));
+            const u32 m = (u32)(__builtin_amdgcn_ballot_w64(keep) >> (32 * half));
+            const int pos = __popc(m & ((1u << l32) - 1u));
+            const bool w = keep && pos < R;
+            if (w) row[pos] = k;
+            bool cd = false;
+            if (w) {
+                const u32 v = key_id(k);
+                if (cand[v]) {
+                    atomicAdd(&cnt_in[v], 1);
+                    cd = true;
+                }
+            }
+            const u32 nm = (u32)(__builtin_amdgcn_ballot_w64(w && (k & 1ull)) >> (32 * half));
+            const u32 cm = (u32)(__builtin_amdgcn_ballot_w64(cd) >> (32 * half));
+            if (have && l32 == 0) {
+                int nd = __popc(m);
+                if (nd > R) nd = R;
+                deg[xh] = nd;
+                fill[xh] = 0;
+                rowflag[xh] = (int8_t)(cm != 0 ? 0 : -1);      // class 0 of a compaction = the flagged vertices
+                vcls[xh] = nm ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
+            }
+        } else {
+            for (int h = 0; h < 2; ++h) {
+                const long long x = x0 + h;
+                if (x >= N) break;
+                u64 *row = keys + (size_t)x * W;
+                const int c = __shfl(ch, 32 * h);
+                int nd = __shfl(nbh, 32 * h);
+                if (c == 0 && nd > R) nd = R;   // Alg. 5 cuts every out-list to its R shortest; the row is sorted and distinct
+                if (c > 0) {
+                    bool any_new;
+                    const int ca = c < INBOX_CAP ? c : INBOX_CAP;
+                    wave_sync();    // the staging area may still be read by the previous vertex
+                    nd = wave_merge_row(row, nd, inbox + (size_t)x * INBOX_CAP, ca, bins + (c > ca ? binoff[x] : 0), c - ca, R,
+                                        s_stage[wave], lane, &any_new);
+                    wave_sync();    // the list is read back below by other lanes of this wavefront
+                }
+                bool nw_ = false, cd = false;
+                for (int e = lane; e < nd; e += 64) {
+                    const u64 k = row[e];
+                    nw_ = nw_ || (k & 1ull);
+                    const u32 v = key_id(k);
+                    if (cand[v]) {
+                        atomicAdd(&cnt_in[v], 1);
+                        cd = true;
+                    }
+                }
+                const u64 bn = __builtin_amdgcn_ballot_w64(nw_), bc = __builtin_amdgcn_ballot_w64(cd);
+                if (lane == 0) {
+                    deg[x] = nd;
+                    fill[x] = 0;
+                    rowflag[x] = (int8_t)(bc != 0 ? 0 : -1);
+                    vcls[x] = bn ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
+                }
             }
         }
-        const u32 nm = (u32)(__builtin_amdgcn_ballot_w64(w && (k & 1ull)) >> (32 * half));
-        const u32 cm = (u32)(__builtin_amdgcn_ballot_w64(cd) >> (32 * half));
-        if (have && l32 == 0) {
-            int nd = __popc(m);
-            if (nd > R) nd = R;
-            deg[xh] = nd;
-            fill[xh] = 0;
-            rowflag[xh] = (int8_t)(cm != 0);
-            vcls[xh] = nm ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
-        }
-        return;
-    }
-    for (int h = 0; h < 2; ++h) {
-        const long long x = x0 + h;
-        if (x >= N) break;
-        u64 *row = keys + (size_t)x * W;
-        const int c = fill[x];
-        int nd = deg[x];
-        if (c == 0 && nd > R) nd = R;   // Alg. 5 cuts every out-list to its R shortest; the row is sorted and distinct
-        if (c > 0) {
-            bool any_new;
-            const int ca = c < INBOX_CAP ? c : INBOX_CAP;
-            wave_sync();    // the staging area may still be read by the previous vertex
-            nd = wave_merge_row(row, nd, inbox + (size_t)x * INBOX_CAP, ca, bins + (c > ca ? binoff[x] : 0), c - ca, R,
-                                s_stage[wave], lane, &any_new);
-            wave_sync();    // the list is read back below by other lanes of this wavefront
-        }
-        bool nw = false, cd = false;
-        for (int e = lane; e < nd; e += 64) {
-            const u64 k = row[e];
-            nw = nw || (k & 1ull);
-            const u32 v = key_id(k);
-            if (cand[v]) {
-                atomicAdd(&cnt_in[v], 1);
-                cd = true;
-            }
-        }
-        const u64 b = __builtin_amdgcn_ballot_w64(nw), bc = __builtin_amdgcn_ballot_w64(cd);
-        if (lane == 0) {
-            deg[x] = nd;
-            fill[x] = 0;
-            rowflag[x] = (int8_t)(bc != 0);
-            vcls[x] = b ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
-        }
+        cur = nxt;
     }
 }
 
@@ -1121,35 +1150,38 @@ __global__ __launch_bounds__(BLOCK) void k_incap_threshold(int R, const int *lis
 }
 
 // Alg. 5, in-degree cut, second half: edge (u, v) survives iff (delta, u) <= thr[v]; vcls[u] follows the
-// new degree.  Nothing to do when no vertex has more than R incoming edges (*n_hubs == 0).
-__global__ __launch_bounds__(BLOCK) void k_incap_filter(long long N, int R, u64 *keys, int *deg,
-                                                        const u64 *thr, const int8_t *rowflag, int8_t *vcls,
+// new degree.  Only the flagged lists (those with an edge to a candidate) can lose an edge; they come as a list.
+// Nothing to do when no vertex has more than R incoming edges (*n_hubs == 0).
+__global__ __launch_bounds__(BLOCK) void k_incap_filter(int R, u64 *keys, int *deg, const u64 *thr,
+                                                        const int *flagged, const u32 *n_flagged, int8_t *vcls,
                                                         int use_classes, const u32 *n_hubs)
 {
     if (*n_hubs == 0u) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
-    if (u >= N || !rowflag[u]) return;   // a list without an edge to a candidate cannot lose one
-    const int m = deg[u];
-    u64 *row = keys + (size_t)u * R;
-    u64 k[2];
-    bool keep[2];
+    const u32 n = *n_flagged, nw = gridDim.x * WAVES_PER_BLOCK;
+    for (u32 it = blockIdx.x * WAVES_PER_BLOCK + wave; it < n; it += nw) {
+        const int u = flagged[it];
+        const int m = deg[u];
+        u64 *row = keys + (size_t)u * R;
+        u64 k[2];
+        bool keep[2];
 #pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        int e = r * 64 + lane;
-        k[r] = e < m ? row[e] : KEY_PAD;
-        keep[r] = e < m && make_key(key_dist(k[r]), (u32)u, 0u) <= thr[key_id(k[r])];
-    }
-    const u64 m0 = __builtin_amdgcn_ballot_w64(keep[0]), m1 = __builtin_amdgcn_ballot_w64(keep[1]);
-    const u64 n0 = __builtin_amdgcn_ballot_w64(keep[0] && (k[0] & 1ull));
-    const u64 n1 = __builtin_amdgcn_ballot_w64(keep[1] && (k[1] & 1ull));
-    const int c0 = __popcll(m0);
-    if (keep[0]) row[__popcll(m0 & lanes_below(lane))] = k[0];
-    if (keep[1]) row[c0 + __popcll(m1 & lanes_below(lane))] = k[1];
-    if (lane == 0) {
-        const int nd = c0 + __popcll(m1);
-        deg[u] = nd;
-        vcls[u] = (n0 | n1) ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
+        for (int r = 0; r < 2; ++r) {
+            int e = r * 64 + lane;
+            k[r] = e < m ? row[e] : KEY_PAD;
+            keep[r] = e < m && make_key(key_dist(k[r]), (u32)u, 0u) <= thr[key_id(k[r])];
+        }
+        const u64 m0 = __builtin_amdgcn_ballot_w64(keep[0]), m1 = __builtin_amdgcn_ballot_w64(keep[1]);
+        const u64 n0 = __builtin_amdgcn_ballot_w64(keep[0] && (k[0] & 1ull));
+        const u64 n1 = __builtin_amdgcn_ballot_w64(keep[1] && (k[1] & 1ull));
+        const int c0 = __popcll(m0);
+        if (keep[0]) row[__popcll(m0 & lanes_below(lane))] = k[0];
+        if (keep[1]) row[c0 + __popcll(m1 & lanes_below(lane))] = k[1];
+        if (lane == 0) {
+            const int nd = c0 + __popcll(m1);
+            deg[u] = nd;
+            vcls[u] = (n0 | n1) ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
+        }
     }
 }
 
@@ -1280,7 +1312,7 @@ struct Workspace {
     int *lists = nullptr;   // [NDEG*N] active lists by degree class
     int8_t *vcls = nullptr, *tcls = nullptr;   // [N], [NMRG*N]
     RoundCtr *ctr = nullptr;   // [n_ctr]
-    u32 *misc = nullptr;       // [8]: small cursors for AddReverseEdges
+    u32 *misc = nullptr;       // [16]: small cursors for AddReverseEdges
     u32 *blockhist = nullptr;  // binned transposition: [blocks of BIN_CHUNK vertices][ranges], null when N is out of its range
     u32 *range_tot = nullptr, *range_base = nullptr;   // [RANGE_MAX + 1] each
     int n_ctr = 0;
@@ -1308,7 +1340,7 @@ static size_t ws_layout(Workspace &w, long long N, int R, int n_ctr, bool own_gr
     size_t o_xs = take(xs_bytes);
     size_t o_lists = take((size_t)N * 4 * NDEG);
     size_t o_vcls = take((size_t)N), o_tcls = take((size_t)N * NMRG);
-    size_t o_misc = take(8 * 4);
+    size_t o_misc = take(16 * 4);
     const bool binnable = N >= 2 && (unsigned long long)N <= (unsigned long long)RANGE_MAX * RANGE_TARGETS;
     size_t o_range = take(binnable ? (size_t)2 * (RANGE_MAX + 1) * 4 : 0);
     size_t o_blockhist = take(binnable ? bin_blocks(N) * bin_ranges(N) * 4 : 0);
@@ -1648,7 +1680,7 @@ static void launch_compact_all(const Workspace &w, long long N, int t_next, hipS
 // AddReverseEdges; the active lists for round t_next are rebuilt from scratch (t_next < 0: only vcls[], the
 // class of every vertex that holds a "new" entry, is written).  Expects fill[] == 0
 // and leaves it so.  Between rounds nprop[], tcls[], props[] and touched[] are free: they serve as the
-// second in-edge count, the per-vertex marks, the late arrival numbers and their position masks.  misc: [0] bin cursor, [1] vertices with a bin (union and out-degree cut),
+// second in-edge count, the per-vertex marks, the late arrival numbers and their position masks.  misc: [0] bin cursor, [1] vertices with a bin (union and out-degree cut), [4..11] lengths of the compaction of rowflag[] ([4]: the flagged lists),
 // [2] bin cursor, [3] vertices with more than R incoming edges (in-degree cut).
 static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use_classes, u64 *keys, int *deg,
                                  int t_next, hipStream_t st, hipEvent_t e_stop = nullptr, int W = 0)
@@ -1659,7 +1691,7 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
     int8_t *cand = w.tcls, *rowflag = w.tcls + N, *mark = w.tcls + 2 * N;
     u32 *late = (u32 *)w.props;          // one word per list slot (props is 16 bytes per slot)
     u64 *over = (u64 *)w.touched;        // two words per vertex (touched is 16 bytes per vertex)
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, (size_t)8);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.misc, (size_t)16);
     if (t_next >= 0) hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, w.ctr[t_next].n_active, (size_t)NDEG);
     // union with reversed edges, out-lists cut to R
     // the transposition: one arrival-number atomic per edge, or (large N, see k_bin_count) binned by target range
@@ -1681,17 +1713,24 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
         hipLaunchKernelGGL(k_reverse_surplus, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, late, over, mark, w.binoff,
                            w.bins, w.misc + 1);
     }
-    hipLaunchKernelGGL(k_reverse_merge, dim3((vb + 1) / 2), dim3(BLOCK), 0, st, N, W, R, keys, deg, w.fill, w.inbox, w.binoff,
-                       w.bins, cand, cnt_in, rowflag, w.vcls, use_classes);
-    // in-lists cut to R; only vertices with more than R incoming edges need a bin
+    static const int rmerge_per_cu = resident_blocks_per_cu(k_reverse_merge, 6);
+    const int rm_blocks = cu_count() * rmerge_per_cu;
+    hipLaunchKernelGGL(k_reverse_merge, dim3(rm_blocks < (vb + 1) / 2 ? rm_blocks : (vb + 1) / 2), dim3(BLOCK), 0, st, N, W, R, keys,
+                       deg, w.fill, w.inbox, w.binoff, w.bins, cand, cnt_in, rowflag, w.vcls, use_classes);
+    // in-lists cut to R; only vertices with more than R incoming edges need a bin, and only the flagged lists
+    // (class 0 of rowflag[]) are walked: they are compacted into the first active list, which is free until
+    // the lists of the next round are rebuilt at the end
+    int *flagged = w.lists;
+    hipLaunchKernelGGL(k_compact_classes, dim3(256, 1), dim3(1024), 0, st, (const u32 *)nullptr, (u32)N, (const int *)nullptr,
+                       (const int8_t *)rowflag, flagged, N, w.misc + 4, 0u, (int8_t *)nullptr);
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, cnt_in, R, R, 0, w.binoff, w.misc + 2, w.hubs,
                        w.misc + 3, w.cnt, (int *)nullptr, w.thr, (const int *)nullptr, 0, (int8_t *)nullptr);
-    hipLaunchKernelGGL(k_fill_bins, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, deg, rowflag, w.binoff, w.cnt, w.bins,
-                       0u, w.misc + 3);
+    hipLaunchKernelGGL(k_fill_bins, dim3(persistent_blocks()), dim3(BLOCK), 0, st, W, (const u64 *)keys, (const int *)deg,
+                       (const int *)flagged, (const u32 *)(w.misc + 4), w.binoff, w.cnt, w.bins, 0u, w.misc + 3);
     hipLaunchKernelGGL(k_incap_threshold, dim3(persistent_blocks()), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 3,
                        cnt_in, w.binoff, w.bins, w.thr);
-    hipLaunchKernelGGL(k_incap_filter, dim3(vb), dim3(BLOCK), 0, st, N, W, keys, deg, w.thr, rowflag, w.vcls,
-                       use_classes, w.misc + 3);
+    hipLaunchKernelGGL(k_incap_filter, dim3(persistent_blocks()), dim3(BLOCK), 0, st, W, keys, deg, w.thr,
+                       (const int *)flagged, (const u32 *)(w.misc + 4), w.vcls, use_classes, w.misc + 3);
     if (t_next >= 0) launch_compact_all(w, N, t_next, st, e_stop);
     else if (e_stop) (void)hipEventRecord(e_stop, st);
     return hipGetLastError();
