@@ -4,9 +4,9 @@
 A "step" is one complete rnnd_build (RandomGraph + T1*T2 UpdateNeighbors rounds + T1-1
 AddReverseEdges) over one synthetic database that is already resident in HBM.  The default
 workload is cfg3 of workloads.py (N = 1,000,000, d = 128, uint8, S=20 R=96 T1=4 T2=15), the
-one the "1M-vector graph build time" metric is quoted on; next to it the two float
-configurations of the metric (cfg4: 1M x 96, cfg5: 1M x 960) are measured the same way with
-fewer steps and reported under "workloads".  Prints ONE JSON line.
+one the "1M-vector graph build time" metric is quoted on; next to it the other four
+configurations (cfg1, cfg2: small uint8; cfg4: 1M x 96 and cfg5: 1M x 960 float32) are measured
+the same way (the 1M float ones with two steps) and reported under "workloads".  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--also none] [--no-cpu-baseline]
 """
@@ -269,7 +269,7 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--also", default="auto",
                     help="comma-separated further workloads measured with fewer steps and reported under "
-                         "\"workloads\" (auto: cfg4,cfg5 next to the default cfg3, none otherwise; 'none')")
+                         "\"workloads\" (auto: cfg1,cfg2,cfg4,cfg5 next to the default cfg3, none otherwise; 'none')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--queries", type=int, default=10000, help="queries of the search-quality leg (at most the config's)")
@@ -334,7 +334,7 @@ def main():
     # the other 1M configurations of the metric (float rows), fewer steps, same measurement
     also = args.also
     if also == "auto":
-        also = "cfg4,cfg5" if (args.workload == "cfg3" and not (args.n or args.merge_cap or args.blocks)) else "none"
+        also = "cfg1,cfg2,cfg4,cfg5" if (args.workload == "cfg3" and not (args.n or args.merge_cap or args.blocks)) else "none"
     names = [w for w in also.split(",") if w and w != "none" and w != args.workload]
     if names:
         del X, Xd
@@ -346,7 +346,9 @@ def main():
             t0 = time.perf_counter()
             X2, Xd2, esz2, st2 = load_workload(c2, args.storage)
             g2 = time.perf_counter() - t0
-            sub, _ = measure(rn, c2, X2, Xd2, esz2, st2, max(1, min(args.steps, 2)), 1, args,
+            # the small configurations build in milliseconds: the same number of steps; the 1M float ones: two
+            k2 = args.steps if c2.N < 1_000_000 else max(1, min(args.steps, 2))
+            sub, _ = measure(rn, c2, X2, Xd2, esz2, st2, k2, 1 if c2.N >= 1_000_000 else max(1, args.warmup), args,
                              with_search=not args.no_recall)
             sub["data_gen_s"] = g2
             sub["metric"] = "1M-vector graph build time" if c2.N == 1_000_000 else "graph build time"

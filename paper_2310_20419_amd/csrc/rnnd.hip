@@ -1428,6 +1428,14 @@ static int cu_count()
 
 static int persistent_blocks() { return cu_count() * 8; }   // 32 wavefronts per CU
 
+// A grid that walks a list of at most N vertices, one or more per wavefront of a 4-wavefront block, needs no more
+// than N / 4 blocks: small inputs get small grids (a launch costs by its workgroups even when they find no work).
+static unsigned capped(long long blocks, long long N)
+{
+    const long long need = (N + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    return (unsigned)(blocks < need ? blocks : (need < 1 ? 1 : need));
+}
+
 static inline int vertex_blocks(long long N) { return (int)((N + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK); }
 
 // Blocks of `kernel` (256 threads, static LDS only) that one CU keeps resident; the persistent
@@ -1456,7 +1464,7 @@ static void launch_mfma_scan(const Workspace &w, int R, u64 *keys, int *deg, lon
                              hipStream_t st, hipEvent_t e_stop)
 {
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8<NG, KS>, NG == 2 ? 3 : 2);
-    hipExtLaunchKernelGGL((k_update_scan_mfma_u8<NG, KS>), dim3(cu_count() * per_cu), dim3(256), 0, st, nullptr,
+    hipExtLaunchKernelGGL((k_update_scan_mfma_u8<NG, KS>), dim3(capped(cu_count() * per_cu, N)), dim3(256), 0, st, nullptr,
                           e_stop, 0, (const int8_t *)w.xs, R, keys, deg, w.lists + (size_t)(NG + 1) * N,
                           &c->n_active[NG + 1], w.props, w.nprop, c);
 }
@@ -1479,7 +1487,7 @@ static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_small<KS>, 4);
     const int n_big = (R > 32) + (R > 64) + (R > 96);   // launches after the short-list kernel
     const int ny = 1 + (R > 8) + (R > 16);
-    hipExtLaunchKernelGGL((k_update_scan_mfma_u8_small<KS>), dim3(cu_count() * per_cu, ny), dim3(256), 0, st,
+    hipExtLaunchKernelGGL((k_update_scan_mfma_u8_small<KS>), dim3(capped(cu_count() * per_cu, N), ny), dim3(256), 0, st,
                           re.scan_start, n_big == 0 ? re.scan_stop : nullptr, 0, (const int8_t *)w.xs, R, keys, deg,
                           w.lists, N, w.props, w.nprop, c);
     if (R > 32) launch_mfma_scan<2, KS>(w, R, keys, deg, N, c, st, n_big == 1 ? re.scan_stop : nullptr);
@@ -1499,11 +1507,11 @@ static void launch_f32_scan_dt(const Workspace &w, const void *X, int d, int R, 
     static const int per_cu_fast = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, true, DT>, NG == 1 ? 4 : 2);
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_f32<NG, CH, NRC, false, DT>, NG == 1 ? 4 : NG == 2 ? 2 : 1);
     if (g_kernel_variant != 2)
-        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, true, DT>), dim3(cu_count() * per_cu_fast), dim3(256), 0,
+        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, true, DT>), dim3(capped(cu_count() * per_cu_fast, N)), dim3(256), 0,
                               st, e_start, e_stop, 0, (const char *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
                               &c->n_active[cls], w.props, w.nprop, c, (int *)w.bins, &c->n_redo[0]);
     else
-        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, false, DT>), dim3(cu_count() * per_cu), dim3(256), 0,
+        hipExtLaunchKernelGGL((k_update_scan_mfma_f32<NG, CH, NRC, false, DT>), dim3(capped(cu_count() * per_cu, N)), dim3(256), 0,
                               st, e_start, e_stop, 0, (const char *)X, d, R, keys, deg, w.lists + (size_t)cls * N,
                               &c->n_active[cls], w.props, w.nprop, c, (int *)nullptr, (u32 *)nullptr);
 }
@@ -1556,7 +1564,7 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
                                       hipStream_t st, const RoundEvents &re = RoundEvents(),
                                       const VertexRun *run = nullptr)
 {
-    const int pb = persistent_blocks();
+    const unsigned pb = capped(persistent_blocks(), N);
     RoundCtr *c = w.ctr + t;
     const int use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
     if (run) {
@@ -1629,7 +1637,7 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
     hipLaunchKernelGGL(k_scatter_surplus, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop,
                        w.binoff, w.bins);
     static const int merge_per_cu = resident_blocks_per_cu(k_merge, 6);
-    hipLaunchKernelGGL(k_merge, dim3(cu_count() * merge_per_cu, NMRG), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
+    hipLaunchKernelGGL(k_merge, dim3(capped(cu_count() * merge_per_cu, N), NMRG), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
                        w.fill, w.inbox, w.binoff, w.bins, w.tcls, use_classes);
     if (run)
         hipLaunchKernelGGL(k_store_classes, dim3(64, NMRG), dim3(256), 0, st, (const u32 *)c->n_touched,
@@ -1725,11 +1733,11 @@ static hipError_t launch_reverse(const Workspace &w, long long N, int R, int use
                        (const int8_t *)rowflag, flagged, N, w.misc + 4, 0u, (int8_t *)nullptr);
     hipLaunchKernelGGL(k_assign_bins, dim3(tb), dim3(1024), 0, st, N, cnt_in, R, R, 0, w.binoff, w.misc + 2, w.hubs,
                        w.misc + 3, w.cnt, (int *)nullptr, w.thr, (const int *)nullptr, 0, (int8_t *)nullptr);
-    hipLaunchKernelGGL(k_fill_bins, dim3(persistent_blocks()), dim3(BLOCK), 0, st, W, (const u64 *)keys, (const int *)deg,
+    hipLaunchKernelGGL(k_fill_bins, dim3(capped(persistent_blocks(), N)), dim3(BLOCK), 0, st, W, (const u64 *)keys, (const int *)deg,
                        (const int *)flagged, (const u32 *)(w.misc + 4), w.binoff, w.cnt, w.bins, 0u, w.misc + 3);
-    hipLaunchKernelGGL(k_incap_threshold, dim3(persistent_blocks()), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 3,
+    hipLaunchKernelGGL(k_incap_threshold, dim3(capped(persistent_blocks(), N)), dim3(BLOCK), 0, st, R, w.hubs, w.misc + 3,
                        cnt_in, w.binoff, w.bins, w.thr);
-    hipLaunchKernelGGL(k_incap_filter, dim3(persistent_blocks()), dim3(BLOCK), 0, st, W, keys, deg, w.thr,
+    hipLaunchKernelGGL(k_incap_filter, dim3(capped(persistent_blocks(), N)), dim3(BLOCK), 0, st, W, keys, deg, w.thr,
                        (const int *)flagged, (const u32 *)(w.misc + 4), w.vcls, use_classes, w.misc + 3);
     if (t_next >= 0) launch_compact_all(w, N, t_next, st, e_stop);
     else if (e_stop) (void)hipEventRecord(e_stop, st);
