@@ -22,11 +22,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
-# HBM bytes per scan launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by
-# a plain 1 GiB copy in the same run); see profiles/update_scan_cfg3_hbm_traffic.txt and
-# profiles/update_scan_cfg5_hbm_traffic.txt.  Keyed by (workload, kernel variant); None where it has
-# not been measured.
-TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.022e9, ("cfg5", 3): 8.337e10}
+# HBM bytes per scan launch (one round's scan kernels together) measured with rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE (two runs, each scaled by what the same counter reads for a plain 1 GiB copy in the same run);
+# see profiles/update_scan_cfg{3,4,5}_hbm_traffic.txt.  Keyed by (workload, kernel variant); None where it
+# has not been measured.
+TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.0226e9, ("cfg4", 3): 8.912e9, ("cfg5", 3): 8.3374e10}
 
 
 def host_cpu():
