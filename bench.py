@@ -243,6 +243,8 @@ def measure(rn, cfg, X, Xd, esz, st16, steps, warmup, args, with_search=True, wi
         "gpu_ms": {"total": s["total_ms"], "init": s["init_ms"], "rounds": sum(s["round_ms"]),
                    "scan": scan_ms, "reverse": sum(s["reverse_ms"])},
         "mean_degree": float(degree.float().mean().item()), "max_degree": int(degree.max().item()),
+        # list entries the merges dropped because a row was full (the paper's UpdateNeighbors never drops one)
+        "dropped_entries": int(sum(s["dropped"])),
         # out-degrees 0, 1-8, 9-16, 17-32, 33-64, 65-96, 97-128
         "degree_histogram": torch.histc(degree.float(), bins=1, min=-0.5, max=0.5).int().tolist()
         + [int(((degree > lo) & (degree <= hi)).sum().item()) for lo, hi in

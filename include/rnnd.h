@@ -80,6 +80,11 @@ typedef struct {
     int64_t algo_evals[RNND_MAX_ROUNDS];
     int64_t exec_evals[RNND_MAX_ROUNDS];
     int64_t gathered_rows[RNND_MAX_ROUNDS]; /* rows of X the round kernel fetched */
+    int64_t dropped[RNND_MAX_ROUNDS];       /* list entries the round's merges dropped because a list was full (rows
+                                               are R, or M, slots wide; the paper's UpdateNeighbors never drops one:
+                                               where this is 0 in every round of rnnd_build_wide, its graph is the
+                                               one unbounded lists give).  A hub that receives more than 128 edges in
+                                               one round may count an edge twice. */
 } rnnd_stats;
 
 /* Alg. 6, RNN-Descent(S, R, T1, T2), with synchronous rounds:

@@ -38,6 +38,7 @@ class Stats(ctypes.Structure):
         ("algo_evals", ctypes.c_int64 * RNND_MAX_ROUNDS),
         ("exec_evals", ctypes.c_int64 * RNND_MAX_ROUNDS),
         ("gathered_rows", ctypes.c_int64 * RNND_MAX_ROUNDS),
+        ("dropped", ctypes.c_int64 * RNND_MAX_ROUNDS),
     ]
 
     def as_dict(self) -> dict:
@@ -51,6 +52,7 @@ class Stats(ctypes.Structure):
             "init_evals": self.init_evals, "active": list(self.active[:n]),
             "proposals": list(self.proposals[:n]), "algo_evals": list(self.algo_evals[:n]),
             "exec_evals": list(self.exec_evals[:n]), "gathered_rows": list(self.gathered_rows[:n]),
+            "dropped": list(self.dropped[:n]),
         }
 
 

@@ -46,8 +46,9 @@ struct RoundCtr {
     u32 pad[2];
     u32 n_redo[NDEG];     // float scan: vertices the single-precision form left to the double-precision one
     // statistics, spread over STAT_SLOTS addresses so that the adds of many blocks do not queue up
-    // on one: [slot][0..3] = algorithmic evals, executed evals, rows gathered, edges redirected
-    u64 stat[STAT_SLOTS][4];
+    // on one: [slot][0..4] = algorithmic evals, executed evals, rows gathered, edges redirected, entries a merge
+    // dropped because the list was full
+    u64 stat[STAT_SLOTS][5];
 };
 
 // One add per wavefront into the slot of its block.
@@ -483,8 +484,9 @@ __device__ __forceinline__ MergeItem merge_item_load(int x, int R, const u64 *ke
 template <int G>
 __device__ __forceinline__ void merge_group_body(int R, u64 *keys, int *deg, const int *tlist,
                                                  const u32 *n_ptr, int *cnt, const u64 *inbox,
-                                                 int8_t *tcls, int use_classes)
+                                                 int8_t *tcls, int use_classes, RoundCtr *ctr)
 {
+    int dropped = 0;
     static_assert(G <= INBOX_CAP, "a group merge reads the received edges from the inbox only");
     const int lane = threadIdx.x & 63, sub = lane & (G - 1), shift = lane & ~(G - 1);
     const u64 gmask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull);
@@ -516,13 +518,14 @@ __device__ __forceinline__ void merge_group_body(int R, u64 *keys, int *deg, con
         const u64 nm = (__builtin_amdgcn_ballot_w64(w && (k & 1ull)) >> shift) & gmask;
         if (sub == 0) {
             int nd = __popcll(m);
-            if (nd > R) nd = R;
+            if (nd > R) { dropped += nd - R; nd = R; }
             deg[x] = nd;
             cnt[x] = 0;
             tcls[it] = nm ? (int8_t)degree_class(nd, use_classes) : (int8_t)-1;
         }
         cur = nxt;
     }
+    if (dropped) atomicAdd(&ctr->stat[blockIdx.x & (STAT_SLOTS - 1)][4], (u64)dropped);
 }
 
 // General merge (any size): one touched vertex per wavefront; kept entries + inbox + surplus bin.
@@ -553,8 +556,9 @@ __device__ __forceinline__ WideItem wide_item_load(int x, int R, const u64 *keys
 __device__ __forceinline__ void merge_general_body(int R, u64 *keys, int *deg, const int *tlist,
                                                    const u32 *n_ptr, int *cnt, const u64 *inbox,
                                                    const int *binoff, const u64 *bins, int8_t *tcls,
-                                                   int use_classes, u64 (*s_stage)[RNND_MAX_R])
+                                                   int use_classes, u64 (*s_stage)[RNND_MAX_R], RoundCtr *ctr)
 {
+    int dropped = 0;
     static_assert(INBOX_CAP == 64, "lane l prefetches inbox slot 63 - l");
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
@@ -578,11 +582,11 @@ __device__ __forceinline__ void merge_general_body(int R, u64 *keys, int *deg, c
             k[0] = lane < nb ? cur.r0 : KEY_PAD;
             k[1] = lane + 64 < nb ? cur.r1 : (63 - lane < c ? cur.in : KEY_PAD);
             wave_sort<2>(k, lane);
-            nd = wave_unique_prefix<2>(k, lane, R, keys + (size_t)x * R, &any_new);
+            nd = wave_unique_prefix<2>(k, lane, R, keys + (size_t)x * R, &any_new, &dropped);
         } else {
             const int ca = c < INBOX_CAP ? c : INBOX_CAP;
             nd = wave_merge_row(keys + (size_t)x * R, nb, inbox + (size_t)x * INBOX_CAP, ca,
-                                bins + (c > ca ? binoff[x] : 0), c - ca, R, s_stage[wave], lane, &any_new);
+                                bins + (c > ca ? binoff[x] : 0), c - ca, R, s_stage[wave], lane, &any_new, &dropped);
         }
         if (lane == 0) {
             deg[x] = nd;
@@ -591,22 +595,23 @@ __device__ __forceinline__ void merge_general_body(int R, u64 *keys, int *deg, c
         }
         cur = nxt;
     }
+    if (lane == 0 && dropped) atomicAdd(&ctr->stat[blockIdx.x & (STAT_SLOTS - 1)][4], (u64)dropped);
 }
 
 // All four merge classes in one launch: blockIdx.y = merge class (touched list y, tcls + y*N).
 __global__ __launch_bounds__(BLOCK) void k_merge(long long N, int R, u64 *keys, int *deg, const int *tlists,
                                                  const u32 *n_touched, int *cnt, const u64 *inbox,
                                                  const int *binoff, const u64 *bins, int8_t *tcls,
-                                                 int use_classes)
+                                                 int use_classes, RoundCtr *ctr)
 {
     __shared__ u64 s_stage[WAVES_PER_BLOCK][RNND_MAX_R];
     const int y = blockIdx.y;
     const int *tlist = tlists + (size_t)y * N;
     int8_t *tc = tcls + (size_t)y * N;
-    if (y == 0) merge_group_body<16>(R, keys, deg, tlist, n_touched + 0, cnt, inbox, tc, use_classes);
-    else if (y == 1) merge_group_body<32>(R, keys, deg, tlist, n_touched + 1, cnt, inbox, tc, use_classes);
-    else if (y == 2) merge_group_body<64>(R, keys, deg, tlist, n_touched + 2, cnt, inbox, tc, use_classes);
-    else merge_general_body(R, keys, deg, tlist, n_touched + 3, cnt, inbox, binoff, bins, tc, use_classes, s_stage);
+    if (y == 0) merge_group_body<16>(R, keys, deg, tlist, n_touched + 0, cnt, inbox, tc, use_classes, ctr);
+    else if (y == 1) merge_group_body<32>(R, keys, deg, tlist, n_touched + 1, cnt, inbox, tc, use_classes, ctr);
+    else if (y == 2) merge_group_body<64>(R, keys, deg, tlist, n_touched + 2, cnt, inbox, tc, use_classes, ctr);
+    else merge_general_body(R, keys, deg, tlist, n_touched + 3, cnt, inbox, binoff, bins, tc, use_classes, s_stage, ctr);
 }
 
 // Items i < n with cls[first + i] >= 0 are appended to list cls[first + i]; item i stands for vertex idx[i]
@@ -1638,7 +1643,7 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
                        w.binoff, w.bins);
     static const int merge_per_cu = resident_blocks_per_cu(k_merge, 6);
     hipLaunchKernelGGL(k_merge, dim3(capped(cu_count() * merge_per_cu, N), NMRG), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,
-                       w.fill, w.inbox, w.binoff, w.bins, w.tcls, use_classes);
+                       w.fill, w.inbox, w.binoff, w.bins, w.tcls, use_classes, c);
     if (run)
         hipLaunchKernelGGL(k_store_classes, dim3(64, NMRG), dim3(256), 0, st, (const u32 *)c->n_touched,
                            (const int *)w.touched, (const int8_t *)w.tcls, N, w.vcls);
@@ -1755,6 +1760,7 @@ static void fill_round_stats(rnnd_stats *s, const RoundCtr *h, int rounds)
             s->exec_evals[t] += (int64_t)h[t].stat[k][1];
             s->gathered_rows[t] += (int64_t)h[t].stat[k][2];
             s->proposals[t] += (int64_t)h[t].stat[k][3];
+            s->dropped[t] += (int64_t)h[t].stat[k][4];
         }
     }
 }
@@ -1918,6 +1924,7 @@ static void fill_pass_stats(rnnd_stats *s, const RoundCtr *h, int passes, int pe
             s->exec_evals[p] += one.exec_evals[0];
             s->gathered_rows[p] += one.gathered_rows[0];
             s->proposals[p] += one.proposals[0];
+            s->dropped[p] += one.dropped[0];
         }
     }
 }

@@ -138,9 +138,10 @@ __device__ __forceinline__ u64 group_sort(u64 k, int lane)
 // k[] sorted ascending.  Drops KEY_PAD and every key equal (ignoring the flag bit) to its
 // predecessor, and writes the first `cap` survivors, in order, to out[0..) (LDS or global).
 // Returns how many were written; *any_new is set if one of them has the flag bit.
+// *dropped (may be null) grows by the number of survivors beyond `cap`.
 template <int E>
 __device__ __forceinline__ int wave_unique_prefix(const u64 (&k)[E], int lane, int cap, u64 *out,
-                                                 bool *any_new)
+                                                 bool *any_new, int *dropped = nullptr)
 {
     int base = 0;
     u64 newacc = 0;
@@ -161,14 +162,17 @@ __device__ __forceinline__ int wave_unique_prefix(const u64 (&k)[E], int lane, i
         base += __popcll(m);
     }
     *any_new = newacc != 0;
+    if (dropped && base > cap) *dropped += base - cap;
     return base < cap ? base : cap;
 }
 
 // Row `row` (nb keys, ascending) merged with c = ca + cb keys in any order (the first ca at binA, the
 // rest at binB): the first R distinct keys of the union, ascending, are written back to row[0..);
 // returns the new length.  `stage` is 128 keys of LDS private to this wavefront.
+// *dropped (may be null) grows by the number of distinct keys that did not fit (in the streaming case an edge that
+// arrives in two different chunks after it was dropped counts twice).
 __device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *binA, int ca, const u64 *binB,
-                                              int cb, int R, u64 *stage, int lane, bool *any_new)
+                                              int cb, int R, u64 *stage, int lane, bool *any_new, int *dropped = nullptr)
 {
     const int c = ca + cb;
     const int total = nb + c;
@@ -178,7 +182,7 @@ __device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *binA,
         u64 k[1];
         k[0] = lane < nb ? row[lane] : (lane < total ? bin_at(lane - nb) : KEY_PAD);
         wave_sort<1>(k, lane);
-        n = wave_unique_prefix<1>(k, lane, R, row, any_new);
+        n = wave_unique_prefix<1>(k, lane, R, row, any_new, dropped);
     } else if (total <= 128) {
         u64 k[2];
 #pragma unroll
@@ -187,7 +191,7 @@ __device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *binA,
             k[r] = e < nb ? row[e] : (e < total ? bin_at(e - nb) : KEY_PAD);
         }
         wave_sort<2>(k, lane);
-        n = wave_unique_prefix<2>(k, lane, R, row, any_new);
+        n = wave_unique_prefix<2>(k, lane, R, row, any_new, dropped);
     } else {
         // stream the bin through in chunks of 128 against the best R found so far
         u64 k[4];
@@ -199,7 +203,7 @@ __device__ __forceinline__ int wave_merge_row(u64 *row, int nb, const u64 *binA,
             k[2] = e0 < c ? bin_at(e0) : KEY_PAD;
             k[3] = e1 < c ? bin_at(e1) : KEY_PAD;
             wave_sort<4>(k, lane);
-            n = wave_unique_prefix<4>(k, lane, R, stage, any_new);
+            n = wave_unique_prefix<4>(k, lane, R, stage, any_new, dropped);
             wave_sync();
             k[0] = lane < n ? stage[lane] : KEY_PAD;
             k[1] = lane + 64 < n ? stage[lane + 64] : KEY_PAD;

@@ -97,3 +97,32 @@ def test_reverse_edges_cut_a_long_list_that_receives_nothing(rn, oracle_mod):
     keys, deg = snapshot_to_device(snap, False, M)
     rn.rnnd_add_reverse_edges_wide(keys, deg, R)
     assert_snapshot_equal(want, False, keys, deg, "lonely long lists")
+
+
+def test_no_dropped_entry_means_the_unbounded_build(rn, oracle_mod):
+    """The paper's UpdateNeighbors never drops an edge for lack of room (Sec. 4.4); rows here are at most 128
+    slots wide.  The build counts the entries its merges had to drop (stats.dropped): where the count is zero in
+    every round, the graph must be the one lists without any bound give -- the oracle with rows N - 1 wide.  And
+    where lists are cut (rows only R wide on the same data), the count must say so."""
+    X = _data("dense_u8", 900, 64, 3)
+    n, S, R, T1, T2 = len(X), 8, 12, 3, 3
+    unbounded = oracle_mod.build_wide(X, S, R, n - 1, T1, T2, 1)        # a list cannot hold more than N - 1 entries
+    longest = int(unbounded.snap.deg.max())
+    assert R < longest <= 128                                            # lists outgrow R, but fit 128 slots
+    graph, degree, keys, st = rn.rnnd_build_wide(cuda(X), S, R, 128, T1, T2, 1)
+    assert sum(st.dropped[:T1 * T2]) == 0
+    import oracle
+    cut = oracle.Snapshot(unbounded.snap.ids[:, :128].copy(), unbounded.snap.dist[:, :128].copy(),
+                          unbounded.snap.flags[:, :128].copy(), unbounded.snap.deg.copy())
+    assert_snapshot_equal(cut, False, keys, degree, "rows of 128 slots against unbounded lists")
+    assert list(st.algo_evals[:T1 * T2]) == unbounded.round_evals.tolist()
+    # rows only R wide: entries are dropped, and counted
+    _, _, _, st_r = rn.rnnd_build_ex(cuda(X), S, R, T1, T2, 1)
+    assert sum(st_r.dropped[:T1 * T2]) > 0
+    # an intermediate width that still cuts somewhere during the build
+    narrow = max(R + 1, longest // 2)
+    want = oracle_mod.build_wide(X, S, R, narrow, T1, T2, 1)
+    g2, d2, k2, st2 = rn.rnnd_build_wide(cuda(X), S, R, narrow, T1, T2, 1)
+    assert_snapshot_equal(want.snap, False, k2, d2, "rows of %d slots" % narrow)
+    print("longest unbounded list %d; dropped with rows of %d slots: %d, of %d slots: %d"
+          % (longest, R, sum(st_r.dropped[:T1 * T2]), narrow, sum(st2.dropped[:T1 * T2])))
