@@ -213,8 +213,8 @@ int rnnd_export_graph(int64_t N, int32_t R, const uint64_t *keys, const int32_t 
  *              uint8 data, the float's bit pattern for float32); 0xFFFFFFFF where out_ids is -1.
  *   dist_evals host, or NULL: number of delta(q, .) evaluations over all queries.
  * Work is enqueued on `stream` and the call returns after it has completed; a bitmap of N bits per
- * wavefront in flight (at most 1 GiB in all) is allocated and freed inside the call.  Caller keeps
- * ownership of every buffer.  Errors as for rnnd_build (RNND_ERR_BAD_PARAM for L, K, k, row_stride). */
+ * wavefront in flight (at most 1 GiB in all) lives in the workspace block the library keeps between calls
+ * (see rnnd_workspace_bytes).  Caller keeps ownership of every buffer.  Errors as for rnnd_build (RNND_ERR_BAD_PARAM for L, K, k, row_stride). */
 int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int metric, const int32_t *graph,
                 const int32_t *degree, int32_t row_stride, const void *Q, int64_t nq, int32_t L,
                 int32_t K, int32_t k, uint64_t seed, int32_t *out_ids, uint32_t *out_dist_bits,

@@ -2245,8 +2245,12 @@ extern "C" int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int m
     const size_t bm_bytes = (size_t)blocks * 4 * bitmap_words * 4;
     char *base = nullptr;
     unsigned long long h_evals = 0;
-    HIPCHK(hipMalloc((void **)&base, bm_bytes + 256));
-    HIPCHK(hipMemsetAsync(base + bm_bytes, 0, 256, st));     // the evaluation counter; bitmaps are cleared per query
+    WsLease lease;
+    rc = ws_acquire(bm_bytes + 256, false, st, &lease);      // the block kept between calls, like the builds' workspace
+    if (rc) return rc;
+    base = lease.base;
+    // the evaluation counter; the bitmaps are cleared by their wavefronts before every query
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, st, (u32 *)(base + bm_bytes), (size_t)64);
     {
         u32 *bitmaps = (u32 *)base;
         unsigned long long *d_evals = (unsigned long long *)(base + bm_bytes);
@@ -2270,7 +2274,8 @@ extern "C" int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int m
         if (dist_evals) *dist_evals = (int64_t)h_evals;
     }
 done:
-    if (base) (void)hipFree(base);
+    if (rc == RNND_ERR_HIP || rc == RNND_ERR_OOM) (void)hipStreamSynchronize(st);
+    ws_release(&lease);
     return rc;
 }
 
