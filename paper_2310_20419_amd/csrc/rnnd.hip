@@ -430,16 +430,28 @@ __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int 
         if (lane == 63) s_sum[k][wave] = in;
     }
     __syncthreads();
-    if (threadIdx.x < NMRG) {
-        u32 tot = 0;
-        for (int k = 0; k < TC_TILES; ++k)
-            for (int w = 0; w < 16; ++w) { u32 a = s_cnt[k][w][threadIdx.x]; s_cnt[k][w][threadIdx.x] = tot; tot += a; }
-        s_base[threadIdx.x] = tot ? atomicAdd(&ctr->n_touched[threadIdx.x], tot) : 0u;
-    } else if (threadIdx.x == NMRG) {
-        u32 ts = 0;
-        for (int k = 0; k < TC_TILES; ++k)
-            for (int w = 0; w < 16; ++w) { u32 a = s_sum[k][w]; s_sum[k][w] = ts; ts += a; }
-        s_base[NMRG] = ts ? atomicAdd(&ctr->bin_cursor, ts) : 0u;
+    if (wave == 0) {
+        // exclusive prefix over the TC_TILES x 16 wavefront totals, in (tile, wavefront) order: lane = tile * 16 + wavefront
+        static_assert(TC_TILES * 16 == 64, "one lane of the first wavefront per (tile, wavefront)");
+        const int k = lane >> 4, w = lane & 15;
+#pragma unroll
+        for (int q = 0; q <= NMRG; ++q) {
+            const u32 a = q < NMRG ? s_cnt[k][w][q] : s_sum[k][w];
+            u32 in = a;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                u32 v = __shfl_up(in, o);
+                if (lane >= o) in += v;
+            }
+            if (q < NMRG) s_cnt[k][w][q] = in - a;
+            else s_sum[k][w] = in - a;
+            if (lane == 63) s_base[q] = in;
+        }
+        wave_sync();
+        if (lane <= NMRG) {     // the block's atomics are in flight together
+            const u32 tot = s_base[lane];
+            s_base[lane] = tot ? atomicAdd(lane < NMRG ? &ctr->n_touched[lane] : &ctr->bin_cursor, tot) : 0u;
+        }
     }
     __syncthreads();
 #pragma unroll

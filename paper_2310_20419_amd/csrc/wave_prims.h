@@ -53,13 +53,15 @@ __device__ __forceinline__ u64 shfl_up1_u64(u64 v)
 
 // Value of lane (l xor S), S a power of two below 64.  Within rows of 16 lanes the exchange is a
 // DPP move (no LDS round trip) where the ISA has one: quad permutations for S = 1, 2 and a rotation
-// by 8 for S = 8; S = 4 and 16 use the LDS swizzle unit, S = 32 the permute unit.
+// by 8 for S = 8; S = 4 and 16 use the LDS swizzle unit, S = 32 the permute unit.  Every lane of these
+// DPP patterns has a source lane, so bound_ctrl changes no value: it only tells the compiler that the
+// destination needs no initial value (two moves less per 64-bit exchange).
 template <int S>
 __device__ __forceinline__ u32 xor_lane_u32(u32 v)
 {
-    if constexpr (S == 1) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false);        // quad_perm [1,0,3,2]
-    else if constexpr (S == 2) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
-    else if constexpr (S == 8) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, false);  // row_ror:8
+    if constexpr (S == 1) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);        // quad_perm [1,0,3,2]
+    else if constexpr (S == 2) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+    else if constexpr (S == 8) return (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, true);  // row_ror:8
     else if constexpr (S == 4) return (u32)__builtin_amdgcn_ds_swizzle((int)v, 0x101F);                     // xor 4, and 0x1F
     else if constexpr (S == 16) return (u32)__builtin_amdgcn_ds_swizzle((int)v, 0x401F);                    // xor 16, and 0x1F
     else return (u32)__shfl_xor((int)v, S);
