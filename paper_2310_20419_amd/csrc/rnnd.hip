@@ -120,7 +120,11 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
     }
     wave_sync();
     u64 *row = keys + (size_t)u * R;
-    if (S <= 64) {
+    if (S <= 32) {     // the upper half of the wavefront sorts padding
+        u64 k = lane < S ? make_key(s_dist[wave][lane], (u32)ids[lane], 1u) : KEY_PAD;
+        k = group_sort<32>(k, lane);
+        if (lane < S) row[lane] = k;
+    } else if (S <= 64) {
         u64 k[1];
         k[0] = lane < S ? make_key(s_dist[wave][lane], (u32)ids[lane], 1u) : KEY_PAD;
         wave_sort<1>(k, lane);

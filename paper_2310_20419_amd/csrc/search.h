@@ -49,8 +49,8 @@ __device__ __forceinline__ void wave_random_ids(u64 seed, long long n, long long
         const int id = (int)(c + (c >= (u64)u ? 1 : 0));
         bool ok = lane < W && j < jmax;
         for (int k = 0; k < cnt; ++k) ok = ok && (ids[k] != id);
-        for (int l = 0; l < W - 1; ++l) {
-            const int o = __shfl(id, l);
+        for (int l = 0; l < W - 1; ++l) {       // l is the same for the whole wavefront: a scalar read of lane l
+            const int o = __builtin_amdgcn_readlane(id, l);
             if (l < lane && o == id) ok = false;
         }
         const u64 m = __builtin_amdgcn_ballot_w64(ok);
