@@ -176,12 +176,26 @@ def measure(rn, cfg, X, Xd, esz, st16, steps, warmup, args, with_search=True, wi
     rounds = s["rounds"]
     algo = s["init_evals"] + sum(s["algo_evals"])
     execd = s["init_evals"] + sum(s["exec_evals"])
+    # The timed builds take their per-round times from the device's own clock (free: a build with statistics is as
+    # fast as one without).  The roofline's launch duration comes from HIP events attached to the scan launches on
+    # the build's stream, in extra builds right after the timed ones: such an event holds the queue for 4-7
+    # microseconds after its kernel, three per round, which would add about 1 ms to each timed cfg3 build.
+    scan_ms_clock = sum(s["scan_ms"])
+    scan_ms_events = None
+    if args.event_steps > 0 and not args.blocks:
+        rn.rnnd_set_event_timing(True)
+        try:
+            for _ in range(args.event_steps):
+                _, _, _, st_ev = step()
+            scan_ms_events = sum(st_ev.as_dict()["scan_ms"])
+        finally:
+            rn.rnnd_set_event_timing(False)
     # dominant kernel: the UpdateNeighbors scan (the class launches of one round taken together).
     # Algorithmic bytes of one launch = rows of X it must gather (d*esz each) + the list entries it reads
     # (8 B) and writes back (8 B) + the redirected edges it emits (16 B); summed over the T1*T2 launches of
     # the last timed build, durations by HIP events on the build's stream.
     scan_bytes = sum(g * (cfg.d * esz + 16) + 16 * p for g, p in zip(s["gathered_rows"], s["proposals"]))
-    scan_ms = sum(s["scan_ms"])
+    scan_ms = scan_ms_events if scan_ms_events else scan_ms_clock
     hbm_gbs = scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
     kv = s["kernel_variant"]
     kname = {1: "k_update_scan",
@@ -213,6 +227,9 @@ def measure(rn, cfg, X, Xd, esz, st16, steps, warmup, args, with_search=True, wi
                 "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": traffic,
                 "launches": rounds, "avg_launch_ms": scan_ms / max(1, rounds),
                 "algorithmic_bytes_per_launch": scan_bytes / max(1, rounds)}
+    roof["launch_timing"] = ("HIP events attached to the first and last scan launch of every round, %d extra build(s) after "
+                             "the timed ones" % args.event_steps) if scan_ms_events else "device clock, the timed builds"
+    roof["avg_launch_ms_device_clock"] = scan_ms_clock / max(1, rounds)    # over the timed builds (last one)
     if traffic:
         roof["traffic_over_algorithmic"] = traffic / (scan_bytes / max(1, rounds))
     if with_ceiling:
@@ -241,7 +258,7 @@ def measure(rn, cfg, X, Xd, esz, st16, steps, warmup, args, with_search=True, wi
         "executed_distance_evals_per_s": execd / (ms_per_step * 1e-3),
         "algorithmic_distance_evals": algo, "executed_distance_evals": execd,
         "gpu_ms": {"total": s["total_ms"], "init": s["init_ms"], "rounds": sum(s["round_ms"]),
-                   "scan": scan_ms, "reverse": sum(s["reverse_ms"])},
+                   "scan": scan_ms_clock, "reverse": sum(s["reverse_ms"])},      # of the last timed build
         "mean_degree": float(degree.float().mean().item()), "max_degree": int(degree.max().item()),
         # list entries the merges dropped because a row was full (the paper's UpdateNeighbors never drops one)
         "dropped_entries": int(sum(s["dropped"])),
@@ -272,6 +289,9 @@ def main():
     ap.add_argument("--also", default="auto",
                     help="comma-separated further workloads measured with fewer steps and reported under "
                          "\"workloads\" (auto: cfg1,cfg2,cfg4,cfg5 next to the default cfg3, none otherwise; 'none')")
+    ap.add_argument("--event-steps", type=int, default=1,
+                    help="extra builds after the timed ones whose scan launches carry HIP events (roofline's launch duration); "
+                         "0: take it from the device clock of the timed builds")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--queries", type=int, default=10000, help="queries of the search-quality leg (at most the config's)")

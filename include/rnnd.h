@@ -70,9 +70,9 @@ typedef struct {
     int32_t reverse_calls;                  /* AddReverseEdges calls run (T1-1) */
     int32_t kernel_variant;                 /* UpdateNeighbors scan kernel used: 1 generic, 2 int8 MFMA, 3 float MFMA (fp32, then f64) */
     int32_t reserved;
-    float total_ms, init_ms;                /* GPU time of the whole call / of RandomGraph */
-    float round_ms[RNND_MAX_ROUNDS];        /* GPU time of each UpdateNeighbors round */
-    float scan_ms[RNND_MAX_ROUNDS];         /* of which: the scan kernel (Alg. 4's loop body) */
+    float total_ms, init_ms;                /* GPU time of the whole call / of RandomGraph (HIP events) */
+    float round_ms[RNND_MAX_ROUNDS];        /* GPU time of each UpdateNeighbors round (see rnnd_set_event_timing) */
+    float scan_ms[RNND_MAX_ROUNDS];         /* of which: the scan kernels (Alg. 4's loop body) */
     float reverse_ms[RNND_MAX_ROUNDS];      /* GPU time of each AddReverseEdges call */
     int64_t init_evals;                     /* N*S */
     int64_t active[RNND_MAX_ROUNDS];        /* vertices with at least one "new" entry */
@@ -169,6 +169,15 @@ int rnnd_build_static(const void *X, int64_t N, int32_t d, int dtype, int metric
  * 0xA5 bytes before a call clears what it needs cleared, so that a kernel that relies on memory the library
  * never initialised shows up as a wrong result instead of passing on zeroed pages.  Process-wide. */
 int rnnd_set_workspace_poison(int on);
+
+/* Where the per-round times of rnnd_stats (round_ms, scan_ms, reverse_ms) come from.  Process-wide.
+ *   0 (default)  the device's constant-rate clock, read by the kernels themselves (the first workgroup of a round's
+ *                first scan launch, of its scatter launch, ...): costs nothing, so a build with statistics takes as
+ *                long as one without; a scan's time then includes the dispatch of the kernel that follows it
+ *   1            HIP events attached to the launches (hipExtLaunchKernelGGL): each holds the queue for 4-7
+ *                microseconds after its kernel, three per round
+ * Block-sequential builds always use events (one per pass).  Returns RNND_OK. */
+int rnnd_set_event_timing(int on);
 
 /* RandomGraph(S) (first step of Alg. 6): row u <- S distinct ids != u drawn from a counter-based
  * generator (draw j of vertex u = mix64(mix64(seed + G*(u+1)) + G*(j+1)), mix64 = splitmix64's

@@ -107,6 +107,7 @@ def load_library():
         L.rnnd_probe_gather.argtypes = [vp, i64, i64, i64, u64, c.POINTER(c.c_double), vp]
         L.rnnd_set_kernel_variant.argtypes = [c.c_int]
         L.rnnd_set_transpose_path.argtypes = [c.c_int]
+        L.rnnd_set_event_timing.argtypes = [c.c_int]
         L.rnnd_strerror.argtypes = [c.c_int]
         L.rnnd_strerror.restype = c.c_char_p
         L.rnnd_version.restype = c.c_int
@@ -114,7 +115,8 @@ def load_library():
                      "rnnd_update_neighbors", "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search",
                      "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks",
                      "rnnd_probe_gather", "rnnd_build_wide", "rnnd_build_static", "rnnd_release_workspace",
-                     "rnnd_set_workspace_poison", "rnnd_add_reverse_edges_wide", "rnnd_set_transpose_path"):
+                     "rnnd_set_workspace_poison", "rnnd_add_reverse_edges_wide", "rnnd_set_transpose_path",
+                     "rnnd_set_event_timing"):
             getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -176,6 +178,11 @@ def rnnd_release_workspace():
 
 def rnnd_set_workspace_poison(on: bool):
     _check(load_library().rnnd_set_workspace_poison(1 if on else 0))
+
+
+def rnnd_set_event_timing(on: bool):
+    """Per-round times of the statistics from HIP events (True) or from the device clock (False, the default)."""
+    _check(load_library().rnnd_set_event_timing(1 if on else 0))
 
 
 def rnnd_build_static(X, S: int, R: int, T1: int, T2: int, seed: int, graph, degree, metric: int = RNND_L2SQ,

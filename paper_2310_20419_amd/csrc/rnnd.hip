@@ -45,6 +45,10 @@ struct RoundCtr {
     u32 has_surplus;      // some vertex received more than INBOX_CAP edges this round
     u32 pad[2];
     u32 n_redo[NDEG];     // float scan: vertices the single-precision form left to the double-precision one
+    // ticks of the device's constant-rate clock (0 = not taken): the round's first scan launch starts, its scatter
+    // starts (= the scan has ended: launches of one stream run back to back), the round's / the following
+    // AddReverseEdges call's last kernel has ended (taken by k_stamp, only where statistics ask for it)
+    u64 t_scan_start, t_scan_stop, t_round_stop, t_reverse_stop;
     // statistics, spread over STAT_SLOTS addresses so that the adds of many blocks do not queue up
     // on one: [slot][0..4] = algorithmic evals, executed evals, rows gathered, edges redirected, entries a merge
     // dropped because the list was full
@@ -60,6 +64,18 @@ __device__ __forceinline__ void add_round_stats(RoundCtr *ctr, u64 algo, u64 exe
     atomicAdd(&s[2], rows);
     atomicAdd(&s[3], props);
 }
+
+// Statistics take the scan time of a round from the device's own clock instead of events attached to the launches:
+// an event costs 4-7 microseconds of idle queue after its kernel, three per round used to add 1 ms to a 27 ms build.
+__device__ __forceinline__ void stamp_scan_start(RoundCtr *ctr)
+{   // the first scan launch of a round that comes by fills the field
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && ctr->t_scan_start == 0ull) ctr->t_scan_start = wall_clock64();
+}
+__device__ __forceinline__ void stamp_scan_stop(RoundCtr *ctr)
+{
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) ctr->t_scan_stop = wall_clock64();
+}
+__global__ void k_stamp(u64 *dst) { if (threadIdx.x == 0) *dst = wall_clock64(); }
 
 struct Prop {          // one redirected edge (Alg. 4, the edge update): `key` enters `tgt`'s list
     u64 key;
@@ -165,6 +181,7 @@ __global__ __launch_bounds__(BLOCK) void k_update_scan(const void *X, int d, int
     const u32 n_active = *n_list;
     const size_t rowbytes = (size_t)d * dt_size(DT);
     u64 *sk = s_key[wave];
+    stamp_scan_start(ctr);
     u64 evals_algo = 0, evals_exec = 0, rows = 0, nprops_total = 0;
     for (u32 it = gw; it < n_active; it += nw) {
         const int u = list[it];
@@ -304,6 +321,7 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int
     const u32 n = ctr->n_active[c];
     const int *list = lists + (size_t)c * N;
     bool surplus = false;
+    stamp_scan_stop(ctr);
     if (g >= n) return;
     // the loads of the next vertex (its count and its first 16 edges) are issued before the atomics
     // of the current one; the list entry of the vertex after that is fetched one trip earlier still
@@ -1314,6 +1332,7 @@ __global__ __launch_bounds__(256) void k_probe_gather(const uint4 *X, u32 n_rows
 
 static char g_last_hip_error[512];
 static int g_kernel_variant = 0;
+static int g_event_timing = 0;    // 1: per-round times of the statistics from HIP events attached to the launches
 static int g_transpose_path = 0;   // AddReverseEdges' transposition: 0 by size, 1 atomics, 2 binned
 #define BIN_MIN_N 262144            // below this the binned transposition's extra launches cost more than its atomics save
 
@@ -1965,8 +1984,11 @@ static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric
     hipStream_t st = (hipStream_t)stream;
     const int rounds = T1 * T2, n_ctr = (int)(rounds * per_pass) + 2, vec_ok = vec_ok_for(X, d, dtype);
     const int variant = scan_variant_for(X, d, dtype), use_classes = variant == 2 ? 2 : variant == 3 ? 1 : 0;
-    // events (only when statistics are wanted): 0 start, 1 end of init, 2 + 3t .. 4 + 3t = scan start, scan stop,
-    // end of round t (block-sequential passes record only the last), then the end of each reverse call, then the end
+    // events (only when statistics are wanted): 0 start, 1 end of init, last: the end.  Per-round times come from the
+    // device clock (RoundCtr::t_*), which costs nothing; with rnnd_set_event_timing(1), and for block-sequential
+    // passes, from events as well: 2 + 3t .. 4 + 3t = scan start, scan stop, end of round t (block-sequential passes
+    // record only the last), then the end of each reverse call
+    const bool ev_rounds = stats && (g_event_timing || blocks);
     const int e_rev = 2 + 3 * rounds, e_end = e_rev + T1, n_ev = stats ? e_end + 1 : 0;
     Workspace w;
     WsLease lease;
@@ -1982,7 +2004,8 @@ static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric
         ev = (hipEvent_t *)calloc(n_ev + 1, sizeof(hipEvent_t));
         hctr = (RoundCtr *)calloc(n_ctr, sizeof(RoundCtr));
         if (!ev || !hctr) { rc = RNND_ERR_OOM; goto done; }
-        for (; n_ev_made < n_ev; ++n_ev_made) HIPCHK(hipEventCreate(&ev[n_ev_made]));
+        for (; n_ev_made < n_ev; ++n_ev_made)
+            if (ev_rounds || n_ev_made < 2 || n_ev_made == e_end) HIPCHK(hipEventCreate(&ev[n_ev_made]));
     }
     {
         int t = 0;
@@ -2004,17 +2027,21 @@ static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric
                 }
                 RoundEvents re;
                 // a round ends where the next one starts; only the last round before a reverse call or
-                // the export needs an event of its own for that (every event costs a few microseconds)
-                if (stats) {
+                // the export needs a mark of its own for that
+                if (ev_rounds) {
                     re.scan_start = ev[2 + 3 * t];
                     re.scan_stop = ev[3 + 3 * t];
                     if (t2 == T2 - 1) re.round_stop = ev[4 + 3 * t];
                 }
                 HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, M, w.keys, w.deg, t, st, re));
+                if (stats && !ev_rounds && t2 == T2 - 1)
+                    hipLaunchKernelGGL(k_stamp, dim3(1), dim3(64), 0, st, &w.ctr[t].t_round_stop);
             }
-            if (t1 != T1 - 1)
+            if (t1 != T1 - 1) {
                 HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, blocks ? -1 : t, st,
-                                      stats ? ev[e_rev + t1] : nullptr, M));
+                                      ev_rounds ? ev[e_rev + t1] : nullptr, M));
+                if (stats && !ev_rounds) hipLaunchKernelGGL(k_stamp, dim3(1), dim3(64), 0, st, &w.ctr[t - 1].t_reverse_stop);
+            }
         }
         launch_export(N, M, w.keys, w.deg, graph_out, degree_out, st);
         HIPCHK(hipGetLastError());
@@ -2035,7 +2062,20 @@ static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric
             float ms = 0;
             (void)hipEventElapsedTime(&ms, ev[0], ev[1]); stats->init_ms = ms;
             int tt = 0;
-            for (int t1 = 0; t1 < T1; ++t1) {
+            // device clock: ticks per millisecond, and the time between two marks (0 where one is missing)
+            int dev = 0, khz = 0;
+            (void)hipGetDevice(&dev);
+            (void)hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
+            auto clk_ms = [khz](u64 a, u64 b) { return (a && b > a && khz > 0) ? (float)((double)(b - a) / (double)khz) : 0.f; };
+            for (int t1 = 0; t1 < T1 && !ev_rounds; ++t1) {
+                for (int t2 = 0; t2 < T2; ++t2, ++tt) {
+                    if (tt >= RNND_MAX_ROUNDS) continue;
+                    stats->scan_ms[tt] = clk_ms(hctr[tt].t_scan_start, hctr[tt].t_scan_stop);
+                    stats->round_ms[tt] = clk_ms(hctr[tt].t_scan_start, t2 == T2 - 1 ? hctr[tt].t_round_stop : hctr[tt + 1].t_scan_start);
+                }
+                if (t1 != T1 - 1 && t1 < RNND_MAX_ROUNDS) stats->reverse_ms[t1] = clk_ms(hctr[tt - 1].t_round_stop, hctr[tt - 1].t_reverse_stop);
+            }
+            for (int t1 = 0; t1 < T1 && ev_rounds; ++t1) {
                 for (int t2 = 0; t2 < T2; ++t2, ++tt) {
                     if (tt >= RNND_MAX_ROUNDS) continue;
                     if (blocks) {
@@ -2059,7 +2099,8 @@ static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric
     }
 done:
     if (rc == RNND_ERR_HIP || rc == RNND_ERR_OOM) (void)hipStreamSynchronize(st);   // nothing may still use the workspace
-    for (int i = 0; i < n_ev_made; ++i) (void)hipEventDestroy(ev[i]);
+    for (int i = 0; i < n_ev_made; ++i)
+        if (ev[i]) (void)hipEventDestroy(ev[i]);
     free(ev);
     free(hctr);
     ws_release(&lease);
@@ -2349,6 +2390,12 @@ extern "C" int rnnd_set_kernel_variant(int variant)
 {
     if (variant < 0 || variant > 2) return RNND_ERR_BAD_PARAM;
     g_kernel_variant = variant;
+    return RNND_OK;
+}
+
+extern "C" int rnnd_set_event_timing(int on)
+{
+    g_event_timing = on ? 1 : 0;
     return RNND_OK;
 }
 

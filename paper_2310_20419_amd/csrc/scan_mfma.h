@@ -601,6 +601,7 @@ __global__ __launch_bounds__(256, 4) void k_update_scan_mfma_u8_small(
     const int y = blockIdx.y;
     const int *list = lists + (size_t)y * N;
     const u32 n = ctr->n_active[y];
+    stamp_scan_start(ctr);
     if (y == 0) scan_packed_body<4, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm);
     else if (y == 1) scan_packed_body<2, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm);
     else scan_packed_body<1, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm);

@@ -306,6 +306,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
     u64 tiles = 0, rows = 0, nprops_total = 0;
     u32 ev_lane = 0;
 
+    stamp_scan_start(ctr);
     if (gw >= n_active) return;
     ScanItem cur = scan_item_load<NG>(list[gw], keys, deg, R, lane);
     ScanItem nxt = scan_item_load<NG>(gw + nw < n_active ? list[gw + nw] : -1, keys, deg, R, lane);

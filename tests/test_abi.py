@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported(lib):
             "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search", "rnnd_workspace_bytes",
             "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant", "rnnd_build_blocks",
             "rnnd_update_neighbors_blocks", "rnnd_probe_gather", "rnnd_build_wide", "rnnd_release_workspace",
-            "rnnd_set_workspace_poison"} <= set(names)
+            "rnnd_set_workspace_poison", "rnnd_set_event_timing"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
