@@ -40,7 +40,7 @@ __device__ __forceinline__ int sqdiff_word_u8(uint32_t a, uint32_t b, int acc)
 }
 
 // UF (float rows): 16-byte chunks per lane whose loads are issued together before the (ordered)
-// accumulation; it changes how many loads are in flight, never the order of the arithmetic.
+// accumulation; it changes how many loads are in flight, never the order of the arithmetic.  UF >= 2.
 template <int DT, int UF = 4>
 __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void *pb, int d,
                                                      int vec_ok, int sub)
@@ -87,13 +87,23 @@ __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void 
                         acc = fma(t, t, acc);
                     }
             }
-            for (; c < nchunk; c += 8) {
-                const us8 va = pa8[c], vb = pb8[c];
+            if (c < nchunk) {
+                // the last, shorter trip: its loads are issued together as well; a chunk past the end reads as zeros,
+                // and adding the square of 0 - 0 leaves the sum as it is, so the arithmetic is that of the short loop
+                us8 va[UF - 1 > 0 ? UF - 1 : 1], vb[UF - 1 > 0 ? UF - 1 : 1];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const double t = (double)coord16_to_float<DT>(va[e]) - (double)coord16_to_float<DT>(vb[e]);
-                    acc = fma(t, t, acc);
+                for (int k = 0; k < UF - 1; ++k) {
+                    const bool in = c + 8 * k < nchunk;
+                    va[k] = in ? pa8[c + 8 * k] : (us8)(0);
+                    vb[k] = in ? pb8[c + 8 * k] : (us8)(0);
                 }
+#pragma unroll
+                for (int k = 0; k < UF - 1; ++k)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const double t = (double)coord16_to_float<DT>(va[k][e]) - (double)coord16_to_float<DT>(vb[k][e]);
+                        acc = fma(t, t, acc);
+                    }
             }
         } else {
             for (int e = sub; e < d; e += 8) {
@@ -126,13 +136,24 @@ __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void 
                     t = (double)va[k].w - (double)vb[k].w; acc = fma(t, t, acc);
                 }
             }
-            for (; c < nchunk; c += 8) {
-                float4 va = pa4[c], vb = pb4[c];
-                double t;
-                t = (double)va.x - (double)vb.x; acc = fma(t, t, acc);
-                t = (double)va.y - (double)vb.y; acc = fma(t, t, acc);
-                t = (double)va.z - (double)vb.z; acc = fma(t, t, acc);
-                t = (double)va.w - (double)vb.w; acc = fma(t, t, acc);
+            if (c < nchunk) {
+                // the last, shorter trip: its loads are issued together as well; a chunk past the end reads as zeros,
+                // and adding the square of 0 - 0 leaves the sum as it is, so the arithmetic is that of the short loop
+                float4 va[UF - 1 > 0 ? UF - 1 : 1], vb[UF - 1 > 0 ? UF - 1 : 1];
+#pragma unroll
+                for (int k = 0; k < UF - 1; ++k) {
+                    const bool in = c + 8 * k < nchunk;
+                    va[k] = in ? pa4[c + 8 * k] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    vb[k] = in ? pb4[c + 8 * k] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int k = 0; k < UF - 1; ++k) {
+                    double t;
+                    t = (double)va[k].x - (double)vb[k].x; acc = fma(t, t, acc);
+                    t = (double)va[k].y - (double)vb[k].y; acc = fma(t, t, acc);
+                    t = (double)va[k].z - (double)vb[k].z; acc = fma(t, t, acc);
+                    t = (double)va[k].w - (double)vb[k].w; acc = fma(t, t, acc);
+                }
             }
         } else {
             for (int e = sub; e < d; e += 8) {
