@@ -187,7 +187,7 @@ int rnnd_random_graph(const void *X, int64_t N, int32_t d, int dtype, int metric
                       int32_t R, uint64_t seed, uint64_t *keys, int32_t *deg, void *stream);
 
 /* n_rounds synchronous UpdateNeighbors rounds (Alg. 4) applied in place to a snapshot.
- * stats (host, may be NULL) receives the per-round counters. */
+ * stats (host, may be NULL) receives the per-round counters, round_ms and scan_ms (device clock). */
 int rnnd_update_neighbors(const void *X, int64_t N, int32_t d, int dtype, int metric, int32_t R,
                           uint64_t *keys, int32_t *deg, int32_t n_rounds, rnnd_stats *stats,
                           void *stream);

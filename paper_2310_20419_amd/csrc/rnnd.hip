@@ -2201,13 +2201,26 @@ static int update_impl(const void *X, int64_t N, int32_t d, int dtype, int metri
             HIPCHK(launch_update_round(w, X, N, d, dtype, vec_ok, variant, R, (u64 *)keys, deg, t, st));
         }
     }
-    if (stats) HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
+    if (stats) {
+        if (!blocks) hipLaunchKernelGGL(k_stamp, dim3(1), dim3(64), 0, st, &w.ctr[n_rounds - 1].t_round_stop);
+        HIPCHK(hipMemcpyAsync(hctr, w.ctr, (size_t)n_ctr * sizeof(RoundCtr), hipMemcpyDeviceToHost, st));
+    }
     HIPCHK(hipStreamSynchronize(st));
     if (stats) {
         memset(stats, 0, sizeof *stats);
         if (blocks) fill_pass_stats(stats, hctr, n_rounds, (int)per_pass);
         else fill_round_stats(stats, hctr, n_rounds);
         stats->kernel_variant = variant;
+        if (!blocks) {      // per-round times from the device clock (see build_impl)
+            int dev = 0, khz = 0;
+            (void)hipGetDevice(&dev);
+            (void)hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
+            auto clk_ms = [khz](u64 a, u64 b) { return (a && b > a && khz > 0) ? (float)((double)(b - a) / (double)khz) : 0.f; };
+            for (int t = 0; t < n_rounds && t < RNND_MAX_ROUNDS; ++t) {
+                stats->scan_ms[t] = clk_ms(hctr[t].t_scan_start, hctr[t].t_scan_stop);
+                stats->round_ms[t] = clk_ms(hctr[t].t_scan_start, t == n_rounds - 1 ? hctr[t].t_round_stop : hctr[t + 1].t_scan_start);
+            }
+        }
     }
 done:
     if (rc == RNND_ERR_HIP || rc == RNND_ERR_OOM) (void)hipStreamSynchronize(st);

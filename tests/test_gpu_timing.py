@@ -79,3 +79,17 @@ def test_statistics_cost_nothing_with_the_device_clock(rn):
     with_stats = timed(lambda: rn.rnnd_build_ex(X, cfg.S, cfg.R, cfg.T1, cfg.T2, wl.BUILD_SEED, want_keys=False))
     print("cfg2 build: %.3f ms without statistics, %.3f ms with" % (plain * 1e3, with_stats * 1e3))
     assert with_stats <= plain * 1.04 + 2e-4, (plain, with_stats)
+
+
+def test_step_wise_rounds_report_their_times(rn):
+    """rnnd_update_neighbors fills round_ms and scan_ms of the rounds it ran (device clock)."""
+    import torch
+    X = torch.from_numpy(wl.custom("heavy_u8", 50000, 128, 5)).cuda()
+    R, S, rounds = 48, 12, 4
+    keys, deg = rn.rnnd_random_graph(X, S, R, 3)
+    st = rn.rnnd_update_neighbors(X, keys, deg, R, rounds).as_dict()
+    assert st["rounds"] == rounds
+    for t in range(rounds):
+        assert 0.0 < st["scan_ms"][t] <= st["round_ms"][t] * 1.001, (t, st["scan_ms"][t], st["round_ms"][t])
+        assert st["round_ms"][t] < 50.0
+    assert len(st["scan_ms"]) == rounds
