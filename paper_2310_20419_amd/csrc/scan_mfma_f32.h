@@ -64,25 +64,6 @@ __device__ __forceinline__ u32 transpose16_bits(u32 w, int lane)
     return w & 0xFFFFu;
 }
 
-// The same for two 16x16 bit matrices at once, one in the low and one in the high half of the word.
-template <int SH, u32 M>
-__device__ __forceinline__ u32 transpose_step16x2(u32 w, int lane)
-{
-    constexpr u32 M2 = M | (M << 16);
-    const u32 p = (u32)__shfl_xor((int)w, SH);
-    const u32 lo = (w & M2) | ((p & M2) << SH);
-    const u32 hi = ((p >> SH) & M2) | (w & ~M2);
-    return (lane & SH) ? hi : lo;
-}
-__device__ __forceinline__ u32 transpose16_bits_x2(u32 w, int lane)
-{
-    w = transpose_step16x2<8, 0x00FFu>(w, lane);
-    w = transpose_step16x2<4, 0x0F0Fu>(w, lane);
-    w = transpose_step16x2<2, 0x3333u>(w, lane);
-    w = transpose_step16x2<1, 0x5555u>(w, lane);
-    return w;
-}
-
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
@@ -459,6 +440,11 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                             // delta(v,w), which the bound's constant covers
                             const float dj = sm.distf[16 * J + r16];
                             const float nJf = (float)nr[J];
+                            // The outcomes with group I's slot as the tested row are taken as wavefront-wide masks:
+                            // accumulator v of lane (r16, q) is (row 4q + v, column r16), so bit 16q + c of the mask
+                            // of accumulator v is (row 4q + v, column c), and the row a lane stands for, r16, finds
+                            // its 16 column bits in mask r16 % 4 at 16 (r16 / 4): no transposition.
+                            u64 fire_m[4], amb_m[4];
 #pragma unroll
                             for (int v = 0; v < 4; ++v) {
                                 const int rsel = 4 * q + v;
@@ -466,11 +452,15 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                                 const float dvw = fmaf(-2.f, acc[t][v], nsum);
                                 const float tol = epskf * nsum;
                                 const float ta = dIf[v] - dvw, tb = dj - dvw;
-                                fa |= (ta >= 0.f) ? (1u << rsel) : 0u;
+                                fire_m[v] = __builtin_amdgcn_ballot_w64(ta >= 0.f);
+                                amb_m[v] = __builtin_amdgcn_ballot_w64(!(fabsf(ta) > tol));      // also when not finite
                                 fb |= (tb >= 0.f) ? (1u << rsel) : 0u;
-                                fa |= !(fabsf(ta) > tol) ? (0x10000u << rsel) : 0u;      // also when not finite
                                 fb |= !(fabsf(tb) > tol) ? (0x10000u << rsel) : 0u;
                             }
+                            const int vs = r16 & 3, sh = 16 * (r16 >> 2);
+                            const u64 mf = vs == 0 ? fire_m[0] : vs == 1 ? fire_m[1] : vs == 2 ? fire_m[2] : fire_m[3];
+                            const u64 ma = vs == 0 ? amb_m[0] : vs == 1 ? amb_m[1] : vs == 2 ? amb_m[2] : amb_m[3];
+                            fa = ((u32)(mf >> sh) & 0xFFFFu) | (((u32)(ma >> sh) & 0xFFFFu) << 16);
                         } else {
                             const float dj = __uint_as_float(key_dist(sm.key[16 * J + r16]));
 #pragma unroll
@@ -484,9 +474,13 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                                 fb |= (dj >= dvw) ? (1u << rsel) : 0u;
                             }
                         }
-                        fa |= (u32)__shfl_xor((int)fa, 16);
-                        fa |= (u32)__shfl_xor((int)fa, 32);
-                        FA[t] = FAST ? transpose16_bits_x2(fa, lane) : transpose16_bits(fa, lane);
+                        if constexpr (FAST) {
+                            FA[t] = fa;
+                        } else {
+                            fa |= (u32)__shfl_xor((int)fa, 16);
+                            fa |= (u32)__shfl_xor((int)fa, 32);
+                            FA[t] = transpose16_bits(fa, lane);
+                        }
                         if (I != J) {
                             fb |= (u32)__shfl_xor((int)fb, 16);
                             fb |= (u32)__shfl_xor((int)fb, 32);
