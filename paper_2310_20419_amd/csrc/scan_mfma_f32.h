@@ -241,6 +241,13 @@ __device__ __forceinline__ int popc_below(u64 m0, u64 m1, int p)   // set bits o
     if (p == 64) return __popcll(m0);
     return __popcll(m0) + __popcll(m1 & ((p >= 128) ? ~0ull : ((1ull << (p - 64)) - 1ull)));
 }
+// the same when the mask has at most 64 bits in use (ONE_WORD: m1 == 0) and 0 <= p <= 64
+template <bool ONE_WORD>
+__device__ __forceinline__ int popc_below_w(u64 m0, u64 m1, int p)
+{
+    if constexpr (ONE_WORD) return p >= 64 ? __popcll(m0) : __popcll(m0 & ((1ull << (p & 63)) - 1ull));
+    else return popc_below(m0, m1, p);
+}
 
 // NRC = 16-row groups of the list (lists of at most 16 NRC entries); NG = ceil(NRC / 2) names the
 // degree class family; CH = 64-byte chunks of every row fetched per loop iteration (rows a multiple of
@@ -326,7 +333,7 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                 const int p = 64 * h + lane;
                 if (p < m) {
                     const bool isnew = kreg[h] & 1ull;
-                    const int s = isnew ? popc_below(new0, new1, p) : n_new + popc_below(old0, old1, p);
+                    const int s = isnew ? popc_below_w<(NRC <= 4)>(new0, new1, p) : n_new + popc_below_w<(NRC <= 4)>(old0, old1, p);
                     sm.key[s] = kreg[h];
                     sm.pos[s] = p;
                     sm.distf[s] = __uint_as_float(key_dist(kreg[h]));
@@ -502,8 +509,8 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                 valid[e] = rg < NRC && s < m;
                 mypos[e] = valid[e] ? sm.pos[s] : 0;
                 const bool snew = s < n_new;
-                const int a = popc_below(new0, new1, mypos[e]);     // new entries before mine in the list
-                const int b = popc_below(old0, old1, mypos[e]);     // old entries before mine
+                const int a = popc_below_w<(NRC <= 4)>(new0, new1, mypos[e]);     // new entries before mine in the list
+                const int b = popc_below_w<(NRC <= 4)>(old0, old1, mypos[e]);     // old entries before mine
 #pragma unroll
                 for (int c = 0; c < NWD; ++c) {
                     // column groups 2c and 2c + 1
@@ -537,13 +544,15 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                 for (int e = 0; e < NSET; ++e)
 #pragma unroll
                     for (int c = 0; c < NWD; ++c) mine += __popc(Aw[e][c]);
-                int incl = mine;
+                int incl = mine, total = 0;
+                if (__builtin_amdgcn_ballot_w64(mine != 0) != 0ull) {     // most vertices have no undecided pair at all
 #pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const int up = __shfl_up(incl, o);
-                    if (lane >= o) incl += up;
+                    for (int o = 1; o < 64; o <<= 1) {
+                        const int up = __shfl_up(incl, o);
+                        if (lane >= o) incl += up;
+                    }
+                    total = __shfl(incl, 63);
                 }
-                const int total = __shfl(incl, 63);
                 if (total > F32_AMB_CAP) {
                     defer = true;
                     if (lane == 0) redo[atomicAdd(n_redo, 1u)] = u;
@@ -653,8 +662,8 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                     int ta = 16 * NRC, tb = 16 * NRC;      // no target: everything before me
                     if (tgt >= 0) {
                         const int pt = sm.pos[tgt];
-                        ta = popc_below(new0, new1, pt) + (tgt < n_new ? 1 : 0);
-                        tb = popc_below(old0, old1, pt) + (tgt < n_new ? 0 : 1);
+                        ta = popc_below_w<(NRC <= 4)>(new0, new1, pt) + (tgt < n_new ? 1 : 0);
+                        tb = popc_below_w<(NRC <= 4)>(old0, old1, pt) + (tgt < n_new ? 0 : 1);
                     }
 #pragma unroll
                     for (int c = 0; c < NWD; ++c) {
