@@ -74,14 +74,12 @@ __device__ __forceinline__ void scan_gather(const int8_t *__restrict__ X, const 
     for (int g = 0; g < NG; ++g) {
         const u32 idr = key_id(it.k[g >> 1]);
         const int id = __shfl((int)idr, 32 * (g & 1) + l32);
+        // a lane without a list entry reads row 0 of X (every load unconditional: no registers to clear, no
+        // branch); what such a row contributes is never selected by a mask
         const bool valid = it.u >= 0 && 32 * g + l32 < m;
-        const int8_t *p = X + (size_t)id * d + half * 16;
+        const int8_t *p = X + (size_t)(valid ? id : 0) * d + half * 16;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            v4i v = {0, 0, 0, 0};
-            if (valid) v = *(const v4i *)(p + s * 32);
-            A[g][s] = v;
-        }
+        for (int s = 0; s < KS; ++s) A[g][s] = *(const v4i *)(p + s * 32);
     }
 }
 
@@ -146,7 +144,7 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
     for (int I = 0; I < NG; ++I) {
         if (32 * I < m) {                   // wave-uniform
             // the Gram tile of the block with itself; n of its rows is the diagonal, read back through
-            // LDS (rows past the list are zero rows that no mask ever selects)
+            // LDS (rows past the list hold row 0 of X; no mask ever selects them)
             v16i G = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int s = 0; s < KS; ++s) G = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[I][s], A[I][s], G, 0, 0, 0);
@@ -389,14 +387,11 @@ __device__ __forceinline__ void pack_gather(const int8_t *__restrict__ X, const 
                                             int half, v4i (&A)[KS])
 {
     constexpr int d = KS * 32, W = 32 / P;
+    // a lane without a list entry reads row 0 of X (see scan_gather)
     const bool valid = it.u >= 0 && pos < (it.m < W ? it.m : W);
-    const int8_t *p = X + (size_t)key_id(it.k) * d + half * 16;
+    const int8_t *p = X + (size_t)(valid ? key_id(it.k) : 0u) * d + half * 16;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        v4i v = {0, 0, 0, 0};
-        if (valid) v = *(const v4i *)(p + s * 32);
-        A[s] = v;
-    }
+    for (int s = 0; s < KS; ++s) A[s] = *(const v4i *)(p + s * 32);
 }
 
 template <int P, int KS>
@@ -427,8 +422,8 @@ __device__ __forceinline__ void pack_vertices_u8(const PackItem &cur, v4i (&A)[K
         const u32 vmask = (u32)__builtin_amdgcn_ballot_w64(valid && half == 0);
         wave_sync();   // the previous group is done with the LDS tables
         if (half == 0) sm.id[l32] = (int)key_id(kb);
-        // n of every row: the diagonal of the Gram tile, through LDS (rows past a list are zero rows
-        // that no mask ever selects)
+        // n of every row: the diagonal of the Gram tile, through LDS (rows past a list hold row 0 of X;
+        // no mask ever selects them)
         // lane: row l32; G[a]: <x_row, x_col> for column 8(a/4) + 4 half + a%4
         v16i G = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
