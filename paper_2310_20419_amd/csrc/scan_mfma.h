@@ -50,16 +50,14 @@ __device__ __forceinline__ ScanItem scan_item_load(int u, const u64 *__restrict_
                                                    const int *__restrict__ deg, int R, int lane)
 {
     // the list is read without waiting for the degree: slots past it exist (rows are R wide) and are masked later
+    // past the end of the work list (u < 0) vertex 0 is read instead and given degree 0: loads without branches
     ScanItem it;
+    const u64 *row = keys + (size_t)(u >= 0 ? u : 0) * R;
+    const int m = deg[u >= 0 ? u : 0];
     it.u = u;
-    it.m = 0;
-    it.k[0] = it.k[1] = KEY_PAD;
-    if (u >= 0) {
-        const u64 *row = keys + (size_t)u * R;
-        it.m = deg[u];
-        if (lane < R) it.k[0] = row[lane];
-        if (NG > 2 && lane + 64 < R) it.k[1] = row[lane + 64];
-    }
+    it.m = u >= 0 ? m : 0;
+    it.k[0] = row[lane < R ? lane : R - 1];                                  // positions past the degree are masked later
+    it.k[1] = NG > 2 ? row[lane + 64 < R ? lane + 64 : R - 1] : KEY_PAD;
     return it;
 }
 
@@ -371,14 +369,12 @@ template <int P>
 __device__ __forceinline__ PackItem pack_item_load(int u, const u64 *__restrict__ keys,
                                                    const int *__restrict__ deg, int R, int pos)
 {
+    // past the end of the work list (u < 0) vertex 0 is read instead and given degree 0: loads without branches
     PackItem it;
+    const int m = deg[u >= 0 ? u : 0];
     it.u = u;
-    it.m = 0;
-    it.k = KEY_PAD;
-    if (u >= 0) {
-        it.m = deg[u];
-        if (pos < R) it.k = keys[(size_t)u * R + pos];   // slots past the degree exist and are masked later
-    }
+    it.m = u >= 0 ? m : 0;
+    it.k = keys[(size_t)(u >= 0 ? u : 0) * R + (pos < R ? pos : R - 1)];   // slots past the degree exist and are masked later
     return it;
 }
 
