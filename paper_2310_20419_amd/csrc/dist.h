@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "wave_prims.h"
+
 #define DT_U8 0
 #define DT_F32 1
 #define DT_F16 2
@@ -21,6 +23,23 @@
 
 // bytes of one coordinate
 __host__ __device__ constexpr int dt_size(int dt) { return dt == DT_U8 ? 1 : (dt == DT_F16 || dt == DT_BF16) ? 2 : 4; }
+
+// Sum over the 8 lanes of a group, every lane receiving it: partner 1, then 2, then 4 (a fixed order, so the
+// double sums are the same bits wherever they are formed).  The exchanges inside a quad are DPP moves.
+__device__ __forceinline__ int group8_sum(int v)
+{
+    v += (int)xor_lane_u32<1>((uint32_t)v);
+    v += (int)xor_lane_u32<2>((uint32_t)v);
+    v += (int)xor_lane_u32<4>((uint32_t)v);
+    return v;
+}
+__device__ __forceinline__ double group8_sum(double v)
+{
+    v += __builtin_bit_cast(double, xor_lane_u64(__builtin_bit_cast(unsigned long long, v), 1));
+    v += __builtin_bit_cast(double, xor_lane_u64(__builtin_bit_cast(unsigned long long, v), 2));
+    v += __builtin_bit_cast(double, xor_lane_u64(__builtin_bit_cast(unsigned long long, v), 4));
+    return v;
+}
 
 // a 16-bit stored coordinate as the float it stands for (exact)
 template <int DT>
@@ -63,9 +82,7 @@ __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void 
                 acc += t * t;
             }
         }
-        acc += __shfl_xor(acc, 1);
-        acc += __shfl_xor(acc, 2);
-        acc += __shfl_xor(acc, 4);
+        acc = group8_sum(acc);
         return (uint32_t)acc;
     } else if (DT == DT_F16 || DT == DT_BF16) {
         const unsigned short *a = (const unsigned short *)pa, *b = (const unsigned short *)pb;
@@ -111,9 +128,7 @@ __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void 
                 acc = fma(t, t, acc);
             }
         }
-        acc += __shfl_xor(acc, 1);
-        acc += __shfl_xor(acc, 2);
-        acc += __shfl_xor(acc, 4);
+        acc = group8_sum(acc);
         return __float_as_uint((float)acc);
     } else {
         const float *a = (const float *)pa, *b = (const float *)pb;
@@ -161,9 +176,7 @@ __device__ __forceinline__ uint32_t group8_dist_bits(const void *pa, const void 
                 acc = fma(t, t, acc);
             }
         }
-        acc += __shfl_xor(acc, 1);
-        acc += __shfl_xor(acc, 2);
-        acc += __shfl_xor(acc, 4);
+        acc = group8_sum(acc);
         return __float_as_uint((float)acc);
     }
 }

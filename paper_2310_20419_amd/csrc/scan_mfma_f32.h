@@ -658,17 +658,22 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                     }
                     if (tn >= 0 && to >= 0) tgt = sm.pos[tn] < sm.pos[to] ? tn : to;
                     else tgt = tn >= 0 ? tn : to;
-                    // the evaluations Alg. 4 makes for this row: tested kept candidates up to and including w
-                    int ta = 16 * NRC, tb = 16 * NRC;      // no target: everything before me
-                    if (tgt >= 0) {
-                        const int pt = sm.pos[tgt];
-                        ta = popc_below_w<(NRC <= 4)>(new0, new1, pt) + (tgt < n_new ? 1 : 0);
-                        tb = popc_below_w<(NRC <= 4)>(old0, old1, pt) + (tgt < n_new ? 0 : 1);
-                    }
+                }
+                // the evaluations Alg. 4 makes for this row: tested kept candidates up to and including w, i.e. the
+                // slots before w in the list -- the mask the lane that owns slot w holds as its own `before` -- and w
+                // (no target: everything that was tested)
+                {
+                    const int tl = tgt >= 0 ? (tgt & 15) + 16 * ((tgt >> 4) & 3) : lane;
 #pragma unroll
                     for (int c = 0; c < NWD; ++c) {
-                        const u32 upto = range_word(0, ta, c) | range_word(n_new, n_new + tb, c);
-                        ev += __popc(Ew[e][c] & Kw[c] & upto);
+                        u32 upto = (u32)__shfl((int)Bw[0][c], tl);
+                        if (NSET > 1) {
+                            const u32 hi = (u32)__shfl((int)Bw[NSET - 1][c], tl);
+                            upto = (tgt >> 6) ? hi : upto;
+                        }
+                        if ((tgt >> 5) == c) upto |= 1u << (tgt & 31);
+                        if (tgt < 0) upto = 0xFFFFFFFFu;
+                        if (valid[e]) ev += __popc(Ew[e][c] & Kw[c] & upto);
                     }
                 }
                 ev_lane += (u32)ev;
