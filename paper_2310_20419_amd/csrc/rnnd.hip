@@ -502,16 +502,15 @@ template <int G>
 __device__ __forceinline__ MergeItem merge_item_load(int x, int R, const u64 *keys, const int *deg,
                                                      const int *cnt, const u64 *inbox, int sub)
 {
+    // past the end of the list (x < 0) vertex 0 is read instead and given no entries: loads without branches
     MergeItem m;
+    const size_t xx = (size_t)(x >= 0 ? x : 0);
+    const int nb = deg[xx], c = cnt[xx];
     m.x = x;
-    m.nb = m.c = 0;
-    m.kr = m.ki = KEY_PAD;
-    if (x >= 0) {
-        m.nb = deg[x];
-        m.c = cnt[x];
-        if (sub < R) m.kr = keys[(size_t)x * R + sub];
-        m.ki = inbox[(size_t)x * INBOX_CAP + (G - 1 - sub)];
-    }
+    m.nb = x >= 0 ? nb : 0;
+    m.c = x >= 0 ? c : 0;
+    m.kr = keys[xx * R + (sub < R ? sub : R - 1)];
+    m.ki = inbox[xx * INBOX_CAP + (G - 1 - sub)];
     return m;
 }
 
@@ -527,14 +526,15 @@ __device__ __forceinline__ void merge_group_body(int R, u64 *keys, int *deg, con
     const u32 gid = (blockIdx.x * BLOCK + threadIdx.x) / G, ngrp = (gridDim.x * BLOCK) / G;
     const u32 n = *n_ptr;
     if (gid >= n) return;
-    auto vertex_at = [&](unsigned long long i) -> int { return i < n ? tlist[i] : -1; };
+    // list indices fit 32 bits with room to spare: n <= 2^31 and three strides of the grid are far below 2^31
+    auto vertex_at = [&](u32 i) -> int { const int v = tlist[i < n ? i : n - 1u]; return i < n ? v : -1; };
     MergeItem cur = merge_item_load<G>(vertex_at(gid), R, keys, deg, cnt, inbox, sub);
-    int x_next = vertex_at((unsigned long long)gid + ngrp);
-    int x_after = vertex_at((unsigned long long)gid + 2ull * ngrp);
-    for (unsigned long long it = gid; it < n; it += ngrp) {
+    int x_next = vertex_at(gid + ngrp);
+    int x_after = vertex_at(gid + 2u * ngrp);
+    for (u32 it = gid; it < n; it += ngrp) {
         const MergeItem nxt = merge_item_load<G>(x_next, R, keys, deg, cnt, inbox, sub);
         x_next = x_after;
-        x_after = vertex_at(it + 3ull * ngrp);
+        x_after = vertex_at(it + 3u * ngrp);
 
         const int x = cur.x, nb = cur.nb, c = cur.c;
         u64 *row = keys + (size_t)x * R;
@@ -574,16 +574,14 @@ __device__ __forceinline__ WideItem wide_item_load(int x, int R, const u64 *keys
                                                    const u64 *inbox, int lane)
 {
     WideItem m;
+    const size_t xx = (size_t)(x >= 0 ? x : 0);      // as in merge_item_load
+    const int nb = deg[xx], c = cnt[xx];
     m.x = x;
-    m.nb = m.c = 0;
-    m.r0 = m.r1 = m.in = KEY_PAD;
-    if (x >= 0) {
-        m.nb = deg[x];
-        m.c = cnt[x];
-        if (lane < R) m.r0 = keys[(size_t)x * R + lane];
-        if (lane + 64 < R) m.r1 = keys[(size_t)x * R + lane + 64];
-        m.in = inbox[(size_t)x * INBOX_CAP + (INBOX_CAP - 1 - lane)];
-    }
+    m.nb = x >= 0 ? nb : 0;
+    m.c = x >= 0 ? c : 0;
+    m.r0 = keys[xx * R + (lane < R ? lane : R - 1)];
+    m.r1 = keys[xx * R + (lane + 64 < R ? lane + 64 : R - 1)];
+    m.in = inbox[xx * INBOX_CAP + (INBOX_CAP - 1 - lane)];
     return m;
 }
 
@@ -598,14 +596,14 @@ __device__ __forceinline__ void merge_general_body(int R, u64 *keys, int *deg, c
     const u32 gw = blockIdx.x * WAVES_PER_BLOCK + wave, nw = gridDim.x * WAVES_PER_BLOCK;
     const u32 n = *n_ptr;
     if (gw >= n) return;
-    auto vertex_at = [&](unsigned long long i) -> int { return i < n ? tlist[i] : -1; };
+    auto vertex_at = [&](u32 i) -> int { const int v = tlist[i < n ? i : n - 1u]; return i < n ? v : -1; };
     WideItem cur = wide_item_load(vertex_at(gw), R, keys, deg, cnt, inbox, lane);
-    int x_next = vertex_at((unsigned long long)gw + nw);
-    int x_after = vertex_at((unsigned long long)gw + 2ull * nw);
-    for (unsigned long long it = gw; it < n; it += nw) {
+    int x_next = vertex_at(gw + nw);
+    int x_after = vertex_at(gw + 2u * nw);
+    for (u32 it = gw; it < n; it += nw) {
         const WideItem nxt = wide_item_load(x_next, R, keys, deg, cnt, inbox, lane);
         x_next = x_after;
-        x_after = vertex_at(it + 3ull * nw);
+        x_after = vertex_at(it + 3u * nw);
 
         const int x = __builtin_amdgcn_readfirstlane(cur.x);
         const int nb = __builtin_amdgcn_readfirstlane(cur.nb), c = __builtin_amdgcn_readfirstlane(cur.c);
