@@ -34,6 +34,23 @@ __device__ __forceinline__ u64 splitmix_finish(u64 z)
     return z;
 }
 
+// Does `id` equal the value some rotation R in [FIRST, END) of `src` within rows of 16 lanes brings to this lane,
+// counting only rotations R <= limit (rotation R brings lane (l - R) mod 16: with limit = l the earlier lanes of the row)?
+template <int R, int END>
+__device__ __forceinline__ bool rotations_match(int id, int src, int limit)
+{
+    if constexpr (R >= END) {
+        return false;
+    } else {
+        int o = src;
+        if constexpr (R > 0) o = __builtin_amdgcn_update_dpp(0, src, 0x120 + R, 0xF, 0xF, true);      // row_ror:R
+        // no short-circuit: every lane must take part in every rotation
+        const bool here = (o == id) & (R <= limit);
+        const bool rest = rotations_match<R + 1, END>(id, src, limit);
+        return here | rest;
+    }
+}
+
 __device__ __forceinline__ void wave_random_ids(u64 seed, long long n, long long u, int S, int *ids, int lane)
 {
     const u64 G = 0x9E3779B97F4A7C15ull;
@@ -49,9 +66,20 @@ __device__ __forceinline__ void wave_random_ids(u64 seed, long long n, long long
         const int id = (int)(c + (c >= (u64)u ? 1 : 0));
         bool ok = lane < W && j < jmax;
         for (int k = 0; k < cnt; ++k) ok = ok && (ids[k] != id);
-        for (int l = 0; l < W - 1; ++l) {       // l is the same for the whole wavefront: a scalar read of lane l
-            const int o = __builtin_amdgcn_readlane(id, l);
-            if (l < lane && o == id) ok = false;
+        if (W <= 32) {
+            // the draws under examination sit in lanes 0 .. 31: every lane meets the other 15 of its row of 16 through
+            // row rotations (rotation r brings the id of lane (l - r) mod 16, an earlier lane iff r <= l), and the
+            // second row meets the whole first one through its copy swapped across rows
+            const int l16 = lane & 15;
+            const int x = __builtin_amdgcn_ds_swizzle(id, 0x401F);                              // lane xor 16
+            const bool in_row = rotations_match<1, 16>(id, id, l16), in_other = rotations_match<0, 16>(id, x, 16);
+            const bool dupe = in_row | (((lane & 16) != 0) & in_other);
+            ok = ok && !dupe;
+        } else {
+            for (int l = 0; l < W - 1; ++l) {   // l is the same for the whole wavefront: a scalar read of lane l
+                const int o = __builtin_amdgcn_readlane(id, l);
+                if (l < lane && o == id) ok = false;
+            }
         }
         const u64 m = __builtin_amdgcn_ballot_w64(ok);
         const int pos = cnt + __popcll(m & lanes_below(lane));
