@@ -118,31 +118,26 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
                                                         int S, int R, u64 seed, u64 *keys, int *deg,
                                                         int8_t *vcls, int use_classes)
 {
-    __shared__ int s_ids[WAVES_PER_BLOCK][RNND_MAX_R];
-    __shared__ u32 s_dist[WAVES_PER_BLOCK][RNND_MAX_R];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, sub = lane & 7, grp = lane >> 3;
+    static_assert(SEARCH_MAX_L >= RNND_MAX_R, "the id / distance tables of the search hold a whole list");
+    __shared__ SearchSmem s_tab[WAVES_PER_BLOCK];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long u = (long long)blockIdx.x * WAVES_PER_BLOCK + wave;
     if (u >= N) return;
-    int *ids = s_ids[wave];
+    int *ids = s_tab[wave].id;
     const size_t rowbytes = (size_t)d * dt_size(DT);
     wave_random_ids(seed, N, u, S, ids, lane);
-    // delta(u, id): 8 rows at a time, 8 lanes per row
-    const char *xu = (const char *)X + (size_t)u * rowbytes;
-    for (int b = 0; b < S; b += 8) {
-        int p = b + grp;
-        int id = ids[p < S ? p : S - 1];
-        u32 db = group8_dist_bits<DT>(xu, (const char *)X + (size_t)id * rowbytes, d, vec_ok, sub);
-        if (p < S && sub == 0) s_dist[wave][p] = db;
-    }
+    wave_sync();
+    // delta(u, id), 8 lanes per row; short uint8 rows: the loads of up to 32 rows in flight together
+    search_eval<DT>(X, (const char *)X + (size_t)u * rowbytes, d, vec_ok, rowbytes, s_tab[wave], S, lane);
     wave_sync();
     u64 *row = keys + (size_t)u * R;
     if (S <= 32) {     // the upper half of the wavefront sorts padding
-        u64 k = lane < S ? make_key(s_dist[wave][lane], (u32)ids[lane], 1u) : KEY_PAD;
+        u64 k = lane < S ? make_key(s_tab[wave].dist[lane], (u32)ids[lane], 1u) : KEY_PAD;
         k = group_sort<32>(k, lane);
         if (lane < S) row[lane] = k;
     } else if (S <= 64) {
         u64 k[1];
-        k[0] = lane < S ? make_key(s_dist[wave][lane], (u32)ids[lane], 1u) : KEY_PAD;
+        k[0] = lane < S ? make_key(s_tab[wave].dist[lane], (u32)ids[lane], 1u) : KEY_PAD;
         wave_sort<1>(k, lane);
         if (lane < S) row[lane] = k[0];
     } else {
@@ -150,7 +145,7 @@ __global__ __launch_bounds__(BLOCK) void k_random_graph(const void *X, long long
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             int e = r * 64 + lane;
-            k[r] = e < S ? make_key(s_dist[wave][e], (u32)ids[e], 1u) : KEY_PAD;
+            k[r] = e < S ? make_key(s_tab[wave].dist[e], (u32)ids[e], 1u) : KEY_PAD;
         }
         wave_sort<2>(k, lane);
         if (lane < S) row[lane] = k[0];

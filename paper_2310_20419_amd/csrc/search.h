@@ -137,9 +137,7 @@ __device__ __forceinline__ void search_eval(const void *X, const void *qv, int d
                 acc = sqdiff_word_u8(q4.y, x4[j].y, acc);
                 acc = sqdiff_word_u8(q4.z, x4[j].z, acc);
                 acc = sqdiff_word_u8(q4.w, x4[j].w, acc);
-                acc += __shfl_xor(acc, 1);
-                acc += __shfl_xor(acc, 2);
-                acc += __shfl_xor(acc, 4);
+                acc = group8_sum(acc);
                 if (p < cnt && sub == 0) sm.dist[p] = (u32)acc;
             }
         }
