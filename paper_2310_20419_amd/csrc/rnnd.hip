@@ -1056,15 +1056,14 @@ struct RevItem {       // what a half-wave holds of its vertex before it is that
 __device__ __forceinline__ RevItem rev_item_load(long long x, long long N, int W, const u64 *keys, const int *deg,
                                                  const int *fill, const u64 *inbox, int l32)
 {
+    // past the last vertex, vertex 0 is read instead and given nothing: loads without branches
     RevItem it;
-    it.c = it.nb = 0;
-    it.kr = it.ki = KEY_PAD;
-    if (x < N) {
-        it.c = fill[x];
-        it.nb = deg[x];
-        if (l32 < W) it.kr = keys[(size_t)x * W + l32];
-        it.ki = inbox[(size_t)x * INBOX_CAP + (31 - l32)];
-    }
+    const size_t xx = x < N ? (size_t)x : 0;
+    const int c = fill[xx], nb = deg[xx];
+    it.c = x < N ? c : 0;
+    it.nb = x < N ? nb : 0;
+    it.kr = keys[xx * W + (l32 < W ? l32 : W - 1)];
+    it.ki = inbox[xx * INBOX_CAP + (31 - l32)];
     return it;
 }
 
