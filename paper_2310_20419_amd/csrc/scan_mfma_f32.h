@@ -331,16 +331,14 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
 #pragma unroll
             for (int h = 0; h < (NRC > 4 ? 2 : 1); ++h) {
                 const int p = 64 * h + lane;
-                if (p < m) {
-                    const bool isnew = kreg[h] & 1ull;
-                    const int s = isnew ? popc_below_w<(NRC <= 4)>(new0, new1, p) : n_new + popc_below_w<(NRC <= 4)>(old0, old1, p);
-                    sm.key[s] = kreg[h];
+                if (p < 16 * NRC) {
+                    // a position past the list fills the slot of its own number: vertex 0, never tested
+                    const bool in = p < m, isnew = kreg[h] & 1ull;
+                    const int sn = popc_below_w<(NRC <= 4)>(new0, new1, p), so = n_new + popc_below_w<(NRC <= 4)>(old0, old1, p);
+                    const int s = in ? (isnew ? sn : so) : p;
+                    sm.key[s] = in ? kreg[h] : 0ull;
                     sm.pos[s] = p;
-                    sm.distf[s] = __uint_as_float(key_dist(kreg[h]));
-                } else if (p < 16 * NRC) {
-                    sm.key[p] = 0;      // slots past the list: vertex 0, never tested
-                    sm.pos[p] = p;
-                    sm.distf[p] = 0.f;
+                    sm.distf[s] = in ? __uint_as_float(key_dist(kreg[h])) : 0.f;
                 }
             }
             rows += m;
