@@ -408,10 +408,9 @@ __global__ __launch_bounds__(64 * 4, (FAST ? (NRC <= 2 ? 4 : NRC <= 4 ? 3 : 2) :
                     nr[g] += __shfl_xor(nr[g], 16);
                     nr[g] += __shfl_xor(nr[g], 32);     // n of slot 16 g + r16, in all four quarter-waves
                 }
-                if (q == 0) {
-                    if (FAST) sm.nrmf[16 * g + r16] = (float)nr[g];
-                    else sm.nrm[16 * g + r16] = (double)nr[g];
-                }
+                // all four quarter-waves hold the same sum and store it (no branch)
+                if (FAST) sm.nrmf[16 * g + r16] = (float)nr[g];
+                else sm.nrm[16 * g + r16] = (double)nr[g];
             }
             wave_sync();
 
