@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # WRITE_SIZE (two runs, each scaled by what the same counter reads for a plain 1 GiB copy in the same run);
 # see profiles/update_scan_cfg{3,4,5}_hbm_traffic.txt.  Keyed by (workload, kernel variant); None where it
 # has not been measured.
-TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.0228e9, ("cfg4", 3): 8.578e9, ("cfg5", 3): 8.3522e10}
+TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.0228e9, ("cfg4", 3): 8.544e9, ("cfg5", 3): 8.3522e10}
 
 
 def host_cpu():
