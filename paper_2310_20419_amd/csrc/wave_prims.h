@@ -43,11 +43,12 @@ __device__ __forceinline__ u64 shfl_u64(u64 v, int src)
     hi = __shfl(hi, src);
     return ((u64)hi << 32) | lo;
 }
+// value of lane l - 1 (lane 0: its own): a wavefront-wide DPP shift, no LDS round trip
 __device__ __forceinline__ u64 shfl_up1_u64(u64 v)
 {
     u32 lo = (u32)v, hi = (u32)(v >> 32);
-    lo = __shfl_up(lo, 1);
-    hi = __shfl_up(hi, 1);
+    lo = (u32)__builtin_amdgcn_update_dpp((int)lo, (int)lo, 0x138, 0xF, 0xF, false);     // wave_shr:1
+    hi = (u32)__builtin_amdgcn_update_dpp((int)hi, (int)hi, 0x138, 0xF, 0xF, false);
     return ((u64)hi << 32) | lo;
 }
 
