@@ -302,6 +302,19 @@ __global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cn
     }
 }
 
+// Bit j set iff lane j of this lane's row of 16 holds the same value, for the lanes reached by rotations R .. 15.
+template <int R>
+__device__ __forceinline__ u32 same_target_mask(u32 tgt, int sub)
+{
+    if constexpr (R >= 16) {
+        return 0u;
+    } else {
+        const u32 t = (u32)__builtin_amdgcn_update_dpp(0, (int)tgt, 0x120 + R, 0xF, 0xF, true);     // row_ror:R
+        const u32 here = (t == tgt ? 1u : 0u) << ((sub - R) & 15);
+        return here | same_target_mask<R + 1>(tgt, sub);
+    }
+}
+
 #define SURPLUS_MARK 0x40000000   // set in nprop[u]: some edge redirected by u arrived past its target's inbox
 
 // Every active vertex moves its redirected edges to their targets, 16 lanes per vertex.  Lanes of a
@@ -347,12 +360,8 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int
             if (p0 > 0 && have) pr = props[(size_t)u * R + p];
             if (!have) pr.tgt = 0xFFFFFFFFu;
             // lanes of my group with my target
-            u32 same = 0;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const u32 t = (u32)__shfl((int)pr.tgt, gbase + j);
-                same |= (t == pr.tgt ? 1u : 0u) << j;
-            }
+            // rotation r of the group's row brings the target of lane (sub - r) mod 16
+            const u32 same = (1u << sub) | same_target_mask<1>(pr.tgt, sub);
             const int leader = __builtin_ctz(same), rank = __popc(same & ((1u << sub) - 1u));
             int base = 0;
             if (have && sub == leader) base = atomicAdd(&fill[pr.tgt], __popc(same));
