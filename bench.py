@@ -311,6 +311,9 @@ def main():
     ap.add_argument("--blocks", type=int, default=0,
                     help="block-sequential passes with this many runs of consecutive ids per pass "
                          "(rnnd_build_blocks; 0 = the synchronous build the metric is quoted on)")
+    ap.add_argument("--gather-maps", action="store_true",
+                    help="instead of a build: the rate of random whole-row gathers from a matrix of the workload's shape "
+                         "(random bytes; --n overrides the rows) for 1, 2, 4 and 8 lanes per row, one JSON line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -330,6 +333,18 @@ def main():
     if args.n:
         import dataclasses
         cfg = dataclasses.replace(cfg, N=args.n, name="%s_n%d" % (cfg.name, args.n))
+    if args.gather_maps:
+        # which lane -> address map gathers rows fastest (the operand layout of a matrix instruction fixes it)
+        row_bytes = cfg.d * (1 if cfg.dtype == "u8" else 4)
+        M = torch.empty((cfg.N, row_bytes), dtype=torch.uint8, device="cuda").random_()
+        n_gather = max(1, int(8e9 // row_bytes))
+        rates = {}
+        for lanes in (1, 2, 4, 8):
+            if (row_bytes // 16) % lanes == 0 and (row_bytes // 16) // lanes in (1, 2, 4, 8):
+                rates[str(lanes)] = max(rn.rnnd_probe_gather_map(M, n_gather, lanes, seed=s) for s in (1, 2, 3))
+        print(json.dumps({"mode": "gather-maps", "rows": cfg.N, "row_bytes": row_bytes, "matrix_GB": cfg.N * row_bytes / 1e9,
+                          "rows_gathered": n_gather, "GBps_by_lanes_per_row": rates}))
+        return
     t0 = time.perf_counter()
     X, Xd, esz, st16 = load_workload(cfg, args.storage)
     gen_s = time.perf_counter() - t0

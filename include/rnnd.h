@@ -240,6 +240,17 @@ int rnnd_search(const void *X, int64_t N, int32_t d, int dtype, int metric, cons
 int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t n_gather, uint64_t seed,
                       double *gbytes_per_s, void *stream);
 
+/* A second probe with the lane -> address map as its only variable: lanes_per_row = 1, 2, 4 or 8 lanes read
+ * one row together, each its share of the row's 16-byte pieces (lanes_per_row pieces apart), so that one load
+ * instruction of a wavefront touches 64 / lanes_per_row rows with 16 x lanes_per_row contiguous bytes of each
+ * (2 is the operand layout of the 32x32x32 int8 matrix instruction that the uint8 scan gathers into, 4 that
+ * of the 16x16x64 one, 8 whole 128-byte lines).  Every lane keeps 8 loads of 16 bytes in flight whatever the
+ * map.  row_bytes / 16 / lanes_per_row must be 1, 2, 4 or 8 (else RNND_ERR_BAD_PARAM).  Everything else as for
+ * rnnd_probe_gather.  For deciding whether a different operand layout could gather faster, without writing
+ * the kernel first. */
+int rnnd_probe_gather_map(const void *X, int64_t n_rows, int64_t row_bytes, int64_t n_gather, int lanes_per_row,
+                          uint64_t seed, double *gbytes_per_s, void *stream);
+
 /* Selects the UpdateNeighbors scan kernel: 0 = automatic (default), 1 = generic pair-at-a-time
  * kernel for every input, 2 = automatic, but the float matrix-core scan works in double precision
  * throughout.  Automatic uses the dense Gram-block kernels on the matrix cores where they apply

@@ -105,6 +105,7 @@ def load_library():
         L.rnnd_search.argtypes = [vp, i64, i32, c.c_int, c.c_int, vp, vp, i32, vp, i64, i32, i32, i32, c.c_uint64,
                                   vp, vp, c.POINTER(c.c_int64), vp]
         L.rnnd_probe_gather.argtypes = [vp, i64, i64, i64, u64, c.POINTER(c.c_double), vp]
+        L.rnnd_probe_gather_map.argtypes = [vp, i64, i64, i64, c.c_int, u64, c.POINTER(c.c_double), vp]
         L.rnnd_set_kernel_variant.argtypes = [c.c_int]
         L.rnnd_set_transpose_path.argtypes = [c.c_int]
         L.rnnd_set_event_timing.argtypes = [c.c_int]
@@ -116,7 +117,7 @@ def load_library():
                      "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks",
                      "rnnd_probe_gather", "rnnd_build_wide", "rnnd_build_static", "rnnd_release_workspace",
                      "rnnd_set_workspace_poison", "rnnd_add_reverse_edges_wide", "rnnd_set_transpose_path",
-                     "rnnd_set_event_timing"):
+                     "rnnd_set_event_timing", "rnnd_probe_gather_map"):
             getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -291,6 +292,15 @@ def rnnd_probe_gather(X, n_gather: int, seed: int = 1, stream=None) -> float:
     out = ctypes.c_double(0.0)
     _check(load_library().rnnd_probe_gather(X.data_ptr(), X.shape[0], X.shape[1] * X.element_size(), n_gather, seed,
                                             ctypes.byref(out), _stream(stream)))
+    return out.value
+
+
+def rnnd_probe_gather_map(X, n_gather: int, lanes_per_row: int, seed: int = 1, stream=None) -> float:
+    """GB/s of random whole-row gathers from X with lanes_per_row lanes reading a row together."""
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2
+    out = ctypes.c_double(0.0)
+    _check(load_library().rnnd_probe_gather_map(X.data_ptr(), X.shape[0], X.shape[1] * X.element_size(), n_gather,
+                                                lanes_per_row, seed, ctypes.byref(out), _stream(stream)))
     return out.value
 
 

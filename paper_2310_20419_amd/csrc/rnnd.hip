@@ -1319,6 +1319,34 @@ __global__ __launch_bounds__(256) void k_probe_gather(const uint4 *X, u32 n_rows
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc;
 }
 
+// The same with the lane -> address map as the only variable: LPR lanes per row, each reading its PPL pieces
+// of the row (16 bytes, LPR pieces apart), 8 / PPL rows per lane: 8 loads of 16 bytes per lane in flight
+// whatever the map, all issued before the first is used.
+template <int LPR, int PPL>
+__global__ __launch_bounds__(256) void k_probe_gather_map(const uint4 *X, u32 n_rows, u64 trips, u64 seed, u32 *sink)
+{
+    constexpr int RPI = 64 / LPR, ROWS = 8 / PPL;
+    const int lane = threadIdx.x & 63, r = lane / LPR, q = lane % LPR;
+    const u64 gw = ((u64)blockIdx.x * 256 + threadIdx.x) >> 6, nw = ((u64)gridDim.x * 256) >> 6;
+    u32 acc = 0;
+    for (u64 t = gw; t < trips; t += nw) {
+        uint4 v[ROWS][PPL];
+#pragma unroll
+        for (int k = 0; k < ROWS; ++k) {
+            const u64 z = splitmix_finish(seed + 0x9E3779B97F4A7C15ull * (t * (ROWS * RPI) + (u64)(k * RPI + r) + 1));
+            const u32 row = (u32)(((z >> 32) * (u64)n_rows) >> 32);
+            const uint4 *p = X + (size_t)row * (LPR * PPL) + q;
+#pragma unroll
+            for (int j = 0; j < PPL; ++j) v[k][j] = p[j * LPR];
+        }
+#pragma unroll
+        for (int k = 0; k < ROWS; ++k)
+#pragma unroll
+            for (int j = 0; j < PPL; ++j) acc ^= v[k][j].x + v[k][j].y + v[k][j].z + v[k][j].w;
+    }
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc;
+}
+
 // ===================================================================== host side
 #define HIPCHK(x)                                                                  \
     do {                                                                           \
@@ -2358,8 +2386,21 @@ static void launch_probe_gather(const void *X, u32 n_rows, u32 pieces, u64 trips
                        seed, sink);
 }
 
-extern "C" int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t n_gather, uint64_t seed,
-                                 double *gbytes_per_s, void *stream)
+template <int LPR>
+static void launch_probe_gather_map(int ppl, const void *X, u32 n_rows, u64 trips, u64 seed, u32 *sink, int blocks,
+                                    hipStream_t st)
+{
+    const uint4 *x = (const uint4 *)X;
+    if (ppl == 1) hipLaunchKernelGGL((k_probe_gather_map<LPR, 1>), dim3(blocks), dim3(256), 0, st, x, n_rows, trips, seed, sink);
+    else if (ppl == 2) hipLaunchKernelGGL((k_probe_gather_map<LPR, 2>), dim3(blocks), dim3(256), 0, st, x, n_rows, trips, seed, sink);
+    else if (ppl == 4) hipLaunchKernelGGL((k_probe_gather_map<LPR, 4>), dim3(blocks), dim3(256), 0, st, x, n_rows, trips, seed, sink);
+    else hipLaunchKernelGGL((k_probe_gather_map<LPR, 8>), dim3(blocks), dim3(256), 0, st, x, n_rows, trips, seed, sink);
+}
+
+// lanes_per_row 0: the probe of the benchmark line (the largest power of two that divides the number of 16-byte
+// pieces, at most 8 lanes per row; four rows per lane in flight, any row length); otherwise the map probe
+static int probe_gather_impl(const void *X, int64_t n_rows, int64_t row_bytes, int64_t n_gather, int lanes_per_row,
+                             uint64_t seed, double *gbytes_per_s, void *stream)
 {
     int rc = RNND_OK;
     if (!X || !gbytes_per_s) return RNND_ERR_NULL;
@@ -2368,9 +2409,15 @@ extern "C" int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_byte
         return RNND_ERR_BAD_PARAM;
     hipStream_t st = (hipStream_t)stream;
     const u32 pieces = (u32)(row_bytes / 16);
-    // lanes per row: the largest power of two that divides the number of 16-byte pieces, at most 8
-    const int lpr = pieces % 8 == 0 ? 8 : pieces % 4 == 0 ? 4 : pieces % 2 == 0 ? 2 : 1;
-    const int rows_per_trip = 4 * (64 / lpr);
+    int ppl = 0;        // pieces per lane of the map probe
+    if (lanes_per_row != 0) {
+        if (lanes_per_row != 1 && lanes_per_row != 2 && lanes_per_row != 4 && lanes_per_row != 8) return RNND_ERR_BAD_PARAM;
+        if (pieces % (u32)lanes_per_row != 0) return RNND_ERR_BAD_PARAM;
+        ppl = (int)(pieces / (u32)lanes_per_row);
+        if (ppl != 1 && ppl != 2 && ppl != 4 && ppl != 8) return RNND_ERR_BAD_PARAM;
+    }
+    const int lpr = lanes_per_row ? lanes_per_row : pieces % 8 == 0 ? 8 : pieces % 4 == 0 ? 4 : pieces % 2 == 0 ? 2 : 1;
+    const int rows_per_trip = ppl ? (8 / ppl) * (64 / lpr) : 4 * (64 / lpr);
     const u64 trips = ((u64)n_gather + rows_per_trip - 1) / rows_per_trip;
     const int blocks = persistent_blocks();
     u32 *sink = nullptr;
@@ -2381,7 +2428,12 @@ extern "C" int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_byte
     HIPCHK(hipEventCreate(&e1));
     for (int rep = 0; rep < 2; ++rep) {     // the second pass is the one that is timed
         HIPCHK(hipEventRecord(e0, st));
-        if (lpr == 8) launch_probe_gather<8>(X, (u32)n_rows, pieces, trips, seed + rep, sink, blocks, st);
+        if (ppl) {
+            if (lpr == 8) launch_probe_gather_map<8>(ppl, X, (u32)n_rows, trips, seed + rep, sink, blocks, st);
+            else if (lpr == 4) launch_probe_gather_map<4>(ppl, X, (u32)n_rows, trips, seed + rep, sink, blocks, st);
+            else if (lpr == 2) launch_probe_gather_map<2>(ppl, X, (u32)n_rows, trips, seed + rep, sink, blocks, st);
+            else launch_probe_gather_map<1>(ppl, X, (u32)n_rows, trips, seed + rep, sink, blocks, st);
+        } else if (lpr == 8) launch_probe_gather<8>(X, (u32)n_rows, pieces, trips, seed + rep, sink, blocks, st);
         else if (lpr == 4) launch_probe_gather<4>(X, (u32)n_rows, pieces, trips, seed + rep, sink, blocks, st);
         else if (lpr == 2) launch_probe_gather<2>(X, (u32)n_rows, pieces, trips, seed + rep, sink, blocks, st);
         else launch_probe_gather<1>(X, (u32)n_rows, pieces, trips, seed + rep, sink, blocks, st);
@@ -2396,6 +2448,19 @@ done:
     if (e1) (void)hipEventDestroy(e1);
     if (sink) (void)hipFree(sink);
     return rc;
+}
+
+extern "C" int rnnd_probe_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t n_gather, uint64_t seed,
+                                 double *gbytes_per_s, void *stream)
+{
+    return probe_gather_impl(X, n_rows, row_bytes, n_gather, 0, seed, gbytes_per_s, stream);
+}
+
+extern "C" int rnnd_probe_gather_map(const void *X, int64_t n_rows, int64_t row_bytes, int64_t n_gather,
+                                     int lanes_per_row, uint64_t seed, double *gbytes_per_s, void *stream)
+{
+    if (lanes_per_row == 0) return RNND_ERR_BAD_PARAM;
+    return probe_gather_impl(X, n_rows, row_bytes, n_gather, lanes_per_row, seed, gbytes_per_s, stream);
 }
 
 // 0: automatic; 1: generic scan for every input; 2: automatic, but the float matrix-core scan runs in

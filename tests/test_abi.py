@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported(lib):
             "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search", "rnnd_workspace_bytes",
             "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant", "rnnd_build_blocks",
             "rnnd_update_neighbors_blocks", "rnnd_probe_gather", "rnnd_build_wide", "rnnd_release_workspace",
-            "rnnd_set_workspace_poison", "rnnd_set_event_timing"} <= set(names)
+            "rnnd_set_workspace_poison", "rnnd_set_event_timing", "rnnd_probe_gather_map"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -79,6 +79,13 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert lib.rnnd_probe_gather(c.c_void_p(16), 0, 128, 100, 1, c.byref(out), None) == -2
     assert lib.rnnd_probe_gather(c.c_void_p(16), 10, 100, 100, 1, c.byref(out), None) == -3      # not a multiple of 16
     assert lib.rnnd_probe_gather(c.c_void_p(8), 10, 128, 100, 1, c.byref(out), None) == -3       # misaligned
+    lib.rnnd_probe_gather_map.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_uint64,
+                                          c.POINTER(c.c_double), c.c_void_p]
+    assert lib.rnnd_probe_gather_map(None, 10, 128, 100, 2, 1, c.byref(out), None) == -1
+    assert lib.rnnd_probe_gather_map(c.c_void_p(16), 10, 128, 100, 3, 1, c.byref(out), None) == -3   # 1, 2, 4 or 8 lanes
+    assert lib.rnnd_probe_gather_map(c.c_void_p(16), 10, 128, 100, 0, 1, c.byref(out), None) == -3
+    assert lib.rnnd_probe_gather_map(c.c_void_p(16), 10, 96, 100, 4, 1, c.byref(out), None) == -3    # 6 pieces, 4 lanes
+    assert lib.rnnd_probe_gather_map(c.c_void_p(16), 10, 96, 100, 2, 1, c.byref(out), None) == -3    # 3 pieces per lane
     # rnnd_search: parameters are checked before pointers, pointers before any GPU call
     def search(**kw):
         a = dict(dict(X=one, N=100, d=16, dtype=0, metric=0, g=one, dg=one, W=8, Q=one, nq=3, L=16, K=8, k=5,

@@ -517,6 +517,20 @@ def test_gather_probe_reports_a_plausible_rate(rn):
         assert 1.0 < rate < 100_000.0, (rows, width, rate)
 
 
+def test_gather_probe_with_a_chosen_lane_map(rn):
+    """Every lanes-per-row setting that leaves 1, 2, 4 or 8 pieces per lane runs and reports a plausible rate; one
+    that does not is refused."""
+    import torch
+    X = torch.zeros((100_000, 128), dtype=torch.uint8, device="cuda")
+    for lanes in (1, 2, 4, 8):
+        rate = rn.rnnd_probe_gather_map(X, 1_000_000, lanes)
+        assert 1.0 < rate < 100_000.0, (lanes, rate)
+    Y = torch.zeros((10_000, 64), dtype=torch.uint8, device="cuda")     # 4 pieces
+    assert 1.0 < rn.rnnd_probe_gather_map(Y, 100_000, 2) < 100_000.0
+    with pytest.raises(rn.RnndError):
+        rn.rnnd_probe_gather_map(Y, 100_000, 8)
+
+
 def test_build_on_a_side_stream_and_repeated_calls(rn):
     """All work goes to the stream handed in (default priority) and the call returns after it has completed;
     the result does not depend on the stream, and repeated calls leave nothing behind that changes it."""
