@@ -108,6 +108,7 @@ def load_library():
         L.rnnd_probe_gather_map.argtypes = [vp, i64, i64, i64, c.c_int, u64, c.POINTER(c.c_double), vp]
         L.rnnd_set_kernel_variant.argtypes = [c.c_int]
         L.rnnd_set_transpose_path.argtypes = [c.c_int]
+        L.rnnd_set_scan_launches.argtypes = [c.c_int]
         L.rnnd_set_event_timing.argtypes = [c.c_int]
         L.rnnd_strerror.argtypes = [c.c_int]
         L.rnnd_strerror.restype = c.c_char_p
@@ -117,7 +118,7 @@ def load_library():
                      "rnnd_set_kernel_variant", "rnnd_build_blocks", "rnnd_update_neighbors_blocks",
                      "rnnd_probe_gather", "rnnd_build_wide", "rnnd_build_static", "rnnd_release_workspace",
                      "rnnd_set_workspace_poison", "rnnd_add_reverse_edges_wide", "rnnd_set_transpose_path",
-                     "rnnd_set_event_timing", "rnnd_probe_gather_map"):
+                     "rnnd_set_event_timing", "rnnd_probe_gather_map", "rnnd_set_scan_launches"):
             getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -349,6 +350,10 @@ def rnnd_search(X, graph, degree, Q, L: int, K: int, k: int, seed: int, want_dis
 
 def rnnd_set_transpose_path(path: int):
     _check(load_library().rnnd_set_transpose_path(path))
+
+
+def rnnd_set_scan_launches(mode: int):
+    _check(load_library().rnnd_set_scan_launches(mode))
 
 
 def rnnd_set_kernel_variant(variant: int):

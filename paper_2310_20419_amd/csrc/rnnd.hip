@@ -1363,6 +1363,10 @@ static char g_last_hip_error[512];
 static int g_kernel_variant = 0;
 static int g_event_timing = 0;    // 1: per-round times of the statistics from HIP events attached to the launches
 static int g_transpose_path = 0;   // AddReverseEdges' transposition: 0 by size, 1 atomics, 2 binned
+static int g_scan_launches = 0;    // uint8 matrix-core scan: 0 by size, 1 one launch per group of classes, 2 one launch for all
+#define ALL_CLASSES_MAX_N 524288   // up to here one launch for all classes is the faster form (measured, whole build against
+                                   // launches per class: 0.75 x at 50,000 vertices, 0.78 x at 100,000, 0.90 x at 300,000, 0.955 x
+                                   // at 500,000; 1.02 x at 1M, where it wins only in rounds with fewer than 250,000 active lists)
 #define BIN_MIN_N 262144            // below this the binned transposition's extra launches cost more than its atomics save
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -1555,6 +1559,21 @@ static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *
 {
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_small<KS>, 4);
     const int n_big = (R > 32) + (R > 64) + (R > 96);   // launches after the short-list kernel
+    // small inputs: every class in one launch (see k_update_scan_mfma_u8_all)
+    if (n_big > 0 && g_scan_launches != 1 && (g_scan_launches == 2 || N <= ALL_CLASSES_MAX_N)) {
+        unsigned gx = capped((long long)cu_count() * 2, N);
+        if (gx < 8) gx = 8;      // a block at least for every class
+        if (n_big == 1)
+            hipExtLaunchKernelGGL((k_update_scan_mfma_u8_all<KS, 4>), dim3(gx), dim3(256), 0, st, re.scan_start, re.scan_stop, 0,
+                                  (const int8_t *)w.xs, R, keys, deg, w.lists, N, w.props, w.nprop, c);
+        else if (n_big == 2)
+            hipExtLaunchKernelGGL((k_update_scan_mfma_u8_all<KS, 5>), dim3(gx), dim3(256), 0, st, re.scan_start, re.scan_stop, 0,
+                                  (const int8_t *)w.xs, R, keys, deg, w.lists, N, w.props, w.nprop, c);
+        else
+            hipExtLaunchKernelGGL((k_update_scan_mfma_u8_all<KS, 6>), dim3(gx), dim3(256), 0, st, re.scan_start, re.scan_stop, 0,
+                                  (const int8_t *)w.xs, R, keys, deg, w.lists, N, w.props, w.nprop, c);
+        return;
+    }
     const int ny = 1 + (R > 8) + (R > 16);
     hipExtLaunchKernelGGL((k_update_scan_mfma_u8_small<KS>), dim3(capped(cu_count() * per_cu, N), ny), dim3(256), 0, st,
                           re.scan_start, n_big == 0 ? re.scan_stop : nullptr, 0, (const int8_t *)w.xs, R, keys, deg,
@@ -2469,6 +2488,13 @@ extern "C" int rnnd_set_kernel_variant(int variant)
 {
     if (variant < 0 || variant > 2) return RNND_ERR_BAD_PARAM;
     g_kernel_variant = variant;
+    return RNND_OK;
+}
+
+extern "C" int rnnd_set_scan_launches(int mode)
+{
+    if (mode < 0 || mode > 2) return RNND_ERR_BAD_PARAM;
+    g_scan_launches = mode;
     return RNND_OK;
 }
 

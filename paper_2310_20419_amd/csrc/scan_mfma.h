@@ -290,18 +290,16 @@ __device__ __forceinline__ void scan_vertex_u8(const ScanItem &cur, v4i (&A)[NG]
 // vertex i+1 are already in flight and the list of vertex i+2 is being fetched, so that the chain
 // list -> degree/list entries -> rows of X is paid once per wavefront, not once per vertex.  The loop
 // body is written out twice so that the two row buffers swap roles without being copied.
+// block `block` of `nblocks` walks the work list
 template <int NG, int KS>
-__global__ __launch_bounds__(256, (NG == 1 ? 5 : NG == 2 ? 3 : 2)) void k_update_scan_mfma_u8(
-    const int8_t *__restrict__ X, int R, u64 *__restrict__ keys,
-    int *__restrict__ deg, const int *__restrict__ list, const u32 *__restrict__ n_list,
-    Prop *__restrict__ props, int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
+__device__ __forceinline__ void scan_list_body(const int8_t *__restrict__ X, int R, u64 *__restrict__ keys,
+                                               int *__restrict__ deg, const int *__restrict__ list, u32 n_active,
+                                               Prop *__restrict__ props, int *__restrict__ nprop,
+                                               RoundCtr *__restrict__ ctr, MfmaScanSmem<NG> &sm, u32 block, u32 nblocks)
 {
-    __shared__ MfmaScanSmem<NG> smem[4];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the loop control stays on the scalar unit
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
-    const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
-    const u32 n_active = *n_list;
-    MfmaScanSmem<NG> &sm = smem[wave];
+    const u32 gw = block * 4 + wave, nw = nblocks * 4;
     u64 tiles = 0, rows = 0, nprops_total = 0;   // tiles: 32x32 blocks of pair distances computed
     u32 ev_lane = 0;   // per-lane share of the algorithmic evaluation count, summed at the end
 
@@ -351,6 +349,16 @@ __global__ __launch_bounds__(256, (NG == 1 ? 5 : NG == 2 ? 3 : 2)) void k_update
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) evals_algo += shfl_xor_u64(evals_algo, o);
     if (lane == 0 && rows) add_round_stats(ctr, evals_algo, tiles * 1024ull, rows, nprops_total);
+}
+
+template <int NG, int KS>
+__global__ __launch_bounds__(256, (NG == 1 ? 5 : NG == 2 ? 3 : 2)) void k_update_scan_mfma_u8(
+    const int8_t *__restrict__ X, int R, u64 *__restrict__ keys,
+    int *__restrict__ deg, const int *__restrict__ list, const u32 *__restrict__ n_list,
+    Prop *__restrict__ props, int *__restrict__ nprop, RoundCtr *__restrict__ ctr)
+{
+    __shared__ MfmaScanSmem<NG> smem[4];
+    scan_list_body<NG, KS>(X, R, keys, deg, list, *n_list, props, nprop, ctr, smem[threadIdx.x >> 6], blockIdx.x, gridDim.x);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -524,13 +532,13 @@ __device__ __forceinline__ void scan_packed_body(const int8_t *__restrict__ X, i
                                                  int *__restrict__ deg, const int *__restrict__ list,
                                                  u32 n_active, Prop *__restrict__ props,
                                                  int *__restrict__ nprop, RoundCtr *__restrict__ ctr,
-                                                 MfmaScanSmem<1> &sm)
+                                                 MfmaScanSmem<1> &sm, u32 block, u32 nblocks)
 {
     constexpr int W = 32 / P;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the loop control stays on the scalar unit
     const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
     const int seg = l32 / W, pos = l32 % W;
-    const u32 gw = blockIdx.x * 4 + wave, nw = gridDim.x * 4;
+    const u32 gw = block * 4 + wave, nw = nblocks * 4;
     const u32 n_groups = (n_active + (u32)P - 1u) / (u32)P;
     u32 tiles = 0, rows = 0, nprops_total = 0;   // per wavefront: far below 2^32
     u32 ev_lane = 0;
@@ -593,7 +601,72 @@ __global__ __launch_bounds__(256, 4) void k_update_scan_mfma_u8_small(
     const int *list = lists + (size_t)y * N;
     const u32 n = ctr->n_active[y];
     stamp_scan_start(ctr);
-    if (y == 0) scan_packed_body<4, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm);
-    else if (y == 1) scan_packed_body<2, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm);
-    else scan_packed_body<1, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm);
+    if (y == 0) scan_packed_body<4, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm, blockIdx.x, gridDim.x);
+    else if (y == 1) scan_packed_body<2, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm, blockIdx.x, gridDim.x);
+    else scan_packed_body<1, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm, blockIdx.x, gridDim.x);
+}
+
+// Every degree class in one launch, all of them resident together: the grid's blocks are divided among the
+// classes in proportion to their work (active lists x matrix tiles per list), one block at least for a class
+// that has any; every block derives the same division from the round's counters.  For inputs so small that
+// no class alone has enough lists to fill the chip: the classes then share the start-up and the tail that
+// each launch of its own pays.  NC classes: 3 short-list ones, then lists of at most 64, 96, 128 entries.
+// Every block carries the registers and the LDS of the longest class (two blocks per CU), which costs the
+// short-list classes occupancy: with many active lists the launches per class are faster.
+template <int KS, int NC>
+__global__ __launch_bounds__(256, 2) void k_update_scan_mfma_u8_all(
+    const int8_t *__restrict__ X, int R, u64 *__restrict__ keys, int *__restrict__ deg,
+    const int *__restrict__ lists, long long N, Prop *__restrict__ props, int *__restrict__ nprop,
+    RoundCtr *__restrict__ ctr)
+{
+    constexpr int NGMAX = NC - 2;
+    static_assert(NC >= 4 && NC <= 6, "short lists plus one to three long-list classes");
+    __shared__ MfmaScanSmem<NGMAX> smem[4];
+    stamp_scan_start(ctr);
+    // work per list, in quarter tiles: 4, 2, 1 lists per tile; NG (NG + 1) / 2 tiles for NG groups of 32 rows
+    constexpr u32 weight[6] = {1u, 2u, 4u, 12u, 24u, 40u};
+    u32 n[NC];
+    u64 total = 0;
+    u32 nonempty = 0;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        n[c] = ctr->n_active[c];
+        total += (u64)n[c] * weight[c];
+        nonempty += n[c] != 0u;
+    }
+    if (total == 0) return;
+    // A class gets one block plus its share of the rest: the shares are differences of one non-decreasing
+    // function of the running sum that ends at `spare` exactly (total / total = 1), so they add up to the grid
+    // whatever the rounding of the single-precision quotient; every block computes the same numbers.
+    const u32 spare = gridDim.x - nonempty;      // the grid has more blocks than there are classes (and < 2^24)
+    const float scale = (float)spare, ftotal = (float)total;
+    u32 first = 0, mine = 0, below = 0;
+    int cls = -1;
+    u64 cum = 0;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        cum += (u64)n[c] * weight[c];
+        const u32 upto = (u32)(scale * ((float)cum / ftotal));
+        const u32 nb = n[c] ? 1u + upto - below : 0u;
+        below = upto;
+        if (cls < 0 && blockIdx.x < first + nb) {
+            cls = c;
+            mine = nb;
+        }
+        if (cls < 0) first += nb;
+    }
+    if (cls < 0) return;      // cannot happen: the shares add up to the grid
+    const u32 block = blockIdx.x - first;
+    const int *list = lists + (size_t)cls * N;
+    const int wave = threadIdx.x >> 6;
+    MfmaScanSmem<1> &sm1 = *reinterpret_cast<MfmaScanSmem<1> *>(&smem[wave]);
+    if (cls == 0) scan_packed_body<4, KS>(X, R, keys, deg, list, n[0], props, nprop, ctr, sm1, block, mine);
+    else if (cls == 1) scan_packed_body<2, KS>(X, R, keys, deg, list, n[1], props, nprop, ctr, sm1, block, mine);
+    else if (cls == 2) scan_packed_body<1, KS>(X, R, keys, deg, list, n[2], props, nprop, ctr, sm1, block, mine);
+    else if (cls == 3)
+        scan_list_body<2, KS>(X, R, keys, deg, list, n[3], props, nprop, ctr, *reinterpret_cast<MfmaScanSmem<2> *>(&smem[wave]), block, mine);
+    else if (NC > 4 && cls == 4)
+        scan_list_body<3, KS>(X, R, keys, deg, list, n[NC > 4 ? 4 : 0], props, nprop, ctr, *reinterpret_cast<MfmaScanSmem<3> *>(&smem[wave]), block, mine);
+    else if (NC > 5 && cls == 5)
+        scan_list_body<4, KS>(X, R, keys, deg, list, n[NC > 5 ? 5 : 0], props, nprop, ctr, *reinterpret_cast<MfmaScanSmem<4> *>(&smem[wave]), block, mine);
 }

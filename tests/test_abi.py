@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported(lib):
             "rnnd_add_reverse_edges", "rnnd_export_graph", "rnnd_search", "rnnd_workspace_bytes",
             "rnnd_strerror", "rnnd_version", "rnnd_set_kernel_variant", "rnnd_build_blocks",
             "rnnd_update_neighbors_blocks", "rnnd_probe_gather", "rnnd_build_wide", "rnnd_release_workspace",
-            "rnnd_set_workspace_poison", "rnnd_set_event_timing", "rnnd_probe_gather_map"} <= set(names)
+            "rnnd_set_workspace_poison", "rnnd_set_event_timing", "rnnd_probe_gather_map", "rnnd_set_scan_launches"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -56,6 +56,7 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert lib.rnnd_add_reverse_edges(100, 8, None, one, None) == -1
     assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(3) == -3
     assert lib.rnnd_set_kernel_variant(0) == 0
+    assert lib.rnnd_set_scan_launches(3) == -3 and lib.rnnd_set_scan_launches(-1) == -3 and lib.rnnd_set_scan_launches(0) == 0
     # block-sequential entry points: same checks, plus the number of runs
     def blocks(**kw):
         a = dict(ok, **kw)
