@@ -271,12 +271,13 @@ int rnnd_set_kernel_variant(int variant);
  * Process-wide, not thread-safe. */
 int rnnd_set_transpose_path(int path);
 
-/* Selects how the uint8 matrix-core scan of a round is launched: 0 = by size (default: N <= 524,288 one launch
- * for all degree classes, else several), 1 = one launch for the three short-list classes and one per longer
- * class (each with the occupancy that suits it), 2 = one launch in which the blocks are divided among all
- * classes in proportion to their work (the classes share one start-up and one tail; pays when no class alone
- * fills the chip).  Both give identical graphs and counters; this exists for testing and profiling.  No effect
- * on other inputs or where R <= 32 (short lists only).  Process-wide, not thread-safe. */
+/* Selects how the uint8 matrix-core scan of a round is launched: 0 = by size (default: N <= 524,288 as 2, else
+ * as 3), 1 = one launch for the three short-list classes and one per longer class (each with the occupancy that
+ * suits it), 2 = one launch in which the blocks are divided among all classes in proportion to their work (the
+ * classes share one start-up and one tail; pays when no class alone fills the chip), 3 = the short-list launch
+ * and one launch shared by all longer classes.  All give identical graphs and counters; this exists for testing
+ * and profiling.  No effect on other inputs or where R <= 32 (short lists only); 3 is 1 where R <= 64 (one
+ * longer class).  Process-wide, not thread-safe. */
 int rnnd_set_scan_launches(int mode);
 
 const char *rnnd_strerror(int status);

@@ -1363,10 +1363,11 @@ static char g_last_hip_error[512];
 static int g_kernel_variant = 0;
 static int g_event_timing = 0;    // 1: per-round times of the statistics from HIP events attached to the launches
 static int g_transpose_path = 0;   // AddReverseEdges' transposition: 0 by size, 1 atomics, 2 binned
-static int g_scan_launches = 0;    // uint8 matrix-core scan: 0 by size, 1 one launch per group of classes, 2 one launch for all
-#define ALL_CLASSES_MAX_N 524288   // up to here one launch for all classes is the faster form (measured, whole build against
+static int g_scan_launches = 0;    // uint8 matrix-core scan: 0 by size, 1 short lists + one launch per longer class, 2 one launch for all, 3 short lists + one launch for all longer classes
+#define ALL_CLASSES_MAX_N 524288   // up to here one launch for all classes is the fastest form (measured, whole build against
                                    // launches per class: 0.75 x at 50,000 vertices, 0.78 x at 100,000, 0.90 x at 300,000, 0.955 x
-                                   // at 500,000; 1.02 x at 1M, where it wins only in rounds with fewer than 250,000 active lists)
+                                   // at 500,000; 1.02 x at 1M, where it wins only in rounds with fewer than 250,000 active lists).
+                                   // Above: the short-list launch and one launch for all longer classes (0.99 x at 1M)
 #define BIN_MIN_N 262144            // below this the binned transposition's extra launches cost more than its atomics save
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -1560,7 +1561,7 @@ static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_small<KS>, 4);
     const int n_big = (R > 32) + (R > 64) + (R > 96);   // launches after the short-list kernel
     // small inputs: every class in one launch (see k_update_scan_mfma_u8_all)
-    if (n_big > 0 && g_scan_launches != 1 && (g_scan_launches == 2 || N <= ALL_CLASSES_MAX_N)) {
+    if (n_big > 0 && (g_scan_launches == 2 || (g_scan_launches == 0 && N <= ALL_CLASSES_MAX_N))) {
         unsigned gx = capped((long long)cu_count() * 2, N);
         if (gx < 8) gx = 8;      // a block at least for every class
         if (n_big == 1)
@@ -1578,6 +1579,18 @@ static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *
     hipExtLaunchKernelGGL((k_update_scan_mfma_u8_small<KS>), dim3(capped(cu_count() * per_cu, N), ny), dim3(256), 0, st,
                           re.scan_start, n_big == 0 ? re.scan_stop : nullptr, 0, (const int8_t *)w.xs, R, keys, deg,
                           w.lists, N, w.props, w.nprop, c);
+    // large inputs: the short-list launch above, then the longer classes in one launch
+    if (n_big >= 2 && g_scan_launches != 1) {
+        unsigned gx = capped((long long)cu_count() * 2, N);
+        if (gx < 8) gx = 8;      // a block at least for every class
+        if (n_big == 2)
+            hipExtLaunchKernelGGL((k_update_scan_mfma_u8_all<KS, 5, 3>), dim3(gx), dim3(256), 0, st, nullptr, re.scan_stop, 0,
+                                  (const int8_t *)w.xs, R, keys, deg, w.lists, N, w.props, w.nprop, c);
+        else
+            hipExtLaunchKernelGGL((k_update_scan_mfma_u8_all<KS, 6, 3>), dim3(gx), dim3(256), 0, st, nullptr, re.scan_stop, 0,
+                                  (const int8_t *)w.xs, R, keys, deg, w.lists, N, w.props, w.nprop, c);
+        return;
+    }
     if (R > 32) launch_mfma_scan<2, KS>(w, R, keys, deg, N, c, st, n_big == 1 ? re.scan_stop : nullptr);
     if (R > 64) launch_mfma_scan<3, KS>(w, R, keys, deg, N, c, st, n_big == 2 ? re.scan_stop : nullptr);
     if (R > 96) launch_mfma_scan<4, KS>(w, R, keys, deg, N, c, st, n_big == 3 ? re.scan_stop : nullptr);
@@ -2493,7 +2506,7 @@ extern "C" int rnnd_set_kernel_variant(int variant)
 
 extern "C" int rnnd_set_scan_launches(int mode)
 {
-    if (mode < 0 || mode > 2) return RNND_ERR_BAD_PARAM;
+    if (mode < 0 || mode > 3) return RNND_ERR_BAD_PARAM;
     g_scan_launches = mode;
     return RNND_OK;
 }

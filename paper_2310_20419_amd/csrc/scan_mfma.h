@@ -606,14 +606,15 @@ __global__ __launch_bounds__(256, 4) void k_update_scan_mfma_u8_small(
     else scan_packed_body<1, KS>(X, R, keys, deg, list, n, props, nprop, ctr, sm, blockIdx.x, gridDim.x);
 }
 
-// Every degree class in one launch, all of them resident together: the grid's blocks are divided among the
+// Classes C0 .. NC - 1 in one launch, all of them resident together: the grid's blocks are divided among the
 // classes in proportion to their work (active lists x matrix tiles per list), one block at least for a class
-// that has any; every block derives the same division from the round's counters.  For inputs so small that
-// no class alone has enough lists to fill the chip: the classes then share the start-up and the tail that
-// each launch of its own pays.  NC classes: 3 short-list ones, then lists of at most 64, 96, 128 entries.
-// Every block carries the registers and the LDS of the longest class (two blocks per CU), which costs the
-// short-list classes occupancy: with many active lists the launches per class are faster.
-template <int KS, int NC>
+// that has any; every block derives the same division from the round's counters.  The classes then share the
+// start-up and the tail that each launch of its own pays.  NC classes: 3 short-list ones, then lists of at
+// most 64, 96, 128 entries.  Every block carries the registers and the LDS of the longest class (two blocks
+// per CU).  C0 = 0, every class: for inputs so small that no class alone has enough lists to fill the chip
+// (the short-list classes lose occupancy: with many active lists their own launch is faster).  C0 = 3, the
+// long-list classes only, next to k_update_scan_mfma_u8_small: for large inputs.
+template <int KS, int NC, int C0 = 0>
 __global__ __launch_bounds__(256, 2) void k_update_scan_mfma_u8_all(
     const int8_t *__restrict__ X, int R, u64 *__restrict__ keys, int *__restrict__ deg,
     const int *__restrict__ lists, long long N, Prop *__restrict__ props, int *__restrict__ nprop,
@@ -622,15 +623,16 @@ __global__ __launch_bounds__(256, 2) void k_update_scan_mfma_u8_all(
     constexpr int NGMAX = NC - 2;
     static_assert(NC >= 4 && NC <= 6, "short lists plus one to three long-list classes");
     __shared__ MfmaScanSmem<NGMAX> smem[4];
-    stamp_scan_start(ctr);
+    if (C0 == 0) stamp_scan_start(ctr);
     // work per list, in quarter tiles: 4, 2, 1 lists per tile; NG (NG + 1) / 2 tiles for NG groups of 32 rows
+    // (the division is sensitive: 18 or 32 instead of 24 for lists of 65..96 entries costs the 1M build 4 % of its scan time)
     constexpr u32 weight[6] = {1u, 2u, 4u, 12u, 24u, 40u};
     u32 n[NC];
     u64 total = 0;
     u32 nonempty = 0;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        n[c] = ctr->n_active[c];
+        n[c] = c >= C0 ? ctr->n_active[c] : 0u;
         total += (u64)n[c] * weight[c];
         nonempty += n[c] != 0u;
     }
@@ -660,9 +662,9 @@ __global__ __launch_bounds__(256, 2) void k_update_scan_mfma_u8_all(
     const int *list = lists + (size_t)cls * N;
     const int wave = threadIdx.x >> 6;
     MfmaScanSmem<1> &sm1 = *reinterpret_cast<MfmaScanSmem<1> *>(&smem[wave]);
-    if (cls == 0) scan_packed_body<4, KS>(X, R, keys, deg, list, n[0], props, nprop, ctr, sm1, block, mine);
-    else if (cls == 1) scan_packed_body<2, KS>(X, R, keys, deg, list, n[1], props, nprop, ctr, sm1, block, mine);
-    else if (cls == 2) scan_packed_body<1, KS>(X, R, keys, deg, list, n[2], props, nprop, ctr, sm1, block, mine);
+    if (C0 == 0 && cls == 0) scan_packed_body<4, KS>(X, R, keys, deg, list, n[0], props, nprop, ctr, sm1, block, mine);
+    else if (C0 == 0 && cls == 1) scan_packed_body<2, KS>(X, R, keys, deg, list, n[1], props, nprop, ctr, sm1, block, mine);
+    else if (C0 == 0 && cls == 2) scan_packed_body<1, KS>(X, R, keys, deg, list, n[2], props, nprop, ctr, sm1, block, mine);
     else if (cls == 3)
         scan_list_body<2, KS>(X, R, keys, deg, list, n[3], props, nprop, ctr, *reinterpret_cast<MfmaScanSmem<2> *>(&smem[wave]), block, mine);
     else if (NC > 4 && cls == 4)

@@ -56,7 +56,7 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert lib.rnnd_add_reverse_edges(100, 8, None, one, None) == -1
     assert lib.rnnd_set_kernel_variant(7) == -3 and lib.rnnd_set_kernel_variant(3) == -3
     assert lib.rnnd_set_kernel_variant(0) == 0
-    assert lib.rnnd_set_scan_launches(3) == -3 and lib.rnnd_set_scan_launches(-1) == -3 and lib.rnnd_set_scan_launches(0) == 0
+    assert lib.rnnd_set_scan_launches(4) == -3 and lib.rnnd_set_scan_launches(-1) == -3 and lib.rnnd_set_scan_launches(0) == 0
     # block-sequential entry points: same checks, plus the number of runs
     def blocks(**kw):
         a = dict(ok, **kw)

@@ -1,7 +1,8 @@
-"""The uint8 matrix-core scan of a round as several launches (short lists; one per longer class) or as one launch
-whose blocks are divided among all classes.  The default picks by size, so the small parity tests exercise the
-second and the 1M tests the first; here each is forced on the same inputs and must give the oracle's graph, the
-oracle's evaluation and redirect counts, and the same result as the other."""
+"""The uint8 matrix-core scan of a round as several launches (short lists; one per longer class), as one launch
+whose blocks are divided among all classes, or as the short-list launch plus one launch shared by the longer
+classes.  The default picks by size, so the small parity tests exercise the second and the 1M tests the third;
+here each is forced on the same inputs and must give the oracle's graph, the oracle's evaluation and redirect
+counts, and the same result as the others."""
 import numpy as np
 import pytest
 
@@ -49,7 +50,7 @@ def test_both_forms_give_the_oracles_build(rn, oracle_mod, case):
     want = oracle_mod.build_sync(X, S, R, T1, T2, wl.BUILD_SEED)
     out = {}
     try:
-        for mode in (1, 2):
+        for mode in (1, 2, 3):
             rn.rnnd_set_scan_launches(mode)
             graph, degree, keys, st = rn.rnnd_build_ex(cuda(X), S, R, T1, T2, wl.BUILD_SEED)
             assert st.kernel_variant == 2
@@ -60,27 +61,28 @@ def test_both_forms_give_the_oracles_build(rn, oracle_mod, case):
     finally:
         rn.rnnd_set_scan_launches(0)
     import torch
-    assert torch.equal(out[1][0], out[2][0]) and torch.equal(out[1][1], out[2][1])
-    for key in ("active", "proposals", "algo_evals", "exec_evals", "gathered_rows"):
-        assert out[1][2][key] == out[2][2][key], key
+    for mode in (2, 3):
+        assert torch.equal(out[1][0], out[mode][0]) and torch.equal(out[1][1], out[mode][1])
+        for key in ("active", "proposals", "algo_evals", "exec_evals", "gathered_rows"):
+            assert out[1][2][key] == out[mode][2][key], (mode, key)
 
 
 @pytest.mark.parametrize("n", [40_000, 600_000])
 def test_both_forms_agree_at_sizes_on_either_side_of_the_default_rule(rn, n):
-    """cfg2's generator at a size the default gives one launch and at a size it gives several: same graph, same
-    counters either way (the oracle check at such sizes is test_gpu_parity's)."""
+    """cfg2's generator at a size the default gives one launch and at a size it gives two: same graph, same
+    counters whichever form is forced (the oracle check at such sizes is test_gpu_parity's)."""
     import torch
     cfg = wl.CONFIGS["cfg2"]
     X = cuda(wl.custom("heavy_u8", n, 128, 31))
     out = {}
     try:
-        for mode in (0, 1, 2):
+        for mode in (0, 1, 2, 3):
             rn.rnnd_set_scan_launches(mode)
             g, dg, _, st = rn.rnnd_build_ex(X, cfg.S, cfg.R, 2, 6, wl.BUILD_SEED, want_keys=False)
             out[mode] = (g, dg, st.as_dict())
     finally:
         rn.rnnd_set_scan_launches(0)
-    for mode in (1, 2):
+    for mode in (1, 2, 3):
         assert torch.equal(out[0][0], out[mode][0]) and torch.equal(out[0][1], out[mode][1])
         for key in ("active", "proposals", "algo_evals", "exec_evals", "gathered_rows"):
             assert out[0][2][key] == out[mode][2][key], (mode, key)
