@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # WRITE_SIZE (two runs, each scaled by what the same counter reads for a plain 1 GiB copy in the same run);
 # see profiles/update_scan_cfg{3,4,5}_hbm_traffic.txt.  Keyed by (workload, kernel variant); None where it
 # has not been measured.
-TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.0228e9, ("cfg4", 3): 8.544e9, ("cfg5", 3): 8.3522e10}
+TRAFFIC_PER_LAUNCH = {("cfg3", 2): 1.0224e9, ("cfg4", 3): 8.544e9, ("cfg5", 3): 8.3522e10}
 
 
 def host_cpu():
@@ -76,6 +76,19 @@ def cpu_baseline(cfg, X, sample_n, gpu_algo_evals):
         "sample_rows": sample_n, "sample_seconds": dt, "distance_evals_per_s": evals / dt,
         "host": host_cpu(),
     }
+
+
+def u8_scan_kernels(cfg):
+    """The launches that make up one round's uint8 matrix-core scan (the library's rule: by R and N)."""
+    ks = cfg.d // 32
+    if cfg.R <= 32:
+        return "k_update_scan_mfma_u8_small<%d> (one launch per round)" % ks
+    if cfg.N <= 524288:
+        return "k_update_scan_mfma_u8_all<%d,NC> (one launch per round for all degree classes)" % ks
+    if cfg.R <= 64:
+        return "k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8<2,%d> (one round's scan launches, back to back)" % (ks, ks)
+    return ("k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8_all<%d,NC,3> (one round's scan launches: lists of at "
+            "most 32 entries, then the longer classes; back to back)" % (ks, ks))
 
 
 def exact_top10(Xd, Qd):
@@ -199,8 +212,7 @@ def measure(rn, cfg, X, Xd, esz, st16, steps, warmup, args, with_search=True, wi
     hbm_gbs = scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
     kv = s["kernel_variant"]
     kname = {1: "k_update_scan",
-             2: "k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8<NG,%d>, NG = 2,3 (one round's scan launches, "
-                "back to back)" % (cfg.d // 32, cfg.d // 32),
+             2: u8_scan_kernels(cfg),
              3: "k_update_scan_mfma_f32<NG,CH,NRC,fast> (one launch per degree class, back to back per round; "
                 "%s MFMA Gram tiles, undecided pairs by exact distances)" % (st16 if half else "fp32")}[kv]
     traffic = None if half or args.merge_cap or args.blocks else TRAFFIC_PER_LAUNCH.get((cfg.name, kv))
