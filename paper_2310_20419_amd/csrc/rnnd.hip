@@ -302,6 +302,41 @@ __global__ __launch_bounds__(1024) void k_assign_bins(long long N, const int *cn
     }
 }
 
+// The active lists of a round's first ncl degree classes walked as one: start[k] = entries of the classes before k.
+struct ActiveLists {
+    const int *lists;
+    long long N;
+    u32 start[NDEG + 1];
+};
+
+__device__ __forceinline__ ActiveLists active_lists(const int *lists, long long N, const RoundCtr *ctr, int ncl)
+{
+    ActiveLists a;
+    a.lists = lists;
+    a.N = N;
+    u32 sum = 0;
+#pragma unroll
+    for (int k = 0; k < NDEG; ++k) {
+        a.start[k] = sum;
+        sum += k < ncl ? ctr->n_active[k] : 0u;
+    }
+    a.start[NDEG] = sum;
+    return a;
+}
+
+// entry i of the concatenation, i < start[NDEG]
+__device__ __forceinline__ int active_vertex(const ActiveLists &a, u32 i)
+{
+    u32 c = 0, off = i;
+#pragma unroll
+    for (int k = 1; k < NDEG; ++k)
+        if (i >= a.start[k]) {
+            c = (u32)k;
+            off = i - a.start[k];
+        }
+    return a.lists[(size_t)c * (size_t)a.N + off];
+}
+
 // Bit j set iff lane j of this lane's row of 16 holds the same value, for the lanes reached by rotations R .. 15.
 template <int R>
 __device__ __forceinline__ u32 same_target_mask(u32 tgt, int sub)
@@ -321,19 +356,20 @@ __device__ __forceinline__ u32 same_target_mask(u32 tgt, int sub)
 // group that share a target take their arrival numbers with one atomic (a vertex usually redirects
 // several entries to the same kept neighbour).  Arrivals below INBOX_CAP go to the target's inbox;
 // later ones record their number in the edge and are placed by k_scatter_surplus once bins exist.
-__global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int *lists, RoundCtr *ctr,
+__global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int *lists, int ncl, RoundCtr *ctr,
                                                    Prop *props, int *nprop, int *fill, u64 *inbox)
 {
-    const int lane = threadIdx.x & 63, sub = lane & 15, gbase = lane & ~15, c = blockIdx.y;
+    const int lane = threadIdx.x & 63, sub = lane & 15, gbase = lane & ~15;
     const u32 g = (blockIdx.x * BLOCK + threadIdx.x) >> 4, ng = (gridDim.x * BLOCK) >> 4;
-    const u32 n = ctr->n_active[c];
-    const int *list = lists + (size_t)c * N;
+    // the classes' lists as one: the grid is shared by their entries, however they are spread over the classes
+    const ActiveLists al = active_lists(lists, N, ctr, ncl);
+    const u32 n = al.start[NDEG];
     bool surplus = false;
     stamp_scan_stop(ctr);
     if (g >= n) return;
     // the loads of the next vertex (its count and its first 16 edges) are issued before the atomics
     // of the current one; the list entry of the vertex after that is fetched one trip earlier still
-    auto vertex_at = [&](unsigned long long i) -> int { return i < n ? list[i] : -1; };
+    auto vertex_at = [&](unsigned long long i) -> int { return i < n ? active_vertex(al, (u32)i) : -1; };
     auto first_edges = [&](int u, int &np, Prop &pr) {
         np = 0;
         pr.key = 0; pr.tgt = 0xFFFFFFFFu; pr.arrival = 0;
@@ -389,17 +425,17 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(long long N, int R, const int
 }
 
 // Second pass, only when some vertex received more than INBOX_CAP edges: the late arrivals go to bins.
-__global__ __launch_bounds__(BLOCK) void k_scatter_surplus(long long N, int R, const int *lists,
+__global__ __launch_bounds__(BLOCK) void k_scatter_surplus(long long N, int R, const int *lists, int ncl,
                                                            const RoundCtr *ctr, const Prop *props,
                                                            const int *nprop, const int *binoff, u64 *bins)
 {
     if (ctr->has_surplus == 0) return;
-    const int sub = threadIdx.x & 15, c = blockIdx.y;
+    const int sub = threadIdx.x & 15;
     const u32 g = (blockIdx.x * BLOCK + threadIdx.x) >> 4, ng = (gridDim.x * BLOCK) >> 4;
-    const u32 n = ctr->n_active[c];
-    const int *list = lists + (size_t)c * N;
-    for (u32 it = g; it < n; it += ng) {
-        const int u = list[it];
+    const ActiveLists al = active_lists(lists, N, ctr, ncl);
+    const u32 n = al.start[NDEG];
+    for (unsigned long long it = g; it < n; it += ng) {
+        const int u = active_vertex(al, (u32)it);
         int np = nprop[u];
         if (!(np & SURPLUS_MARK)) continue;
         np &= ~SURPLUS_MARK;
@@ -1731,11 +1767,11 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
     }
     // from here on `fill` plays the role of the per-target count of this round
     const int ncl = use_classes ? NDEG : 1;
-    hipLaunchKernelGGL(k_scatter, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop, w.fill,
+    hipLaunchKernelGGL(k_scatter, dim3(pb), dim3(BLOCK), 0, st, N, R, w.lists, ncl, c, w.props, w.nprop, w.fill,
                        w.inbox);
     hipLaunchKernelGGL(k_touch_classify, dim3((unsigned)((N + 1024 * TC_TILES - 1) / (1024 * TC_TILES))), dim3(1024), 0, st, N, w.fill, deg,
                        w.binoff, c, w.touched);
-    hipLaunchKernelGGL(k_scatter_surplus, dim3(pb, ncl), dim3(BLOCK), 0, st, N, R, w.lists, c, w.props, w.nprop,
+    hipLaunchKernelGGL(k_scatter_surplus, dim3(pb), dim3(BLOCK), 0, st, N, R, w.lists, ncl, c, w.props, w.nprop,
                        w.binoff, w.bins);
     static const int merge_per_cu = resident_blocks_per_cu(k_merge, 6);
     hipLaunchKernelGGL(k_merge, dim3(capped(cu_count() * merge_per_cu, N), NMRG), dim3(BLOCK), 0, st, N, R, keys, deg, w.touched, c->n_touched,

@@ -624,9 +624,11 @@ __global__ __launch_bounds__(256, 2) void k_update_scan_mfma_u8_all(
     static_assert(NC >= 4 && NC <= 6, "short lists plus one to three long-list classes");
     __shared__ MfmaScanSmem<NGMAX> smem[4];
     if (C0 == 0) stamp_scan_start(ctr);
-    // work per list, in quarter tiles: 4, 2, 1 lists per tile; NG (NG + 1) / 2 tiles for NG groups of 32 rows
-    // (the division is sensitive: 18 or 32 instead of 24 for lists of 65..96 entries costs the 1M build 4 % of its scan time)
-    constexpr u32 weight[6] = {1u, 2u, 4u, 12u, 24u, 40u};
+    // work per list: 4, 2, 1 lists share a tile; among the longer classes in proportion to their NG (NG + 1) / 2
+    // tiles (3 : 6 : 10; the division is sensitive there: 3 : 4.5 or 3 : 8 costs the 1M build 4 % of its scan time),
+    // and a 64-entry list weighted 2.25 short tiles (measured on 100,000 vertices: 1.5 -> 1.60 ms, 2 -> 1.51, 2.25 ->
+    // 1.49, 3 -> 1.53, 4 -> 1.70 ms of scan time per build)
+    constexpr u32 weight[6] = {4u, 8u, 16u, 36u, 72u, 120u};
     u32 n[NC];
     u64 total = 0;
     u32 nonempty = 0;
