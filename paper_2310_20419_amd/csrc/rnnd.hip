@@ -456,8 +456,10 @@ __device__ __forceinline__ int merge_class(int nb, int c)
 
 // Every vertex x that received edges (cnt[x] > 0) is appended to the touched list of its merge class;
 // if it received more than INBOX_CAP it also gets a bin for the surplus.  A block covers TC_TILES x 1024
-// vertices and takes its space with one atomic per class (and one for the bins).
-#define TC_TILES 4
+// vertices and takes its space with one atomic per class (and one for the bins).  Four tiles per block
+// keep the atomics of a 1M-vertex round few; on small inputs two tiles (twice the blocks, a shorter chain in
+// each) are faster: 100,000 vertices 4.68 -> 4.55 ms per build, 1M 26.0 -> 26.1 ms.
+template <int TC_TILES>
 __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int *cnt, const int *deg,
                                                          int *binoff, RoundCtr *ctr, int *tlists)
 {
@@ -494,19 +496,22 @@ __global__ __launch_bounds__(1024) void k_touch_classify(long long N, const int 
     __syncthreads();
     if (wave == 0) {
         // exclusive prefix over the TC_TILES x 16 wavefront totals, in (tile, wavefront) order: lane = tile * 16 + wavefront
-        static_assert(TC_TILES * 16 == 64, "one lane of the first wavefront per (tile, wavefront)");
-        const int k = lane >> 4, w = lane & 15;
+        static_assert(TC_TILES * 16 <= 64, "one lane of the first wavefront per (tile, wavefront)");
+        const bool used = lane < TC_TILES * 16;
+        const int k = used ? lane >> 4 : 0, w = lane & 15;
 #pragma unroll
         for (int q = 0; q <= NMRG; ++q) {
-            const u32 a = q < NMRG ? s_cnt[k][w][q] : s_sum[k][w];
+            const u32 a = !used ? 0u : q < NMRG ? s_cnt[k][w][q] : s_sum[k][w];
             u32 in = a;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 u32 v = __shfl_up(in, o);
                 if (lane >= o) in += v;
             }
-            if (q < NMRG) s_cnt[k][w][q] = in - a;
-            else s_sum[k][w] = in - a;
+            if (used) {
+                if (q < NMRG) s_cnt[k][w][q] = in - a;
+                else s_sum[k][w] = in - a;
+            }
             if (lane == 63) s_base[q] = in;
         }
         wave_sync();
@@ -1400,7 +1405,7 @@ static int g_kernel_variant = 0;
 static int g_event_timing = 0;    // 1: per-round times of the statistics from HIP events attached to the launches
 static int g_transpose_path = 0;   // AddReverseEdges' transposition: 0 by size, 1 atomics, 2 binned
 static int g_scan_launches = 0;    // uint8 matrix-core scan: 0 by size, 1 short lists + one launch per longer class, 2 one launch for all, 3 short lists + one launch for all longer classes
-#define ALL_CLASSES_MAX_N 524288   // up to here one launch for all classes is the fastest form (measured, whole build against
+#define SMALL_INPUT_MAX_N 524288   // up to here one launch for all classes is the fastest form (measured, whole build against
                                    // launches per class: 0.75 x at 50,000 vertices, 0.78 x at 100,000, 0.90 x at 300,000, 0.955 x
                                    // at 500,000; 1.02 x at 1M, where it wins only in rounds with fewer than 250,000 active lists).
                                    // Above: the short-list launch and one launch for all longer classes (0.99 x at 1M)
@@ -1597,7 +1602,7 @@ static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *
     static const int per_cu = resident_blocks_per_cu(k_update_scan_mfma_u8_small<KS>, 4);
     const int n_big = (R > 32) + (R > 64) + (R > 96);   // launches after the short-list kernel
     // small inputs: every class in one launch (see k_update_scan_mfma_u8_all)
-    if (n_big > 0 && (g_scan_launches == 2 || (g_scan_launches == 0 && N <= ALL_CLASSES_MAX_N))) {
+    if (n_big > 0 && (g_scan_launches == 2 || (g_scan_launches == 0 && N <= SMALL_INPUT_MAX_N))) {
         unsigned gx = capped((long long)cu_count() * 2, N);
         if (gx < 8) gx = 8;      // a block at least for every class
         if (n_big == 1)
@@ -1769,8 +1774,12 @@ static hipError_t launch_update_round(const Workspace &w, const void *X, long lo
     const int ncl = use_classes ? NDEG : 1;
     hipLaunchKernelGGL(k_scatter, dim3(pb), dim3(BLOCK), 0, st, N, R, w.lists, ncl, c, w.props, w.nprop, w.fill,
                        w.inbox);
-    hipLaunchKernelGGL(k_touch_classify, dim3((unsigned)((N + 1024 * TC_TILES - 1) / (1024 * TC_TILES))), dim3(1024), 0, st, N, w.fill, deg,
-                       w.binoff, c, w.touched);
+    if (N <= SMALL_INPUT_MAX_N)
+        hipLaunchKernelGGL(k_touch_classify<2>, dim3((unsigned)((N + 2047) / 2048)), dim3(1024), 0, st, N, w.fill, deg, w.binoff, c,
+                           w.touched);
+    else
+        hipLaunchKernelGGL(k_touch_classify<4>, dim3((unsigned)((N + 4095) / 4096)), dim3(1024), 0, st, N, w.fill, deg, w.binoff, c,
+                           w.touched);
     hipLaunchKernelGGL(k_scatter_surplus, dim3(pb), dim3(BLOCK), 0, st, N, R, w.lists, ncl, c, w.props, w.nprop,
                        w.binoff, w.bins);
     static const int merge_per_cu = resident_blocks_per_cu(k_merge, 6);
