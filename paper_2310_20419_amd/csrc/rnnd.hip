@@ -1409,6 +1409,7 @@ static int g_scan_launches = 0;    // uint8 matrix-core scan: 0 by size, 1 short
                                    // launches per class: 0.75 x at 50,000 vertices, 0.78 x at 100,000, 0.90 x at 300,000, 0.955 x
                                    // at 500,000; 1.02 x at 1M, where it wins only in rounds with fewer than 250,000 active lists).
                                    // Above: the short-list launch and one launch for all longer classes (0.99 x at 1M)
+                                   // (bench.py names the round's scan launches by the same rule; include/rnnd.h states it)
 #define BIN_MIN_N 262144            // below this the binned transposition's extra launches cost more than its atomics save
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
