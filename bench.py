@@ -85,8 +85,9 @@ def u8_scan_kernels(cfg):
         return "k_update_scan_mfma_u8_small<%d> (one launch per round)" % ks
     if cfg.N <= 524288:
         return "k_update_scan_mfma_u8_all<%d,NC> (one launch per round for all degree classes)" % ks
-    if cfg.R <= 64:
-        return "k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8<2,%d> (one round's scan launches, back to back)" % (ks, ks)
+    if cfg.R <= 64 or cfg.N > 2097152:
+        return ("k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8<NG,%d>, NG = 2 .. %d (one round's scan launches, back "
+                "to back)" % (ks, ks, (cfg.R + 31) // 32))
     return ("k_update_scan_mfma_u8_small<%d> + k_update_scan_mfma_u8_all<%d,NC,3> (one round's scan launches: lists of at "
             "most 32 entries, then the longer classes; back to back)" % (ks, ks))
 

@@ -271,8 +271,8 @@ int rnnd_set_kernel_variant(int variant);
  * Process-wide, not thread-safe. */
 int rnnd_set_transpose_path(int path);
 
-/* Selects how the uint8 matrix-core scan of a round is launched: 0 = by size (default: N <= 524,288 as 2, else
- * as 3), 1 = one launch for the three short-list classes and one per longer class (each with the occupancy that
+/* Selects how the uint8 matrix-core scan of a round is launched: 0 = by size (default: N <= 524,288 as 2, N <=
+ * 2,097,152 as 3, else as 1), 1 = one launch for the three short-list classes and one per longer class (each with the occupancy that
  * suits it), 2 = one launch in which the blocks are divided among all classes in proportion to their work (the
  * classes share one start-up and one tail; pays when no class alone fills the chip), 3 = the short-list launch
  * and one launch shared by all longer classes.  All give identical graphs and counters; this exists for testing

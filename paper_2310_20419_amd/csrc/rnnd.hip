@@ -1409,6 +1409,8 @@ static int g_scan_launches = 0;    // uint8 matrix-core scan: 0 by size, 1 short
                                    // launches per class: 0.75 x at 50,000 vertices, 0.78 x at 100,000, 0.90 x at 300,000, 0.955 x
                                    // at 500,000; 1.02 x at 1M, where it wins only in rounds with fewer than 250,000 active lists).
                                    // Above: the short-list launch and one launch for all longer classes (0.99 x at 1M)
+#define LONG_SHARED_MAX_N 2097152  // ... up to here (1.00 x at 2M, 1.01 x at 4M, 1.00 x at 8M, 1.01 x at 20M: no start-up left to
+                                   // share, and each class alone gets the occupancy that suits it); above: a launch per class
                                    // (bench.py names the round's scan launches by the same rule; include/rnnd.h states it)
 #define BIN_MIN_N 262144            // below this the binned transposition's extra launches cost more than its atomics save
 
@@ -1622,7 +1624,7 @@ static void launch_mfma_scan_classes(const Workspace &w, int R, u64 *keys, int *
                           re.scan_start, n_big == 0 ? re.scan_stop : nullptr, 0, (const int8_t *)w.xs, R, keys, deg,
                           w.lists, N, w.props, w.nprop, c);
     // large inputs: the short-list launch above, then the longer classes in one launch
-    if (n_big >= 2 && g_scan_launches != 1) {
+    if (n_big >= 2 && (g_scan_launches == 3 || (g_scan_launches == 0 && N <= LONG_SHARED_MAX_N))) {
         unsigned gx = capped((long long)cu_count() * 2, N);
         if (gx < 8) gx = 8;      // a block at least for every class
         if (n_big == 2)

@@ -1,6 +1,7 @@
 """The uint8 matrix-core scan of a round as several launches (short lists; one per longer class), as one launch
 whose blocks are divided among all classes, or as the short-list launch plus one launch shared by the longer
-classes.  The default picks by size, so the small parity tests exercise the second and the 1M tests the third;
+classes.  The default picks by size, so the small parity tests exercise the second, the 1M tests the third and the 20M test
+the first;
 here each is forced on the same inputs and must give the oracle's graph, the oracle's evaluation and redirect
 counts, and the same result as the others."""
 import numpy as np
