@@ -46,9 +46,10 @@ struct RoundCtr {
     u32 pad[2];
     u32 n_redo[NDEG];     // float scan: vertices the single-precision form left to the double-precision one
     // ticks of the device's constant-rate clock (0 = not taken): the round's first scan launch starts, its scatter
-    // starts (= the scan has ended: launches of one stream run back to back), the round's / the following
-    // AddReverseEdges call's last kernel has ended (taken by k_stamp, only where statistics ask for it)
-    u64 t_scan_start, t_scan_stop, t_round_stop, t_reverse_stop;
+    // starts (= the scan has ended: launches of one stream run back to back), the round's last kernel has ended
+    // (taken by k_stamp after the last round before an AddReverseEdges call or the export, only where statistics
+    // ask for it; every other round, and an AddReverseEdges call, ends where the next round's scan starts)
+    u64 t_scan_start, t_scan_stop, t_round_stop;
     // statistics, spread over STAT_SLOTS addresses so that the adds of many blocks do not queue up
     // on one: [slot][0..4] = algorithmic evals, executed evals, rows gathered, edges redirected, entries a merge
     // dropped because the list was full
@@ -2149,7 +2150,6 @@ static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric
             if (t1 != T1 - 1) {
                 HIPCHK(launch_reverse(w, N, R, use_classes, w.keys, w.deg, blocks ? -1 : t, st,
                                       ev_rounds ? ev[e_rev + t1] : nullptr, M));
-                if (stats && !ev_rounds) hipLaunchKernelGGL(k_stamp, dim3(1), dim3(64), 0, st, &w.ctr[t - 1].t_reverse_stop);
             }
         }
         launch_export(N, M, w.keys, w.deg, graph_out, degree_out, st);
@@ -2182,7 +2182,8 @@ static int build_impl(const void *X, int64_t N, int32_t d, int dtype, int metric
                     stats->scan_ms[tt] = clk_ms(hctr[tt].t_scan_start, hctr[tt].t_scan_stop);
                     stats->round_ms[tt] = clk_ms(hctr[tt].t_scan_start, t2 == T2 - 1 ? hctr[tt].t_round_stop : hctr[tt + 1].t_scan_start);
                 }
-                if (t1 != T1 - 1 && t1 < RNND_MAX_ROUNDS) stats->reverse_ms[t1] = clk_ms(hctr[tt - 1].t_round_stop, hctr[tt - 1].t_reverse_stop);
+                // an AddReverseEdges call ends where the next round's scan starts
+                if (t1 != T1 - 1 && t1 < RNND_MAX_ROUNDS) stats->reverse_ms[t1] = clk_ms(hctr[tt - 1].t_round_stop, hctr[tt].t_scan_start);
             }
             for (int t1 = 0; t1 < T1 && ev_rounds; ++t1) {
                 for (int t2 = 0; t2 < T2; ++t2, ++tt) {
